@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the GLA forward hot path on one MI355X.
+
+A step is one call of the whole path (gla_fwd_ex: span states, carry, outputs)
+on one batch of synthetic DiG-XL/2 activations at 2048 px (B=1, H=16, T=16384,
+dk=36, dv=72, bf16 q/k/v, fp32 log_alpha, fp32 out), inputs resident in HBM.
+Steps rotate over several independent buffer sets so that every call streams
+from HBM rather than from the 256 MB last-level cache.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def algorithmic_bytes_per_token_head(dk, dv, qkv_bytes, out_bytes):
+    # q, k, v read once, log_alpha (fp32) read once, out written once
+    return 2 * dk * qkv_bytes + dk * 4 + dv * qkv_bytes + dv * out_bytes
+
+
+def algorithmic_flops_per_token_head(dk, dv, chunk=64):
+    # state update + state read: 4*dk*dv ; causal half of the in-chunk scores and their use: (C+1)(dk+dv)
+    return 4 * dk * dv + (chunk + 1) * (dk + dv)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="dig_xl2_2048")
+    ap.add_argument("--scan", type=int, default=0)
+    ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated over (1 = cache-warm)")
+    ap.add_argument("--chunks-per-span", type=int, default=0)
+    ap.add_argument("--engine", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (no collectives or sharding exist here)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2405_18428_amd as gla
+    from paper_2405_18428_amd import inputs as gi
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    gla.load_library()  # raises if the HIP library is not built; there is no fallback
+    gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, args.chunks_per_span)
+    gla.gla_set_option(gla.OPT_ENGINE, args.engine)
+
+    cfg = gi.CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    d = gi.make_config_inputs(cfg)
+    B, H, T, dk, dv = cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv
+    if cfg.dtype == "bf16":
+        host = [torch.from_numpy(d[n + "_bits"].view(np.int16)).view(torch.bfloat16) for n in ("q", "k", "v")]
+    else:
+        host = [torch.from_numpy(d[n]) for n in ("q", "k", "v")]
+    host.append(torch.from_numpy(d["log_alpha"]))
+    out_dt = torch.float32 if args.out_dtype == "f32" else torch.bfloat16
+    qdt = gla.DT_BF16 if cfg.dtype == "bf16" else gla.DT_F32
+    ws_bytes = gla.gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
+
+    sets = []
+    for _ in range(max(1, args.sets)):
+        q, k, v, la = (t.to(dev) for t in host)
+        sets.append(dict(q=q, k=k, v=v, la=la,
+                         out=torch.empty((B, H, T, dv), dtype=out_dt, device=dev),
+                         fin=torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev),
+                         ws=torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)))
+
+    def step(i):
+        s = sets[i % len(sets)]
+        gla.gla_fwd_ex(s["q"], s["k"], s["v"], s["la"], cfg.grid_h, cfg.grid_w, args.scan,
+                       out=s["out"], final_state=s["fin"], workspace=s["ws"])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = B * T / (ms_per_step * 1e-3)
+
+    # per-kernel durations with HIP events on the launch stream, rotating over the same sets
+    phase = np.zeros(4)
+    reps = 0
+    for r in range(8):
+        for s in sets:
+            ms = gla.gla_fwd_timed(s["q"], s["k"], s["v"], s["la"], cfg.grid_h, cfg.grid_w, args.scan,
+                                   s["out"], s["fin"], s["ws"], iters=1)
+            if r >= 2:
+                phase += np.array(ms)
+                reps += 1
+    phase /= max(reps, 1)
+    names = ["span_state", "carry", "output"]
+    dom = int(np.argmax(phase[:3]))
+    qb = 2 if cfg.dtype == "bf16" else 4
+    ob = 4 if args.out_dtype == "f32" else 2
+    alg_bytes = algorithmic_bytes_per_token_head(dk, dv, qb, ob) * B * H * T
+    alg_flops = algorithmic_flops_per_token_head(dk, dv) * B * H * T
+    achieved = alg_bytes / (phase[dom] * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": names[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "algorithmic_bytes": alg_bytes, "kernel_ms": round(float(phase[dom]), 5),
+        "phase_ms": {n: round(float(x), 5) for n, x in zip(names + ["whole_call"], phase)},
+        "whole_path_frac": round(alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "mfma_tflops": round(alg_flops / (ms_per_step * 1e-3) / 1e12, 2),
+        "mfma_frac": round(alg_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5),
+    }
+
+    result = {
+        "metric": "GLA fwd tokens/s at DiG-XL/2 shape T=16384; % bf16 MFMA roofline",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={B} H={H} T={T} ({cfg.grid_h}x{cfg.grid_w}) dk={dk} dv={dv} "
+                               f"{cfg.dtype} q/k/v, fp32 log_alpha, {args.out_dtype} out, scan={args.scan}",
+                   "buffer_sets": len(sets), "engine": gla.gla_get_option(gla.OPT_ENGINE),
+                   "chunks_per_span": gla.gla_get_option(gla.OPT_CHUNKS_PER_SPAN)},
+        "roofline": roofline,
+    }
+
+    if not args.no_check or not args.no_cpu_baseline:
+        from oracle import gla_oracle
+        q64, k64, v64, g64 = (np.asarray(d[n], dtype=np.float64) for n in ("q", "k", "v", "log_alpha"))
+        best = None
+        runs = 1 if args.no_cpu_baseline else 3
+        for _ in range(runs):
+            c0 = time.perf_counter()
+            ref, ref_fin = gla_oracle.gla_fwd(q64, k64, v64, g64, cfg.grid_h, cfg.grid_w, args.scan)
+            c1 = time.perf_counter()
+            best = c1 - c0 if best is None else min(best, c1 - c0)
+        if not args.no_cpu_baseline:
+            result["cpu_baseline"] = {
+                "value": round(B * T / best, 1), "unit": "tokens/s",
+                "cores": min(gla_oracle.threads(), B * H), "kind": "oracle",
+                "sample": f"the whole workload ({B * H} sequences of {T} tokens), best of {runs} runs, "
+                          f"fp64 token-by-token C loop, OpenMP over batch*head",
+            }
+        if not args.no_check:
+            s = sets[0]
+            step(0)
+            torch.cuda.synchronize()
+            rms = float(np.sqrt(np.mean(ref ** 2)))
+            err = float(np.abs(s["out"].float().cpu().numpy() - ref).max() / rms)
+            result["max_err_over_rms"] = round(err, 6)
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,154 @@
+/*
+ * gla.h - C ABI of the MI355X (gfx950) forward pass of the gated-linear-attention
+ * (GLA) token mixer used in the DiG diffusion backbone.
+ *
+ * Operation (DiG paper, Sec. 3.1 "Gated Linear Attention Transformer",
+ * Eq. (attn_gla), rows 1-3, with the gate G_t reduced to its key-side factor
+ * alpha_t, i.e. beta_t = 1):
+ *
+ *     S_t = diag(alpha_t) S_{t-1} + k_t^T v_t ,     o_t = q_t S_t ,     S_0 = 0
+ *
+ * per (batch, head), S in R^{dk x dv}, evaluated in the chunk-parallel form of
+ * Sec. 3.5 ("Efficiency Analysis": the sequence is cut into chunks that are
+ * computed on-chip, cost O(T M D + T D^2)).  The tokens of one image form a
+ * grid_h x grid_w grid; the recurrence runs along one of the four scan orders
+ * that the DiG block obtains by alternately transposing and flipping the token
+ * grid (Sec. 3.3, Algorithm 1; operators of the supplementary Algorithms 2-4).
+ * The permutation is folded into the kernels' address arithmetic: tensors stay
+ * in canonical order and nothing is transposed in memory.
+ *
+ * Conventions common to every entry point
+ * ---------------------------------------
+ * Pointers marked DEVICE are device (HBM) addresses owned by the caller; the
+ * library never frees, reallocates or retains them.  All tensors are dense,
+ * row-major, in canonical token order n = r * grid_w + c for every scan order:
+ *
+ *     q, k        : [B, H, T, dk]   element type qkv_dtype (bf16 or fp32)
+ *     log_alpha   : [B, H, T, dk]   fp32, log(alpha_t) <= 0 (e.g. logsigmoid(z)/tau)
+ *     v           : [B, H, T, dv]   element type qkv_dtype
+ *     out         : [B, H, T, dv]   element type out_dtype; out[n] = o at token n
+ *     final_state : [B, H, dk, dv]  fp32, the state after the last scan step; may be NULL
+ *
+ * T must equal grid_h * grid_w.  No 1/sqrt(dk) scale is applied (the recurrence
+ * has none); scale q beforehand.  Supported head sizes: 1 <= dk <= 64,
+ * 1 <= dv <= 128.  T need not be a multiple of the chunk length.
+ *
+ * Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
+ * default stream) and return without synchronising the host; results are valid
+ * once the stream reaches that point.  Inputs must stay unmodified until then.
+ * Outputs must not alias inputs.  The current HIP device must be the one that
+ * owns the buffers.
+ *
+ * Every function returns a gla_status (0 = success).  On any error nothing has
+ * been enqueued and no output byte has been written.  Preconditions that are
+ * not checked on the device: log_alpha <= 0 and finite inputs.  The bf16 tensor-
+ * core engine additionally needs the summed |log_alpha| over any 64 consecutive
+ * scan steps of one key channel to stay below 80 (true for alpha =
+ * sigmoid(z)^(1/16) whenever z > -20); GLA_ENGINE_RECURRENT has no such limit.
+ */
+#ifndef GLA_H_
+#define GLA_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GLA_OK = 0,
+    GLA_ERR_NULL = 1,        /* a required pointer is NULL */
+    GLA_ERR_SHAPE = 2,       /* non-positive size, grid_h*grid_w != T, or a bad enum value */
+    GLA_ERR_UNSUPPORTED = 3, /* dk > 64, dv > 128, or a dtype / engine combination not built */
+    GLA_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned */
+    GLA_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than gla_fwd_workspace_bytes() */
+    GLA_ERR_HIP = 6          /* the HIP runtime reported an error (allocation or launch) */
+} gla_status;
+
+/* Scan orders (Sec. 3.3 / Algorithm 1).  Scan step s visits canonical token n:
+ *   ROW_FWD  n = s                       ROW_REV  n = T-1-s
+ *   COL_FWD  n = (s % grid_h) * grid_w + s / grid_h   (down a column, then the next column)
+ *   COL_REV  the COL_FWD sequence read from its last step backwards              */
+typedef enum { GLA_SCAN_ROW_FWD = 0, GLA_SCAN_ROW_REV = 1,
+               GLA_SCAN_COL_FWD = 2, GLA_SCAN_COL_REV = 3 } gla_scan_dir;
+
+typedef enum { GLA_DT_F32 = 0, GLA_DT_BF16 = 1 } gla_dtype;
+
+/* Options for gla_set_option (process-wide, meant for tuning and tests). */
+typedef enum {
+    GLA_OPT_CHUNKS_PER_SPAN = 0, /* 0 = choose automatically; n > 0 = n 64-token chunks per work-group */
+    GLA_OPT_ENGINE = 1           /* gla_engine */
+} gla_option;
+typedef enum {
+    GLA_ENGINE_AUTO = 0,      /* bf16 inputs with dk % 4 == 0 and dv % 2 == 0 -> MFMA, else recurrent */
+    GLA_ENGINE_RECURRENT = 1, /* fp32 token-by-token arithmetic inside each span; any dtype, any gates */
+    GLA_ENGINE_MFMA = 2       /* bf16 MFMA chunk form (Sec. 3.5); bf16 inputs only */
+} gla_engine;
+
+typedef void *gla_stream_t; /* a hipStream_t */
+
+/*
+ * gla_fwd - GLA forward for bf16 q/k/v, fp32 log_alpha, fp32 out
+ * (Eq. (attn_gla) rows 1-3 along `scan_dir`; chunk form of Sec. 3.5).
+ *
+ *   q, k, v      DEVICE, bf16, layouts above            (read)
+ *   log_alpha    DEVICE, fp32                           (read)
+ *   out          DEVICE, fp32 [B,H,T,dv]                (written)
+ *   final_state  DEVICE, fp32 [B,H,dk,dv] or NULL       (written if not NULL)
+ *
+ * Uses a library-owned scratch buffer per device that grows on demand with
+ * hipMalloc (which synchronises the device the first time a larger problem is
+ * seen) and is kept until the process ends; concurrent calls on different
+ * streams of one device would share it and are not supported - use gla_fwd_ex
+ * with separate workspaces for that.
+ */
+int gla_fwd(const void *q, const void *k, const void *v, const float *log_alpha,
+            int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+            float *out, float *final_state, gla_stream_t stream);
+
+/*
+ * gla_fwd_ex - the same operation with explicit element types and a caller-owned
+ * workspace; never allocates.
+ *
+ *   qkv_dtype        gla_dtype of q, k, v
+ *   out_dtype        gla_dtype of out (final_state is always fp32)
+ *   workspace        DEVICE, 16-byte aligned, at least gla_fwd_workspace_bytes(...) bytes;
+ *                    contents on entry are ignored, contents on return are unspecified
+ */
+int gla_fwd_ex(const void *q, const void *k, const void *v, const float *log_alpha,
+               int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+               int qkv_dtype, int out_dtype, void *out, float *final_state,
+               void *workspace, size_t workspace_bytes, gla_stream_t stream);
+
+/* Bytes of workspace gla_fwd_ex needs for this problem (an upper bound over all
+ * launch plans, so it does not depend on tuning options).  0 on invalid sizes. */
+size_t gla_fwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);
+
+/*
+ * gla_fwd_timed - measurement aid: runs gla_fwd_ex `iters` times on `stream`
+ * with HIP events around each of the three phases of the chunk-parallel plan
+ * (Sec. 3.5 cut into spans: local span states, carry across spans, outputs) and
+ * returns mean milliseconds per call in phase_ms (HOST pointer to 4 floats:
+ * span-state kernel, carry kernel, output kernel, whole call).  Synchronises
+ * the stream before returning.  Phases a plan skips report 0.
+ */
+int gla_fwd_timed(const void *q, const void *k, const void *v, const float *log_alpha,
+                  int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                  int qkv_dtype, int out_dtype, void *out, float *final_state,
+                  void *workspace, size_t workspace_bytes, gla_stream_t stream,
+                  int iters, float *phase_ms);
+
+/* Process-wide tuning knobs; returns GLA_ERR_SHAPE for an unknown option or value. */
+int gla_set_option(int option, int value);
+int gla_get_option(int option);
+
+/* Static, NUL-terminated description of a status code. */
+const char *gla_status_string(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int gla_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GLA_H_ */

@@ -1,0 +1,14 @@
+"""MI355X-native forward pass of the gated-linear-attention token mixer of DiG.
+
+The compute lives in hand-written HIP kernels behind the C ABI declared in
+``include/gla.h`` (built into ``libgla.so`` next to ``csrc/``); this package
+only marshals arguments.  Importing the package does not load the library;
+calling any entry point without a built library raises.
+"""
+from .binding import (  # noqa: F401
+    GlaError, gla_fwd, gla_fwd_ex, gla_fwd_workspace_bytes, gla_fwd_timed,
+    gla_set_option, gla_get_option, gla_status_string, gla_version,
+    library_path, load_library, lib_symbols,
+    SCAN_ROW_FWD, SCAN_ROW_REV, SCAN_COL_FWD, SCAN_COL_REV, DT_F32, DT_BF16,
+    OPT_CHUNKS_PER_SPAN, OPT_ENGINE, ENGINE_AUTO, ENGINE_RECURRENT, ENGINE_MFMA,
+)

@@ -1,0 +1,195 @@
+"""ctypes binding of ``include/gla.h`` (argument marshalling only).
+
+Tensors are torch tensors on an AMD GPU; torch is used for device memory and
+the current stream, nothing else.  Every arithmetic step runs inside
+``libgla.so``; if that library has not been built the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+from typing import List, Optional
+
+SCAN_ROW_FWD, SCAN_ROW_REV, SCAN_COL_FWD, SCAN_COL_REV = 0, 1, 2, 3
+DT_F32, DT_BF16 = 0, 1
+OPT_CHUNKS_PER_SPAN, OPT_ENGINE = 0, 1
+ENGINE_AUTO, ENGINE_RECURRENT, ENGINE_MFMA = 0, 1, 2
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "csrc", "libgla.so")
+_HEADER = os.path.join(os.path.dirname(_PKG), "include", "gla.h")
+_lib = None
+
+
+class GlaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"gla status {status}: {message}")
+        self.status = status
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib_symbols() -> List[str]:
+    """Names of the functions that include/gla.h declares."""
+    text = open(_HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gla_[a-z_]+)\s*\(", text)))
+
+
+def load_library():
+    """Load libgla.so (built by ``__graft_entry__.build()`` / ``csrc/build.py``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build the HIP library first "
+            "(python -c 'import __graft_entry__ as g; g.build()'). There is no fallback path.")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i, fp, sz = ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.c_size_t
+    shape = [i] * 8
+    lib.gla_fwd.restype = i
+    lib.gla_fwd.argtypes = [vp, vp, vp, vp] + shape + [vp, vp, vp]
+    lib.gla_fwd_ex.restype = i
+    lib.gla_fwd_ex.argtypes = [vp, vp, vp, vp] + shape + [i, i, vp, vp, vp, sz, vp]
+    lib.gla_fwd_timed.restype = i
+    lib.gla_fwd_timed.argtypes = [vp, vp, vp, vp] + shape + [i, i, vp, vp, vp, sz, vp, i, fp]
+    lib.gla_fwd_workspace_bytes.restype = sz
+    lib.gla_fwd_workspace_bytes.argtypes = [i] * 6
+    lib.gla_set_option.restype = i
+    lib.gla_set_option.argtypes = [i, i]
+    lib.gla_get_option.restype = i
+    lib.gla_get_option.argtypes = [i]
+    lib.gla_status_string.restype = ctypes.c_char_p
+    lib.gla_status_string.argtypes = [i]
+    lib.gla_version.restype = i
+    lib.gla_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def gla_status_string(status: int) -> str:
+    return load_library().gla_status_string(int(status)).decode()
+
+
+def gla_version() -> int:
+    return int(load_library().gla_version())
+
+
+def gla_set_option(option: int, value: int) -> None:
+    _check(load_library().gla_set_option(int(option), int(value)))
+
+
+def gla_get_option(option: int) -> int:
+    return int(load_library().gla_get_option(int(option)))
+
+
+def gla_fwd_workspace_bytes(B, H, T, dk, dv, qkv_dtype=DT_BF16) -> int:
+    return int(load_library().gla_fwd_workspace_bytes(B, H, T, dk, dv, qkv_dtype))
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise GlaError(status, gla_status_string(status))
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dt(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.bfloat16:
+        return DT_BF16
+    if t.dtype == torch.float32:
+        return DT_F32
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def _prep(q, k, v, log_alpha, grid_h, grid_w):
+    torch = _torch()
+    for name, t in (("q", q), ("k", k), ("v", v), ("log_alpha", log_alpha)):
+        if not t.is_cuda:
+            raise ValueError(f"{name} must live on the GPU")
+        if not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous")
+    if q.dim() != 4 or q.shape != k.shape or q.shape != log_alpha.shape:
+        raise ValueError("q, k, log_alpha must be [B,H,T,dk] with equal shapes")
+    if v.dim() != 4 or v.shape[:3] != q.shape[:3]:
+        raise ValueError("v must be [B,H,T,dv]")
+    if q.dtype != k.dtype or q.dtype != v.dtype:
+        raise TypeError("q, k, v must share one element type")
+    if log_alpha.dtype != torch.float32:
+        raise TypeError("log_alpha must be fp32")
+    B, H, T, dk = q.shape
+    return B, H, T, dk, v.shape[3]
+
+
+def _stream_ptr(stream) -> int:
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def gla_fwd(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD,
+            want_final_state=True, out=None, final_state=None, stream=None):
+    """bf16 q/k/v -> fp32 out (and fp32 final state); library-owned scratch."""
+    torch = _torch()
+    lib = load_library()
+    B, H, T, dk, dv = _prep(q, k, v, log_alpha, grid_h, grid_w)
+    if q.dtype != torch.bfloat16:
+        raise TypeError("gla_fwd takes bf16 q/k/v; use gla_fwd_ex for fp32")
+    if out is None:
+        out = torch.empty((B, H, T, dv), dtype=torch.float32, device=q.device)
+    if final_state is None and want_final_state:
+        final_state = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device)
+    with torch.cuda.device(q.device):
+        _check(lib.gla_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(),
+                           B, H, T, dk, dv, grid_h, grid_w, scan_dir,
+                           out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
+                           _stream_ptr(stream)))
+    return out, final_state
+
+
+def gla_fwd_ex(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD,
+               out_dtype=None, want_final_state=True, out=None, final_state=None,
+               workspace=None, stream=None):
+    """Explicit element types and caller-owned workspace (a uint8 GPU tensor)."""
+    torch = _torch()
+    lib = load_library()
+    B, H, T, dk, dv = _prep(q, k, v, log_alpha, grid_h, grid_w)
+    qdt = _dt(q)
+    if out is None:
+        odt = torch.float32 if out_dtype is None else out_dtype
+        out = torch.empty((B, H, T, dv), dtype=odt, device=q.device)
+    if final_state is None and want_final_state:
+        final_state = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        nbytes = gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
+        workspace = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=q.device)
+    with torch.cuda.device(q.device):
+        _check(lib.gla_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(),
+                              B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt, _dt(out),
+                              out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
+                              workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return out, final_state
+
+
+def gla_fwd_timed(q, k, v, log_alpha, grid_h, grid_w, scan_dir, out, final_state,
+                  workspace, iters=10, stream=None):
+    """Mean milliseconds per call: [span-state kernel, carry kernel, output kernel, whole call]."""
+    torch = _torch()
+    lib = load_library()
+    B, H, T, dk, dv = _prep(q, k, v, log_alpha, grid_h, grid_w)
+    ms = (ctypes.c_float * 4)()
+    with torch.cuda.device(q.device):
+        _check(lib.gla_fwd_timed(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(),
+                                 B, H, T, dk, dv, grid_h, grid_w, scan_dir, _dt(q), _dt(out),
+                                 out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
+                                 workspace.data_ptr(), workspace.numel(), _stream_ptr(stream),
+                                 int(iters), ms))
+    return [float(x) for x in ms]

@@ -1,0 +1,264 @@
+// Host side of the C ABI declared in include/gla.h: argument validation, launch
+// plan, library-owned scratch for gla_fwd, and the timing aid.
+#include <mutex>
+#include <vector>
+
+#include "gla_common.h"
+
+namespace gla {
+namespace {
+
+constexpr int kVersion = 100;  // 0.1.0
+
+int g_opt_chunks_per_span = 0;
+int g_opt_engine = GLA_ENGINE_AUTO;
+
+struct Scratch {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+};
+std::mutex g_scratch_mutex;
+Scratch g_scratch[64];  // indexed by HIP device ordinal
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+size_t workspace_bytes(int B, int H, int T, int dk, int dv) {
+    // upper bound: one span per chunk
+    size_t nspans = ((size_t)T + kChunk - 1) / kChunk;
+    size_t bh = (size_t)B * H;
+    size_t state = align_up(bh * nspans * dk * dv * sizeof(float), 256);
+    size_t lgam = align_up(bh * nspans * dk * sizeof(float), 256);
+    return state + lgam;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int validate(const void *q, const void *k, const void *v, const float *log_alpha,
+             int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+             int qkv_dtype, int out_dtype, const void *out, const float *final_state) {
+    if (!q || !k || !v || !log_alpha || !out) return GLA_ERR_NULL;
+    if (B <= 0 || H <= 0 || T <= 0 || dk <= 0 || dv <= 0 || grid_h <= 0 || grid_w <= 0) return GLA_ERR_SHAPE;
+    if ((long long)grid_h * grid_w != (long long)T) return GLA_ERR_SHAPE;
+    if (scan_dir < 0 || scan_dir > 3) return GLA_ERR_SHAPE;
+    if (qkv_dtype != GLA_DT_F32 && qkv_dtype != GLA_DT_BF16) return GLA_ERR_SHAPE;
+    if (out_dtype != GLA_DT_F32 && out_dtype != GLA_DT_BF16) return GLA_ERR_SHAPE;
+    if ((long long)B * H > 0x7fffffffLL / (((long long)T + kChunk - 1) / kChunk)) return GLA_ERR_SHAPE;
+    if (dk > kMaxDk || dv > kMaxDv) return GLA_ERR_UNSUPPORTED;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(log_alpha) || misaligned(out) ||
+        (final_state && misaligned(final_state)))
+        return GLA_ERR_ALIGN;
+    return GLA_OK;
+}
+
+// Chooses how many 64-token chunks one work-group walks.  Long spans amortise
+// the state traffic of phases 1-3 (about 4 * dk * dv * 4 bytes per span) but
+// leave fewer work-groups for the 256 compute units.
+int plan_chunks_per_span(int bh, int nchunks) {
+    int cps = g_opt_chunks_per_span;
+    if (cps <= 0) {
+        const long long target_groups = 1024;
+        cps = (int)(((long long)bh * nchunks) / target_groups);
+        if (cps < 1) cps = 1;
+        if (cps == 1 && nchunks >= 2 && (long long)bh * nchunks >= 512) cps = 2;
+    }
+    if (cps > nchunks) cps = nchunks;
+    return cps;
+}
+
+struct PhaseEvents {
+    hipEvent_t ev[4];
+};
+
+int run(const void *q, const void *k, const void *v, const float *log_alpha,
+        int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+        int qkv_dtype, int out_dtype, void *out, float *final_state,
+        void *workspace, size_t ws_bytes, hipStream_t stream, PhaseEvents *events) {
+    int st = validate(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir,
+                      qkv_dtype, out_dtype, out, final_state);
+    if (st != GLA_OK) return st;
+    if (!workspace || misaligned(workspace) || ws_bytes < workspace_bytes(B, H, T, dk, dv))
+        return GLA_ERR_WORKSPACE;
+
+    Params p{};
+    p.q = q; p.k = k; p.v = v; p.log_alpha = log_alpha; p.out = out; p.final_state = final_state;
+    p.B = B; p.H = H; p.T = T; p.dk = dk; p.dv = dv;
+    p.grid_h = grid_h; p.grid_w = grid_w; p.scan_dir = scan_dir;
+    p.qkv_dtype = qkv_dtype; p.out_dtype = out_dtype;
+
+    const int nchunks = (T + kChunk - 1) / kChunk;
+    const int cps = plan_chunks_per_span(B * H, nchunks);
+    p.span_len = cps * kChunk;
+    p.nspans = (nchunks + cps - 1) / cps;
+    const size_t bh = (size_t)B * H;
+    p.ws_state = static_cast<float *>(workspace);
+    p.ws_lgam = reinterpret_cast<float *>(static_cast<char *>(workspace) +
+                                          align_up(bh * p.nspans * dk * dv * sizeof(float), 256));
+
+    bool use_mfma;
+    if (g_opt_engine == GLA_ENGINE_RECURRENT) {
+        use_mfma = false;
+    } else if (g_opt_engine == GLA_ENGINE_MFMA) {
+        if (!mfma_engine_supports(p)) return GLA_ERR_UNSUPPORTED;
+        use_mfma = true;
+    } else {
+        use_mfma = mfma_engine_supports(p);
+    }
+    auto span = [&](SpanMode mode) {
+        return use_mfma ? launch_mfma_span(p, mode, stream) : launch_recurrent_span(p, mode, stream);
+    };
+    auto mark = [&](int i) {
+        if (events) (void)hipEventRecord(events->ev[i], stream);
+    };
+
+    hipError_t e = hipSuccess;
+    mark(0);
+    if (p.nspans > 1) {
+        e = span(kModeState);
+        if (e != hipSuccess) return GLA_ERR_HIP;
+    }
+    mark(1);
+    if (p.nspans > 1) {
+        e = launch_carry(p, stream);
+        if (e != hipSuccess) return GLA_ERR_HIP;
+    }
+    mark(2);
+    e = span(kModeOutput);
+    if (e != hipSuccess) return GLA_ERR_HIP;
+    mark(3);
+    return GLA_OK;
+}
+
+}  // namespace
+}  // namespace gla
+
+using namespace gla;
+
+extern "C" {
+
+int gla_fwd_ex(const void *q, const void *k, const void *v, const float *log_alpha,
+               int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+               int qkv_dtype, int out_dtype, void *out, float *final_state,
+               void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
+    return run(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype, out_dtype,
+               out, final_state, workspace, workspace_bytes_, static_cast<hipStream_t>(stream), nullptr);
+}
+
+int gla_fwd(const void *q, const void *k, const void *v, const float *log_alpha,
+            int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+            float *out, float *final_state, gla_stream_t stream) {
+    int st = validate(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir,
+                      GLA_DT_BF16, GLA_DT_F32, out, final_state);
+    if (st != GLA_OK) return st;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return GLA_ERR_HIP;
+    const size_t need = workspace_bytes(B, H, T, dk, dv);
+    void *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        Scratch &s = g_scratch[dev];
+        if (s.bytes < need) {
+            if (s.ptr) {
+                // earlier calls may still be reading the old buffer
+                if (hipDeviceSynchronize() != hipSuccess) return GLA_ERR_HIP;
+                (void)hipFree(s.ptr);
+                s.ptr = nullptr;
+                s.bytes = 0;
+            }
+            void *fresh = nullptr;
+            if (hipMalloc(&fresh, need) != hipSuccess) return GLA_ERR_HIP;
+            s.ptr = fresh;
+            s.bytes = need;
+        }
+        ws = s.ptr;
+    }
+    return run(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir, GLA_DT_BF16, GLA_DT_F32,
+               out, final_state, ws, need, static_cast<hipStream_t>(stream), nullptr);
+}
+
+size_t gla_fwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype) {
+    if (B <= 0 || H <= 0 || T <= 0 || dk <= 0 || dv <= 0) return 0;
+    if (qkv_dtype != GLA_DT_F32 && qkv_dtype != GLA_DT_BF16) return 0;
+    return workspace_bytes(B, H, T, dk, dv);
+}
+
+int gla_fwd_timed(const void *q, const void *k, const void *v, const float *log_alpha,
+                  int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                  int qkv_dtype, int out_dtype, void *out, float *final_state,
+                  void *workspace, size_t workspace_bytes_, gla_stream_t stream,
+                  int iters, float *phase_ms) {
+    if (!phase_ms) return GLA_ERR_NULL;
+    if (iters <= 0 || iters > 4096) return GLA_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    std::vector<PhaseEvents> evs((size_t)iters);
+    int created = 0;
+    int status = GLA_OK;
+    for (int i = 0; i < iters && status == GLA_OK; ++i) {
+        for (int j = 0; j < 4; ++j) {
+            if (hipEventCreate(&evs[i].ev[j]) != hipSuccess) { status = GLA_ERR_HIP; break; }
+            ++created;
+        }
+    }
+    int done = 0;
+    for (int i = 0; i < iters && status == GLA_OK; ++i) {
+        status = run(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype, out_dtype,
+                     out, final_state, workspace, workspace_bytes_, s, &evs[i]);
+        if (status == GLA_OK) ++done;
+    }
+    if (hipStreamSynchronize(s) != hipSuccess && status == GLA_OK) status = GLA_ERR_HIP;
+    double sum[4] = {0, 0, 0, 0};
+    if (status == GLA_OK) {
+        for (int i = 0; i < done; ++i) {
+            float ms = 0.f;
+            for (int j = 0; j < 3; ++j) {
+                if (hipEventElapsedTime(&ms, evs[i].ev[j], evs[i].ev[j + 1]) != hipSuccess) status = GLA_ERR_HIP;
+                sum[j] += ms;
+            }
+            if (hipEventElapsedTime(&ms, evs[i].ev[0], evs[i].ev[3]) != hipSuccess) status = GLA_ERR_HIP;
+            sum[3] += ms;
+        }
+    }
+    for (int n = 0; n < created; ++n) (void)hipEventDestroy(evs[n / 4].ev[n % 4]);
+    if (status == GLA_OK)
+        for (int j = 0; j < 4; ++j) phase_ms[j] = (float)(sum[j] / done);
+    return status;
+}
+
+int gla_set_option(int option, int value) {
+    switch (option) {
+    case GLA_OPT_CHUNKS_PER_SPAN:
+        if (value < 0 || value > 65536) return GLA_ERR_SHAPE;
+        g_opt_chunks_per_span = value;
+        return GLA_OK;
+    case GLA_OPT_ENGINE:
+        if (value < GLA_ENGINE_AUTO || value > GLA_ENGINE_MFMA) return GLA_ERR_SHAPE;
+        g_opt_engine = value;
+        return GLA_OK;
+    default:
+        return GLA_ERR_SHAPE;
+    }
+}
+
+int gla_get_option(int option) {
+    switch (option) {
+    case GLA_OPT_CHUNKS_PER_SPAN: return g_opt_chunks_per_span;
+    case GLA_OPT_ENGINE: return g_opt_engine;
+    default: return -1;
+    }
+}
+
+const char *gla_status_string(int status) {
+    switch (status) {
+    case GLA_OK: return "ok";
+    case GLA_ERR_NULL: return "a required pointer is NULL";
+    case GLA_ERR_SHAPE: return "invalid size, grid, enum value or option";
+    case GLA_ERR_UNSUPPORTED: return "head size, element type or engine not supported";
+    case GLA_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
+    case GLA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case GLA_ERR_HIP: return "the HIP runtime reported an error";
+    default: return "unknown status";
+    }
+}
+
+int gla_version(void) { return kVersion; }
+
+}  // extern "C"

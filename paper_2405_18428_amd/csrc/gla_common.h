@@ -1,0 +1,73 @@
+// Shared declarations of the GLA forward library (host + gfx950 device code).
+//
+// The operation is the gated recurrence of the DiG paper, Sec. 3.1 Eq. (attn_gla)
+// rows 1-3 with beta = 1:  S_t = diag(alpha_t) S_{t-1} + k_t^T v_t,  o_t = q_t S_t,
+// evaluated span by span (Sec. 3.5: chunks that are computed on-chip):
+//   phase 1  every span computes, from a zero state, its local state U and the
+//            log of its total decay, log Gamma = sum of log_alpha over the span;
+//   phase 2  the spans of one (batch, head) are chained:
+//            S_start(r+1) = diag(Gamma_r) S_start(r) + U_r;
+//   phase 3  every span recomputes its tokens from S_start(r) and writes o_t.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/gla.h"
+
+namespace gla {
+
+constexpr int kChunk = 64;      // tokens per chunk (the paper's M)
+constexpr int kMaxDk = 64;
+constexpr int kMaxDv = 128;
+
+enum SpanMode : int {
+    kModeState = 0,   // phase 1: no outputs, write U and log Gamma of the span
+    kModeOutput = 1   // phase 3 (or the single pass): write outputs
+};
+
+struct Params {
+    const void *q, *k, *v;
+    const float *log_alpha;
+    void *out;
+    float *final_state;     // may be null
+    float *ws_state;        // [B*H, nspans, dk, dv]  U_r after phase 1, S_start(r) after phase 2
+    float *ws_lgam;         // [B*H, nspans, dk]      log Gamma_r
+    int B, H, T, dk, dv, grid_h, grid_w, scan_dir;
+    int nspans;             // spans per (batch, head)
+    int span_len;           // tokens per span, a multiple of kChunk
+    int qkv_dtype, out_dtype;
+};
+
+// Scan step s -> canonical token index (Sec. 3.3 / Algorithm 1 orders).
+__host__ __device__ inline int scan_token(int scan_dir, int s, int T, int grid_h, int grid_w) {
+    if (scan_dir & 1) s = T - 1 - s;
+    if (scan_dir < 2) return s;
+    int c = s / grid_h;
+    int r = s - c * grid_h;
+    return r * grid_w + c;
+}
+
+// bf16 <-> fp32 on raw bit patterns (round to nearest even; inputs are finite).
+__host__ __device__ inline float bf16_bits_to_float(uint16_t b) {
+    union { uint32_t u; float f; } x;
+    x.u = ((uint32_t)b) << 16;
+    return x.f;
+}
+__host__ __device__ inline uint16_t float_to_bf16_bits(float f) {
+    union { uint32_t u; float f; } x;
+    x.f = f;
+    uint32_t u = x.u;
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Launchers (defined in the .hip files); each enqueues on `stream` and returns
+// hipGetLastError().
+hipError_t launch_recurrent_span(const Params &p, SpanMode mode, hipStream_t stream);
+hipError_t launch_mfma_span(const Params &p, SpanMode mode, hipStream_t stream);
+hipError_t launch_carry(const Params &p, hipStream_t stream);
+bool mfma_engine_supports(const Params &p);
+
+}  // namespace gla

@@ -1,0 +1,153 @@
+// Token-by-token fp32 engine for one span of the GLA recurrence
+// (DiG paper, Sec. 3.1 Eq. (attn_gla) rows 1-3, beta = 1).
+//
+// One work-group walks the scan steps of its span in order.  Thread n owns
+// column n of the dk x dv state in registers; q, k and alpha = exp(log_alpha) of
+// a tile of tokens are staged in LDS and read as wave-wide broadcasts.  There is
+// no factorised decay here, so any gate value (alpha down to 0) is exact; this
+// engine serves fp32 inputs, odd head sizes, and as the fallback of the MFMA
+// engine.
+#include "gla_common.h"
+
+namespace gla {
+namespace {
+
+constexpr int kThreads = 128;  // >= kMaxDv
+constexpr int kTile = 16;      // tokens staged per round
+
+template <typename T> __device__ inline float load_elem(const void *base, size_t idx);
+template <> __device__ inline float load_elem<float>(const void *base, size_t idx) {
+    return static_cast<const float *>(base)[idx];
+}
+template <> __device__ inline float load_elem<uint16_t>(const void *base, size_t idx) {
+    return bf16_bits_to_float(static_cast<const uint16_t *>(base)[idx]);
+}
+template <typename T> __device__ inline void store_elem(void *base, size_t idx, float x);
+template <> __device__ inline void store_elem<float>(void *base, size_t idx, float x) {
+    static_cast<float *>(base)[idx] = x;
+}
+template <> __device__ inline void store_elem<uint16_t>(void *base, size_t idx, float x) {
+    static_cast<uint16_t *>(base)[idx] = float_to_bf16_bits(x);
+}
+
+template <int MODE, typename TIn, typename TOut>
+__global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
+    __shared__ float s_q[kTile][kMaxDk];
+    __shared__ float s_k[kTile][kMaxDk];
+    __shared__ float s_a[kTile][kMaxDk];
+    __shared__ float s_v[kTile][kMaxDv];
+    __shared__ float s_lsum[2][kMaxDk];
+    __shared__ int s_tok[kTile];
+
+    const int tid = threadIdx.x;
+    const int bh = blockIdx.x / p.nspans;
+    const int sp = blockIdx.x - bh * p.nspans;
+    const int dk = p.dk, dv = p.dv, T = p.T;
+    const int s_begin = sp * p.span_len;
+    const int s_end = min(T, s_begin + p.span_len);
+    const size_t base_k = (size_t)bh * T * dk;
+    const size_t base_v = (size_t)bh * T * dv;
+    const bool col_active = tid < dv;
+
+    float S[kMaxDk];
+#pragma unroll
+    for (int c = 0; c < kMaxDk; ++c) S[c] = 0.f;
+    if (MODE == kModeOutput && p.nspans > 1 && col_active) {
+        const float *s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
+#pragma unroll
+        for (int c = 0; c < kMaxDk; ++c)
+            if (c < dk) S[c] = s0[(size_t)c * dv + tid];
+    }
+
+    // staging role: channel sc, token rows sj, sj+2, ...
+    const int sc = tid & 63;
+    const int sj = tid >> 6;
+    float lsum = 0.f;
+
+    for (int t0 = s_begin; t0 < s_end; t0 += kTile) {
+        __syncthreads();
+        if (tid < kTile) {
+            int s = t0 + tid;
+            s_tok[tid] = (s < s_end) ? scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w) : -1;
+        }
+        __syncthreads();
+        if (sc < dk) {
+            for (int j = sj; j < kTile; j += 2) {
+                int n = s_tok[j];
+                if (n >= 0) {
+                    size_t e = base_k + (size_t)n * dk + sc;
+                    float g = p.log_alpha[e];
+                    lsum += g;
+                    s_a[j][sc] = expf(g);
+                    s_k[j][sc] = load_elem<TIn>(p.k, e);
+                    if (MODE == kModeOutput) s_q[j][sc] = load_elem<TIn>(p.q, e);
+                }
+            }
+        }
+        for (int idx = tid; idx < kTile * dv; idx += kThreads) {
+            int j = idx / dv, n2 = idx - j * dv;
+            int n = s_tok[j];
+            if (n >= 0) s_v[j][n2] = load_elem<TIn>(p.v, base_v + (size_t)n * dv + n2);
+        }
+        __syncthreads();
+        if (col_active) {
+            for (int j = 0; j < kTile; ++j) {
+                int n = s_tok[j];
+                if (n < 0) break;
+                float vn = s_v[j][tid];
+                float o = 0.f;
+#pragma unroll
+                for (int c = 0; c < kMaxDk; ++c) {
+                    if (c < dk) {
+                        S[c] = fmaf(s_a[j][c], S[c], s_k[j][c] * vn);
+                        if (MODE == kModeOutput) o = fmaf(s_q[j][c], S[c], o);
+                    }
+                }
+                if (MODE == kModeOutput) store_elem<TOut>(p.out, base_v + (size_t)n * dv + tid, o);
+            }
+        }
+    }
+
+    if (MODE == kModeState) {
+        // U of this span and the log of its total decay
+        if (col_active) {
+            float *u = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
+#pragma unroll
+            for (int c = 0; c < kMaxDk; ++c)
+                if (c < dk) u[(size_t)c * dv + tid] = S[c];
+        }
+        s_lsum[sj][sc] = lsum;
+        __syncthreads();
+        if (tid < dk)
+            p.ws_lgam[((size_t)bh * p.nspans + sp) * dk + tid] = s_lsum[0][tid] + s_lsum[1][tid];
+    } else if (p.nspans == 1 && p.final_state != nullptr && col_active) {
+        float *f = p.final_state + (size_t)bh * dk * dv;
+#pragma unroll
+        for (int c = 0; c < kMaxDk; ++c)
+            if (c < dk) f[(size_t)c * dv + tid] = S[c];
+    }
+}
+
+template <int MODE>
+hipError_t dispatch(const Params &p, hipStream_t stream) {
+    dim3 grid((unsigned)(p.B * p.H * p.nspans)), block(kThreads);
+    const bool in_bf16 = p.qkv_dtype == GLA_DT_BF16;
+    const bool out_bf16 = p.out_dtype == GLA_DT_BF16;
+    if (in_bf16 && out_bf16)
+        hipLaunchKernelGGL((recurrent_span_kernel<MODE, uint16_t, uint16_t>), grid, block, 0, stream, p);
+    else if (in_bf16)
+        hipLaunchKernelGGL((recurrent_span_kernel<MODE, uint16_t, float>), grid, block, 0, stream, p);
+    else if (out_bf16)
+        hipLaunchKernelGGL((recurrent_span_kernel<MODE, float, uint16_t>), grid, block, 0, stream, p);
+    else
+        hipLaunchKernelGGL((recurrent_span_kernel<MODE, float, float>), grid, block, 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_recurrent_span(const Params &p, SpanMode mode, hipStream_t stream) {
+    return mode == kModeState ? dispatch<kModeState>(p, stream) : dispatch<kModeOutput>(p, stream);
+}
+
+}  // namespace gla
