@@ -1,6 +1,586 @@
-// placeholder until the MFMA engine lands
+// bf16 MFMA engine for one span of the GLA recurrence in its chunk form
+// (DiG paper, Sec. 3.5: chunks of M = 64 tokens computed on-chip; recurrence of
+// Sec. 3.1 Eq. (attn_gla) rows 1-3 with beta = 1).
+//
+// With b_j = sum_{i<=j} log_alpha_i inside a chunk (inclusive, per key channel)
+// and b_C its value at the chunk's last token, unrolling the recurrence gives
+//     o_j  = sum_{i<=j} (q~_j . k~_i) v_i + q~_j S_0 ,   q~_j = q_j * exp(b_j),  k~_i = k_i * exp(-b_i)
+//     S_C  = diag(exp(b_C)) S_0 + K^^T V ,               k^_i = k_i * exp(b_C - b_i)
+// i.e. four dense contractions per chunk, all on v_mfma_f32_16x16x32_bf16:
+//     A^T = K~ Q~^T (causal tiles only),  O = A V + Q~ S_0,  S += K^^T V.
+// Every gated operand (q~, k~, k^, A, S_0) is split into a bf16 "hi" part and a
+// bf16 "lo" remainder so that the products carry about 16 mantissa bits; v is
+// used as given.  The state S lives in fp32 MFMA accumulators for the whole span.
+//
+// Work-group = 256 threads = 4 waves; per chunk:
+//   (a) registers prefetched from HBM -> LDS: raw log_alpha / q / k rows, V transposed
+//       (lane = column pair, 16 tokens per wave), S_0 as bf16 hi/lo;
+//   (b) lane = token: DPP wave scan of log_alpha per channel, exp, gating, hi/lo
+//       split, operands written in MFMA order;
+//   (c) MFMA: wave w owns output rows 16w..16w+15 and a quarter of the state tiles.
+// The scan order only enters through the per-row token index in LDS.
 #include "gla_common.h"
+
 namespace gla {
-bool mfma_engine_supports(const Params &) { return false; }
-hipError_t launch_mfma_span(const Params &, SpanMode, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+constexpr int kTokStride = kChunk + 8;  // bf16 elements per row of the token-contiguous operands
+
+__device__ inline f32x4 mfma(u32x4 a, u32x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                   c, 0, 0, 0);
+}
+
+__device__ inline uint32_t pack_bf16(float lo, float hi) {
+    f32x2 x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+}
+__device__ inline float bf16_lo_as_float(uint32_t packed) { return __builtin_bit_cast(float, packed << 16); }
+__device__ inline float bf16_hi_as_float(uint32_t packed) { return __builtin_bit_cast(float, packed & 0xffff0000u); }
+
+// x0, x1 -> packed bf16 pair of the rounded values and packed pair of the remainders
+struct HiLo {
+    uint32_t hi, lo;
+};
+__device__ inline HiLo split_pair_val(float x0, float x1) {
+    HiLo r;
+    r.hi = pack_bf16(x0, x1);
+    r.lo = pack_bf16(x0 - bf16_lo_as_float(r.hi), x1 - bf16_hi_as_float(r.hi));
+    return r;
+}
+// (vector elements cannot bind to references, hence a macro for the two outputs)
+#define SPLIT_PAIR(x0, x1, hi_out, lo_out)            \
+    do {                                              \
+        const HiLo hl_ = split_pair_val((x0), (x1));  \
+        (hi_out) = hl_.hi;                            \
+        (lo_out) = hl_.lo;                            \
+    } while (0)
+
+template <int CTRL, int ROW_MASK, bool BOUND>
+__device__ inline float dpp_move(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK,
+                                                                 0xF, BOUND));
+}
+// Inclusive prefix sum over the 64 lanes of a wave (lane = token).
+__device__ inline float wave_inclusive_scan(float v) {
+    v += dpp_move<0x111, 0xF, true>(v);  // row_shr:1
+    v += dpp_move<0x112, 0xF, true>(v);  // row_shr:2
+    v += dpp_move<0x114, 0xF, true>(v);  // row_shr:4
+    v += dpp_move<0x118, 0xF, true>(v);  // row_shr:8   -> prefix inside each row of 16
+    v += dpp_move<0x142, 0xA, false>(v); // row_bcast:15 into rows 1 and 3
+    v += dpp_move<0x143, 0xC, false>(v); // row_bcast:31 into rows 2 and 3
+    return v;
+}
+__device__ inline float wave_last(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
+// LDS layout (byte offsets), sized by the padded head dimensions.
+template <int MODE, int NDK8, int NDV16>
+struct Layout {
+    static constexpr int kDkp = NDK8 * 8;                                 // channels incl. padding
+    static constexpr int kDvp = NDV16 * 16;                               // value columns incl. padding
+    static constexpr int kChStride = kDkp + ((NDK8 % 4 == 0) ? 8 : 0);    // bf16 per row of channel-contiguous operands
+    static constexpr int kLaStride = kDkp + 4;                            // fp32 per row of raw log_alpha
+    static constexpr bool kOut = MODE == kModeOutput;
+    static constexpr int kRowOp = kChunk * kChStride * 2;                 // one [64][channels] bf16 operand
+    static constexpr int kKhat = kDkp * kTokStride * 2;                   // one [channels][64] bf16 operand
+    static constexpr int kVt = kDvp * kTokStride * 2;
+    static constexpr int kSt = kDvp * kChStride * 2;
+
+    static constexpr int oTok = 0;                                        // int[2][64]
+    static constexpr int oGam = oTok + 2 * kChunk * 4;                    // float[64]  exp(b_C) of this chunk
+    static constexpr int oLg = oGam + 64 * 4;                             // float[64]  sum of b_C over the span
+    static constexpr int oLa = oLg + 64 * 4;                              // raw log_alpha
+    static constexpr int oKraw = oLa + kChunk * kLaStride * 4;
+    static constexpr int oKhHi = oKraw + kRowOp;
+    static constexpr int oKhLo = oKhHi + kKhat;
+    static constexpr int oVt = oKhLo + kKhat;
+    static constexpr int oEndState = oVt + kVt;
+    // output mode only
+    static constexpr int oQraw = oEndState;
+    static constexpr int oQHi = oQraw + kRowOp;
+    static constexpr int oQLo = oQHi + kRowOp;
+    static constexpr int oKHi = oQLo + kRowOp;
+    static constexpr int oKLo = oKHi + kRowOp;
+    static constexpr int oStHi = oKLo + kRowOp;
+    static constexpr int oStLo = oStHi + kSt;
+    static constexpr int oEndOut = oStLo + kSt;
+    static constexpr int kBytes = kOut ? oEndOut : oEndState;
+};
+
+template <int MODE, int NDK8, int NDV16, typename TOut>
+__global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
+    using L = Layout<MODE, NDK8, NDV16>;
+    constexpr bool OUT = MODE == kModeOutput;
+    constexpr int CHS = L::kChStride;
+    constexpr int LAS = L::kLaStride;
+    constexpr int KS = (NDK8 + 3) / 4;          // 32-channel steps of the channel contractions
+    constexpr int NCT = (NDK8 + 1) / 2;         // 16-channel row tiles of the state
+    constexpr int NT = NCT * NDV16;             // state tiles
+    constexpr int TPW = (NT + kWaves - 1) / kWaves;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    int *s_tok = reinterpret_cast<int *>(smem + L::oTok);
+    float *s_gam = reinterpret_cast<float *>(smem + L::oGam);
+    float *s_lg = reinterpret_cast<float *>(smem + L::oLg);
+    float *s_la = reinterpret_cast<float *>(smem + L::oLa);
+    uint16_t *s_kraw = reinterpret_cast<uint16_t *>(smem + L::oKraw);
+    uint16_t *s_khhi = reinterpret_cast<uint16_t *>(smem + L::oKhHi);
+    uint16_t *s_khlo = reinterpret_cast<uint16_t *>(smem + L::oKhLo);
+    uint16_t *s_vt = reinterpret_cast<uint16_t *>(smem + L::oVt);
+    uint16_t *s_qraw = reinterpret_cast<uint16_t *>(smem + L::oQraw);
+    uint16_t *s_qhi = reinterpret_cast<uint16_t *>(smem + L::oQHi);
+    uint16_t *s_qlo = reinterpret_cast<uint16_t *>(smem + L::oQLo);
+    uint16_t *s_khi = reinterpret_cast<uint16_t *>(smem + L::oKHi);
+    uint16_t *s_klo = reinterpret_cast<uint16_t *>(smem + L::oKLo);
+    uint16_t *s_sthi = reinterpret_cast<uint16_t *>(smem + L::oStHi);
+    uint16_t *s_stlo = reinterpret_cast<uint16_t *>(smem + L::oStLo);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = tid >> 6;
+    const int lm = lane & 15;
+    const int g = lane >> 4;
+
+    // Work-groups are dealt round-robin to the 8 XCDs; give each XCD a contiguous
+    // range of spans so that neighbouring spans (which share cache lines in the
+    // column scans) meet in one L2.
+    int blk = blockIdx.x;
+    {
+        const int nb = gridDim.x;
+        if ((nb & 7) == 0) blk = (blk & 7) * (nb >> 3) + (blk >> 3);
+    }
+    const int bh = blk / p.nspans;
+    const int sp = blk - bh * p.nspans;
+    const int dk = p.dk, dv = p.dv, T = p.T;
+    const int s_begin = sp * p.span_len;
+    const int s_end = min(T, s_begin + p.span_len);
+    const int nch = (s_end - s_begin + kChunk - 1) / kChunk;
+
+    const uint16_t *gq = static_cast<const uint16_t *>(p.q) + (size_t)bh * T * dk;
+    const uint16_t *gk = static_cast<const uint16_t *>(p.k) + (size_t)bh * T * dk;
+    const uint16_t *gv = static_cast<const uint16_t *>(p.v) + (size_t)bh * T * dv;
+    const float *gla_ = p.log_alpha + (size_t)bh * T * dk;
+    TOut *gout = static_cast<TOut *>(p.out) + (size_t)bh * T * dv;
+
+    // ---- prologue: clear LDS (pads must read as zero), first token map ----
+    for (int i = tid; i < L::kBytes / 16; i += kThreads)
+        reinterpret_cast<u32x4 *>(smem)[i] = u32x4{0, 0, 0, 0};
+    __syncthreads();
+    if (tid < kChunk) {
+        int s = s_begin + tid;
+        s_tok[tid] = (s < s_end) ? scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w) : -1;
+    }
+    __syncthreads();
+
+    // ---- state tiles owned by this wave ----
+    f32x4 acc[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (OUT && p.nspans > 1) {
+        const float *s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            const int t = w + kWaves * i;
+            if (t < NT) {
+                const int ct = t / NDV16, nt = t - ct * NDV16;
+                const int n = 16 * nt + lm;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int c = 16 * ct + 4 * g + r;
+                    if (c < dk && n < dv) acc[i][r] = s0[(size_t)c * dv + n];
+                }
+            }
+        }
+    }
+
+    // ---- register staging of one chunk's HBM rows ----
+    const int pcs = dk >> 2;                         // 4-channel pieces per row
+    constexpr int kPieces = (kChunk * NDK8 * 2 + kThreads - 1) / kThreads;
+    u32x4 r_la[kPieces];
+    u32x2 r_k[kPieces];
+    u32x2 r_q[OUT ? kPieces : 1];
+    uint32_t r_v[16];
+    const int npieces = kChunk * pcs;
+    const bool v_lane = lane < (dv >> 1);
+
+    auto load_chunk = [&](int chunk) {
+        const int *tok = s_tok + (chunk & 1) * kChunk;
+#pragma unroll
+        for (int m = 0; m < kPieces; ++m) {
+            const int idx = tid + m * kThreads;
+            r_la[m] = u32x4{0, 0, 0, 0};
+            r_k[m] = u32x2{0, 0};
+            if constexpr (OUT) r_q[m] = u32x2{0, 0};
+            if (idx < npieces) {
+                const int j = idx / pcs, pc = idx - j * pcs;
+                const int n = tok[j];
+                if (n >= 0) {
+                    const size_t e = (size_t)n * dk + 4 * pc;
+                    r_la[m] = *reinterpret_cast<const u32x4 *>(gla_ + e);
+                    r_k[m] = *reinterpret_cast<const u32x2 *>(gk + e);
+                    if constexpr (OUT) r_q[m] = *reinterpret_cast<const u32x2 *>(gq + e);
+                }
+            }
+        }
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+            const int n = tok[16 * w + jj];
+            r_v[jj] = 0;
+            if (v_lane && n >= 0) r_v[jj] = *reinterpret_cast<const uint32_t *>(gv + (size_t)n * dv + 2 * lane);
+        }
+    };
+
+    load_chunk(0);
+
+    for (int chunk = 0; chunk < nch; ++chunk) {
+        const int *tok = s_tok + (chunk & 1) * kChunk;
+
+        // ================= (a) registers -> LDS =================
+#pragma unroll
+        for (int m = 0; m < kPieces; ++m) {
+            const int idx = tid + m * kThreads;
+            if (idx < npieces) {
+                const int j = idx / pcs, pc = idx - j * pcs;
+                *reinterpret_cast<u32x4 *>(s_la + j * LAS + 4 * pc) = r_la[m];
+                *reinterpret_cast<u32x2 *>(s_kraw + j * CHS + 4 * pc) = r_k[m];
+                if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qraw + j * CHS + 4 * pc) = r_q[m];
+            }
+        }
+        if (v_lane) {
+            // lane holds columns 2*lane, 2*lane+1 of 16 consecutive tokens: write them token-contiguous
+            u32x4 c0a, c0b, c1a, c1b;
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                c0a[h] = (r_v[2 * h] & 0xffffu) | (r_v[2 * h + 1] << 16);
+                c1a[h] = (r_v[2 * h] >> 16) | (r_v[2 * h + 1] & 0xffff0000u);
+                c0b[h] = (r_v[8 + 2 * h] & 0xffffu) | (r_v[8 + 2 * h + 1] << 16);
+                c1b[h] = (r_v[8 + 2 * h] >> 16) | (r_v[8 + 2 * h + 1] & 0xffff0000u);
+            }
+            uint16_t *row0 = s_vt + (2 * lane) * kTokStride + 16 * w;
+            uint16_t *row1 = row0 + kTokStride;
+            *reinterpret_cast<u32x4 *>(row0) = c0a;
+            *reinterpret_cast<u32x4 *>(row0 + 8) = c0b;
+            *reinterpret_cast<u32x4 *>(row1) = c1a;
+            *reinterpret_cast<u32x4 *>(row1 + 8) = c1b;
+        }
+        if (OUT) {
+            // S_0 (state entering the chunk) as bf16 hi/lo, value-column-major for the B operand
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                const int t = w + kWaves * i;
+                if (t < NT) {
+                    const int ct = t / NDV16, nt = t - ct * NDV16;
+                    const int c0 = 16 * ct + 4 * g;
+                    if (c0 < L::kDkp) {
+                        u32x2 hi, lo;
+                        SPLIT_PAIR(acc[i][0], acc[i][1], hi[0], lo[0]);
+                        SPLIT_PAIR(acc[i][2], acc[i][3], hi[1], lo[1]);
+                        const int off = (16 * nt + lm) * CHS + c0;
+                        *reinterpret_cast<u32x2 *>(s_sthi + off) = hi;
+                        *reinterpret_cast<u32x2 *>(s_stlo + off) = lo;
+                    }
+                }
+            }
+        }
+        if (tid < kChunk && chunk + 1 < nch) {
+            int s = s_begin + (chunk + 1) * kChunk + tid;
+            s_tok[((chunk + 1) & 1) * kChunk + tid] =
+                (s < s_end) ? scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w) : -1;
+        }
+        __syncthreads();
+
+        // ================= (b) gates: lane = token =================
+        {
+            const int j = lane;
+            const int nfull = dk >> 3;
+            // full groups of 8 channels: group index w, w+4
+#pragma unroll
+            for (int gi = 0; gi < 2; ++gi) {
+                const int kg = w + 4 * gi;
+                if (kg < nfull) {
+                    const int c0 = 8 * kg;
+                    float bb[8];
+                    {
+                        // (no bit_cast on a vector element: it would read element 0 every time)
+                        const f32x4 x0 = *reinterpret_cast<const f32x4 *>(s_la + j * LAS + c0);
+                        const f32x4 x1 = *reinterpret_cast<const f32x4 *>(s_la + j * LAS + c0 + 4);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float g0 = x0[i], g1 = x1[i];
+                            bb[i] = wave_inclusive_scan(g0);
+                            bb[4 + i] = wave_inclusive_scan(g1);
+                        }
+                    }
+                    const u32x4 kr = *reinterpret_cast<const u32x4 *>(s_kraw + j * CHS + c0);
+                    u32x4 qr = u32x4{0, 0, 0, 0};
+                    if (OUT) qr = *reinterpret_cast<const u32x4 *>(s_qraw + j * CHS + c0);
+                    u32x4 qhi, qlo, khi, klo;
+                    uint32_t hh[4], hl[4];
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        const float b0 = bb[2 * h], b1 = bb[2 * h + 1];
+                        const float bc0 = wave_last(b0), bc1 = wave_last(b1);
+                        const float k0 = bf16_lo_as_float(kr[h]), k1 = bf16_hi_as_float(kr[h]);
+                        SPLIT_PAIR(k0 * __expf(bc0 - b0), k1 * __expf(bc1 - b1), hh[h], hl[h]);
+                        if (OUT) {
+                            const float q0 = bf16_lo_as_float(qr[h]), q1 = bf16_hi_as_float(qr[h]);
+                            SPLIT_PAIR(q0 * __expf(b0), q1 * __expf(b1), qhi[h], qlo[h]);
+                            SPLIT_PAIR(k0 * __expf(fminf(-b0, 85.f)), k1 * __expf(fminf(-b1, 85.f)), khi[h], klo[h]);
+                        }
+                        if (lane == 63) {
+                            s_gam[c0 + 2 * h] = __expf(bc0);
+                            s_gam[c0 + 2 * h + 1] = __expf(bc1);
+                            if (!OUT) {
+                                s_lg[c0 + 2 * h] += bc0;
+                                s_lg[c0 + 2 * h + 1] += bc1;
+                            }
+                        }
+                    }
+                    if (OUT) {
+                        *reinterpret_cast<u32x4 *>(s_qhi + j * CHS + c0) = qhi;
+                        *reinterpret_cast<u32x4 *>(s_qlo + j * CHS + c0) = qlo;
+                        *reinterpret_cast<u32x4 *>(s_khi + j * CHS + c0) = khi;
+                        *reinterpret_cast<u32x4 *>(s_klo + j * CHS + c0) = klo;
+                    }
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        s_khhi[(c0 + 2 * h) * kTokStride + j] = (uint16_t)(hh[h] & 0xffffu);
+                        s_khhi[(c0 + 2 * h + 1) * kTokStride + j] = (uint16_t)(hh[h] >> 16);
+                        s_khlo[(c0 + 2 * h) * kTokStride + j] = (uint16_t)(hl[h] & 0xffffu);
+                        s_khlo[(c0 + 2 * h + 1) * kTokStride + j] = (uint16_t)(hl[h] >> 16);
+                    }
+                }
+            }
+            // the trailing half group (dk % 8 == 4): one channel per wave
+            if ((dk & 7) != 0) {
+                const int c = 8 * nfull + w;
+                const float b = wave_inclusive_scan(s_la[j * LAS + c]);
+                const float bc = wave_last(b);
+                const float kx = bf16_bits_to_float(s_kraw[j * CHS + c]);
+                uint32_t hi, lo;
+                SPLIT_PAIR(kx * __expf(bc - b), 0.f, hi, lo);
+                s_khhi[c * kTokStride + j] = (uint16_t)(hi & 0xffffu);
+                s_khlo[c * kTokStride + j] = (uint16_t)(lo & 0xffffu);
+                if (OUT) {
+                    const float qx = bf16_bits_to_float(s_qraw[j * CHS + c]);
+                    uint32_t h2, l2;
+                    SPLIT_PAIR(qx * __expf(b), kx * __expf(fminf(-b, 85.f)), h2, l2);
+                    s_qhi[j * CHS + c] = (uint16_t)(h2 & 0xffffu);
+                    s_qlo[j * CHS + c] = (uint16_t)(l2 & 0xffffu);
+                    s_khi[j * CHS + c] = (uint16_t)(h2 >> 16);
+                    s_klo[j * CHS + c] = (uint16_t)(l2 >> 16);
+                }
+                if (lane == 63) {
+                    s_gam[c] = __expf(bc);
+                    if (!OUT) s_lg[c] += bc;
+                }
+            }
+        }
+        __syncthreads();
+
+        // next chunk's rows start their trip from HBM while this chunk is on the MFMA units
+        if (chunk + 1 < nch) load_chunk(chunk + 1);
+
+        // ================= (c) contractions =================
+        if (OUT) {
+            // Q~ fragments of this wave's 16 output rows (also the B operand of A^T = K~ Q~^T)
+            u32x4 qfh[KS], qfl[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int kg = 4 * ks + g;
+                qfh[ks] = u32x4{0, 0, 0, 0};
+                qfl[ks] = u32x4{0, 0, 0, 0};
+                if (kg < NDK8) {
+                    qfh[ks] = *reinterpret_cast<const u32x4 *>(s_qhi + (16 * w + lm) * CHS + 8 * kg);
+                    qfl[ks] = *reinterpret_cast<const u32x4 *>(s_qlo + (16 * w + lm) * CHS + 8 * kg);
+                }
+            }
+            // causal score tiles, transposed: lane (lm, g) ends up with A[i = 16w+lm][j = 16jt+4g+r]
+            u32x2 ph[kWaves], pl[kWaves];
+#pragma unroll
+            for (int jt = 0; jt < kWaves; ++jt) {
+                ph[jt] = u32x2{0, 0};
+                pl[jt] = u32x2{0, 0};
+                if (jt <= w) {
+                    f32x4 d = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        const int kg = 4 * ks + g;
+                        u32x4 kh = u32x4{0, 0, 0, 0}, kl = u32x4{0, 0, 0, 0};
+                        if (kg < NDK8) {
+                            kh = *reinterpret_cast<const u32x4 *>(s_khi + (16 * jt + lm) * CHS + 8 * kg);
+                            kl = *reinterpret_cast<const u32x4 *>(s_klo + (16 * jt + lm) * CHS + 8 * kg);
+                        }
+                        d = mfma(kh, qfh[ks], d);
+                        d = mfma(kh, qfl[ks], d);
+                        d = mfma(kl, qfh[ks], d);
+                    }
+                    if (jt == w) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (4 * g + r > lm) d[r] = 0.f;
+                    }
+                    SPLIT_PAIR(d[0], d[1], ph[jt][0], pl[jt][0]);
+                    SPLIT_PAIR(d[2], d[3], ph[jt][1], pl[jt][1]);
+                }
+            }
+            f32x4 o[NDV16];
+#pragma unroll
+            for (int nt = 0; nt < NDV16; ++nt) o[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            // O += A V : contraction slot (g, e) of a 32-token step is token 32q + 16(e/4) + 4g + e%4
+#pragma unroll
+            for (int q32 = 0; q32 < 2; ++q32) {
+                if (2 * q32 <= w) {
+                    const u32x4 ah = u32x4{ph[2 * q32][0], ph[2 * q32][1], ph[2 * q32 + 1][0], ph[2 * q32 + 1][1]};
+                    const u32x4 al = u32x4{pl[2 * q32][0], pl[2 * q32][1], pl[2 * q32 + 1][0], pl[2 * q32 + 1][1]};
+#pragma unroll
+                    for (int nt = 0; nt < NDV16; ++nt) {
+                        const uint16_t *vr = s_vt + (16 * nt + lm) * kTokStride + 32 * q32 + 4 * g;
+                        const u32x2 v0 = *reinterpret_cast<const u32x2 *>(vr);
+                        const u32x2 v1 = *reinterpret_cast<const u32x2 *>(vr + 16);
+                        const u32x4 b = u32x4{v0[0], v0[1], v1[0], v1[1]};
+                        o[nt] = mfma(ah, b, o[nt]);
+                        o[nt] = mfma(al, b, o[nt]);
+                    }
+                }
+            }
+            // O += Q~ S_0
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int kg = 4 * ks + g;
+#pragma unroll
+                for (int nt = 0; nt < NDV16; ++nt) {
+                    u32x4 sh = u32x4{0, 0, 0, 0}, sl = u32x4{0, 0, 0, 0};
+                    if (kg < NDK8) {
+                        sh = *reinterpret_cast<const u32x4 *>(s_sthi + (16 * nt + lm) * CHS + 8 * kg);
+                        sl = *reinterpret_cast<const u32x4 *>(s_stlo + (16 * nt + lm) * CHS + 8 * kg);
+                    }
+                    o[nt] = mfma(qfh[ks], sh, o[nt]);
+                    o[nt] = mfma(qfl[ks], sh, o[nt]);
+                    o[nt] = mfma(qfh[ks], sl, o[nt]);
+                }
+            }
+            // rows 16w + 4g + r, columns 16nt + lm
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int n_tok = tok[16 * w + 4 * g + r];
+                if (n_tok >= 0) {
+                    TOut *orow = gout + (size_t)n_tok * dv;
+#pragma unroll
+                    for (int nt = 0; nt < NDV16; ++nt) {
+                        const int n = 16 * nt + lm;
+                        if (n < dv) {
+                            if (sizeof(TOut) == 4)
+                                reinterpret_cast<float *>(orow)[n] = o[nt][r];
+                            else
+                                reinterpret_cast<uint16_t *>(orow)[n] = (uint16_t)(pack_bf16(o[nt][r], 0.f) & 0xffffu);
+                        }
+                    }
+                }
+            }
+        }
+        // S = diag(exp(b_C)) S + K^^T V on the tiles this wave owns
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            const int t = w + kWaves * i;
+            if (t < NT) {
+                const int ct = t / NDV16, nt = t - ct * NDV16;
+                const f32x4 gm = *reinterpret_cast<const f32x4 *>(s_gam + 16 * ct + 4 * g);
+                f32x4 a = acc[i];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) a[r] *= gm[r];
+                const int crow = 16 * ct + lm;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    u32x4 kh = u32x4{0, 0, 0, 0}, kl = u32x4{0, 0, 0, 0};
+                    if (crow < L::kDkp) {
+                        kh = *reinterpret_cast<const u32x4 *>(s_khhi + crow * kTokStride + 32 * ks + 8 * g);
+                        kl = *reinterpret_cast<const u32x4 *>(s_khlo + crow * kTokStride + 32 * ks + 8 * g);
+                    }
+                    const u32x4 b = *reinterpret_cast<const u32x4 *>(s_vt + (16 * nt + lm) * kTokStride + 32 * ks + 8 * g);
+                    a = mfma(kh, b, a);
+                    a = mfma(kl, b, a);
+                }
+                acc[i] = a;
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: the span's state ----
+    float *dst = nullptr;
+    if (!OUT)
+        dst = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
+    else if (p.nspans == 1 && p.final_state != nullptr)
+        dst = p.final_state + (size_t)bh * dk * dv;
+    if (dst != nullptr) {
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            const int t = w + kWaves * i;
+            if (t < NT) {
+                const int ct = t / NDV16, nt = t - ct * NDV16;
+                const int n = 16 * nt + lm;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int c = 16 * ct + 4 * g + r;
+                    if (c < dk && n < dv) dst[(size_t)c * dv + n] = acc[i][r];
+                }
+            }
+        }
+    }
+    if (!OUT && tid < dk) p.ws_lgam[((size_t)bh * p.nspans + sp) * dk + tid] = s_lg[tid];
+}
+
+template <int MODE, int NDK8, int NDV16, typename TOut>
+hipError_t launch_one(const Params &p, hipStream_t stream) {
+    using L = Layout<MODE, NDK8, NDV16>;
+    auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, TOut>;
+    static bool configured = false;  // per instantiation; the attribute is per function, set once
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    dim3 grid((unsigned)(p.B * p.H * p.nspans)), block(kThreads);
+    hipLaunchKernelGGL(kernel, grid, block, L::kBytes, stream, p);
+    return hipGetLastError();
+}
+
+template <int MODE, int NDK8, int NDV16>
+hipError_t launch_dt(const Params &p, hipStream_t stream) {
+    if (MODE == kModeOutput && p.out_dtype == GLA_DT_BF16)
+        return launch_one<MODE, NDK8, NDV16, uint16_t>(p, stream);
+    return launch_one<MODE, NDK8, NDV16, float>(p, stream);
+}
+
+template <int MODE>
+hipError_t launch_mode(const Params &p, hipStream_t stream) {
+    const int ndk8 = (p.dk + 7) / 8, ndv16 = (p.dv + 15) / 16;
+    if (ndk8 <= 4 && ndv16 <= 4) return launch_dt<MODE, 4, 4>(p, stream);
+    if (ndk8 <= 5 && ndv16 <= 5) return launch_dt<MODE, 5, 5>(p, stream);
+    return launch_dt<MODE, 8, 8>(p, stream);
+}
+
+}  // namespace
+
+bool mfma_engine_supports(const Params &p) {
+    return p.qkv_dtype == GLA_DT_BF16 && p.dk % 4 == 0 && p.dv % 2 == 0 && p.dk <= kMaxDk && p.dv <= kMaxDv;
+}
+
+hipError_t launch_mfma_span(const Params &p, SpanMode mode, hipStream_t stream) {
+    return mode == kModeState ? launch_mode<kModeState>(p, stream) : launch_mode<kModeOutput>(p, stream);
+}
+
 }  // namespace gla
