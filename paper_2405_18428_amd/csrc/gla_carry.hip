@@ -14,6 +14,8 @@ namespace {
 
 constexpr int kCarryThreads = 256;
 
+constexpr int kBatch = 16;  // spans whose loads are in flight together
+
 __global__ __launch_bounds__(kCarryThreads) void carry_kernel(Params p) {
     const int bh = blockIdx.y;
     const int e = blockIdx.x * kCarryThreads + threadIdx.x;
@@ -23,11 +25,22 @@ __global__ __launch_bounds__(kCarryThreads) void carry_kernel(Params p) {
     float *st = p.ws_state + (size_t)bh * p.nspans * ne + e;
     const float *lg = p.ws_lgam + (size_t)bh * p.nspans * p.dk + c;
     float s = 0.f;
-    for (int r = 0; r < p.nspans; ++r) {
-        float u = st[(size_t)r * ne];
-        float gam = expf(lg[(size_t)r * p.dk]);
-        st[(size_t)r * ne] = s;
-        s = fmaf(gam, s, u);
+    for (int r0 = 0; r0 < p.nspans; r0 += kBatch) {
+        // all loads of a batch are issued before the first dependent multiply-add
+        float u[kBatch], gl[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const int r = min(r0 + i, p.nspans - 1);
+            u[i] = st[(size_t)r * ne];
+            gl[i] = lg[(size_t)r * p.dk];
+        }
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            if (r0 + i < p.nspans) {
+                st[(size_t)(r0 + i) * ne] = s;
+                s = fmaf(expf(gl[i]), s, u[i]);
+            }
+        }
     }
     if (p.final_state != nullptr) p.final_state[(size_t)bh * ne + e] = s;
 }

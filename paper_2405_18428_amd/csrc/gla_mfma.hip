@@ -5,18 +5,19 @@
 // With b_j = sum_{i<=j} log_alpha_i inside a chunk (inclusive, per key channel)
 // and b_C its value at the chunk's last token, unrolling the recurrence gives
 //     o_j  = sum_{i<=j} (q~_j . k~_i) v_i + q~_j S_0 ,   q~_j = q_j * exp(b_j),  k~_i = k_i * exp(-b_i)
-//     S_C  = diag(exp(b_C)) S_0 + K^^T V ,               k^_i = k_i * exp(b_C - b_i)
+//     S_C  = diag(exp(b_C)) (S_0 + K~^T V)
 // i.e. four dense contractions per chunk, all on v_mfma_f32_16x16x32_bf16:
-//     A^T = K~ Q~^T (causal tiles only),  O = A V + Q~ S_0,  S += K^^T V.
-// Every gated operand (q~, k~, k^, A, S_0) is split into a bf16 "hi" part and a
-// bf16 "lo" remainder so that the products carry about 16 mantissa bits; v is
-// used as given.  The state S lives in fp32 MFMA accumulators for the whole span.
+//     A^T = K~ Q~^T (causal tiles only),  O = A V + Q~ S_0,  S += K~^T V (then scaled by exp(b_C)).
+// Every gated operand (q~, k~, A, S_0) is split into a bf16 "hi" part and a bf16
+// "lo" remainder so that the products carry about 16 mantissa bits; v is used as
+// given.  The state S lives in fp32 MFMA accumulators for the whole span.
+// Exponentials run in base 2 (log_alpha is scaled by log2(e) once, before the scan).
 //
 // Work-group = 256 threads = 4 waves; per chunk:
 //   (a) registers prefetched from HBM -> LDS: raw log_alpha / q / k rows, V transposed
 //       (lane = column pair, 16 tokens per wave), S_0 as bf16 hi/lo;
-//   (b) lane = token: DPP wave scan of log_alpha per channel, exp, gating, hi/lo
-//       split, operands written in MFMA order;
+//   (b) lane = token: DPP wave scan of log_alpha per channel, exp2, gating, hi/lo
+//       split, operands written in MFMA order (q~, k~ in place over the raw rows);
 //   (c) MFMA: wave w owns output rows 16w..16w+15 and a quarter of the state tiles.
 // The scan order only enters through the per-row token index in LDS.
 #include "gla_common.h"
@@ -34,6 +35,9 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kTokStride = kChunk + 8;  // bf16 elements per row of the token-contiguous operands
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kMaxExp2 = 120.f;       // clamp of -b (base 2) before exp2: keeps k~ finite
 
 __device__ inline f32x4 mfma(u32x4 a, u32x4 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
@@ -46,6 +50,7 @@ __device__ inline uint32_t pack_bf16(float lo, float hi) {
 }
 __device__ inline float bf16_lo_as_float(uint32_t packed) { return __builtin_bit_cast(float, packed << 16); }
 __device__ inline float bf16_hi_as_float(uint32_t packed) { return __builtin_bit_cast(float, packed & 0xffff0000u); }
+__device__ inline float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // x0, x1 -> packed bf16 pair of the rounded values and packed pair of the remainders
 struct HiLo {
@@ -80,9 +85,6 @@ __device__ inline float wave_inclusive_scan(float v) {
     v += dpp_move<0x143, 0xC, false>(v); // row_bcast:31 into rows 2 and 3
     return v;
 }
-__device__ inline float wave_last(float v) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-}
 
 // LDS layout (byte offsets), sized by the padded head dimensions.
 template <int MODE, int NDK8, int NDV16>
@@ -93,26 +95,24 @@ struct Layout {
     static constexpr int kLaStride = kDkp + 4;                            // fp32 per row of raw log_alpha
     static constexpr bool kOut = MODE == kModeOutput;
     static constexpr int kRowOp = kChunk * kChStride * 2;                 // one [64][channels] bf16 operand
-    static constexpr int kKhat = kDkp * kTokStride * 2;                   // one [channels][64] bf16 operand
+    static constexpr int kKt = kDkp * kTokStride * 2;                     // one [channels][64] bf16 operand
     static constexpr int kVt = kDvp * kTokStride * 2;
     static constexpr int kSt = kDvp * kChStride * 2;
 
     static constexpr int oTok = 0;                                        // int[2][64]
     static constexpr int oGam = oTok + 2 * kChunk * 4;                    // float[64]  exp(b_C) of this chunk
-    static constexpr int oLg = oGam + 64 * 4;                             // float[64]  sum of b_C over the span
+    static constexpr int oLg = oGam + 64 * 4;                             // float[64]  sum of b_C over the span (base 2)
     static constexpr int oLa = oLg + 64 * 4;                              // raw log_alpha
-    static constexpr int oKraw = oLa + kChunk * kLaStride * 4;
-    static constexpr int oKhHi = oKraw + kRowOp;
-    static constexpr int oKhLo = oKhHi + kKhat;
-    static constexpr int oVt = oKhLo + kKhat;
+    static constexpr int oKHi = oLa + kChunk * kLaStride * 4;             // raw k rows, then k~ hi in place
+    static constexpr int oKtHi = oKHi + kRowOp;                           // k~ transposed
+    static constexpr int oKtLo = oKtHi + kKt;
+    static constexpr int oVt = oKtLo + kKt;
     static constexpr int oEndState = oVt + kVt;
     // output mode only
-    static constexpr int oQraw = oEndState;
-    static constexpr int oQHi = oQraw + kRowOp;
+    static constexpr int oKLo = oEndState;
+    static constexpr int oQHi = oKLo + kRowOp;                            // raw q rows, then q~ hi in place
     static constexpr int oQLo = oQHi + kRowOp;
-    static constexpr int oKHi = oQLo + kRowOp;
-    static constexpr int oKLo = oKHi + kRowOp;
-    static constexpr int oStHi = oKLo + kRowOp;
+    static constexpr int oStHi = oQLo + kRowOp;
     static constexpr int oStLo = oStHi + kSt;
     static constexpr int oEndOut = oStLo + kSt;
     static constexpr int kBytes = kOut ? oEndOut : oEndState;
@@ -134,21 +134,19 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     float *s_gam = reinterpret_cast<float *>(smem + L::oGam);
     float *s_lg = reinterpret_cast<float *>(smem + L::oLg);
     float *s_la = reinterpret_cast<float *>(smem + L::oLa);
-    uint16_t *s_kraw = reinterpret_cast<uint16_t *>(smem + L::oKraw);
-    uint16_t *s_khhi = reinterpret_cast<uint16_t *>(smem + L::oKhHi);
-    uint16_t *s_khlo = reinterpret_cast<uint16_t *>(smem + L::oKhLo);
-    uint16_t *s_vt = reinterpret_cast<uint16_t *>(smem + L::oVt);
-    uint16_t *s_qraw = reinterpret_cast<uint16_t *>(smem + L::oQraw);
-    uint16_t *s_qhi = reinterpret_cast<uint16_t *>(smem + L::oQHi);
-    uint16_t *s_qlo = reinterpret_cast<uint16_t *>(smem + L::oQLo);
     uint16_t *s_khi = reinterpret_cast<uint16_t *>(smem + L::oKHi);
     uint16_t *s_klo = reinterpret_cast<uint16_t *>(smem + L::oKLo);
+    uint16_t *s_kthi = reinterpret_cast<uint16_t *>(smem + L::oKtHi);
+    uint16_t *s_ktlo = reinterpret_cast<uint16_t *>(smem + L::oKtLo);
+    uint16_t *s_vt = reinterpret_cast<uint16_t *>(smem + L::oVt);
+    uint16_t *s_qhi = reinterpret_cast<uint16_t *>(smem + L::oQHi);
+    uint16_t *s_qlo = reinterpret_cast<uint16_t *>(smem + L::oQLo);
     uint16_t *s_sthi = reinterpret_cast<uint16_t *>(smem + L::oStHi);
     uint16_t *s_stlo = reinterpret_cast<uint16_t *>(smem + L::oStLo);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int w = tid >> 6;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, known uniform
     const int lm = lane & 15;
     const int g = lane >> 4;
 
@@ -167,11 +165,12 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     const int s_end = min(T, s_begin + p.span_len);
     const int nch = (s_end - s_begin + kChunk - 1) / kChunk;
 
-    const uint16_t *gq = static_cast<const uint16_t *>(p.q) + (size_t)bh * T * dk;
-    const uint16_t *gk = static_cast<const uint16_t *>(p.k) + (size_t)bh * T * dk;
-    const uint16_t *gv = static_cast<const uint16_t *>(p.v) + (size_t)bh * T * dv;
-    const float *gla_ = p.log_alpha + (size_t)bh * T * dk;
-    TOut *gout = static_cast<TOut *>(p.out) + (size_t)bh * T * dv;
+    // per-(batch, head) bases; everything below is a 32-bit byte offset from them
+    const char *gq = static_cast<const char *>(p.q) + (size_t)bh * T * dk * 2;
+    const char *gk = static_cast<const char *>(p.k) + (size_t)bh * T * dk * 2;
+    const char *gv = static_cast<const char *>(p.v) + (size_t)bh * T * dv * 2;
+    const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + (size_t)bh * T * dk * 4;
+    char *gout = static_cast<char *>(p.out) + (size_t)bh * T * dv * sizeof(TOut);
 
     // ---- prologue: clear LDS (pads must read as zero), first token map ----
     for (int i = tid; i < L::kBytes / 16; i += kThreads)
@@ -198,46 +197,54 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int c = 16 * ct + 4 * g + r;
-                    if (c < dk && n < dv) acc[i][r] = s0[(size_t)c * dv + n];
+                    if (c < dk && n < dv) acc[i][r] = s0[c * dv + n];
                 }
             }
         }
     }
 
-    // ---- register staging of one chunk's HBM rows ----
-    const int pcs = dk >> 2;                         // 4-channel pieces per row
+    // ---- which HBM pieces this thread stages (the same for every chunk) ----
+    // log_alpha: 16-byte pieces (4 channels); q, k: 8-byte pieces (4 channels)
+    const int pcs = dk >> 2;
     constexpr int kPieces = (kChunk * NDK8 * 2 + kThreads - 1) / kThreads;
-    u32x4 r_la[kPieces];
+    int pj[kPieces];       // row (token slot) of the piece, -1 = none
+    int pch[kPieces];      // first channel of the piece
+#pragma unroll
+    for (int m = 0; m < kPieces; ++m) {
+        const int idx = tid + m * kThreads;
+        const int j = idx / pcs;
+        pj[m] = (idx < kChunk * pcs) ? j : -1;
+        pch[m] = 4 * (idx - j * pcs);
+    }
+    const bool v_lane = lane < (dv >> 1);
+    const uint32_t v_lane_off = 4u * (uint32_t)lane;
+    const uint32_t dk2 = 2u * (uint32_t)dk, dv2 = 2u * (uint32_t)dv;
+
+    f32x4 r_la[kPieces];
     u32x2 r_k[kPieces];
     u32x2 r_q[OUT ? kPieces : 1];
     uint32_t r_v[16];
-    const int npieces = kChunk * pcs;
-    const bool v_lane = lane < (dv >> 1);
 
     auto load_chunk = [&](int chunk) {
         const int *tok = s_tok + (chunk & 1) * kChunk;
 #pragma unroll
         for (int m = 0; m < kPieces; ++m) {
-            const int idx = tid + m * kThreads;
-            r_la[m] = u32x4{0, 0, 0, 0};
+            r_la[m] = f32x4{0.f, 0.f, 0.f, 0.f};
             r_k[m] = u32x2{0, 0};
             if constexpr (OUT) r_q[m] = u32x2{0, 0};
-            if (idx < npieces) {
-                const int j = idx / pcs, pc = idx - j * pcs;
-                const int n = tok[j];
-                if (n >= 0) {
-                    const size_t e = (size_t)n * dk + 4 * pc;
-                    r_la[m] = *reinterpret_cast<const u32x4 *>(gla_ + e);
-                    r_k[m] = *reinterpret_cast<const u32x2 *>(gk + e);
-                    if constexpr (OUT) r_q[m] = *reinterpret_cast<const u32x2 *>(gq + e);
-                }
+            const int n = (pj[m] >= 0) ? tok[pj[m]] : -1;
+            if (n >= 0) {
+                const uint32_t e2 = (uint32_t)n * dk2 + 2u * (uint32_t)pch[m];
+                r_la[m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
+                r_k[m] = *reinterpret_cast<const u32x2 *>(gk + e2);
+                if constexpr (OUT) r_q[m] = *reinterpret_cast<const u32x2 *>(gq + e2);
             }
         }
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) {
-            const int n = tok[16 * w + jj];
+            const int n = __builtin_amdgcn_readfirstlane(tok[16 * w + jj]);  // one token per wave step
             r_v[jj] = 0;
-            if (v_lane && n >= 0) r_v[jj] = *reinterpret_cast<const uint32_t *>(gv + (size_t)n * dv + 2 * lane);
+            if (n >= 0 && v_lane) r_v[jj] = *reinterpret_cast<const uint32_t *>(gv + (uint32_t)n * dv2 + v_lane_off);
         }
     };
 
@@ -249,12 +256,10 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
         // ================= (a) registers -> LDS =================
 #pragma unroll
         for (int m = 0; m < kPieces; ++m) {
-            const int idx = tid + m * kThreads;
-            if (idx < npieces) {
-                const int j = idx / pcs, pc = idx - j * pcs;
-                *reinterpret_cast<u32x4 *>(s_la + j * LAS + 4 * pc) = r_la[m];
-                *reinterpret_cast<u32x2 *>(s_kraw + j * CHS + 4 * pc) = r_k[m];
-                if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qraw + j * CHS + 4 * pc) = r_q[m];
+            if (pj[m] >= 0) {
+                *reinterpret_cast<f32x4 *>(s_la + pj[m] * LAS + pch[m]) = r_la[m];
+                *reinterpret_cast<u32x2 *>(s_khi + pj[m] * CHS + pch[m]) = r_k[m];
+                if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + pj[m] * CHS + pch[m]) = r_q[m];
             }
         }
         if (v_lane) {
@@ -274,7 +279,7 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
             *reinterpret_cast<u32x4 *>(row1) = c1a;
             *reinterpret_cast<u32x4 *>(row1 + 8) = c1b;
         }
-        if (OUT) {
+        if constexpr (OUT) {
             // S_0 (state entering the chunk) as bf16 hi/lo, value-column-major for the B operand
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
@@ -312,78 +317,98 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
                     const int c0 = 8 * kg;
                     float bb[8];
                     {
-                        // (no bit_cast on a vector element: it would read element 0 every time)
                         const f32x4 x0 = *reinterpret_cast<const f32x4 *>(s_la + j * LAS + c0);
                         const f32x4 x1 = *reinterpret_cast<const f32x4 *>(s_la + j * LAS + c0 + 4);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            const float g0 = x0[i], g1 = x1[i];
+                            const float g0 = x0[i] * kLog2e, g1 = x1[i] * kLog2e;
                             bb[i] = wave_inclusive_scan(g0);
                             bb[4 + i] = wave_inclusive_scan(g1);
                         }
                     }
-                    const u32x4 kr = *reinterpret_cast<const u32x4 *>(s_kraw + j * CHS + c0);
-                    u32x4 qr = u32x4{0, 0, 0, 0};
-                    if (OUT) qr = *reinterpret_cast<const u32x4 *>(s_qraw + j * CHS + c0);
-                    u32x4 qhi, qlo, khi, klo;
-                    uint32_t hh[4], hl[4];
+                    const u32x4 kr = *reinterpret_cast<const u32x4 *>(s_khi + j * CHS + c0);
+                    u32x4 khi, klo;
+                    if constexpr (OUT) {
+                        const u32x4 qr = *reinterpret_cast<const u32x4 *>(s_qhi + j * CHS + c0);
+                        u32x4 qhi, qlo;
+                        float eq[8];
 #pragma unroll
-                    for (int h = 0; h < 4; ++h) {
-                        const float b0 = bb[2 * h], b1 = bb[2 * h + 1];
-                        const float bc0 = wave_last(b0), bc1 = wave_last(b1);
-                        const float k0 = bf16_lo_as_float(kr[h]), k1 = bf16_hi_as_float(kr[h]);
-                        SPLIT_PAIR(k0 * __expf(bc0 - b0), k1 * __expf(bc1 - b1), hh[h], hl[h]);
-                        if (OUT) {
-                            const float q0 = bf16_lo_as_float(qr[h]), q1 = bf16_hi_as_float(qr[h]);
-                            SPLIT_PAIR(q0 * __expf(b0), q1 * __expf(b1), qhi[h], qlo[h]);
-                            SPLIT_PAIR(k0 * __expf(fminf(-b0, 85.f)), k1 * __expf(fminf(-b1, 85.f)), khi[h], klo[h]);
+                        for (int h = 0; h < 4; ++h) {
+                            const uint32_t qw = qr[h], kw = kr[h];
+                            eq[2 * h] = exp2_fast(bb[2 * h]);
+                            eq[2 * h + 1] = exp2_fast(bb[2 * h + 1]);
+                            SPLIT_PAIR(bf16_lo_as_float(qw) * eq[2 * h], bf16_hi_as_float(qw) * eq[2 * h + 1],
+                                       qhi[h], qlo[h]);
+                            SPLIT_PAIR(bf16_lo_as_float(kw) * exp2_fast(fminf(-bb[2 * h], kMaxExp2)),
+                                       bf16_hi_as_float(kw) * exp2_fast(fminf(-bb[2 * h + 1], kMaxExp2)),
+                                       khi[h], klo[h]);
                         }
-                        if (lane == 63) {
-                            s_gam[c0 + 2 * h] = __expf(bc0);
-                            s_gam[c0 + 2 * h + 1] = __expf(bc1);
-                            if (!OUT) {
-                                s_lg[c0 + 2 * h] += bc0;
-                                s_lg[c0 + 2 * h + 1] += bc1;
-                            }
-                        }
-                    }
-                    if (OUT) {
                         *reinterpret_cast<u32x4 *>(s_qhi + j * CHS + c0) = qhi;
                         *reinterpret_cast<u32x4 *>(s_qlo + j * CHS + c0) = qlo;
                         *reinterpret_cast<u32x4 *>(s_khi + j * CHS + c0) = khi;
                         *reinterpret_cast<u32x4 *>(s_klo + j * CHS + c0) = klo;
+                        if (lane == 63) {  // the last token's exp(b) is the chunk's total decay
+                            *reinterpret_cast<f32x4 *>(s_gam + c0) = f32x4{eq[0], eq[1], eq[2], eq[3]};
+                            *reinterpret_cast<f32x4 *>(s_gam + c0 + 4) = f32x4{eq[4], eq[5], eq[6], eq[7]};
+                        }
+                    } else {
+#pragma unroll
+                        for (int h = 0; h < 4; ++h) {
+                            const uint32_t kw = kr[h];
+                            SPLIT_PAIR(bf16_lo_as_float(kw) * exp2_fast(fminf(-bb[2 * h], kMaxExp2)),
+                                       bf16_hi_as_float(kw) * exp2_fast(fminf(-bb[2 * h + 1], kMaxExp2)),
+                                       khi[h], klo[h]);
+                        }
+                        if (lane == 63) {
+                            f32x4 l0 = *reinterpret_cast<const f32x4 *>(s_lg + c0);
+                            f32x4 l1 = *reinterpret_cast<const f32x4 *>(s_lg + c0 + 4);
+                            f32x4 g0, g1;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                g0[i] = exp2_fast(bb[i]);
+                                g1[i] = exp2_fast(bb[4 + i]);
+                                l0[i] += bb[i];
+                                l1[i] += bb[4 + i];
+                            }
+                            *reinterpret_cast<f32x4 *>(s_gam + c0) = g0;
+                            *reinterpret_cast<f32x4 *>(s_gam + c0 + 4) = g1;
+                            *reinterpret_cast<f32x4 *>(s_lg + c0) = l0;
+                            *reinterpret_cast<f32x4 *>(s_lg + c0 + 4) = l1;
+                        }
                     }
 #pragma unroll
                     for (int h = 0; h < 4; ++h) {
-                        s_khhi[(c0 + 2 * h) * kTokStride + j] = (uint16_t)(hh[h] & 0xffffu);
-                        s_khhi[(c0 + 2 * h + 1) * kTokStride + j] = (uint16_t)(hh[h] >> 16);
-                        s_khlo[(c0 + 2 * h) * kTokStride + j] = (uint16_t)(hl[h] & 0xffffu);
-                        s_khlo[(c0 + 2 * h + 1) * kTokStride + j] = (uint16_t)(hl[h] >> 16);
+                        const uint32_t hw = khi[h], lw = klo[h];
+                        s_kthi[(c0 + 2 * h) * kTokStride + j] = (uint16_t)(hw & 0xffffu);
+                        s_kthi[(c0 + 2 * h + 1) * kTokStride + j] = (uint16_t)(hw >> 16);
+                        s_ktlo[(c0 + 2 * h) * kTokStride + j] = (uint16_t)(lw & 0xffffu);
+                        s_ktlo[(c0 + 2 * h + 1) * kTokStride + j] = (uint16_t)(lw >> 16);
                     }
                 }
             }
             // the trailing half group (dk % 8 == 4): one channel per wave
             if ((dk & 7) != 0) {
                 const int c = 8 * nfull + w;
-                const float b = wave_inclusive_scan(s_la[j * LAS + c]);
-                const float bc = wave_last(b);
-                const float kx = bf16_bits_to_float(s_kraw[j * CHS + c]);
-                uint32_t hi, lo;
-                SPLIT_PAIR(kx * __expf(bc - b), 0.f, hi, lo);
-                s_khhi[c * kTokStride + j] = (uint16_t)(hi & 0xffffu);
-                s_khlo[c * kTokStride + j] = (uint16_t)(lo & 0xffffu);
-                if (OUT) {
-                    const float qx = bf16_bits_to_float(s_qraw[j * CHS + c]);
-                    uint32_t h2, l2;
-                    SPLIT_PAIR(qx * __expf(b), kx * __expf(fminf(-b, 85.f)), h2, l2);
-                    s_qhi[j * CHS + c] = (uint16_t)(h2 & 0xffffu);
-                    s_qlo[j * CHS + c] = (uint16_t)(l2 & 0xffffu);
-                    s_khi[j * CHS + c] = (uint16_t)(h2 >> 16);
-                    s_klo[j * CHS + c] = (uint16_t)(l2 >> 16);
+                const float b = wave_inclusive_scan(s_la[j * LAS + c] * kLog2e);
+                const float kx = bf16_bits_to_float(s_khi[j * CHS + c]) * exp2_fast(fminf(-b, kMaxExp2));
+                float qx = 0.f, e = 0.f;
+                if constexpr (OUT) {
+                    e = exp2_fast(b);
+                    qx = bf16_bits_to_float(s_qhi[j * CHS + c]) * e;
                 }
-                if (lane == 63) {
-                    s_gam[c] = __expf(bc);
-                    if (!OUT) s_lg[c] += bc;
+                uint32_t h2, l2;
+                SPLIT_PAIR(kx, qx, h2, l2);
+                s_kthi[c * kTokStride + j] = (uint16_t)(h2 & 0xffffu);
+                s_ktlo[c * kTokStride + j] = (uint16_t)(l2 & 0xffffu);
+                if constexpr (OUT) {
+                    s_khi[j * CHS + c] = (uint16_t)(h2 & 0xffffu);
+                    s_klo[j * CHS + c] = (uint16_t)(l2 & 0xffffu);
+                    s_qhi[j * CHS + c] = (uint16_t)(h2 >> 16);
+                    s_qlo[j * CHS + c] = (uint16_t)(l2 >> 16);
+                    if (lane == 63) s_gam[c] = e;
+                } else if (lane == 63) {
+                    s_gam[c] = exp2_fast(b);
+                    s_lg[c] += b;
                 }
             }
         }
@@ -393,7 +418,7 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
         if (chunk + 1 < nch) load_chunk(chunk + 1);
 
         // ================= (c) contractions =================
-        if (OUT) {
+        if constexpr (OUT) {
             // Q~ fragments of this wave's 16 output rows (also the B operand of A^T = K~ Q~^T)
             u32x4 qfh[KS], qfl[KS];
 #pragma unroll
@@ -476,42 +501,42 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
             for (int r = 0; r < 4; ++r) {
                 const int n_tok = tok[16 * w + 4 * g + r];
                 if (n_tok >= 0) {
-                    TOut *orow = gout + (size_t)n_tok * dv;
+                    char *orow = gout + ((uint32_t)n_tok * (uint32_t)dv + (uint32_t)lm) * (uint32_t)sizeof(TOut);
 #pragma unroll
                     for (int nt = 0; nt < NDV16; ++nt) {
-                        const int n = 16 * nt + lm;
-                        if (n < dv) {
-                            if (sizeof(TOut) == 4)
-                                reinterpret_cast<float *>(orow)[n] = o[nt][r];
+                        if (16 * nt + lm < dv) {
+                            if constexpr (sizeof(TOut) == 4)
+                                *reinterpret_cast<float *>(orow + 64 * nt) = o[nt][r];
                             else
-                                reinterpret_cast<uint16_t *>(orow)[n] = (uint16_t)(pack_bf16(o[nt][r], 0.f) & 0xffffu);
+                                *reinterpret_cast<uint16_t *>(orow + 32 * nt) =
+                                    (uint16_t)(pack_bf16(o[nt][r], 0.f) & 0xffffu);
                         }
                     }
                 }
             }
         }
-        // S = diag(exp(b_C)) S + K^^T V on the tiles this wave owns
+        // S = diag(exp(b_C)) (S + K~^T V) on the tiles this wave owns
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             const int t = w + kWaves * i;
             if (t < NT) {
                 const int ct = t / NDV16, nt = t - ct * NDV16;
-                const f32x4 gm = *reinterpret_cast<const f32x4 *>(s_gam + 16 * ct + 4 * g);
                 f32x4 a = acc[i];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) a[r] *= gm[r];
                 const int crow = 16 * ct + lm;
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     u32x4 kh = u32x4{0, 0, 0, 0}, kl = u32x4{0, 0, 0, 0};
                     if (crow < L::kDkp) {
-                        kh = *reinterpret_cast<const u32x4 *>(s_khhi + crow * kTokStride + 32 * ks + 8 * g);
-                        kl = *reinterpret_cast<const u32x4 *>(s_khlo + crow * kTokStride + 32 * ks + 8 * g);
+                        kh = *reinterpret_cast<const u32x4 *>(s_kthi + crow * kTokStride + 32 * ks + 8 * g);
+                        kl = *reinterpret_cast<const u32x4 *>(s_ktlo + crow * kTokStride + 32 * ks + 8 * g);
                     }
                     const u32x4 b = *reinterpret_cast<const u32x4 *>(s_vt + (16 * nt + lm) * kTokStride + 32 * ks + 8 * g);
                     a = mfma(kh, b, a);
                     a = mfma(kl, b, a);
                 }
+                const f32x4 gm = *reinterpret_cast<const f32x4 *>(s_gam + 16 * ct + 4 * g);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) a[r] *= gm[r];
                 acc[i] = a;
             }
         }
@@ -534,12 +559,13 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int c = 16 * ct + 4 * g + r;
-                    if (c < dk && n < dv) dst[(size_t)c * dv + n] = acc[i][r];
+                    if (c < dk && n < dv) dst[c * dv + n] = acc[i][r];
                 }
             }
         }
     }
-    if (!OUT && tid < dk) p.ws_lgam[((size_t)bh * p.nspans + sp) * dk + tid] = s_lg[tid];
+    // the workspace keeps natural logarithms
+    if (!OUT && tid < dk) p.ws_lgam[((size_t)bh * p.nspans + sp) * dk + tid] = s_lg[tid] * kLn2;
 }
 
 template <int MODE, int NDK8, int NDV16, typename TOut>
@@ -576,7 +602,10 @@ hipError_t launch_mode(const Params &p, hipStream_t stream) {
 }  // namespace
 
 bool mfma_engine_supports(const Params &p) {
-    return p.qkv_dtype == GLA_DT_BF16 && p.dk % 4 == 0 && p.dv % 2 == 0 && p.dk <= kMaxDk && p.dv <= kMaxDv;
+    // 32-bit byte offsets inside one (batch, head) slab
+    const long long slab = (long long)p.T * (p.dk > p.dv ? p.dk : p.dv) * 4;
+    return p.qkv_dtype == GLA_DT_BF16 && p.dk % 4 == 0 && p.dv % 2 == 0 && p.dk <= kMaxDk && p.dv <= kMaxDv &&
+           slab < (1LL << 31);
 }
 
 hipError_t launch_mfma_span(const Params &p, SpanMode mode, hipStream_t stream) {
