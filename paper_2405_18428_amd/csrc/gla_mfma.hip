@@ -14,11 +14,15 @@
 // Exponentials run in base 2 (log_alpha is scaled by log2(e) once, before the scan).
 //
 // Work-group = 256 threads = 4 waves; per chunk:
-//   (a) registers prefetched from HBM -> LDS: raw log_alpha / q / k rows, V transposed
-//       (lane = column pair, 16 tokens per wave), S_0 as bf16 hi/lo;
+//   (a) registers prefetched from HBM -> LDS: raw log_alpha / q / k / v rows (all
+//       token-major, 16- or 8-byte pieces), S_0 as bf16 hi/lo;
 //   (b) lane = token: DPP wave scan of log_alpha per channel, exp2, gating, hi/lo
-//       split, operands written in MFMA order (q~, k~ in place over the raw rows);
+//       split, q~ and k~ written in place over the raw rows;
 //   (c) MFMA: wave w owns output rows 16w..16w+15 and a quarter of the state tiles.
+// Operands whose contraction runs over tokens (V, and K~ in the state update) are
+// fetched from the token-major rows with ds_read_b64_tr_b16, which hands lane i of
+// a 16-lane group element i%4 of the 8 bytes read by lane 4e + i/4 (e = 0..3): 16
+// lanes reading a 4-token x 16-column block each end up with 4 tokens of one column.
 // The scan order only enters through the per-row token index in LDS.
 #include "gla_common.h"
 
@@ -34,7 +38,6 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
-constexpr int kTokStride = kChunk + 8;  // bf16 elements per row of the token-contiguous operands
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kMaxExp2 = 120.f;       // clamp of -b (base 2) before exp2: keeps k~ finite
@@ -51,6 +54,13 @@ __device__ inline uint32_t pack_bf16(float lo, float hi) {
 __device__ inline float bf16_lo_as_float(uint32_t packed) { return __builtin_bit_cast(float, packed << 16); }
 __device__ inline float bf16_hi_as_float(uint32_t packed) { return __builtin_bit_cast(float, packed & 0xffff0000u); }
 __device__ inline float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+// Transposing 8-byte LDS read (see the header comment for the lane shuffle).
+__device__ inline u32x2 lds_read_tr(const uint16_t *p) {
+    typedef __attribute__((address_space(3))) s16x4 *lds_ptr;
+    return __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p));
+}
 
 // x0, x1 -> packed bf16 pair of the rounded values and packed pair of the remainders
 struct HiLo {
@@ -89,14 +99,18 @@ __device__ inline float wave_inclusive_scan(float v) {
 // LDS layout (byte offsets), sized by the padded head dimensions.
 template <int MODE, int NDK8, int NDV16>
 struct Layout {
-    static constexpr int kDkp = NDK8 * 8;                                 // channels incl. padding
-    static constexpr int kDvp = NDV16 * 16;                               // value columns incl. padding
-    static constexpr int kChStride = kDkp + ((NDK8 % 4 == 0) ? 8 : 0);    // bf16 per row of channel-contiguous operands
+    static constexpr int kDkp = NDK8 * 8;                                 // channels incl. padding to 8
+    static constexpr int kDvp = NDV16 * 16;                               // value columns incl. padding to 16
+    // bf16 per row of the channel-major operands: a multiple of 16 channels (the state update reads 16-channel
+    // tiles) that leaves one all-zero group of 8 after the data when dk is not a multiple of 32 (lanes whose
+    // channel group lies beyond dk read that group instead of being masked); +8 skews rows across LDS banks.
+    static constexpr int kChStride = (NDK8 % 4 == 0) ? kDkp + 8 : ((kDkp + 8 + 15) / 16) * 16;
+    static constexpr int kZeroCol = kDkp;                                 // first column of the all-zero group
+    static constexpr int kVStride = kDvp + 8;                             // bf16 per row of V
     static constexpr int kLaStride = kDkp + 4;                            // fp32 per row of raw log_alpha
     static constexpr bool kOut = MODE == kModeOutput;
     static constexpr int kRowOp = kChunk * kChStride * 2;                 // one [64][channels] bf16 operand
-    static constexpr int kKt = kDkp * kTokStride * 2;                     // one [channels][64] bf16 operand
-    static constexpr int kVt = kDvp * kTokStride * 2;
+    static constexpr int kV = kChunk * kVStride * 2;
     static constexpr int kSt = kDvp * kChStride * 2;
 
     static constexpr int oTok = 0;                                        // int[2][64]
@@ -104,13 +118,11 @@ struct Layout {
     static constexpr int oLg = oGam + 64 * 4;                             // float[64]  sum of b_C over the span (base 2)
     static constexpr int oLa = oLg + 64 * 4;                              // raw log_alpha
     static constexpr int oKHi = oLa + kChunk * kLaStride * 4;             // raw k rows, then k~ hi in place
-    static constexpr int oKtHi = oKHi + kRowOp;                           // k~ transposed
-    static constexpr int oKtLo = oKtHi + kKt;
-    static constexpr int oVt = oKtLo + kKt;
-    static constexpr int oEndState = oVt + kVt;
+    static constexpr int oKLo = oKHi + kRowOp;
+    static constexpr int oV = oKLo + kRowOp;
+    static constexpr int oEndState = oV + kV;
     // output mode only
-    static constexpr int oKLo = oEndState;
-    static constexpr int oQHi = oKLo + kRowOp;                            // raw q rows, then q~ hi in place
+    static constexpr int oQHi = oEndState;                                // raw q rows, then q~ hi in place
     static constexpr int oQLo = oQHi + kRowOp;
     static constexpr int oStHi = oQLo + kRowOp;
     static constexpr int oStLo = oStHi + kSt;
@@ -123,6 +135,7 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     using L = Layout<MODE, NDK8, NDV16>;
     constexpr bool OUT = MODE == kModeOutput;
     constexpr int CHS = L::kChStride;
+    constexpr int VS = L::kVStride;
     constexpr int LAS = L::kLaStride;
     constexpr int KS = (NDK8 + 3) / 4;          // 32-channel steps of the channel contractions
     constexpr int NCT = (NDK8 + 1) / 2;         // 16-channel row tiles of the state
@@ -136,9 +149,7 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     float *s_la = reinterpret_cast<float *>(smem + L::oLa);
     uint16_t *s_khi = reinterpret_cast<uint16_t *>(smem + L::oKHi);
     uint16_t *s_klo = reinterpret_cast<uint16_t *>(smem + L::oKLo);
-    uint16_t *s_kthi = reinterpret_cast<uint16_t *>(smem + L::oKtHi);
-    uint16_t *s_ktlo = reinterpret_cast<uint16_t *>(smem + L::oKtLo);
-    uint16_t *s_vt = reinterpret_cast<uint16_t *>(smem + L::oVt);
+    uint16_t *s_v = reinterpret_cast<uint16_t *>(smem + L::oV);
     uint16_t *s_qhi = reinterpret_cast<uint16_t *>(smem + L::oQHi);
     uint16_t *s_qlo = reinterpret_cast<uint16_t *>(smem + L::oQLo);
     uint16_t *s_sthi = reinterpret_cast<uint16_t *>(smem + L::oStHi);
@@ -204,7 +215,7 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     }
 
     // ---- which HBM pieces this thread stages (the same for every chunk) ----
-    // log_alpha: 16-byte pieces (4 channels); q, k: 8-byte pieces (4 channels)
+    // log_alpha: 16-byte pieces (4 channels); q, k: 8-byte pieces (4 channels); v: 16-byte pieces (8 columns)
     const int pcs = dk >> 2;
     constexpr int kPieces = (kChunk * NDK8 * 2 + kThreads - 1) / kThreads;
     int pj[kPieces];       // row (token slot) of the piece, -1 = none
@@ -216,14 +227,22 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
         pj[m] = (idx < kChunk * pcs) ? j : -1;
         pch[m] = 4 * (idx - j * pcs);
     }
-    const bool v_lane = lane < (dv >> 1);
-    const uint32_t v_lane_off = 4u * (uint32_t)lane;
+    const int vpcs = dv >> 3;
+    constexpr int kVPieces = (kChunk * NDV16 * 2 + kThreads - 1) / kThreads;
+    int vj[kVPieces], vcol[kVPieces];
+#pragma unroll
+    for (int m = 0; m < kVPieces; ++m) {
+        const int idx = tid + m * kThreads;
+        const int j = idx / vpcs;
+        vj[m] = (idx < kChunk * vpcs) ? j : -1;
+        vcol[m] = 8 * (idx - j * vpcs);
+    }
     const uint32_t dk2 = 2u * (uint32_t)dk, dv2 = 2u * (uint32_t)dv;
 
     f32x4 r_la[kPieces];
     u32x2 r_k[kPieces];
     u32x2 r_q[OUT ? kPieces : 1];
-    uint32_t r_v[16];
+    u32x4 r_v[kVPieces];
 
     auto load_chunk = [&](int chunk) {
         const int *tok = s_tok + (chunk & 1) * kChunk;
@@ -241,12 +260,20 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
             }
         }
 #pragma unroll
-        for (int jj = 0; jj < 16; ++jj) {
-            const int n = __builtin_amdgcn_readfirstlane(tok[16 * w + jj]);  // one token per wave step
-            r_v[jj] = 0;
-            if (n >= 0 && v_lane) r_v[jj] = *reinterpret_cast<const uint32_t *>(gv + (uint32_t)n * dv2 + v_lane_off);
+        for (int m = 0; m < kVPieces; ++m) {
+            r_v[m] = u32x4{0, 0, 0, 0};
+            const int n = (vj[m] >= 0) ? tok[vj[m]] : -1;
+            if (n >= 0) r_v[m] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)n * dv2 + 2u * (uint32_t)vcol[m]);
         }
     };
+
+    // ---- per-lane LDS offsets (bf16 elements) that do not change from chunk to chunk ----
+    // channel group read by this lane in 32-channel step ks; groups beyond dk alias the all-zero group
+    int colk[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) colk[ks] = (4 * ks + g < NDK8) ? 8 * (4 * ks + g) : L::kZeroCol;
+    // transposing reads: this lane supplies row lm/4 (of 4 tokens) and column quad lm%4 (of 16 columns)
+    const int tr_row = lm >> 2, tr_col = 4 * (lm & 3);
 
     load_chunk(0);
 
@@ -262,23 +289,9 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
                 if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + pj[m] * CHS + pch[m]) = r_q[m];
             }
         }
-        if (v_lane) {
-            // lane holds columns 2*lane, 2*lane+1 of 16 consecutive tokens: write them token-contiguous
-            u32x4 c0a, c0b, c1a, c1b;
 #pragma unroll
-            for (int h = 0; h < 4; ++h) {
-                c0a[h] = (r_v[2 * h] & 0xffffu) | (r_v[2 * h + 1] << 16);
-                c1a[h] = (r_v[2 * h] >> 16) | (r_v[2 * h + 1] & 0xffff0000u);
-                c0b[h] = (r_v[8 + 2 * h] & 0xffffu) | (r_v[8 + 2 * h + 1] << 16);
-                c1b[h] = (r_v[8 + 2 * h] >> 16) | (r_v[8 + 2 * h + 1] & 0xffff0000u);
-            }
-            uint16_t *row0 = s_vt + (2 * lane) * kTokStride + 16 * w;
-            uint16_t *row1 = row0 + kTokStride;
-            *reinterpret_cast<u32x4 *>(row0) = c0a;
-            *reinterpret_cast<u32x4 *>(row0 + 8) = c0b;
-            *reinterpret_cast<u32x4 *>(row1) = c1a;
-            *reinterpret_cast<u32x4 *>(row1 + 8) = c1b;
-        }
+        for (int m = 0; m < kVPieces; ++m)
+            if (vj[m] >= 0) *reinterpret_cast<u32x4 *>(s_v + vj[m] * VS + vcol[m]) = r_v[m];
         if constexpr (OUT) {
             // S_0 (state entering the chunk) as bf16 hi/lo, value-column-major for the B operand
 #pragma unroll
@@ -328,61 +341,48 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
                     }
                     const u32x4 kr = *reinterpret_cast<const u32x4 *>(s_khi + j * CHS + c0);
                     u32x4 khi, klo;
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        const uint32_t kw = kr[h];
+                        SPLIT_PAIR(bf16_lo_as_float(kw) * exp2_fast(fminf(-bb[2 * h], kMaxExp2)),
+                                   bf16_hi_as_float(kw) * exp2_fast(fminf(-bb[2 * h + 1], kMaxExp2)),
+                                   khi[h], klo[h]);
+                    }
+                    *reinterpret_cast<u32x4 *>(s_khi + j * CHS + c0) = khi;
+                    *reinterpret_cast<u32x4 *>(s_klo + j * CHS + c0) = klo;
                     if constexpr (OUT) {
                         const u32x4 qr = *reinterpret_cast<const u32x4 *>(s_qhi + j * CHS + c0);
                         u32x4 qhi, qlo;
                         float eq[8];
 #pragma unroll
                         for (int h = 0; h < 4; ++h) {
-                            const uint32_t qw = qr[h], kw = kr[h];
+                            const uint32_t qw = qr[h];
                             eq[2 * h] = exp2_fast(bb[2 * h]);
                             eq[2 * h + 1] = exp2_fast(bb[2 * h + 1]);
                             SPLIT_PAIR(bf16_lo_as_float(qw) * eq[2 * h], bf16_hi_as_float(qw) * eq[2 * h + 1],
                                        qhi[h], qlo[h]);
-                            SPLIT_PAIR(bf16_lo_as_float(kw) * exp2_fast(fminf(-bb[2 * h], kMaxExp2)),
-                                       bf16_hi_as_float(kw) * exp2_fast(fminf(-bb[2 * h + 1], kMaxExp2)),
-                                       khi[h], klo[h]);
                         }
                         *reinterpret_cast<u32x4 *>(s_qhi + j * CHS + c0) = qhi;
                         *reinterpret_cast<u32x4 *>(s_qlo + j * CHS + c0) = qlo;
-                        *reinterpret_cast<u32x4 *>(s_khi + j * CHS + c0) = khi;
-                        *reinterpret_cast<u32x4 *>(s_klo + j * CHS + c0) = klo;
                         if (lane == 63) {  // the last token's exp(b) is the chunk's total decay
                             *reinterpret_cast<f32x4 *>(s_gam + c0) = f32x4{eq[0], eq[1], eq[2], eq[3]};
                             *reinterpret_cast<f32x4 *>(s_gam + c0 + 4) = f32x4{eq[4], eq[5], eq[6], eq[7]};
                         }
-                    } else {
+                    } else if (lane == 63) {
+                        f32x4 l0 = *reinterpret_cast<const f32x4 *>(s_lg + c0);
+                        f32x4 l1 = *reinterpret_cast<const f32x4 *>(s_lg + c0 + 4);
+                        f32x4 g0, g1;
 #pragma unroll
-                        for (int h = 0; h < 4; ++h) {
-                            const uint32_t kw = kr[h];
-                            SPLIT_PAIR(bf16_lo_as_float(kw) * exp2_fast(fminf(-bb[2 * h], kMaxExp2)),
-                                       bf16_hi_as_float(kw) * exp2_fast(fminf(-bb[2 * h + 1], kMaxExp2)),
-                                       khi[h], klo[h]);
+                        for (int i = 0; i < 4; ++i) {
+                            g0[i] = exp2_fast(bb[i]);
+                            g1[i] = exp2_fast(bb[4 + i]);
+                            l0[i] += bb[i];
+                            l1[i] += bb[4 + i];
                         }
-                        if (lane == 63) {
-                            f32x4 l0 = *reinterpret_cast<const f32x4 *>(s_lg + c0);
-                            f32x4 l1 = *reinterpret_cast<const f32x4 *>(s_lg + c0 + 4);
-                            f32x4 g0, g1;
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                g0[i] = exp2_fast(bb[i]);
-                                g1[i] = exp2_fast(bb[4 + i]);
-                                l0[i] += bb[i];
-                                l1[i] += bb[4 + i];
-                            }
-                            *reinterpret_cast<f32x4 *>(s_gam + c0) = g0;
-                            *reinterpret_cast<f32x4 *>(s_gam + c0 + 4) = g1;
-                            *reinterpret_cast<f32x4 *>(s_lg + c0) = l0;
-                            *reinterpret_cast<f32x4 *>(s_lg + c0 + 4) = l1;
-                        }
-                    }
-#pragma unroll
-                    for (int h = 0; h < 4; ++h) {
-                        const uint32_t hw = khi[h], lw = klo[h];
-                        s_kthi[(c0 + 2 * h) * kTokStride + j] = (uint16_t)(hw & 0xffffu);
-                        s_kthi[(c0 + 2 * h + 1) * kTokStride + j] = (uint16_t)(hw >> 16);
-                        s_ktlo[(c0 + 2 * h) * kTokStride + j] = (uint16_t)(lw & 0xffffu);
-                        s_ktlo[(c0 + 2 * h + 1) * kTokStride + j] = (uint16_t)(lw >> 16);
+                        *reinterpret_cast<f32x4 *>(s_gam + c0) = g0;
+                        *reinterpret_cast<f32x4 *>(s_gam + c0 + 4) = g1;
+                        *reinterpret_cast<f32x4 *>(s_lg + c0) = l0;
+                        *reinterpret_cast<f32x4 *>(s_lg + c0 + 4) = l1;
                     }
                 }
             }
@@ -398,11 +398,9 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
                 }
                 uint32_t h2, l2;
                 SPLIT_PAIR(kx, qx, h2, l2);
-                s_kthi[c * kTokStride + j] = (uint16_t)(h2 & 0xffffu);
-                s_ktlo[c * kTokStride + j] = (uint16_t)(l2 & 0xffffu);
+                s_khi[j * CHS + c] = (uint16_t)(h2 & 0xffffu);
+                s_klo[j * CHS + c] = (uint16_t)(l2 & 0xffffu);
                 if constexpr (OUT) {
-                    s_khi[j * CHS + c] = (uint16_t)(h2 & 0xffffu);
-                    s_klo[j * CHS + c] = (uint16_t)(l2 & 0xffffu);
                     s_qhi[j * CHS + c] = (uint16_t)(h2 >> 16);
                     s_qlo[j * CHS + c] = (uint16_t)(l2 >> 16);
                     if (lane == 63) s_gam[c] = e;
@@ -423,13 +421,8 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
             u32x4 qfh[KS], qfl[KS];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const int kg = 4 * ks + g;
-                qfh[ks] = u32x4{0, 0, 0, 0};
-                qfl[ks] = u32x4{0, 0, 0, 0};
-                if (kg < NDK8) {
-                    qfh[ks] = *reinterpret_cast<const u32x4 *>(s_qhi + (16 * w + lm) * CHS + 8 * kg);
-                    qfl[ks] = *reinterpret_cast<const u32x4 *>(s_qlo + (16 * w + lm) * CHS + 8 * kg);
-                }
+                qfh[ks] = *reinterpret_cast<const u32x4 *>(s_qhi + (16 * w + lm) * CHS + colk[ks]);
+                qfl[ks] = *reinterpret_cast<const u32x4 *>(s_qlo + (16 * w + lm) * CHS + colk[ks]);
             }
             // causal score tiles, transposed: lane (lm, g) ends up with A[i = 16w+lm][j = 16jt+4g+r]
             u32x2 ph[kWaves], pl[kWaves];
@@ -441,12 +434,8 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
                     f32x4 d = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
-                        const int kg = 4 * ks + g;
-                        u32x4 kh = u32x4{0, 0, 0, 0}, kl = u32x4{0, 0, 0, 0};
-                        if (kg < NDK8) {
-                            kh = *reinterpret_cast<const u32x4 *>(s_khi + (16 * jt + lm) * CHS + 8 * kg);
-                            kl = *reinterpret_cast<const u32x4 *>(s_klo + (16 * jt + lm) * CHS + 8 * kg);
-                        }
+                        const u32x4 kh = *reinterpret_cast<const u32x4 *>(s_khi + (16 * jt + lm) * CHS + colk[ks]);
+                        const u32x4 kl = *reinterpret_cast<const u32x4 *>(s_klo + (16 * jt + lm) * CHS + colk[ks]);
                         d = mfma(kh, qfh[ks], d);
                         d = mfma(kh, qfl[ks], d);
                         d = mfma(kl, qfh[ks], d);
@@ -469,11 +458,11 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
                 if (2 * q32 <= w) {
                     const u32x4 ah = u32x4{ph[2 * q32][0], ph[2 * q32][1], ph[2 * q32 + 1][0], ph[2 * q32 + 1][1]};
                     const u32x4 al = u32x4{pl[2 * q32][0], pl[2 * q32][1], pl[2 * q32 + 1][0], pl[2 * q32 + 1][1]};
+                    const uint16_t *vrow = s_v + (32 * q32 + 4 * g + tr_row) * VS + tr_col;
 #pragma unroll
                     for (int nt = 0; nt < NDV16; ++nt) {
-                        const uint16_t *vr = s_vt + (16 * nt + lm) * kTokStride + 32 * q32 + 4 * g;
-                        const u32x2 v0 = *reinterpret_cast<const u32x2 *>(vr);
-                        const u32x2 v1 = *reinterpret_cast<const u32x2 *>(vr + 16);
+                        const u32x2 v0 = lds_read_tr(vrow + 16 * nt);
+                        const u32x2 v1 = lds_read_tr(vrow + 16 * VS + 16 * nt);
                         const u32x4 b = u32x4{v0[0], v0[1], v1[0], v1[1]};
                         o[nt] = mfma(ah, b, o[nt]);
                         o[nt] = mfma(al, b, o[nt]);
@@ -483,14 +472,10 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
             // O += Q~ S_0
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const int kg = 4 * ks + g;
 #pragma unroll
                 for (int nt = 0; nt < NDV16; ++nt) {
-                    u32x4 sh = u32x4{0, 0, 0, 0}, sl = u32x4{0, 0, 0, 0};
-                    if (kg < NDK8) {
-                        sh = *reinterpret_cast<const u32x4 *>(s_sthi + (16 * nt + lm) * CHS + 8 * kg);
-                        sl = *reinterpret_cast<const u32x4 *>(s_stlo + (16 * nt + lm) * CHS + 8 * kg);
-                    }
+                    const u32x4 sh = *reinterpret_cast<const u32x4 *>(s_sthi + (16 * nt + lm) * CHS + colk[ks]);
+                    const u32x4 sl = *reinterpret_cast<const u32x4 *>(s_stlo + (16 * nt + lm) * CHS + colk[ks]);
                     o[nt] = mfma(qfh[ks], sh, o[nt]);
                     o[nt] = mfma(qfl[ks], sh, o[nt]);
                     o[nt] = mfma(qfh[ks], sl, o[nt]);
@@ -515,29 +500,34 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
                 }
             }
         }
-        // S = diag(exp(b_C)) (S + K~^T V) on the tiles this wave owns
+        // S = diag(exp(b_C)) (S + K~^T V) on the tiles this wave owns; contraction slot (g, e) of a
+        // 32-token step is token 32ks + 8g + e, fetched for K~ (A operand) and V (B operand) alike
+        {
+            const uint16_t *krow_h = s_khi + (8 * g + tr_row) * CHS + tr_col;
+            const uint16_t *krow_l = s_klo + (8 * g + tr_row) * CHS + tr_col;
+            const uint16_t *vrow = s_v + (8 * g + tr_row) * VS + tr_col;
 #pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            const int t = w + kWaves * i;
-            if (t < NT) {
-                const int ct = t / NDV16, nt = t - ct * NDV16;
-                f32x4 a = acc[i];
-                const int crow = 16 * ct + lm;
+            for (int i = 0; i < TPW; ++i) {
+                const int t = w + kWaves * i;
+                if (t < NT) {
+                    const int ct = t / NDV16, nt = t - ct * NDV16;
+                    f32x4 a = acc[i];
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    u32x4 kh = u32x4{0, 0, 0, 0}, kl = u32x4{0, 0, 0, 0};
-                    if (crow < L::kDkp) {
-                        kh = *reinterpret_cast<const u32x4 *>(s_kthi + crow * kTokStride + 32 * ks + 8 * g);
-                        kl = *reinterpret_cast<const u32x4 *>(s_ktlo + crow * kTokStride + 32 * ks + 8 * g);
+                    for (int ks = 0; ks < 2; ++ks) {
+                        const int ko = 32 * ks * CHS + 16 * ct;
+                        const u32x2 h0 = lds_read_tr(krow_h + ko), h1 = lds_read_tr(krow_h + ko + 4 * CHS);
+                        const u32x2 l0 = lds_read_tr(krow_l + ko), l1 = lds_read_tr(krow_l + ko + 4 * CHS);
+                        const int vo = 32 * ks * VS + 16 * nt;
+                        const u32x2 v0 = lds_read_tr(vrow + vo), v1 = lds_read_tr(vrow + vo + 4 * VS);
+                        const u32x4 b = u32x4{v0[0], v0[1], v1[0], v1[1]};
+                        a = mfma(u32x4{h0[0], h0[1], h1[0], h1[1]}, b, a);
+                        a = mfma(u32x4{l0[0], l0[1], l1[0], l1[1]}, b, a);
                     }
-                    const u32x4 b = *reinterpret_cast<const u32x4 *>(s_vt + (16 * nt + lm) * kTokStride + 32 * ks + 8 * g);
-                    a = mfma(kh, b, a);
-                    a = mfma(kl, b, a);
-                }
-                const f32x4 gm = *reinterpret_cast<const f32x4 *>(s_gam + 16 * ct + 4 * g);
+                    const f32x4 gm = *reinterpret_cast<const f32x4 *>(s_gam + 16 * ct + 4 * g);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) a[r] *= gm[r];
-                acc[i] = a;
+                    for (int r = 0; r < 4; ++r) a[r] *= gm[r];
+                    acc[i] = a;
+                }
             }
         }
         __syncthreads();
@@ -604,7 +594,7 @@ hipError_t launch_mode(const Params &p, hipStream_t stream) {
 bool mfma_engine_supports(const Params &p) {
     // 32-bit byte offsets inside one (batch, head) slab
     const long long slab = (long long)p.T * (p.dk > p.dv ? p.dk : p.dv) * 4;
-    return p.qkv_dtype == GLA_DT_BF16 && p.dk % 4 == 0 && p.dv % 2 == 0 && p.dk <= kMaxDk && p.dv <= kMaxDv &&
+    return p.qkv_dtype == GLA_DT_BF16 && p.dk % 4 == 0 && p.dv % 8 == 0 && p.dk <= kMaxDk && p.dv <= kMaxDv &&
            slab < (1LL << 31);
 }
 
