@@ -13,6 +13,7 @@ LIB = os.path.join(HERE, "libgla.so")
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 math.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",  # MFMA results feed VALU code: keep them out of AGPRs
          "-Wall", "-Wno-unused-function"]
 
 

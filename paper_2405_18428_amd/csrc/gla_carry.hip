@@ -14,7 +14,7 @@ namespace {
 
 constexpr int kCarryThreads = 256;
 
-constexpr int kBatch = 16;  // spans whose loads are in flight together
+constexpr int kBatch = 32;  // spans whose loads are in flight together
 
 __global__ __launch_bounds__(kCarryThreads) void carry_kernel(Params p) {
     const int bh = blockIdx.y;

@@ -113,8 +113,8 @@ struct Layout {
     static constexpr int kV = kChunk * kVStride * 2;
     static constexpr int kSt = kDvp * kChStride * 2;
 
-    static constexpr int oTok = 0;                                        // int[2][64]
-    static constexpr int oGam = oTok + 2 * kChunk * 4;                    // float[64]  exp(b_C) of this chunk
+    static constexpr int oTok = 0;                                        // int[3][64] (+ pad)
+    static constexpr int oGam = oTok + 4 * kChunk * 4;                    // float[64]  exp(b_C) of this chunk
     static constexpr int oLg = oGam + 64 * 4;                             // float[64]  sum of b_C over the span (base 2)
     static constexpr int oLa = oLg + 64 * 4;                              // raw log_alpha
     static constexpr int oKHi = oLa + kChunk * kLaStride * 4;             // raw k rows, then k~ hi in place
@@ -187,9 +187,9 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     for (int i = tid; i < L::kBytes / 16; i += kThreads)
         reinterpret_cast<u32x4 *>(smem)[i] = u32x4{0, 0, 0, 0};
     __syncthreads();
-    if (tid < kChunk) {
-        int s = s_begin + tid;
-        s_tok[tid] = (s < s_end) ? scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w) : -1;
+    if (tid < 2 * kChunk) {  // token maps of the first two chunks
+        const int s = s_begin + tid;
+        s_tok[tid] = scan_token(p.scan_dir, (s < s_end) ? s : s_begin, T, p.grid_h, p.grid_w);
     }
     __syncthreads();
 
@@ -218,24 +218,24 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     // log_alpha: 16-byte pieces (4 channels); q, k: 8-byte pieces (4 channels); v: 16-byte pieces (8 columns)
     const int pcs = dk >> 2;
     constexpr int kPieces = (kChunk * NDK8 * 2 + kThreads - 1) / kThreads;
-    int pj[kPieces];       // row (token slot) of the piece, -1 = none
+    // Slots past the last piece repeat an earlier piece (same bytes to the same place) rather than
+    // carrying a predicate through the loop.
+    int pj[kPieces];       // row (token slot) of the piece
     int pch[kPieces];      // first channel of the piece
 #pragma unroll
     for (int m = 0; m < kPieces; ++m) {
-        const int idx = tid + m * kThreads;
-        const int j = idx / pcs;
-        pj[m] = (idx < kChunk * pcs) ? j : -1;
-        pch[m] = 4 * (idx - j * pcs);
+        const int idx = (tid + m * kThreads) % (kChunk * pcs);
+        pj[m] = idx / pcs;
+        pch[m] = 4 * (idx - pj[m] * pcs);
     }
     const int vpcs = dv >> 3;
     constexpr int kVPieces = (kChunk * NDV16 * 2 + kThreads - 1) / kThreads;
     int vj[kVPieces], vcol[kVPieces];
 #pragma unroll
     for (int m = 0; m < kVPieces; ++m) {
-        const int idx = tid + m * kThreads;
-        const int j = idx / vpcs;
-        vj[m] = (idx < kChunk * vpcs) ? j : -1;
-        vcol[m] = 8 * (idx - j * vpcs);
+        const int idx = (tid + m * kThreads) % (kChunk * vpcs);
+        vj[m] = idx / vpcs;
+        vcol[m] = 8 * (idx - vj[m] * vpcs);
     }
     const uint32_t dk2 = 2u * (uint32_t)dk, dv2 = 2u * (uint32_t)dv;
 
@@ -244,27 +244,20 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     u32x2 r_q[OUT ? kPieces : 1];
     u32x4 r_v[kVPieces];
 
+    // Rows past the end of a ragged last chunk carry the token of a valid row in s_tok (so the loads
+    // stay in bounds) and are zeroed when they are written to LDS.
     auto load_chunk = [&](int chunk) {
-        const int *tok = s_tok + (chunk & 1) * kChunk;
+        const int *tok = s_tok + (chunk % 3) * kChunk;
 #pragma unroll
         for (int m = 0; m < kPieces; ++m) {
-            r_la[m] = f32x4{0.f, 0.f, 0.f, 0.f};
-            r_k[m] = u32x2{0, 0};
-            if constexpr (OUT) r_q[m] = u32x2{0, 0};
-            const int n = (pj[m] >= 0) ? tok[pj[m]] : -1;
-            if (n >= 0) {
-                const uint32_t e2 = (uint32_t)n * dk2 + 2u * (uint32_t)pch[m];
-                r_la[m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
-                r_k[m] = *reinterpret_cast<const u32x2 *>(gk + e2);
-                if constexpr (OUT) r_q[m] = *reinterpret_cast<const u32x2 *>(gq + e2);
-            }
+            const uint32_t e2 = (uint32_t)tok[pj[m]] * dk2 + 2u * (uint32_t)pch[m];
+            r_la[m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
+            r_k[m] = *reinterpret_cast<const u32x2 *>(gk + e2);
+            if constexpr (OUT) r_q[m] = *reinterpret_cast<const u32x2 *>(gq + e2);
         }
 #pragma unroll
-        for (int m = 0; m < kVPieces; ++m) {
-            r_v[m] = u32x4{0, 0, 0, 0};
-            const int n = (vj[m] >= 0) ? tok[vj[m]] : -1;
-            if (n >= 0) r_v[m] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)n * dv2 + 2u * (uint32_t)vcol[m]);
-        }
+        for (int m = 0; m < kVPieces; ++m)
+            r_v[m] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tok[vj[m]] * dv2 + 2u * (uint32_t)vcol[m]);
     };
 
     // ---- per-lane LDS offsets (bf16 elements) that do not change from chunk to chunk ----
@@ -278,20 +271,33 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     load_chunk(0);
 
     for (int chunk = 0; chunk < nch; ++chunk) {
-        const int *tok = s_tok + (chunk & 1) * kChunk;
+        const int *tok = s_tok + (chunk % 3) * kChunk;
 
         // ================= (a) registers -> LDS =================
+        const int nvalid = min(kChunk, s_end - s_begin - chunk * kChunk);  // rows of this chunk that are tokens
+        if (nvalid < kChunk) {
 #pragma unroll
-        for (int m = 0; m < kPieces; ++m) {
-            if (pj[m] >= 0) {
-                *reinterpret_cast<f32x4 *>(s_la + pj[m] * LAS + pch[m]) = r_la[m];
-                *reinterpret_cast<u32x2 *>(s_khi + pj[m] * CHS + pch[m]) = r_k[m];
-                if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + pj[m] * CHS + pch[m]) = r_q[m];
+            for (int m = 0; m < kPieces; ++m) {
+                if (pj[m] >= nvalid) {
+                    r_la[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    r_k[m] = u32x2{0, 0};
+                    if constexpr (OUT) r_q[m] = u32x2{0, 0};
+                }
             }
+#pragma unroll
+            for (int m = 0; m < kVPieces; ++m)
+                if (vj[m] >= nvalid) r_v[m] = u32x4{0, 0, 0, 0};
         }
 #pragma unroll
-        for (int m = 0; m < kVPieces; ++m)
-            if (vj[m] >= 0) *reinterpret_cast<u32x4 *>(s_v + vj[m] * VS + vcol[m]) = r_v[m];
+        for (int m = 0; m < kPieces; ++m) {
+            *reinterpret_cast<f32x4 *>(s_la + pj[m] * LAS + pch[m]) = r_la[m];
+            *reinterpret_cast<u32x2 *>(s_khi + pj[m] * CHS + pch[m]) = r_k[m];
+            if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + pj[m] * CHS + pch[m]) = r_q[m];
+        }
+#pragma unroll
+        for (int m = 0; m < kVPieces; ++m) *reinterpret_cast<u32x4 *>(s_v + vj[m] * VS + vcol[m]) = r_v[m];
+        // the next chunk's rows start their trip from HBM now and land while this chunk is being computed
+        if (chunk + 1 < nch) load_chunk(chunk + 1);
         if constexpr (OUT) {
             // S_0 (state entering the chunk) as bf16 hi/lo, value-column-major for the B operand
 #pragma unroll
@@ -299,22 +305,21 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
                 const int t = w + kWaves * i;
                 if (t < NT) {
                     const int ct = t / NDV16, nt = t - ct * NDV16;
-                    const int c0 = 16 * ct + 4 * g;
-                    if (c0 < L::kDkp) {
-                        u32x2 hi, lo;
-                        SPLIT_PAIR(acc[i][0], acc[i][1], hi[0], lo[0]);
-                        SPLIT_PAIR(acc[i][2], acc[i][3], hi[1], lo[1]);
-                        const int off = (16 * nt + lm) * CHS + c0;
-                        *reinterpret_cast<u32x2 *>(s_sthi + off) = hi;
-                        *reinterpret_cast<u32x2 *>(s_stlo + off) = lo;
-                    }
+                    // (state rows past dk are exactly zero and land in the zero padding of the row)
+                    static_assert(16 * NCT <= CHS, "state tiles must fit the operand row");
+                    u32x2 hi, lo;
+                    SPLIT_PAIR(acc[i][0], acc[i][1], hi[0], lo[0]);
+                    SPLIT_PAIR(acc[i][2], acc[i][3], hi[1], lo[1]);
+                    const int off = (16 * nt + lm) * CHS + 16 * ct + 4 * g;
+                    *reinterpret_cast<u32x2 *>(s_sthi + off) = hi;
+                    *reinterpret_cast<u32x2 *>(s_stlo + off) = lo;
                 }
             }
         }
-        if (tid < kChunk && chunk + 1 < nch) {
-            int s = s_begin + (chunk + 1) * kChunk + tid;
-            s_tok[((chunk + 1) & 1) * kChunk + tid] =
-                (s < s_end) ? scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w) : -1;
+        if (tid < kChunk && chunk + 2 < nch) {  // token map two chunks ahead (three buffers)
+            const int s = s_begin + (chunk + 2) * kChunk + tid;
+            s_tok[((chunk + 2) % 3) * kChunk + tid] =
+                scan_token(p.scan_dir, (s < s_end) ? s : s_begin, T, p.grid_h, p.grid_w);
         }
         __syncthreads();
 
@@ -412,9 +417,6 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
         }
         __syncthreads();
 
-        // next chunk's rows start their trip from HBM while this chunk is on the MFMA units
-        if (chunk + 1 < nch) load_chunk(chunk + 1);
-
         // ================= (c) contractions =================
         if constexpr (OUT) {
             // Q~ fragments of this wave's 16 output rows (also the B operand of A^T = K~ Q~^T)
@@ -484,8 +486,9 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
             // rows 16w + 4g + r, columns 16nt + lm
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int n_tok = tok[16 * w + 4 * g + r];
-                if (n_tok >= 0) {
+                const int row = 16 * w + 4 * g + r;
+                const int n_tok = tok[row];
+                if (row < nvalid) {
                     char *orow = gout + ((uint32_t)n_tok * (uint32_t)dv + (uint32_t)lm) * (uint32_t)sizeof(TOut);
 #pragma unroll
                     for (int nt = 0; nt < NDV16; ++nt) {
