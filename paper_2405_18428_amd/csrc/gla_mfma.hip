@@ -13,17 +13,21 @@
 // given.  The state S lives in fp32 MFMA accumulators for the whole span.
 // Exponentials run in base 2 (log_alpha is scaled by log2(e) once, before the scan).
 //
-// Work-group = 256 threads = 4 waves; per chunk:
+// A work-group has NW waves (8 for the output pass, 4 for the state-only pass); per chunk:
 //   (a) registers prefetched from HBM -> LDS: raw log_alpha / q / k / v rows (all
 //       token-major, 16- or 8-byte pieces), S_0 as bf16 hi/lo;
 //   (b) lane = token: DPP wave scan of log_alpha per channel, exp2, gating, hi/lo
-//       split, q~ and k~ written in place over the raw rows;
-//   (c) MFMA: wave w owns output rows 16w..16w+15 and a quarter of the state tiles.
+//       split, q~ and k~ written in place over the raw rows; the 4-channel units of
+//       a row are dealt to the waves round-robin, left-over channels one by one;
+//   (c) MFMA: wave w owns output rows 16(w%4)..+15, the value-column tiles of half
+//       w/4, and every NW-th state tile.
 // Operands whose contraction runs over tokens (V, and K~ in the state update) are
 // fetched from the token-major rows with ds_read_b64_tr_b16, which hands lane i of
 // a 16-lane group element i%4 of the 8 bytes read by lane 4e + i/4 (e = 0..3): 16
 // lanes reading a 4-token x 16-column block each end up with 4 tokens of one column.
 // The scan order only enters through the per-row token index in LDS.
+#include <type_traits>
+
 #include "gla_common.h"
 
 namespace gla {
@@ -36,8 +40,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kMaxExp2 = 120.f;       // clamp of -b (base 2) before exp2: keeps k~ finite
@@ -130,17 +132,26 @@ struct Layout {
     static constexpr int kBytes = kOut ? oEndOut : oEndState;
 };
 
-template <int MODE, int NDK8, int NDV16, typename TOut>
-__global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
+template <int N>
+using int_c = std::integral_constant<int, N>;
+
+// MINW = waves per SIMD the register budget must allow (4 -> 128 VGPRs, 2 -> 256 VGPRs).
+template <int MODE, int NDK8, int NDV16, int NW, int MINW, typename TOut>
+__global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     using L = Layout<MODE, NDK8, NDV16>;
     constexpr bool OUT = MODE == kModeOutput;
+    constexpr int NTHR = NW * 64;
     constexpr int CHS = L::kChStride;
     constexpr int VS = L::kVStride;
     constexpr int LAS = L::kLaStride;
     constexpr int KS = (NDK8 + 3) / 4;          // 32-channel steps of the channel contractions
     constexpr int NCT = (NDK8 + 1) / 2;         // 16-channel row tiles of the state
     constexpr int NT = NCT * NDV16;             // state tiles
-    constexpr int TPW = (NT + kWaves - 1) / kWaves;
+    constexpr int TPW = (NT + NW - 1) / NW;     // state tiles per wave
+    constexpr int NHALF = NW / 4;               // waves sharing one 16-row output tile
+    constexpr int NH = (NDV16 + NHALF - 1) / NHALF;  // value-column tiles per wave
+    static_assert(NW == 4 || NW == 8, "4 or 8 waves");
+    static_assert(16 * NCT <= CHS, "state tiles must fit the operand row");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int *s_tok = reinterpret_cast<int *>(smem + L::oTok);
@@ -183,17 +194,17 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + (size_t)bh * T * dk * 4;
     char *gout = static_cast<char *>(p.out) + (size_t)bh * T * dv * sizeof(TOut);
 
-    // ---- prologue: clear LDS (pads must read as zero), first token map ----
-    for (int i = tid; i < L::kBytes / 16; i += kThreads)
+    // ---- prologue: clear LDS (pads must read as zero), token maps of the first two chunks ----
+    for (int i = tid; i < L::kBytes / 16; i += NTHR)
         reinterpret_cast<u32x4 *>(smem)[i] = u32x4{0, 0, 0, 0};
     __syncthreads();
-    if (tid < 2 * kChunk) {  // token maps of the first two chunks
+    if (tid < 2 * kChunk) {
         const int s = s_begin + tid;
         s_tok[tid] = scan_token(p.scan_dir, (s < s_end) ? s : s_begin, T, p.grid_h, p.grid_w);
     }
     __syncthreads();
 
-    // ---- state tiles owned by this wave ----
+    // ---- state tiles owned by this wave: tile t = w + NW*i covers channels 16*(t / NDV16).., columns 16*(t % NDV16).. ----
     f32x4 acc[TPW];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -201,7 +212,7 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
         const float *s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
-            const int t = w + kWaves * i;
+            const int t = w + NW * i;
             if (t < NT) {
                 const int ct = t / NDV16, nt = t - ct * NDV16;
                 const int n = 16 * nt + lm;
@@ -215,49 +226,52 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     }
 
     // ---- which HBM pieces this thread stages (the same for every chunk) ----
-    // log_alpha: 16-byte pieces (4 channels); q, k: 8-byte pieces (4 channels); v: 16-byte pieces (8 columns)
-    const int pcs = dk >> 2;
-    constexpr int kPieces = (kChunk * NDK8 * 2 + kThreads - 1) / kThreads;
-    // Slots past the last piece repeat an earlier piece (same bytes to the same place) rather than
-    // carrying a predicate through the loop.
-    int pj[kPieces];       // row (token slot) of the piece
-    int pch[kPieces];      // first channel of the piece
-#pragma unroll
-    for (int m = 0; m < kPieces; ++m) {
-        const int idx = (tid + m * kThreads) % (kChunk * pcs);
-        pj[m] = idx / pcs;
-        pch[m] = 4 * (idx - pj[m] * pcs);
-    }
-    const int vpcs = dv >> 3;
-    constexpr int kVPieces = (kChunk * NDV16 * 2 + kThreads - 1) / kThreads;
-    int vj[kVPieces], vcol[kVPieces];
-#pragma unroll
-    for (int m = 0; m < kVPieces; ++m) {
-        const int idx = (tid + m * kThreads) % (kChunk * vpcs);
-        vj[m] = idx / vpcs;
-        vcol[m] = 8 * (idx - vj[m] * vpcs);
-    }
+    // A row of log_alpha is cut into 16-byte pieces (4 channels), a row of q or k into 8-byte pieces (the same
+    // 4 channels), a row of v into 16-byte pieces (8 columns).  Slot m of a thread is piece m*PPS + tid%PPS of
+    // row tid/PPS; pieces a row has beyond the last whole slot are dealt, one thread each, to the first waves.
+    // A slot that points past the row repeats an earlier piece (same bytes to the same place).
+    constexpr int PPS = NTHR / kChunk;                     // pieces of one row handled per slot
+    constexpr int kSlots = (NDK8 * 2) / PPS;               // whole slots at the largest dk of this instantiation
+    constexpr int kVSlots = (NDV16 * 2) / PPS;
+    const int prow = tid / PPS, psub = tid % PPS;
+    const int pcs = dk >> 2, vpcs = dv >> 3;
+    const int nslots = min(kSlots, pcs / PPS), nvslots = min(kVSlots, vpcs / PPS);
+    const int prem = pcs - nslots * PPS, vrem = vpcs - nvslots * PPS;   // left-over pieces per row (< PPS)
+    const bool has_rem = w < prem, has_vrem = w < vrem;                 // 64*rem threads = the first rem waves
+    const int rrow = has_rem ? tid / prem : 0, rch = has_rem ? 4 * (nslots * PPS + tid % prem) : 0;
+    const int vrrow = has_vrem ? tid / vrem : 0, vrcol = has_vrem ? 8 * (nvslots * PPS + tid % vrem) : 0;
     const uint32_t dk2 = 2u * (uint32_t)dk, dv2 = 2u * (uint32_t)dv;
 
-    f32x4 r_la[kPieces];
-    u32x2 r_k[kPieces];
-    u32x2 r_q[OUT ? kPieces : 1];
-    u32x4 r_v[kVPieces];
+    f32x4 r_la[kSlots + 1];
+    u32x2 r_k[kSlots + 1];
+    u32x2 r_q[OUT ? kSlots + 1 : 1];
+    u32x4 r_v[kVSlots + 1];
 
     // Rows past the end of a ragged last chunk carry the token of a valid row in s_tok (so the loads
     // stay in bounds) and are zeroed when they are written to LDS.
     auto load_chunk = [&](int chunk) {
         const int *tok = s_tok + (chunk % 3) * kChunk;
+        const uint32_t row_k = (uint32_t)tok[prow] * dk2, row_v = (uint32_t)tok[prow] * dv2;
 #pragma unroll
-        for (int m = 0; m < kPieces; ++m) {
-            const uint32_t e2 = (uint32_t)tok[pj[m]] * dk2 + 2u * (uint32_t)pch[m];
-            r_la[m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
-            r_k[m] = *reinterpret_cast<const u32x2 *>(gk + e2);
-            if constexpr (OUT) r_q[m] = *reinterpret_cast<const u32x2 *>(gq + e2);
+        for (int m = 0; m < kSlots; ++m) {
+            if (m < nslots) {
+                const uint32_t e2 = row_k + 8u * (uint32_t)(m * PPS + psub);
+                r_la[m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
+                r_k[m] = *reinterpret_cast<const u32x2 *>(gk + e2);
+                if constexpr (OUT) r_q[m] = *reinterpret_cast<const u32x2 *>(gq + e2);
+            }
+        }
+        if (has_rem) {
+            const uint32_t e2 = (uint32_t)tok[rrow] * dk2 + 2u * (uint32_t)rch;
+            r_la[kSlots] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
+            r_k[kSlots] = *reinterpret_cast<const u32x2 *>(gk + e2);
+            if constexpr (OUT) r_q[kSlots] = *reinterpret_cast<const u32x2 *>(gq + e2);
         }
 #pragma unroll
-        for (int m = 0; m < kVPieces; ++m)
-            r_v[m] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tok[vj[m]] * dv2 + 2u * (uint32_t)vcol[m]);
+        for (int m = 0; m < kVSlots; ++m)
+            if (m < nvslots) r_v[m] = *reinterpret_cast<const u32x4 *>(gv + row_v + 16u * (uint32_t)(m * PPS + psub));
+        if (has_vrem)
+            r_v[kVSlots] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tok[vrrow] * dv2 + 2u * (uint32_t)vrcol);
     };
 
     // ---- per-lane LDS offsets (bf16 elements) that do not change from chunk to chunk ----
@@ -268,6 +282,14 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     // transposing reads: this lane supplies row lm/4 (of 4 tokens) and column quad lm%4 (of 16 columns)
     const int tr_row = lm >> 2, tr_col = 4 * (lm & 3);
 
+    // ---- gate work of this wave: whole 4-channel units w, w+NW, ..., then single left-over channels ----
+    const int nunits = dk >> 2;
+    const int upw = nunits / NW;                      // units every wave owns
+    const int left0 = 4 * upw * NW;                   // first left-over channel
+    const int lpw = (dk - left0 + NW - 1) / NW;       // left-over channels per wave
+    constexpr int kMaxUnits = 16 / NW;
+    constexpr int kMaxLeft = (NW == 8) ? 4 : 3;
+
     load_chunk(0);
 
     for (int chunk = 0; chunk < nch; ++chunk) {
@@ -276,37 +298,51 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
         // ================= (a) registers -> LDS =================
         const int nvalid = min(kChunk, s_end - s_begin - chunk * kChunk);  // rows of this chunk that are tokens
         if (nvalid < kChunk) {
+            if (prow >= nvalid) {
 #pragma unroll
-            for (int m = 0; m < kPieces; ++m) {
-                if (pj[m] >= nvalid) {
+                for (int m = 0; m < kSlots; ++m) {
                     r_la[m] = f32x4{0.f, 0.f, 0.f, 0.f};
                     r_k[m] = u32x2{0, 0};
                     if constexpr (OUT) r_q[m] = u32x2{0, 0};
                 }
+#pragma unroll
+                for (int m = 0; m < kVSlots; ++m) r_v[m] = u32x4{0, 0, 0, 0};
             }
-#pragma unroll
-            for (int m = 0; m < kVPieces; ++m)
-                if (vj[m] >= nvalid) r_v[m] = u32x4{0, 0, 0, 0};
+            if (rrow >= nvalid) {
+                r_la[kSlots] = f32x4{0.f, 0.f, 0.f, 0.f};
+                r_k[kSlots] = u32x2{0, 0};
+                if constexpr (OUT) r_q[kSlots] = u32x2{0, 0};
+            }
+            if (vrrow >= nvalid) r_v[kVSlots] = u32x4{0, 0, 0, 0};
         }
 #pragma unroll
-        for (int m = 0; m < kPieces; ++m) {
-            *reinterpret_cast<f32x4 *>(s_la + pj[m] * LAS + pch[m]) = r_la[m];
-            *reinterpret_cast<u32x2 *>(s_khi + pj[m] * CHS + pch[m]) = r_k[m];
-            if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + pj[m] * CHS + pch[m]) = r_q[m];
+        for (int m = 0; m < kSlots; ++m) {
+            if (m < nslots) {
+                const int ch = 4 * (m * PPS + psub);
+                *reinterpret_cast<f32x4 *>(s_la + prow * LAS + ch) = r_la[m];
+                *reinterpret_cast<u32x2 *>(s_khi + prow * CHS + ch) = r_k[m];
+                if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + prow * CHS + ch) = r_q[m];
+            }
+        }
+        if (has_rem) {
+            *reinterpret_cast<f32x4 *>(s_la + rrow * LAS + rch) = r_la[kSlots];
+            *reinterpret_cast<u32x2 *>(s_khi + rrow * CHS + rch) = r_k[kSlots];
+            if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + rrow * CHS + rch) = r_q[kSlots];
         }
 #pragma unroll
-        for (int m = 0; m < kVPieces; ++m) *reinterpret_cast<u32x4 *>(s_v + vj[m] * VS + vcol[m]) = r_v[m];
+        for (int m = 0; m < kVSlots; ++m)
+            if (m < nvslots) *reinterpret_cast<u32x4 *>(s_v + prow * VS + 8 * (m * PPS + psub)) = r_v[m];
+        if (has_vrem) *reinterpret_cast<u32x4 *>(s_v + vrrow * VS + vrcol) = r_v[kVSlots];
         // the next chunk's rows start their trip from HBM now and land while this chunk is being computed
         if (chunk + 1 < nch) load_chunk(chunk + 1);
         if constexpr (OUT) {
             // S_0 (state entering the chunk) as bf16 hi/lo, value-column-major for the B operand
+            // (state rows past dk are exactly zero and land in the zero padding of the row)
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
-                const int t = w + kWaves * i;
+                const int t = w + NW * i;
                 if (t < NT) {
                     const int ct = t / NDV16, nt = t - ct * NDV16;
-                    // (state rows past dk are exactly zero and land in the zero padding of the row)
-                    static_assert(16 * NCT <= CHS, "state tiles must fit the operand row");
                     u32x2 hi, lo;
                     SPLIT_PAIR(acc[i][0], acc[i][1], hi[0], lo[0]);
                     SPLIT_PAIR(acc[i][2], acc[i][3], hi[1], lo[1]);
@@ -326,192 +362,187 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
         // ================= (b) gates: lane = token =================
         {
             const int j = lane;
-            const int nfull = dk >> 3;
-            // full groups of 8 channels: group index w, w+4
 #pragma unroll
-            for (int gi = 0; gi < 2; ++gi) {
-                const int kg = w + 4 * gi;
-                if (kg < nfull) {
-                    const int c0 = 8 * kg;
-                    float bb[8];
-                    {
-                        const f32x4 x0 = *reinterpret_cast<const f32x4 *>(s_la + j * LAS + c0);
-                        const f32x4 x1 = *reinterpret_cast<const f32x4 *>(s_la + j * LAS + c0 + 4);
+            for (int ui = 0; ui < kMaxUnits; ++ui) {
+                if (ui < upw) {
+                    const int c0 = 4 * (w + NW * ui);
+                    const f32x4 x = *reinterpret_cast<const f32x4 *>(s_la + j * LAS + c0);
+                    float bb[4];
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float g0 = x0[i] * kLog2e, g1 = x1[i] * kLog2e;
-                            bb[i] = wave_inclusive_scan(g0);
-                            bb[4 + i] = wave_inclusive_scan(g1);
-                        }
+                    for (int i = 0; i < 4; ++i) {
+                        const float gi = x[i] * kLog2e;
+                        bb[i] = wave_inclusive_scan(gi);
                     }
-                    const u32x4 kr = *reinterpret_cast<const u32x4 *>(s_khi + j * CHS + c0);
-                    u32x4 khi, klo;
+                    const u32x2 kr = *reinterpret_cast<const u32x2 *>(s_khi + j * CHS + c0);
+                    u32x2 khi, klo;
 #pragma unroll
-                    for (int h = 0; h < 4; ++h) {
+                    for (int h = 0; h < 2; ++h) {
                         const uint32_t kw = kr[h];
                         SPLIT_PAIR(bf16_lo_as_float(kw) * exp2_fast(fminf(-bb[2 * h], kMaxExp2)),
                                    bf16_hi_as_float(kw) * exp2_fast(fminf(-bb[2 * h + 1], kMaxExp2)),
                                    khi[h], klo[h]);
                     }
-                    *reinterpret_cast<u32x4 *>(s_khi + j * CHS + c0) = khi;
-                    *reinterpret_cast<u32x4 *>(s_klo + j * CHS + c0) = klo;
+                    *reinterpret_cast<u32x2 *>(s_khi + j * CHS + c0) = khi;
+                    *reinterpret_cast<u32x2 *>(s_klo + j * CHS + c0) = klo;
                     if constexpr (OUT) {
-                        const u32x4 qr = *reinterpret_cast<const u32x4 *>(s_qhi + j * CHS + c0);
-                        u32x4 qhi, qlo;
-                        float eq[8];
+                        const u32x2 qr = *reinterpret_cast<const u32x2 *>(s_qhi + j * CHS + c0);
+                        u32x2 qhi, qlo;
+                        float eq[4];
 #pragma unroll
-                        for (int h = 0; h < 4; ++h) {
+                        for (int h = 0; h < 2; ++h) {
                             const uint32_t qw = qr[h];
                             eq[2 * h] = exp2_fast(bb[2 * h]);
                             eq[2 * h + 1] = exp2_fast(bb[2 * h + 1]);
                             SPLIT_PAIR(bf16_lo_as_float(qw) * eq[2 * h], bf16_hi_as_float(qw) * eq[2 * h + 1],
                                        qhi[h], qlo[h]);
                         }
-                        *reinterpret_cast<u32x4 *>(s_qhi + j * CHS + c0) = qhi;
-                        *reinterpret_cast<u32x4 *>(s_qlo + j * CHS + c0) = qlo;
-                        if (lane == 63) {  // the last token's exp(b) is the chunk's total decay
+                        *reinterpret_cast<u32x2 *>(s_qhi + j * CHS + c0) = qhi;
+                        *reinterpret_cast<u32x2 *>(s_qlo + j * CHS + c0) = qlo;
+                        if (lane == 63)  // the last token's exp(b) is the chunk's total decay
                             *reinterpret_cast<f32x4 *>(s_gam + c0) = f32x4{eq[0], eq[1], eq[2], eq[3]};
-                            *reinterpret_cast<f32x4 *>(s_gam + c0 + 4) = f32x4{eq[4], eq[5], eq[6], eq[7]};
-                        }
                     } else if (lane == 63) {
                         f32x4 l0 = *reinterpret_cast<const f32x4 *>(s_lg + c0);
-                        f32x4 l1 = *reinterpret_cast<const f32x4 *>(s_lg + c0 + 4);
-                        f32x4 g0, g1;
+                        f32x4 g0;
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             g0[i] = exp2_fast(bb[i]);
-                            g1[i] = exp2_fast(bb[4 + i]);
                             l0[i] += bb[i];
-                            l1[i] += bb[4 + i];
                         }
                         *reinterpret_cast<f32x4 *>(s_gam + c0) = g0;
-                        *reinterpret_cast<f32x4 *>(s_gam + c0 + 4) = g1;
                         *reinterpret_cast<f32x4 *>(s_lg + c0) = l0;
-                        *reinterpret_cast<f32x4 *>(s_lg + c0 + 4) = l1;
                     }
                 }
             }
-            // the trailing half group (dk % 8 == 4): one channel per wave
-            if ((dk & 7) != 0) {
-                const int c = 8 * nfull + w;
-                const float b = wave_inclusive_scan(s_la[j * LAS + c] * kLog2e);
-                const float kx = bf16_bits_to_float(s_khi[j * CHS + c]) * exp2_fast(fminf(-b, kMaxExp2));
-                float qx = 0.f, e = 0.f;
-                if constexpr (OUT) {
-                    e = exp2_fast(b);
-                    qx = bf16_bits_to_float(s_qhi[j * CHS + c]) * e;
-                }
-                uint32_t h2, l2;
-                SPLIT_PAIR(kx, qx, h2, l2);
-                s_khi[j * CHS + c] = (uint16_t)(h2 & 0xffffu);
-                s_klo[j * CHS + c] = (uint16_t)(l2 & 0xffffu);
-                if constexpr (OUT) {
-                    s_qhi[j * CHS + c] = (uint16_t)(h2 >> 16);
-                    s_qlo[j * CHS + c] = (uint16_t)(l2 >> 16);
-                    if (lane == 63) s_gam[c] = e;
-                } else if (lane == 63) {
-                    s_gam[c] = exp2_fast(b);
-                    s_lg[c] += b;
+#pragma unroll
+            for (int li = 0; li < kMaxLeft; ++li) {
+                const int c = left0 + w * lpw + li;
+                if (li < lpw && c < dk) {
+                    const float b = wave_inclusive_scan(s_la[j * LAS + c] * kLog2e);
+                    const float kx = bf16_bits_to_float(s_khi[j * CHS + c]) * exp2_fast(fminf(-b, kMaxExp2));
+                    float qx = 0.f, e = 0.f;
+                    if constexpr (OUT) {
+                        e = exp2_fast(b);
+                        qx = bf16_bits_to_float(s_qhi[j * CHS + c]) * e;
+                    }
+                    uint32_t h2, l2;
+                    SPLIT_PAIR(kx, qx, h2, l2);
+                    s_khi[j * CHS + c] = (uint16_t)(h2 & 0xffffu);
+                    s_klo[j * CHS + c] = (uint16_t)(l2 & 0xffffu);
+                    if constexpr (OUT) {
+                        s_qhi[j * CHS + c] = (uint16_t)(h2 >> 16);
+                        s_qlo[j * CHS + c] = (uint16_t)(l2 >> 16);
+                        if (lane == 63) s_gam[c] = e;
+                    } else if (lane == 63) {
+                        s_gam[c] = exp2_fast(b);
+                        s_lg[c] += b;
+                    }
                 }
             }
         }
         __syncthreads();
 
         // ================= (c) contractions =================
-        if constexpr (OUT) {
-            // Q~ fragments of this wave's 16 output rows (also the B operand of A^T = K~ Q~^T)
-            u32x4 qfh[KS], qfl[KS];
+        // One straight-line body per wave index: which tiles a wave owns is then known at compile time and the
+        // LDS reads and MFMAs of different tiles can be interleaved freely.
+        auto contract = [&](auto wave_c) {
+            constexpr int W = decltype(wave_c)::value;
+            constexpr int IT = W & 3;                       // 16-row output tile of this wave
+            constexpr int NT0 = (W >> 2) * NH;              // first value-column tile of this wave
+            constexpr int NX = (NDV16 - NT0 < NH) ? NDV16 - NT0 : NH;
+            if constexpr (OUT && NX > 0) {
+                // Q~ fragments of this wave's 16 output rows
+                u32x4 qfh[KS], qfl[KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                qfh[ks] = *reinterpret_cast<const u32x4 *>(s_qhi + (16 * w + lm) * CHS + colk[ks]);
-                qfl[ks] = *reinterpret_cast<const u32x4 *>(s_qlo + (16 * w + lm) * CHS + colk[ks]);
-            }
-            // causal score tiles, transposed: lane (lm, g) ends up with A[i = 16w+lm][j = 16jt+4g+r]
-            u32x2 ph[kWaves], pl[kWaves];
-#pragma unroll
-            for (int jt = 0; jt < kWaves; ++jt) {
-                ph[jt] = u32x2{0, 0};
-                pl[jt] = u32x2{0, 0};
-                if (jt <= w) {
-                    f32x4 d = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
-                        const u32x4 kh = *reinterpret_cast<const u32x4 *>(s_khi + (16 * jt + lm) * CHS + colk[ks]);
-                        const u32x4 kl = *reinterpret_cast<const u32x4 *>(s_klo + (16 * jt + lm) * CHS + colk[ks]);
-                        d = mfma(kh, qfh[ks], d);
-                        d = mfma(kh, qfl[ks], d);
-                        d = mfma(kl, qfh[ks], d);
-                    }
-                    if (jt == w) {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            if (4 * g + r > lm) d[r] = 0.f;
-                    }
-                    SPLIT_PAIR(d[0], d[1], ph[jt][0], pl[jt][0]);
-                    SPLIT_PAIR(d[2], d[3], ph[jt][1], pl[jt][1]);
+                for (int ks = 0; ks < KS; ++ks) {
+                    qfh[ks] = *reinterpret_cast<const u32x4 *>(s_qhi + (16 * IT + lm) * CHS + colk[ks]);
+                    qfl[ks] = *reinterpret_cast<const u32x4 *>(s_qlo + (16 * IT + lm) * CHS + colk[ks]);
                 }
-            }
-            f32x4 o[NDV16];
+                // O^T tiles: lane (lm, g) accumulates o[x][r] = O[i = 16 IT + lm][n = 16 (NT0 + x) + 4g + r], i.e.
+                // four neighbouring output columns of one token per lane (one 16-byte store each)
+                f32x4 o[NX];
 #pragma unroll
-            for (int nt = 0; nt < NDV16; ++nt) o[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            // O += A V : contraction slot (g, e) of a 32-token step is token 32q + 16(e/4) + 4g + e%4
+                for (int x = 0; x < NX; ++x) o[x] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int q32 = 0; q32 < 2; ++q32) {
-                if (2 * q32 <= w) {
-                    const u32x4 ah = u32x4{ph[2 * q32][0], ph[2 * q32][1], ph[2 * q32 + 1][0], ph[2 * q32 + 1][1]};
-                    const u32x4 al = u32x4{pl[2 * q32][0], pl[2 * q32][1], pl[2 * q32 + 1][0], pl[2 * q32 + 1][1]};
-                    const uint16_t *vrow = s_v + (32 * q32 + 4 * g + tr_row) * VS + tr_col;
+                for (int q32 = 0; 2 * q32 <= IT; ++q32) {
+                    // causal score tiles jt = 2 q32, 2 q32 + 1, transposed: lane (lm, g) gets
+                    // A[i = 16 IT + lm][j = 16 jt + 4g + r]
+                    u32x2 ph[2], pl[2];
 #pragma unroll
-                    for (int nt = 0; nt < NDV16; ++nt) {
-                        const u32x2 v0 = lds_read_tr(vrow + 16 * nt);
-                        const u32x2 v1 = lds_read_tr(vrow + 16 * VS + 16 * nt);
+                    for (int u = 0; u < 2; ++u) {
+                        const int jt = 2 * q32 + u;
+                        ph[u] = u32x2{0, 0};
+                        pl[u] = u32x2{0, 0};
+                        if (jt <= IT) {
+                            f32x4 d = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int ks = 0; ks < KS; ++ks) {
+                                const u32x4 kh = *reinterpret_cast<const u32x4 *>(s_khi + (16 * jt + lm) * CHS + colk[ks]);
+                                const u32x4 kl = *reinterpret_cast<const u32x4 *>(s_klo + (16 * jt + lm) * CHS + colk[ks]);
+                                d = mfma(kh, qfh[ks], d);
+                                d = mfma(kh, qfl[ks], d);
+                                d = mfma(kl, qfh[ks], d);
+                            }
+                            if (jt == IT) {
+#pragma unroll
+                                for (int r = 0; r < 4; ++r)
+                                    if (4 * g + r > lm) d[r] = 0.f;
+                            }
+                            SPLIT_PAIR(d[0], d[1], ph[u][0], pl[u][0]);
+                            SPLIT_PAIR(d[2], d[3], ph[u][1], pl[u][1]);
+                        }
+                    }
+                    // O += A V : contraction slot (g, e) of this 32-token step is token 32 q32 + 16 (e/4) + 4g + e%4
+                    const u32x4 ah = u32x4{ph[0][0], ph[0][1], ph[1][0], ph[1][1]};
+                    const u32x4 al = u32x4{pl[0][0], pl[0][1], pl[1][0], pl[1][1]};
+                    const uint16_t *vrow = s_v + (32 * q32 + 4 * g + tr_row) * VS + tr_col + 16 * NT0;
+#pragma unroll
+                    for (int x = 0; x < NX; ++x) {
+                        const u32x2 v0 = lds_read_tr(vrow + 16 * x);
+                        const u32x2 v1 = lds_read_tr(vrow + 16 * VS + 16 * x);
                         const u32x4 b = u32x4{v0[0], v0[1], v1[0], v1[1]};
-                        o[nt] = mfma(ah, b, o[nt]);
-                        o[nt] = mfma(al, b, o[nt]);
+                        o[x] = mfma(b, ah, o[x]);
+                        o[x] = mfma(b, al, o[x]);
                     }
                 }
-            }
-            // O += Q~ S_0
+                // O += Q~ S_0
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
+                for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
-                for (int nt = 0; nt < NDV16; ++nt) {
-                    const u32x4 sh = *reinterpret_cast<const u32x4 *>(s_sthi + (16 * nt + lm) * CHS + colk[ks]);
-                    const u32x4 sl = *reinterpret_cast<const u32x4 *>(s_stlo + (16 * nt + lm) * CHS + colk[ks]);
-                    o[nt] = mfma(qfh[ks], sh, o[nt]);
-                    o[nt] = mfma(qfl[ks], sh, o[nt]);
-                    o[nt] = mfma(qfh[ks], sl, o[nt]);
+                    for (int x = 0; x < NX; ++x) {
+                        const int srow = (16 * (NT0 + x) + lm) * CHS + colk[ks];
+                        const u32x4 sh = *reinterpret_cast<const u32x4 *>(s_sthi + srow);
+                        const u32x4 sl = *reinterpret_cast<const u32x4 *>(s_stlo + srow);
+                        o[x] = mfma(sh, qfh[ks], o[x]);
+                        o[x] = mfma(sh, qfl[ks], o[x]);
+                        o[x] = mfma(sl, qfh[ks], o[x]);
+                    }
                 }
-            }
-            // rows 16w + 4g + r, columns 16nt + lm
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = 16 * w + 4 * g + r;
-                const int n_tok = tok[row];
+                const int row = 16 * IT + lm;
                 if (row < nvalid) {
-                    char *orow = gout + ((uint32_t)n_tok * (uint32_t)dv + (uint32_t)lm) * (uint32_t)sizeof(TOut);
+                    const int col0 = 16 * NT0 + 4 * g;
+                    char *orow = gout + ((uint32_t)tok[row] * (uint32_t)dv + (uint32_t)col0) * (uint32_t)sizeof(TOut);
 #pragma unroll
-                    for (int nt = 0; nt < NDV16; ++nt) {
-                        if (16 * nt + lm < dv) {
+                    for (int x = 0; x < NX; ++x) {
+                        if (col0 + 16 * x < dv) {  // dv is a multiple of 8: all four columns or none
                             if constexpr (sizeof(TOut) == 4)
-                                *reinterpret_cast<float *>(orow + 64 * nt) = o[nt][r];
+                                *reinterpret_cast<f32x4 *>(orow + 64 * x) = o[x];
                             else
-                                *reinterpret_cast<uint16_t *>(orow + 32 * nt) =
-                                    (uint16_t)(pack_bf16(o[nt][r], 0.f) & 0xffffu);
+                                *reinterpret_cast<u32x2 *>(orow + 32 * x) =
+                                    u32x2{pack_bf16(o[x][0], o[x][1]), pack_bf16(o[x][2], o[x][3])};
                         }
                     }
                 }
             }
-        }
-        // S = diag(exp(b_C)) (S + K~^T V) on the tiles this wave owns; contraction slot (g, e) of a
-        // 32-token step is token 32ks + 8g + e, fetched for K~ (A operand) and V (B operand) alike
-        {
+            // S = diag(exp(b_C)) (S + K~^T V) on the tiles this wave owns; contraction slot (g, e) of a
+            // 32-token step is token 32 ks + 8g + e, fetched for K~ (A operand) and V (B operand) alike
             const uint16_t *krow_h = s_khi + (8 * g + tr_row) * CHS + tr_col;
             const uint16_t *krow_l = s_klo + (8 * g + tr_row) * CHS + tr_col;
             const uint16_t *vrow = s_v + (8 * g + tr_row) * VS + tr_col;
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
-                const int t = w + kWaves * i;
+                constexpr int kDummy = 0;
+                (void)kDummy;
+                const int t = W + NW * i;
                 if (t < NT) {
                     const int ct = t / NDV16, nt = t - ct * NDV16;
                     f32x4 a = acc[i];
@@ -532,6 +563,16 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
                     acc[i] = a;
                 }
             }
+        };
+        switch (w) {
+        case 0: contract(int_c<0>{}); break;
+        case 1: contract(int_c<1>{}); break;
+        case 2: contract(int_c<2>{}); break;
+        case 3: contract(int_c<3>{}); break;
+        case 4: if constexpr (NW > 4) contract(int_c<4>{}); break;
+        case 5: if constexpr (NW > 4) contract(int_c<5>{}); break;
+        case 6: if constexpr (NW > 4) contract(int_c<6>{}); break;
+        default: if constexpr (NW > 4) contract(int_c<7>{}); break;
         }
         __syncthreads();
     }
@@ -545,7 +586,7 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
     if (dst != nullptr) {
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
-            const int t = w + kWaves * i;
+            const int t = w + NW * i;
             if (t < NT) {
                 const int ct = t / NDV16, nt = t - ct * NDV16;
                 const int n = 16 * nt + lm;
@@ -564,7 +605,12 @@ __global__ __launch_bounds__(kThreads) void mfma_span_kernel(Params p) {
 template <int MODE, int NDK8, int NDV16, typename TOut>
 hipError_t launch_one(const Params &p, hipStream_t stream) {
     using L = Layout<MODE, NDK8, NDV16>;
-    auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, TOut>;
+    constexpr int NW = (MODE == kModeOutput) ? 8 : 4;
+    // register cap: no tighter than the waves per SIMD that the LDS footprint lets a compute unit hold anyway
+    constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
+    constexpr int kWavesPerSimd = kGroupsPerCu * NW / 4;
+    constexpr int MINW = kWavesPerSimd >= 4 ? 4 : (kWavesPerSimd >= 2 ? 2 : 1);
+    auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, NW, MINW, TOut>;
     static bool configured = false;  // per instantiation; the attribute is per function, set once
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -572,7 +618,7 @@ hipError_t launch_one(const Params &p, hipStream_t stream) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    dim3 grid((unsigned)(p.B * p.H * p.nspans)), block(kThreads);
+    dim3 grid((unsigned)(p.B * p.H * p.nspans)), block(NW * 64);
     hipLaunchKernelGGL(kernel, grid, block, L::kBytes, stream, p);
     return hipGetLastError();
 }
