@@ -33,6 +33,22 @@ def algorithmic_flops_per_token_head(dk, dv, chunk=64):
     return 4 * dk * dv + (chunk + 1) * (dk + dv)
 
 
+def measured_traffic(config_name, kernel, args):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary (None if absent or if
+    this run does not use the configuration the summary was taken with)."""
+    if args.out_dtype != "f32" or args.scan != 0 or args.chunks_per_span != 0 or args.engine != 0:
+        return None
+    path = os.path.join(ROOT, "profiles", f"gla_fwd_{config_name}_hbm_traffic.md")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) >= 3 and parts[0] == "TRAFFIC_BYTES_PER_LAUNCH" and parts[1] == kernel:
+                return int(float(parts[2]))
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -46,6 +62,9 @@ def main():
     ap.add_argument("--engine", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy 10 times (a known-size reference for rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters); not part of the timed region")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -91,6 +110,14 @@ def main():
         gla.gla_fwd_ex(s["q"], s["k"], s["v"], s["la"], cfg.grid_h, cfg.grid_w, args.scan,
                        out=s["out"], final_state=s["fin"], workspace=s["ws"])
 
+    if args.copy_calibration:
+        src = torch.empty((256 << 20,), dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -122,7 +149,8 @@ def main():
     achieved = alg_bytes / (phase[dom] * 1e-3) / 1e9
     roofline = {
         "bound": "hbm", "kernel": names[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": measured_traffic(cfg.name, names[dom], args),
         "algorithmic_bytes": alg_bytes, "kernel_ms": round(float(phase[dom]), 5),
         "phase_ms": {n: round(float(x), 5) for n, x in zip(names + ["whole_call"], phase)},
         "whole_path_frac": round(alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
