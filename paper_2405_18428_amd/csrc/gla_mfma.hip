@@ -13,7 +13,7 @@
 // given.  The state S lives in fp32 MFMA accumulators for the whole span.
 // Exponentials run in base 2 (log_alpha is scaled by log2(e) once, before the scan).
 //
-// A work-group has NW waves (8 for the output pass, 4 for the state-only pass); per chunk:
+// A work-group has NW = 4 waves (the kernel also instantiates for 8); per chunk:
 //   (a) registers prefetched from HBM -> LDS: raw log_alpha / q / k / v rows (all
 //       token-major, 16- or 8-byte pieces), S_0 as bf16 hi/lo;
 //   (b) lane = token: DPP wave scan of log_alpha per channel, exp2, gating, hi/lo
@@ -103,10 +103,11 @@ template <int MODE, int NDK8, int NDV16>
 struct Layout {
     static constexpr int kDkp = NDK8 * 8;                                 // channels incl. padding to 8
     static constexpr int kDvp = NDV16 * 16;                               // value columns incl. padding to 16
-    // bf16 per row of the channel-major operands: a multiple of 16 channels (the state update reads 16-channel
-    // tiles) that leaves one all-zero group of 8 after the data when dk is not a multiple of 32 (lanes whose
-    // channel group lies beyond dk read that group instead of being masked); +8 skews rows across LDS banks.
-    static constexpr int kChStride = (NDK8 % 4 == 0) ? kDkp + 8 : ((kDkp + 8 + 15) / 16) * 16;
+    // bf16 per row of the channel-major operands: room for a multiple of 16 channels (the state update reads
+    // 16-channel tiles) with one all-zero group of 8 after the data when dk is not a multiple of 32 (lanes whose
+    // channel group lies beyond dk read that group instead of being masked), and an odd number of 16-byte units
+    // per row so that the 16-byte operand reads of neighbouring rows fall into different LDS banks.
+    static constexpr int kChStride = (NDK8 % 4 == 0) ? kDkp + 8 : ((kDkp + 8 + 15) / 16) * 16 + 8;
     static constexpr int kZeroCol = kDkp;                                 // first column of the all-zero group
     static constexpr int kVStride = kDvp + 8;                             // bf16 per row of V
     static constexpr int kLaStride = kDkp + 4;                            // fp32 per row of raw log_alpha
@@ -224,6 +225,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             }
         }
     }
+
+    // The start state must have landed before the chunk loop: the compiler's wait-count tracking would otherwise
+    // make every later read of `acc` wait for all outstanding loads, i.e. for the prefetch of the next chunk.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
     // ---- which HBM pieces this thread stages (the same for every chunk) ----
     // A row of log_alpha is cut into 16-byte pieces (4 channels), a row of q or k into 8-byte pieces (the same
@@ -444,78 +449,158 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
         // ================= (c) contractions =================
         // One straight-line body per wave index: which tiles a wave owns is then known at compile time and the
         // LDS reads and MFMAs of different tiles can be interleaved freely.
+        // The scheduler is fenced between batches: the LDS reads of batch k+1 are issued before the MFMAs of
+        // batch k, so one wait covers a whole batch instead of one wait per operand.
         auto contract = [&](auto wave_c) {
             constexpr int W = decltype(wave_c)::value;
             constexpr int IT = W & 3;                       // 16-row output tile of this wave
             constexpr int NT0 = (W >> 2) * NH;              // first value-column tile of this wave
             constexpr int NX = (NDV16 - NT0 < NH) ? NDV16 - NT0 : NH;
-            if constexpr (OUT && NX > 0) {
-                // Q~ fragments of this wave's 16 output rows
-                u32x4 qfh[KS], qfl[KS];
+            constexpr int NTW = (NT - W + NW - 1) / NW;     // state tiles of this wave (tiles W, W+NW, ...)
+
+            // ---- state-update operands of tile i: K~ (A operand) and V (B operand), contraction slot (g, e) of
+            // a 32-token step is token 32 ks + 8g + e for both
+            const uint16_t *krow_h = s_khi + (8 * g + tr_row) * CHS + tr_col;
+            const uint16_t *krow_l = s_klo + (8 * g + tr_row) * CHS + tr_col;
+            const uint16_t *vrow_s = s_v + (8 * g + tr_row) * VS + tr_col;
+            u32x2 ukh[2][2][2], ukl[2][2][2], uv[2][2][2];  // [buffer][ks][half]
+            auto load_state_ops = [&](int buf, int i) {
+                const int t = W + NW * i, ct = t / NDV16, nt = t - ct * NDV16;
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    qfh[ks] = *reinterpret_cast<const u32x4 *>(s_qhi + (16 * IT + lm) * CHS + colk[ks]);
-                    qfl[ks] = *reinterpret_cast<const u32x4 *>(s_qlo + (16 * IT + lm) * CHS + colk[ks]);
+                for (int ks = 0; ks < 2; ++ks) {
+                    const int ko = 32 * ks * CHS + 16 * ct, vo = 32 * ks * VS + 16 * nt;
+                    ukh[buf][ks][0] = lds_read_tr(krow_h + ko);
+                    ukh[buf][ks][1] = lds_read_tr(krow_h + ko + 4 * CHS);
+                    ukl[buf][ks][0] = lds_read_tr(krow_l + ko);
+                    ukl[buf][ks][1] = lds_read_tr(krow_l + ko + 4 * CHS);
+                    uv[buf][ks][0] = lds_read_tr(vrow_s + vo);
+                    uv[buf][ks][1] = lds_read_tr(vrow_s + vo + 4 * VS);
                 }
-                // O^T tiles: lane (lm, g) accumulates o[x][r] = O[i = 16 IT + lm][n = 16 (NT0 + x) + 4g + r], i.e.
-                // four neighbouring output columns of one token per lane (one 16-byte store each)
+            };
+            auto update_state = [&](int buf, int i) {
+                const int t = W + NW * i, ct = t / NDV16;
+                f32x4 a = acc[i];
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    const u32x4 b = u32x4{uv[buf][ks][0][0], uv[buf][ks][0][1], uv[buf][ks][1][0], uv[buf][ks][1][1]};
+                    a = mfma(u32x4{ukh[buf][ks][0][0], ukh[buf][ks][0][1], ukh[buf][ks][1][0], ukh[buf][ks][1][1]}, b, a);
+                    a = mfma(u32x4{ukl[buf][ks][0][0], ukl[buf][ks][0][1], ukl[buf][ks][1][0], ukl[buf][ks][1][1]}, b, a);
+                }
+                const f32x4 gm = *reinterpret_cast<const f32x4 *>(s_gam + 16 * ct + 4 * g);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) a[r] *= gm[r];
+                acc[i] = a;
+            };
+
+            if constexpr (OUT && NX > 0) {
+                const uint16_t *qrow_h = s_qhi + (16 * IT + lm) * CHS, *qrow_l = s_qlo + (16 * IT + lm) * CHS;
+                u32x4 qfh[KS], qfl[KS];            // Q~ fragments of this wave's 16 output rows
+                u32x4 kfh[2][KS], kfl[2][KS];      // K~ fragments of two score tiles
+                u32x2 vt[NX][2];                   // V fragments of one 32-token step
+                u32x4 sth[2][NX], stl[2][NX];      // S_0 fragments of one 32-channel step, two buffers
+                u32x2 ph[2], pl[2];                // two score tiles as bf16 hi/lo (A operand of O += A V)
                 f32x4 o[NX];
+                auto load_ktile = [&](int u, int jt) {
 #pragma unroll
-                for (int x = 0; x < NX; ++x) o[x] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int q32 = 0; 2 * q32 <= IT; ++q32) {
-                    // causal score tiles jt = 2 q32, 2 q32 + 1, transposed: lane (lm, g) gets
-                    // A[i = 16 IT + lm][j = 16 jt + 4g + r]
-                    u32x2 ph[2], pl[2];
-#pragma unroll
-                    for (int u = 0; u < 2; ++u) {
-                        const int jt = 2 * q32 + u;
-                        ph[u] = u32x2{0, 0};
-                        pl[u] = u32x2{0, 0};
-                        if (jt <= IT) {
-                            f32x4 d = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                            for (int ks = 0; ks < KS; ++ks) {
-                                const u32x4 kh = *reinterpret_cast<const u32x4 *>(s_khi + (16 * jt + lm) * CHS + colk[ks]);
-                                const u32x4 kl = *reinterpret_cast<const u32x4 *>(s_klo + (16 * jt + lm) * CHS + colk[ks]);
-                                d = mfma(kh, qfh[ks], d);
-                                d = mfma(kh, qfl[ks], d);
-                                d = mfma(kl, qfh[ks], d);
-                            }
-                            if (jt == IT) {
-#pragma unroll
-                                for (int r = 0; r < 4; ++r)
-                                    if (4 * g + r > lm) d[r] = 0.f;
-                            }
-                            SPLIT_PAIR(d[0], d[1], ph[u][0], pl[u][0]);
-                            SPLIT_PAIR(d[2], d[3], ph[u][1], pl[u][1]);
-                        }
+                    for (int ks = 0; ks < KS; ++ks) {
+                        kfh[u][ks] = *reinterpret_cast<const u32x4 *>(s_khi + (16 * jt + lm) * CHS + colk[ks]);
+                        kfl[u][ks] = *reinterpret_cast<const u32x4 *>(s_klo + (16 * jt + lm) * CHS + colk[ks]);
                     }
-                    // O += A V : contraction slot (g, e) of this 32-token step is token 32 q32 + 16 (e/4) + 4g + e%4
-                    const u32x4 ah = u32x4{ph[0][0], ph[0][1], ph[1][0], ph[1][1]};
-                    const u32x4 al = u32x4{pl[0][0], pl[0][1], pl[1][0], pl[1][1]};
+                };
+                // contraction slot (g, e) of the 32-token step q32 is token 32 q32 + 16 (e/4) + 4g + e%4
+                auto load_v = [&](int q32) {
                     const uint16_t *vrow = s_v + (32 * q32 + 4 * g + tr_row) * VS + tr_col + 16 * NT0;
 #pragma unroll
                     for (int x = 0; x < NX; ++x) {
-                        const u32x2 v0 = lds_read_tr(vrow + 16 * x);
-                        const u32x2 v1 = lds_read_tr(vrow + 16 * VS + 16 * x);
-                        const u32x4 b = u32x4{v0[0], v0[1], v1[0], v1[1]};
-                        o[x] = mfma(b, ah, o[x]);
-                        o[x] = mfma(b, al, o[x]);
+                        vt[x][0] = lds_read_tr(vrow + 16 * x);
+                        vt[x][1] = lds_read_tr(vrow + 16 * VS + 16 * x);
                     }
-                }
-                // O += Q~ S_0
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
+                };
+                auto load_st = [&](int buf, int ks) {
 #pragma unroll
                     for (int x = 0; x < NX; ++x) {
                         const int srow = (16 * (NT0 + x) + lm) * CHS + colk[ks];
-                        const u32x4 sh = *reinterpret_cast<const u32x4 *>(s_sthi + srow);
-                        const u32x4 sl = *reinterpret_cast<const u32x4 *>(s_stlo + srow);
-                        o[x] = mfma(sh, qfh[ks], o[x]);
-                        o[x] = mfma(sh, qfl[ks], o[x]);
-                        o[x] = mfma(sl, qfh[ks], o[x]);
+                        sth[buf][x] = *reinterpret_cast<const u32x4 *>(s_sthi + srow);
+                        stl[buf][x] = *reinterpret_cast<const u32x4 *>(s_stlo + srow);
                     }
+                };
+                // score tile, transposed: lane (lm, g) gets A[i = 16 IT + lm][j = 16 jt + 4g + r]
+                auto score_tile = [&](int u, int jt) {
+                    f32x4 d = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        d = mfma(kfh[u][ks], qfh[ks], d);
+                        d = mfma(kfh[u][ks], qfl[ks], d);
+                        d = mfma(kfl[u][ks], qfh[ks], d);
+                    }
+                    if (jt == IT) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (4 * g + r > lm) d[r] = 0.f;
+                    }
+                    SPLIT_PAIR(d[0], d[1], ph[u][0], pl[u][0]);
+                    SPLIT_PAIR(d[2], d[3], ph[u][1], pl[u][1]);
+                };
+                // O^T += V^T A^T : lane (lm, g) accumulates o[x][r] = O[i = 16 IT + lm][n = 16 (NT0 + x) + 4g + r]
+                auto av = [&]() {
+                    const u32x4 ah = u32x4{ph[0][0], ph[0][1], ph[1][0], ph[1][1]};
+                    const u32x4 al = u32x4{pl[0][0], pl[0][1], pl[1][0], pl[1][1]};
+#pragma unroll
+                    for (int x = 0; x < NX; ++x) {
+                        const u32x4 b = u32x4{vt[x][0][0], vt[x][0][1], vt[x][1][0], vt[x][1][1]};
+                        o[x] = mfma(b, ah, o[x]);
+                        o[x] = mfma(b, al, o[x]);
+                    }
+                };
+                auto qs = [&](int buf, int ks) {
+#pragma unroll
+                    for (int x = 0; x < NX; ++x) {
+                        o[x] = mfma(sth[buf][x], qfh[ks], o[x]);
+                        o[x] = mfma(sth[buf][x], qfl[ks], o[x]);
+                        o[x] = mfma(stl[buf][x], qfh[ks], o[x]);
+                    }
+                };
+
+#pragma unroll
+                for (int x = 0; x < NX; ++x) o[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+                ph[1] = u32x2{0, 0};
+                pl[1] = u32x2{0, 0};
+                // batch 0: Q~ and the first two score tiles' K~
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    qfh[ks] = *reinterpret_cast<const u32x4 *>(qrow_h + colk[ks]);
+                    qfl[ks] = *reinterpret_cast<const u32x4 *>(qrow_l + colk[ks]);
+                }
+                load_ktile(0, 0);
+                if constexpr (IT >= 1) load_ktile(1, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                load_v(0);
+                score_tile(0, 0);
+                if constexpr (IT >= 1) score_tile(1, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (IT >= 2) {
+                    load_ktile(0, 2);
+                    if constexpr (IT >= 3) load_ktile(1, 3);
+                    av();
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_v(1);
+                    ph[1] = u32x2{0, 0};
+                    pl[1] = u32x2{0, 0};
+                    score_tile(0, 2);
+                    if constexpr (IT >= 3) score_tile(1, 3);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                load_st(0, 0);
+                av();
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (KS > 1) load_st(1, 1);
+                else if constexpr (NTW > 0) load_state_ops(0, 0);
+                qs(0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (KS > 1) {
+                    if constexpr (NTW > 0) load_state_ops(0, 0);
+                    qs(1, 1);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
                 const int row = 16 * IT + lm;
                 if (row < nvalid) {
@@ -532,36 +617,16 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                         }
                     }
                 }
+            } else {
+                if constexpr (NTW > 0) load_state_ops(0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            // S = diag(exp(b_C)) (S + K~^T V) on the tiles this wave owns; contraction slot (g, e) of a
-            // 32-token step is token 32 ks + 8g + e, fetched for K~ (A operand) and V (B operand) alike
-            const uint16_t *krow_h = s_khi + (8 * g + tr_row) * CHS + tr_col;
-            const uint16_t *krow_l = s_klo + (8 * g + tr_row) * CHS + tr_col;
-            const uint16_t *vrow = s_v + (8 * g + tr_row) * VS + tr_col;
+            // S = diag(exp(b_C)) (S + K~^T V) on the tiles this wave owns
 #pragma unroll
-            for (int i = 0; i < TPW; ++i) {
-                constexpr int kDummy = 0;
-                (void)kDummy;
-                const int t = W + NW * i;
-                if (t < NT) {
-                    const int ct = t / NDV16, nt = t - ct * NDV16;
-                    f32x4 a = acc[i];
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks) {
-                        const int ko = 32 * ks * CHS + 16 * ct;
-                        const u32x2 h0 = lds_read_tr(krow_h + ko), h1 = lds_read_tr(krow_h + ko + 4 * CHS);
-                        const u32x2 l0 = lds_read_tr(krow_l + ko), l1 = lds_read_tr(krow_l + ko + 4 * CHS);
-                        const int vo = 32 * ks * VS + 16 * nt;
-                        const u32x2 v0 = lds_read_tr(vrow + vo), v1 = lds_read_tr(vrow + vo + 4 * VS);
-                        const u32x4 b = u32x4{v0[0], v0[1], v1[0], v1[1]};
-                        a = mfma(u32x4{h0[0], h0[1], h1[0], h1[1]}, b, a);
-                        a = mfma(u32x4{l0[0], l0[1], l1[0], l1[1]}, b, a);
-                    }
-                    const f32x4 gm = *reinterpret_cast<const f32x4 *>(s_gam + 16 * ct + 4 * g);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) a[r] *= gm[r];
-                    acc[i] = a;
-                }
+            for (int i = 0; i < NTW; ++i) {
+                if (i + 1 < NTW) load_state_ops((i + 1) & 1, i + 1);
+                update_state(i & 1, i);
+                __builtin_amdgcn_sched_barrier(0);
             }
         };
         switch (w) {
@@ -605,7 +670,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
 template <int MODE, int NDK8, int NDV16, typename TOut>
 hipError_t launch_one(const Params &p, hipStream_t stream) {
     using L = Layout<MODE, NDK8, NDV16>;
-    constexpr int NW = (MODE == kModeOutput) ? 8 : 4;
+    constexpr int NW = 4;  // 8 is supported by the kernel but leaves too few registers for the operand batches
     // register cap: no tighter than the waves per SIMD that the LDS footprint lets a compute unit hold anyway
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int kWavesPerSimd = kGroupsPerCu * NW / 4;
