@@ -51,15 +51,16 @@ int validate(const void *q, const void *k, const void *v, const float *log_alpha
 }
 
 // Chooses how many 64-token chunks one work-group walks.  Long spans amortise
-// the state traffic of phases 1-3 (about 4 * dk * dv * 4 bytes per span) but
-// leave fewer work-groups for the 256 compute units.
+// the state traffic of phases 1-3 (about 4 * dk * dv * 4 bytes per span) and the
+// per-work-group prologue; short spans give the 256 compute units more
+// work-groups.  Two resident work-groups per compute unit is the sweet spot
+// measured on MI355X for the output pass.
 int plan_chunks_per_span(int bh, int nchunks) {
     int cps = g_opt_chunks_per_span;
     if (cps <= 0) {
-        const long long target_groups = 1024;
+        const long long target_groups = 512;
         cps = (int)(((long long)bh * nchunks) / target_groups);
         if (cps < 1) cps = 1;
-        if (cps == 1 && nchunks >= 2 && (long long)bh * nchunks >= 512) cps = 2;
     }
     if (cps > nchunks) cps = nchunks;
     return cps;

@@ -5,50 +5,85 @@
 // Sec. 3.1 Eq. (attn_gla) is linear in S, the state entering span r+1 is
 //     S_start(r+1) = diag(Gamma_r) S_start(r) + U_r ,   S_start(0) = 0.
 // Each of the dk*dv state elements is an independent scalar recurrence over the
-// spans, so one thread carries one element; the buffer is rewritten in place
-// (U_r becomes S_start(r)) and the value after the last span is the final state.
+// spans; the buffer is rewritten in place (U_r becomes S_start(r)) and the value
+// after the last span is the final state.
+//
+// The kernel is bound by the latency of its loads, so the spans of one element
+// are cut into kGroups runs handled by kGroups threads: each thread loads its
+// whole run at once, composes it (product of the Gammas, state from zero),
+// the runs are chained through LDS, and each thread then replays its run from
+// its true start state.
 #include "gla_common.h"
 
 namespace gla {
 namespace {
 
-constexpr int kCarryThreads = 256;
-
-constexpr int kBatch = 32;  // spans whose loads are in flight together
+constexpr int kElems = 64;    // state elements per work-group (one wave wide: coalesced rows)
+constexpr int kGroups = 4;    // runs of spans per element
+constexpr int kRun = 16;      // spans per run and pass
+constexpr int kCarryThreads = kElems * kGroups;
 
 __global__ __launch_bounds__(kCarryThreads) void carry_kernel(Params p) {
+    __shared__ float s_gam[kGroups][kElems];
+    __shared__ float s_u[kGroups][kElems];
+
     const int bh = blockIdx.y;
-    const int e = blockIdx.x * kCarryThreads + threadIdx.x;
+    const int el = threadIdx.x % kElems;
+    const int grp = threadIdx.x / kElems;
     const int ne = p.dk * p.dv;
-    if (e >= ne) return;
+    const int e = min(blockIdx.x * kElems + el, ne - 1);  // threads past the end repeat the last element
+    const bool writer = blockIdx.x * kElems + el < ne;
     const int c = e / p.dv;
     float *st = p.ws_state + (size_t)bh * p.nspans * ne + e;
     const float *lg = p.ws_lgam + (size_t)bh * p.nspans * p.dk + c;
-    float s = 0.f;
-    for (int r0 = 0; r0 < p.nspans; r0 += kBatch) {
-        // all loads of a batch are issued before the first dependent multiply-add
-        float u[kBatch], gl[kBatch];
+
+    float carry = 0.f;  // state entering the current pass of kGroups * kRun spans
+    for (int r0 = 0; r0 < p.nspans; r0 += kGroups * kRun) {
+        const int first = r0 + grp * kRun;
+        float u[kRun], gam[kRun];
 #pragma unroll
-        for (int i = 0; i < kBatch; ++i) {
-            const int r = min(r0 + i, p.nspans - 1);
-            u[i] = st[(size_t)r * ne];
-            gl[i] = lg[(size_t)r * p.dk];
+        for (int i = 0; i < kRun; ++i) {
+            const int r = first + i;
+            const bool ok = r < p.nspans;
+            u[i] = ok ? st[(size_t)r * ne] : 0.f;
+            gam[i] = ok ? expf(lg[(size_t)r * p.dk]) : 1.f;
         }
+        // the run composed from a zero state
+        float gprod = 1.f, ulocal = 0.f;
 #pragma unroll
-        for (int i = 0; i < kBatch; ++i) {
-            if (r0 + i < p.nspans) {
-                st[(size_t)(r0 + i) * ne] = s;
-                s = fmaf(expf(gl[i]), s, u[i]);
+        for (int i = 0; i < kRun; ++i) {
+            ulocal = fmaf(gam[i], ulocal, u[i]);
+            gprod *= gam[i];
+        }
+        s_gam[grp][el] = gprod;
+        s_u[grp][el] = ulocal;
+        __syncthreads();
+        // state entering this thread's run, and the state after the whole pass
+        float s = carry, pass_end = carry;
+#pragma unroll
+        for (int q = 0; q < kGroups; ++q) {
+            const float gq = s_gam[q][el], uq = s_u[q][el];
+            if (q < grp) s = fmaf(gq, s, uq);
+            pass_end = fmaf(gq, pass_end, uq);
+        }
+        carry = pass_end;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kRun; ++i) {
+            const int r = first + i;
+            if (r < p.nspans) {
+                if (writer) st[(size_t)r * ne] = s;
+                s = fmaf(gam[i], s, u[i]);
             }
         }
     }
-    if (p.final_state != nullptr) p.final_state[(size_t)bh * ne + e] = s;
+    if (p.final_state != nullptr && writer && grp == 0) p.final_state[(size_t)bh * ne + e] = carry;
 }
 
 }  // namespace
 
 hipError_t launch_carry(const Params &p, hipStream_t stream) {
-    dim3 grid((unsigned)((p.dk * p.dv + kCarryThreads - 1) / kCarryThreads), (unsigned)(p.B * p.H));
+    dim3 grid((unsigned)((p.dk * p.dv + kElems - 1) / kElems), (unsigned)(p.B * p.H));
     hipLaunchKernelGGL(carry_kernel, grid, dim3(kCarryThreads), 0, stream, p);
     return hipGetLastError();
 }

@@ -17,10 +17,10 @@
 //   (a) registers prefetched from HBM -> LDS: raw log_alpha / q / k / v rows (all
 //       token-major, 16- or 8-byte pieces), S_0 as bf16 hi/lo;
 //   (b) lane = token: DPP wave scan of log_alpha per channel, exp2, gating, hi/lo
-//       split, q~ and k~ written in place over the raw rows; the 4-channel units of
+//       split, q~ and k~ written in place over the raw rows; the 8-channel units of
 //       a row are dealt to the waves round-robin, left-over channels one by one;
-//   (c) MFMA: wave w owns output rows 16(w%4)..+15, the value-column tiles of half
-//       w/4, and every NW-th state tile.
+//   (c) MFMA: wave w owns output rows 16(w%4)..+15 (with 8 waves: the value-column tiles
+//       of half w/4) and the state tiles of one 16-channel row tile (shared K~ operand).
 // Operands whose contraction runs over tokens (V, and K~ in the state update) are
 // fetched from the token-major rows with ds_read_b64_tr_b16, which hands lane i of
 // a 16-lane group element i%4 of the 8 bytes read by lane 4e + i/4 (e = 0..3): 16
@@ -136,6 +136,27 @@ struct Layout {
 template <int N>
 using int_c = std::integral_constant<int, N>;
 
+// Which 16x16 tile of the dk x dv state is the i-th tile of wave w.  The output pass gives a wave the tiles of one
+// 16-channel row tile (its K~ operand is then read once, and the wave with the most score tiles owns none); the
+// state-only pass has nothing else to balance against and deals the tiles round-robin.
+template <bool ROW_OWNED, int NW, int NCT, int NDV16>
+struct TileMap {
+    static constexpr int WPC = (NW / NCT) > 0 ? NW / NCT : 1;  // waves sharing a row tile
+    static constexpr int kPerWave = ROW_OWNED ? (NDV16 + WPC - 1) / WPC : (NCT * NDV16 + NW - 1) / NW;
+    __host__ __device__ static constexpr int ct(int w, int i) { return ROW_OWNED ? w / WPC : (w + NW * i) / NDV16; }
+    __host__ __device__ static constexpr int nt(int w, int i) {
+        return ROW_OWNED ? (w % WPC) + WPC * i : (w + NW * i) % NDV16;
+    }
+    __host__ __device__ static constexpr bool valid(int w, int i) {
+        return ROW_OWNED ? (w / WPC < NCT && (w % WPC) + WPC * i < NDV16) : (w + NW * i < NCT * NDV16);
+    }
+    __host__ __device__ static constexpr int count(int w) {
+        int n = 0;
+        for (int i = 0; i < kPerWave; ++i) n += valid(w, i) ? 1 : 0;
+        return n;
+    }
+};
+
 // MINW = waves per SIMD the register budget must allow (4 -> 128 VGPRs, 2 -> 256 VGPRs).
 template <int MODE, int NDK8, int NDV16, int NW, int MINW, typename TOut>
 __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
@@ -147,8 +168,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     constexpr int LAS = L::kLaStride;
     constexpr int KS = (NDK8 + 3) / 4;          // 32-channel steps of the channel contractions
     constexpr int NCT = (NDK8 + 1) / 2;         // 16-channel row tiles of the state
-    constexpr int NT = NCT * NDV16;             // state tiles
-    constexpr int TPW = (NT + NW - 1) / NW;     // state tiles per wave
+    using TM = TileMap<OUT, NW, NCT, NDV16>;
+    constexpr int TPW = TM::kPerWave;           // state tiles per wave
     constexpr int NHALF = NW / 4;               // waves sharing one 16-row output tile
     constexpr int NH = (NDV16 + NHALF - 1) / NHALF;  // value-column tiles per wave
     static_assert(NW == 4 || NW == 8, "4 or 8 waves");
@@ -205,7 +226,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     }
     __syncthreads();
 
-    // ---- state tiles owned by this wave: tile t = w + NW*i covers channels 16*(t / NDV16).., columns 16*(t % NDV16).. ----
+    // ---- state tiles owned by this wave (TileMap) ----
     f32x4 acc[TPW];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -213,19 +234,16 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
         const float *s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
-            const int t = w + NW * i;
-            if (t < NT) {
-                const int ct = t / NDV16, nt = t - ct * NDV16;
-                const int n = 16 * nt + lm;
+            if (TM::valid(w, i)) {
+                const int n = 16 * TM::nt(w, i) + lm;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int c = 16 * ct + 4 * g + r;
+                    const int c = 16 * TM::ct(w, i) + 4 * g + r;
                     if (c < dk && n < dv) acc[i][r] = s0[c * dv + n];
                 }
             }
         }
     }
-
     // The start state must have landed before the chunk loop: the compiler's wait-count tracking would otherwise
     // make every later read of `acc` wait for all outstanding loads, i.e. for the prefetch of the next chunk.
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
@@ -287,13 +305,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     // transposing reads: this lane supplies row lm/4 (of 4 tokens) and column quad lm%4 (of 16 columns)
     const int tr_row = lm >> 2, tr_col = 4 * (lm & 3);
 
-    // ---- gate work of this wave: whole 4-channel units w, w+NW, ..., then single left-over channels ----
-    const int nunits = dk >> 2;
+    // ---- gate work of this wave: whole UW-channel units w, w+NW, ..., then single left-over channels ----
+    constexpr int UW = 32 / NW;                       // channels per unit: 16-byte LDS rows accesses for 4 waves
+    const int nunits = dk / UW;
     const int upw = nunits / NW;                      // units every wave owns
-    const int left0 = 4 * upw * NW;                   // first left-over channel
+    const int left0 = UW * upw * NW;                  // first left-over channel
     const int lpw = (dk - left0 + NW - 1) / NW;       // left-over channels per wave
-    constexpr int kMaxUnits = 16 / NW;
-    constexpr int kMaxLeft = (NW == 8) ? 4 : 3;
+    constexpr int kMaxUnits = kMaxDk / (UW * NW);
+    constexpr int kMaxLeft = (UW * NW - 4 + NW - 1) / NW;
 
     load_chunk(0);
 
@@ -345,13 +364,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             // (state rows past dk are exactly zero and land in the zero padding of the row)
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
-                const int t = w + NW * i;
-                if (t < NT) {
-                    const int ct = t / NDV16, nt = t - ct * NDV16;
+                if (TM::valid(w, i)) {
                     u32x2 hi, lo;
                     SPLIT_PAIR(acc[i][0], acc[i][1], hi[0], lo[0]);
                     SPLIT_PAIR(acc[i][2], acc[i][3], hi[1], lo[1]);
-                    const int off = (16 * nt + lm) * CHS + 16 * ct + 4 * g;
+                    const int off = (16 * TM::nt(w, i) + lm) * CHS + 16 * TM::ct(w, i) + 4 * g;
                     *reinterpret_cast<u32x2 *>(s_sthi + off) = hi;
                     *reinterpret_cast<u32x2 *>(s_stlo + off) = lo;
                 }
@@ -370,51 +387,74 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
 #pragma unroll
             for (int ui = 0; ui < kMaxUnits; ++ui) {
                 if (ui < upw) {
-                    const int c0 = 4 * (w + NW * ui);
-                    const f32x4 x = *reinterpret_cast<const f32x4 *>(s_la + j * LAS + c0);
-                    float bb[4];
+                    const int c0 = UW * (w + NW * ui);
+                    float bb[UW];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float gi = x[i] * kLog2e;
-                        bb[i] = wave_inclusive_scan(gi);
-                    }
-                    const u32x2 kr = *reinterpret_cast<const u32x2 *>(s_khi + j * CHS + c0);
-                    u32x2 khi, klo;
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const uint32_t kw = kr[h];
-                        SPLIT_PAIR(bf16_lo_as_float(kw) * exp2_fast(fminf(-bb[2 * h], kMaxExp2)),
-                                   bf16_hi_as_float(kw) * exp2_fast(fminf(-bb[2 * h + 1], kMaxExp2)),
-                                   khi[h], klo[h]);
-                    }
-                    *reinterpret_cast<u32x2 *>(s_khi + j * CHS + c0) = khi;
-                    *reinterpret_cast<u32x2 *>(s_klo + j * CHS + c0) = klo;
-                    if constexpr (OUT) {
-                        const u32x2 qr = *reinterpret_cast<const u32x2 *>(s_qhi + j * CHS + c0);
-                        u32x2 qhi, qlo;
-                        float eq[4];
-#pragma unroll
-                        for (int h = 0; h < 2; ++h) {
-                            const uint32_t qw = qr[h];
-                            eq[2 * h] = exp2_fast(bb[2 * h]);
-                            eq[2 * h + 1] = exp2_fast(bb[2 * h + 1]);
-                            SPLIT_PAIR(bf16_lo_as_float(qw) * eq[2 * h], bf16_hi_as_float(qw) * eq[2 * h + 1],
-                                       qhi[h], qlo[h]);
-                        }
-                        *reinterpret_cast<u32x2 *>(s_qhi + j * CHS + c0) = qhi;
-                        *reinterpret_cast<u32x2 *>(s_qlo + j * CHS + c0) = qlo;
-                        if (lane == 63)  // the last token's exp(b) is the chunk's total decay
-                            *reinterpret_cast<f32x4 *>(s_gam + c0) = f32x4{eq[0], eq[1], eq[2], eq[3]};
-                    } else if (lane == 63) {
-                        f32x4 l0 = *reinterpret_cast<const f32x4 *>(s_lg + c0);
-                        f32x4 g0;
+                    for (int v4 = 0; v4 < UW / 4; ++v4) {
+                        const f32x4 x = *reinterpret_cast<const f32x4 *>(s_la + j * LAS + c0 + 4 * v4);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            g0[i] = exp2_fast(bb[i]);
-                            l0[i] += bb[i];
+                            const float gi = x[i] * kLog2e;
+                            bb[4 * v4 + i] = wave_inclusive_scan(gi);
                         }
-                        *reinterpret_cast<f32x4 *>(s_gam + c0) = g0;
-                        *reinterpret_cast<f32x4 *>(s_lg + c0) = l0;
+                    }
+                    uint32_t kr[UW / 2], khi[UW / 2], klo[UW / 2];
+#pragma unroll
+                    for (int v2 = 0; v2 < UW / 4; ++v2) {
+                        const u32x2 t = *reinterpret_cast<const u32x2 *>(s_khi + j * CHS + c0 + 4 * v2);
+                        kr[2 * v2] = t[0];
+                        kr[2 * v2 + 1] = t[1];
+                    }
+#pragma unroll
+                    for (int h = 0; h < UW / 2; ++h)
+                        SPLIT_PAIR(bf16_lo_as_float(kr[h]) * exp2_fast(fminf(-bb[2 * h], kMaxExp2)),
+                                   bf16_hi_as_float(kr[h]) * exp2_fast(fminf(-bb[2 * h + 1], kMaxExp2)),
+                                   khi[h], klo[h]);
+#pragma unroll
+                    for (int v2 = 0; v2 < UW / 4; ++v2) {
+                        *reinterpret_cast<u32x2 *>(s_khi + j * CHS + c0 + 4 * v2) = u32x2{khi[2 * v2], khi[2 * v2 + 1]};
+                        *reinterpret_cast<u32x2 *>(s_klo + j * CHS + c0 + 4 * v2) = u32x2{klo[2 * v2], klo[2 * v2 + 1]};
+                    }
+                    if constexpr (OUT) {
+                        uint32_t qr[UW / 2], qhi[UW / 2], qlo[UW / 2];
+                        float eq[UW];
+#pragma unroll
+                        for (int v2 = 0; v2 < UW / 4; ++v2) {
+                            const u32x2 t = *reinterpret_cast<const u32x2 *>(s_qhi + j * CHS + c0 + 4 * v2);
+                            qr[2 * v2] = t[0];
+                            qr[2 * v2 + 1] = t[1];
+                        }
+#pragma unroll
+                        for (int h = 0; h < UW / 2; ++h) {
+                            eq[2 * h] = exp2_fast(bb[2 * h]);
+                            eq[2 * h + 1] = exp2_fast(bb[2 * h + 1]);
+                            SPLIT_PAIR(bf16_lo_as_float(qr[h]) * eq[2 * h], bf16_hi_as_float(qr[h]) * eq[2 * h + 1],
+                                       qhi[h], qlo[h]);
+                        }
+#pragma unroll
+                        for (int v2 = 0; v2 < UW / 4; ++v2) {
+                            *reinterpret_cast<u32x2 *>(s_qhi + j * CHS + c0 + 4 * v2) = u32x2{qhi[2 * v2], qhi[2 * v2 + 1]};
+                            *reinterpret_cast<u32x2 *>(s_qlo + j * CHS + c0 + 4 * v2) = u32x2{qlo[2 * v2], qlo[2 * v2 + 1]};
+                        }
+                        if (lane == 63) {  // the last token's exp(b) is the chunk's total decay
+#pragma unroll
+                            for (int v4 = 0; v4 < UW / 4; ++v4)
+                                *reinterpret_cast<f32x4 *>(s_gam + c0 + 4 * v4) =
+                                    f32x4{eq[4 * v4], eq[4 * v4 + 1], eq[4 * v4 + 2], eq[4 * v4 + 3]};
+                        }
+                    } else if (lane == 63) {
+#pragma unroll
+                        for (int v4 = 0; v4 < UW / 4; ++v4) {
+                            f32x4 l0 = *reinterpret_cast<const f32x4 *>(s_lg + c0 + 4 * v4);
+                            f32x4 g0;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                g0[i] = exp2_fast(bb[4 * v4 + i]);
+                                l0[i] += bb[4 * v4 + i];
+                            }
+                            *reinterpret_cast<f32x4 *>(s_gam + c0 + 4 * v4) = g0;
+                            *reinterpret_cast<f32x4 *>(s_lg + c0 + 4 * v4) = l0;
+                        }
                     }
                 }
             }
@@ -456,40 +496,51 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             constexpr int IT = W & 3;                       // 16-row output tile of this wave
             constexpr int NT0 = (W >> 2) * NH;              // first value-column tile of this wave
             constexpr int NX = (NDV16 - NT0 < NH) ? NDV16 - NT0 : NH;
-            constexpr int NTW = (NT - W + NW - 1) / NW;     // state tiles of this wave (tiles W, W+NW, ...)
+            constexpr int NTW = TM::count(W);               // state tiles of this wave
 
-            // ---- state-update operands of tile i: K~ (A operand) and V (B operand), contraction slot (g, e) of
-            // a 32-token step is token 32 ks + 8g + e for both
+            // ---- state-update operands: K~ (A operand) and V (B operand); contraction slot (g, e) of a 32-token
+            // step is token 32 ks + 8g + e for both.  With row-owned tiles the K~ operand is read once per chunk.
             const uint16_t *krow_h = s_khi + (8 * g + tr_row) * CHS + tr_col;
             const uint16_t *krow_l = s_klo + (8 * g + tr_row) * CHS + tr_col;
             const uint16_t *vrow_s = s_v + (8 * g + tr_row) * VS + tr_col;
-            u32x2 ukh[2][2][2], ukl[2][2][2], uv[2][2][2];  // [buffer][ks][half]
-            auto load_state_ops = [&](int buf, int i) {
-                const int t = W + NW * i, ct = t / NDV16, nt = t - ct * NDV16;
+            constexpr int KB = OUT ? 1 : 2;                 // K~ buffers: shared, or one per tile in flight
+            u32x2 ukh[KB][2][2], ukl[KB][2][2];             // [buffer][ks][half]
+            u32x2 uv[2][2][2];                              // [buffer][ks][half]
+            auto load_state_k = [&](int buf, int i) {
+                const int ko = 16 * TM::ct(W, i);
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
-                    const int ko = 32 * ks * CHS + 16 * ct, vo = 32 * ks * VS + 16 * nt;
-                    ukh[buf][ks][0] = lds_read_tr(krow_h + ko);
-                    ukh[buf][ks][1] = lds_read_tr(krow_h + ko + 4 * CHS);
-                    ukl[buf][ks][0] = lds_read_tr(krow_l + ko);
-                    ukl[buf][ks][1] = lds_read_tr(krow_l + ko + 4 * CHS);
-                    uv[buf][ks][0] = lds_read_tr(vrow_s + vo);
-                    uv[buf][ks][1] = lds_read_tr(vrow_s + vo + 4 * VS);
+                    ukh[buf][ks][0] = lds_read_tr(krow_h + 32 * ks * CHS + ko);
+                    ukh[buf][ks][1] = lds_read_tr(krow_h + 32 * ks * CHS + ko + 4 * CHS);
+                    ukl[buf][ks][0] = lds_read_tr(krow_l + 32 * ks * CHS + ko);
+                    ukl[buf][ks][1] = lds_read_tr(krow_l + 32 * ks * CHS + ko + 4 * CHS);
+                }
+            };
+            auto load_state_ops = [&](int buf, int i) {
+                if (!OUT || i == 0) load_state_k(OUT ? 0 : buf, i);
+                const int vo = 16 * TM::nt(W, i);
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    uv[buf][ks][0] = lds_read_tr(vrow_s + 32 * ks * VS + vo);
+                    uv[buf][ks][1] = lds_read_tr(vrow_s + 32 * ks * VS + vo + 4 * VS);
                 }
             };
             auto update_state = [&](int buf, int i) {
-                const int t = W + NW * i, ct = t / NDV16;
+                const int kb = OUT ? 0 : buf;
                 f32x4 a = acc[i];
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const u32x4 b = u32x4{uv[buf][ks][0][0], uv[buf][ks][0][1], uv[buf][ks][1][0], uv[buf][ks][1][1]};
-                    a = mfma(u32x4{ukh[buf][ks][0][0], ukh[buf][ks][0][1], ukh[buf][ks][1][0], ukh[buf][ks][1][1]}, b, a);
-                    a = mfma(u32x4{ukl[buf][ks][0][0], ukl[buf][ks][0][1], ukl[buf][ks][1][0], ukl[buf][ks][1][1]}, b, a);
+                    a = mfma(u32x4{ukh[kb][ks][0][0], ukh[kb][ks][0][1], ukh[kb][ks][1][0], ukh[kb][ks][1][1]}, b, a);
+                    a = mfma(u32x4{ukl[kb][ks][0][0], ukl[kb][ks][0][1], ukl[kb][ks][1][0], ukl[kb][ks][1][1]}, b, a);
                 }
-                const f32x4 gm = *reinterpret_cast<const f32x4 *>(s_gam + 16 * ct + 4 * g);
+                const f32x4 gm = *reinterpret_cast<const f32x4 *>(s_gam + 16 * TM::ct(W, i) + 4 * g);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) a[r] *= gm[r];
                 acc[i] = a;
+            };
+            auto load_state_first = [&]() {
+                if constexpr (NTW > 0) load_state_ops(0, 0);
             };
 
             if constexpr (OUT && NX > 0) {
@@ -594,11 +645,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 av();
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (KS > 1) load_st(1, 1);
-                else if constexpr (NTW > 0) load_state_ops(0, 0);
+                else load_state_first();
                 qs(0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (KS > 1) {
-                    if constexpr (NTW > 0) load_state_ops(0, 0);
+                    load_state_first();
                     qs(1, 1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -618,7 +669,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     }
                 }
             } else {
-                if constexpr (NTW > 0) load_state_ops(0, 0);
+                load_state_first();
                 __builtin_amdgcn_sched_barrier(0);
             }
             // S = diag(exp(b_C)) (S + K~^T V) on the tiles this wave owns
@@ -651,13 +702,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     if (dst != nullptr) {
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
-            const int t = w + NW * i;
-            if (t < NT) {
-                const int ct = t / NDV16, nt = t - ct * NDV16;
-                const int n = 16 * nt + lm;
+            if (TM::valid(w, i)) {
+                const int n = 16 * TM::nt(w, i) + lm;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int c = 16 * ct + 4 * g + r;
+                    const int c = 16 * TM::ct(w, i) + 4 * g + r;
                     if (c < dk && n < dv) dst[c * dv + n] = acc[i][r];
                 }
             }
