@@ -77,13 +77,23 @@ typedef enum { GLA_DT_F32 = 0, GLA_DT_BF16 = 1 } gla_dtype;
 /* Options for gla_set_option (process-wide, meant for tuning and tests). */
 typedef enum {
     GLA_OPT_CHUNKS_PER_SPAN = 0, /* 0 = choose automatically; n > 0 = n 64-token chunks per work-group */
-    GLA_OPT_ENGINE = 1           /* gla_engine */
+    GLA_OPT_ENGINE = 1,          /* gla_engine */
+    GLA_OPT_CARRY = 2            /* gla_carry */
 } gla_option;
 typedef enum {
-    GLA_ENGINE_AUTO = 0,      /* bf16 inputs with dk % 4 == 0 and dv % 2 == 0 -> MFMA, else recurrent */
+    GLA_ENGINE_AUTO = 0,      /* bf16 inputs with dk % 4 == 0 and dv % 8 == 0 -> MFMA, else recurrent */
     GLA_ENGINE_RECURRENT = 1, /* fp32 token-by-token arithmetic inside each span; any dtype, any gates */
     GLA_ENGINE_MFMA = 2       /* bf16 MFMA chunk form (Sec. 3.5); bf16 inputs only */
 } gla_engine;
+
+/* Where the states of the spans of one (batch, head) are chained, S_start(r+1) = diag(Gamma_r) S_start(r) + U_r
+ * (the recurrence of Eq. (attn_gla) applied span by span). */
+typedef enum {
+    GLA_CARRY_AUTO = 0,          /* in the output pass when the MFMA engine runs with at most 64 spans per head */
+    GLA_CARRY_KERNEL = 1,        /* a kernel of its own between the two passes */
+    GLA_CARRY_IN_OUTPUT_PASS = 2 /* each output work-group chains the local states before its span, whatever the
+                                    span count (the recurrent engine has no such path and keeps the kernel) */
+} gla_carry;
 
 typedef void *gla_stream_t; /* a hipStream_t */
 

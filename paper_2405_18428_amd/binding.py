@@ -13,7 +13,8 @@ from typing import List, Optional
 
 SCAN_ROW_FWD, SCAN_ROW_REV, SCAN_COL_FWD, SCAN_COL_REV = 0, 1, 2, 3
 DT_F32, DT_BF16 = 0, 1
-OPT_CHUNKS_PER_SPAN, OPT_ENGINE = 0, 1
+OPT_CHUNKS_PER_SPAN, OPT_ENGINE, OPT_CARRY = 0, 1, 2
+CARRY_AUTO, CARRY_KERNEL, CARRY_IN_OUTPUT_PASS = 0, 1, 2
 ENGINE_AUTO, ENGINE_RECURRENT, ENGINE_MFMA = 0, 1, 2
 
 _PKG = os.path.dirname(os.path.abspath(__file__))

@@ -12,6 +12,11 @@ constexpr int kVersion = 100;  // 0.1.0
 
 int g_opt_chunks_per_span = 0;
 int g_opt_engine = GLA_ENGINE_AUTO;
+int g_opt_carry = GLA_CARRY_AUTO;
+
+// Most spans per (batch, head) that the output pass chains by itself: work-group r reads the r local states
+// before it, so the reads grow with the square of the span count while a carry kernel's grow linearly.
+constexpr int kMaxChainedSpans = 64;
 
 struct Scratch {
     void *ptr = nullptr;
@@ -111,6 +116,10 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
         if (events) (void)hipEventRecord(events->ev[i], stream);
     };
 
+    p.chain_in_output = use_mfma && p.nspans > 1 &&
+                        (g_opt_carry == GLA_CARRY_IN_OUTPUT_PASS ||
+                         (g_opt_carry == GLA_CARRY_AUTO && p.nspans <= kMaxChainedSpans));
+
     hipError_t e = hipSuccess;
     mark(0);
     if (p.nspans > 1) {
@@ -118,7 +127,7 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
         if (e != hipSuccess) return GLA_ERR_HIP;
     }
     mark(1);
-    if (p.nspans > 1) {
+    if (p.nspans > 1 && !p.chain_in_output) {
         e = launch_carry(p, stream);
         if (e != hipSuccess) return GLA_ERR_HIP;
     }
@@ -234,6 +243,10 @@ int gla_set_option(int option, int value) {
         if (value < GLA_ENGINE_AUTO || value > GLA_ENGINE_MFMA) return GLA_ERR_SHAPE;
         g_opt_engine = value;
         return GLA_OK;
+    case GLA_OPT_CARRY:
+        if (value < GLA_CARRY_AUTO || value > GLA_CARRY_IN_OUTPUT_PASS) return GLA_ERR_SHAPE;
+        g_opt_carry = value;
+        return GLA_OK;
     default:
         return GLA_ERR_SHAPE;
     }
@@ -243,6 +256,7 @@ int gla_get_option(int option) {
     switch (option) {
     case GLA_OPT_CHUNKS_PER_SPAN: return g_opt_chunks_per_span;
     case GLA_OPT_ENGINE: return g_opt_engine;
+    case GLA_OPT_CARRY: return g_opt_carry;
     default: return -1;
     }
 }

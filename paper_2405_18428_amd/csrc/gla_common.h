@@ -8,6 +8,8 @@
 //   phase 2  the spans of one (batch, head) are chained:
 //            S_start(r+1) = diag(Gamma_r) S_start(r) + U_r;
 //   phase 3  every span recomputes its tokens from S_start(r) and writes o_t.
+// Phase 2 is a kernel of its own, or (MFMA engine, few spans per head) the start
+// of phase 3: each work-group then chains the U of the spans before its own.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -36,6 +38,8 @@ struct Params {
     int B, H, T, dk, dv, grid_h, grid_w, scan_dir;
     int nspans;             // spans per (batch, head)
     int span_len;           // tokens per span, a multiple of kChunk
+    int chain_in_output;    // 1: no phase-2 kernel; the output pass chains U_0..U_{r-1} itself and phase 1
+                            //    skips the last span of every (batch, head) (nobody reads its U)
     int qkv_dtype, out_dtype;
 };
 

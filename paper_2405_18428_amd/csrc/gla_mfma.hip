@@ -13,7 +13,7 @@
 // given.  The state S lives in fp32 MFMA accumulators for the whole span.
 // Exponentials run in base 2 (log_alpha is scaled by log2(e) once, before the scan).
 //
-// A work-group has NW = 4 waves (the kernel also instantiates for 8); per chunk:
+// A work-group has NW = 4 waves in the output pass and 8 in the state pass; per chunk:
 //   (a) registers prefetched from HBM -> LDS: raw log_alpha / q / k / v rows (all
 //       token-major, 16- or 8-byte pieces), S_0 as bf16 hi/lo;
 //   (b) lane = token: DPP wave scan of log_alpha per channel, exp2, gating, hi/lo
@@ -172,6 +172,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     constexpr int TPW = TM::kPerWave;           // state tiles per wave
     constexpr int NHALF = NW / 4;               // waves sharing one 16-row output tile
     constexpr int NH = (NDV16 + NHALF - 1) / NHALF;  // value-column tiles per wave
+    constexpr bool LOWREG = MINW >= 4;          // 128 registers per lane: shallow operand batches in the output pass
     static_assert(NW == 4 || NW == 8, "4 or 8 waves");
     static_assert(16 * NCT <= CHS, "state tiles must fit the operand row");
 
@@ -202,8 +203,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
         const int nb = gridDim.x;
         if ((nb & 7) == 0) blk = (blk & 7) * (nb >> 3) + (blk >> 3);
     }
-    const int bh = blk / p.nspans;
-    const int sp = blk - bh * p.nspans;
+    // spans per (batch, head) that this launch covers: the state pass leaves out the last one when the output
+    // pass chains the span states itself (nothing reads that U)
+    const int spans_here = (!OUT && p.chain_in_output) ? p.nspans - 1 : p.nspans;
+    const int bh = blk / spans_here;
+    const int sp = blk - bh * spans_here;
     const int dk = p.dk, dv = p.dv, T = p.T;
     const int s_begin = sp * p.span_len;
     const int s_end = min(T, s_begin + p.span_len);
@@ -216,6 +220,80 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + (size_t)bh * T * dk * 4;
     char *gout = static_cast<char *>(p.out) + (size_t)bh * T * dv * sizeof(TOut);
 
+    // ---- state tiles owned by this wave (TileMap) ----
+    f32x4 acc[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // ---- state entering the span, chained here from the local states of the spans before it ----
+    // S_start(sp) = sum_{r < sp} diag(prod_{r < r' < sp} Gamma_r') U_r, evaluated as the recurrence
+    // s <- Gamma_r s + U_r over r on 4 consecutive state elements per thread (one key channel: dv % 4 == 0),
+    // kRun spans loaded at a time; the result goes through LDS into the MFMA accumulator layout.
+    if constexpr (OUT) {
+        const bool chain = p.chain_in_output && sp > 0;  // uniform over the work-group
+        if (chain) {
+            constexpr int kV4 = (L::kDkp * L::kDvp / 4 + NTHR - 1) / NTHR;  // float4 per thread
+            constexpr int kBudget = MINW >= 4 ? 16 : 32;                    // float4 in flight: 64 or 128 registers of U
+            constexpr int kRun = kBudget / kV4 > 0 ? kBudget / kV4 : 1;     // spans in flight
+            const int ne = dk * dv, ne4 = ne >> 2;
+            const float *ub = p.ws_state + (size_t)bh * p.nspans * ne;
+            const float *lb = p.ws_lgam + (size_t)bh * p.nspans * dk;
+            int e4[kV4], ch[kV4];
+#pragma unroll
+            for (int m = 0; m < kV4; ++m) {
+                e4[m] = min(tid + NTHR * m, ne4 - 1);  // threads past the end repeat the last piece
+                ch[m] = (4 * e4[m]) / dv;
+            }
+            f32x4 st[kV4];
+#pragma unroll
+            for (int m = 0; m < kV4; ++m) st[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int r0 = 0; r0 < sp; r0 += kRun) {
+                f32x4 u[kRun][kV4];
+                float lg[kRun][kV4];
+#pragma unroll
+                for (int i = 0; i < kRun; ++i) {
+                    const int r = min(r0 + i, sp - 1);  // loads past the run's end repeat a valid span
+#pragma unroll
+                    for (int m = 0; m < kV4; ++m) {
+                        u[i][m] = *reinterpret_cast<const f32x4 *>(ub + (size_t)r * ne + 4 * e4[m]);
+                        lg[i][m] = lb[r * dk + ch[m]];
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < kRun; ++i) {
+                    if (r0 + i < sp) {
+#pragma unroll
+                        for (int m = 0; m < kV4; ++m) {
+                            const float gm = exp2_fast(lg[i][m] * kLog2e);
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) st[m][x] = fmaf(gm, st[m][x], u[i][m][x]);
+                        }
+                    }
+                }
+            }
+            float *s_chain = reinterpret_cast<float *>(smem);
+#pragma unroll
+            for (int m = 0; m < kV4; ++m)
+                if (tid + NTHR * m < ne4) *reinterpret_cast<f32x4 *>(s_chain + 4 * e4[m]) = st[m];
+        }
+        __syncthreads();
+        if (chain) {
+            const float *s_chain = reinterpret_cast<const float *>(smem);
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                if (TM::valid(w, i)) {
+                    const int n = 16 * TM::nt(w, i) + lm;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int c = 16 * TM::ct(w, i) + 4 * g + r;
+                        if (c < dk && n < dv) acc[i][r] = s_chain[c * dv + n];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+
     // ---- prologue: clear LDS (pads must read as zero), token maps of the first two chunks ----
     for (int i = tid; i < L::kBytes / 16; i += NTHR)
         reinterpret_cast<u32x4 *>(smem)[i] = u32x4{0, 0, 0, 0};
@@ -226,11 +304,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     }
     __syncthreads();
 
-    // ---- state tiles owned by this wave (TileMap) ----
-    f32x4 acc[TPW];
-#pragma unroll
-    for (int i = 0; i < TPW; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (OUT && p.nspans > 1) {
+    // ---- or the state entering the span as the carry kernel left it ----
+    if (OUT && p.nspans > 1 && !p.chain_in_output) {
         const float *s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
@@ -576,13 +651,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     }
                 };
                 // score tile, transposed: lane (lm, g) gets A[i = 16 IT + lm][j = 16 jt + 4g + r]
-                auto score_tile = [&](int u, int jt) {
+                auto score_tile = [&](int ku, int u, int jt) {  // K~ buffer ku -> score operand slot u
                     f32x4 d = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
-                        d = mfma(kfh[u][ks], qfh[ks], d);
-                        d = mfma(kfh[u][ks], qfl[ks], d);
-                        d = mfma(kfl[u][ks], qfh[ks], d);
+                        d = mfma(kfh[ku][ks], qfh[ks], d);
+                        d = mfma(kfh[ku][ks], qfl[ks], d);
+                        d = mfma(kfl[ku][ks], qfh[ks], d);
                     }
                     if (jt == IT) {
 #pragma unroll
@@ -622,12 +697,56 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     qfh[ks] = *reinterpret_cast<const u32x4 *>(qrow_h + colk[ks]);
                     qfl[ks] = *reinterpret_cast<const u32x4 *>(qrow_l + colk[ks]);
                 }
+                if constexpr (LOWREG) {
+                    // 128-register budget (four waves per SIMD hide the waits instead of deep batches):
+                    // one S_0 step and one K~ tile in registers at a time
+                    load_st(0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    qs(0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (KS > 1) {
+                        load_st(0, 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                        qs(0, 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    load_ktile(0, 0);
+                    load_v(0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    score_tile(0, 0, 0);
+                    if constexpr (IT >= 1) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        load_ktile(0, 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                        score_tile(0, 1, 1);
+                    }
+                    av();
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (IT >= 2) {
+                        load_ktile(0, 2);
+                        load_v(1);
+                        ph[1] = u32x2{0, 0};
+                        pl[1] = u32x2{0, 0};
+                        __builtin_amdgcn_sched_barrier(0);
+                        score_tile(0, 0, 2);
+                        if constexpr (IT >= 3) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            load_ktile(0, 3);
+                            __builtin_amdgcn_sched_barrier(0);
+                            score_tile(0, 1, 3);
+                        }
+                        av();
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    load_state_first();
+                    __builtin_amdgcn_sched_barrier(0);
+                } else {
                 load_ktile(0, 0);
                 if constexpr (IT >= 1) load_ktile(1, 1);
                 __builtin_amdgcn_sched_barrier(0);
                 load_v(0);
-                score_tile(0, 0);
-                if constexpr (IT >= 1) score_tile(1, 1);
+                score_tile(0, 0, 0);
+                if constexpr (IT >= 1) score_tile(1, 1, 1);
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (IT >= 2) {
                     load_ktile(0, 2);
@@ -637,8 +756,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     load_v(1);
                     ph[1] = u32x2{0, 0};
                     pl[1] = u32x2{0, 0};
-                    score_tile(0, 2);
-                    if constexpr (IT >= 3) score_tile(1, 3);
+                    score_tile(0, 0, 2);
+                    if constexpr (IT >= 3) score_tile(1, 1, 3);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 load_st(0, 0);
@@ -652,6 +771,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     load_state_first();
                     qs(1, 1);
                     __builtin_amdgcn_sched_barrier(0);
+                }
                 }
                 const int row = 16 * IT + lm;
                 if (row < nvalid) {
@@ -697,8 +817,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     float *dst = nullptr;
     if (!OUT)
         dst = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
-    else if (p.nspans == 1 && p.final_state != nullptr)
-        dst = p.final_state + (size_t)bh * dk * dv;
+    else if ((p.nspans == 1 || p.chain_in_output) && sp == p.nspans - 1 && p.final_state != nullptr)
+        dst = p.final_state + (size_t)bh * dk * dv;  // the last span ends in the final state
     if (dst != nullptr) {
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
@@ -719,7 +839,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
 template <int MODE, int NDK8, int NDV16, typename TOut>
 hipError_t launch_one(const Params &p, hipStream_t stream) {
     using L = Layout<MODE, NDK8, NDV16>;
-    constexpr int NW = 4;  // 8 is supported by the kernel but leaves too few registers for the operand batches
+    // The state pass is light on registers and runs best with 8 waves (4 per SIMD at two work-groups per compute
+    // unit); the output pass needs the 256-register budget of 4-wave groups for its operand batches.
+    constexpr int NW = (MODE == kModeState) ? 8 : 4;
     // register cap: no tighter than the waves per SIMD that the LDS footprint lets a compute unit hold anyway
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int kWavesPerSimd = kGroupsPerCu * NW / 4;
@@ -732,7 +854,8 @@ hipError_t launch_one(const Params &p, hipStream_t stream) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    dim3 grid((unsigned)(p.B * p.H * p.nspans)), block(NW * 64);
+    const int spans = (MODE == kModeState && p.chain_in_output) ? p.nspans - 1 : p.nspans;
+    dim3 grid((unsigned)(p.B * p.H * spans)), block(NW * 64);
     hipLaunchKernelGGL(kernel, grid, block, L::kBytes, stream, p);
     return hipGetLastError();
 }

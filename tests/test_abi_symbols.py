@@ -42,6 +42,11 @@ def test_options_round_trip():
     gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 0)
     with pytest.raises(gla.GlaError):
         gla.gla_set_option(gla.OPT_ENGINE, 7)
+    gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_IN_OUTPUT_PASS)
+    assert gla.gla_get_option(gla.OPT_CARRY) == gla.CARRY_IN_OUTPUT_PASS
+    gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_AUTO)
+    with pytest.raises(gla.GlaError):
+        gla.gla_set_option(gla.OPT_CARRY, 3)
     with pytest.raises(gla.GlaError):
         gla.gla_set_option(42, 0)
 

@@ -30,12 +30,14 @@ def _need_gpu():
     yield
     gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 0)
     gla.gla_set_option(gla.OPT_ENGINE, gla.ENGINE_AUTO)
+    gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_AUTO)
 
 
 @pytest.fixture(autouse=True)
 def _reset_options():
     gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 0)
     gla.gla_set_option(gla.OPT_ENGINE, gla.ENGINE_AUTO)
+    gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_AUTO)
     yield
 
 
@@ -104,16 +106,36 @@ def test_contract_config(name, scan):
     check(d, cfg.grid_h, cfg.grid_w, scan, ref, ref_fin, tol, simple=(cfg.dtype == "bf16"))
 
 
-@pytest.mark.parametrize("engine", [gla.ENGINE_RECURRENT, gla.ENGINE_MFMA])
+ENGINE_CARRY = [(gla.ENGINE_RECURRENT, gla.CARRY_AUTO), (gla.ENGINE_MFMA, gla.CARRY_KERNEL),
+                (gla.ENGINE_MFMA, gla.CARRY_IN_OUTPUT_PASS)]
+
+
+@pytest.mark.parametrize("engine,carry", ENGINE_CARRY)
 @pytest.mark.parametrize("cps", [1, 2, 3, 1000])
-def test_plans_and_engines_agree_with_oracle(engine, cps):
-    """Every launch plan (chunks per span) and both engines on DiG-XL/2 at 512 px, column-reverse scan."""
+def test_plans_and_engines_agree_with_oracle(engine, carry, cps):
+    """Every launch plan (chunks per span), both engines and both places where the span states are chained, on
+    DiG-XL/2 at 512 px, column-reverse scan."""
     name, scan = "dig_xl2_512", 3
     cfg = gi.CONFIGS[name]
     gla.gla_set_option(gla.OPT_ENGINE, engine)
+    gla.gla_set_option(gla.OPT_CARRY, carry)
     gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, cps)
     ref, ref_fin = _oracle(name, scan)
-    print(f"\nengine={engine} chunks_per_span={cps}", flush=True)
+    print(f"\nengine={engine} carry={carry} chunks_per_span={cps}", flush=True)
+    check(_config_inputs(name), cfg.grid_h, cfg.grid_w, scan, ref, ref_fin, TOL_BF16)
+
+
+@pytest.mark.parametrize("cps,carry", [(1, gla.CARRY_IN_OUTPUT_PASS), (1, gla.CARRY_AUTO), (2, gla.CARRY_AUTO),
+                                       (4, gla.CARRY_KERNEL), (4, gla.CARRY_AUTO)])
+def test_many_spans_per_head_at_full_size(cps, carry):
+    """The 2048 px workload cut into 256, 128 and 64 spans per head: long chains in the output pass (forced at
+    256 spans), the carry kernel above 64 spans, and the automatic choice on both sides of that limit."""
+    name, scan = "dig_xl2_2048", 1
+    cfg = gi.CONFIGS[name]
+    gla.gla_set_option(gla.OPT_CARRY, carry)
+    gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, cps)
+    ref, ref_fin = _oracle(name, scan)
+    print(f"\ncarry={carry} chunks_per_span={cps}", flush=True)
     check(_config_inputs(name), cfg.grid_h, cfg.grid_w, scan, ref, ref_fin, TOL_BF16)
 
 
@@ -137,7 +159,8 @@ SHAPES = [
     (1, 2, 5, 13, 36, 72, "bf16"),       # T = 65: one full chunk + 1 token
     (2, 2, 9, 21, 36, 72, "bf16"),       # T = 189: ragged tail, non-square
     (1, 3, 23, 11, 64, 128, "bf16"),     # largest head sizes
-    (1, 2, 10, 13, 4, 2, "bf16"),        # smallest MFMA-eligible head sizes
+    (1, 2, 10, 13, 4, 8, "bf16"),        # smallest head sizes of the MFMA engine
+    (1, 2, 10, 13, 4, 2, "bf16"),        # dv % 8 != 0 -> recurrent engine
     (1, 2, 17, 19, 40, 96, "bf16"),
     (1, 2, 12, 11, 33, 65, "bf16"),      # odd head sizes -> recurrent engine
     (1, 2, 12, 11, 20, 24, "f32"),
@@ -153,11 +176,13 @@ def test_ragged_shapes_all_scans(shape):
     d = gi.make_inputs(B, H, T, dk, dv, dtype, seed=7)
     tol = TOL_F32 if dtype == "f32" else TOL_BF16
     print(f"\nshape={shape}", flush=True)
-    for cps in (0, 1, 2):
-        gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, cps)
-        for scan in range(4):
-            ref, ref_fin = gla_oracle.gla_fwd(d["q"], d["k"], d["v"], d["log_alpha"], gh, gw, scan)
-            check(d, gh, gw, scan, ref, ref_fin, tol)
+    refs = [gla_oracle.gla_fwd(d["q"], d["k"], d["v"], d["log_alpha"], gh, gw, scan) for scan in range(4)]
+    for carry in (gla.CARRY_KERNEL, gla.CARRY_IN_OUTPUT_PASS):
+        gla.gla_set_option(gla.OPT_CARRY, carry)
+        for cps in (0, 1, 2):
+            gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, cps)
+            for scan in range(4):
+                check(d, gh, gw, scan, refs[scan][0], refs[scan][1], tol)
 
 
 def test_strong_and_absent_decay():
