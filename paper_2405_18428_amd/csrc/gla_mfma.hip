@@ -82,6 +82,13 @@ __device__ inline HiLo split_pair_val(float x0, float x1) {
         (lo_out) = hl_.lo;                            \
     } while (0)
 
+// Identity that the optimiser cannot see through: values derived from the result are recomputed where they are
+// used instead of being hoisted out of the chunk loop and held in registers.
+__device__ inline int recompute_per_chunk(int x) {
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
 template <int CTRL, int ROW_MASK, bool BOUND>
 __device__ inline float dpp_move(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK,
@@ -372,14 +379,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             r_v[kVSlots] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tok[vrrow] * dv2 + 2u * (uint32_t)vrcol);
     };
 
-    // ---- per-lane LDS offsets (bf16 elements) that do not change from chunk to chunk ----
-    // channel group read by this lane in 32-channel step ks; groups beyond dk alias the all-zero group
-    int colk[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) colk[ks] = (4 * ks + g < NDK8) ? 8 * (4 * ks + g) : L::kZeroCol;
-    // transposing reads: this lane supplies row lm/4 (of 4 tokens) and column quad lm%4 (of 16 columns)
-    const int tr_row = lm >> 2, tr_col = 4 * (lm & 3);
-
     // ---- gate work of this wave: whole UW-channel units w, w+NW, ..., then single left-over channels ----
     constexpr int UW = 32 / NW;                       // channels per unit: 16-byte LDS rows accesses for 4 waves
     const int nunits = dk / UW;
@@ -437,6 +436,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
         if constexpr (OUT) {
             // S_0 (state entering the chunk) as bf16 hi/lo, value-column-major for the B operand
             // (state rows past dk are exactly zero and land in the zero padding of the row)
+            const int ln = recompute_per_chunk(lane), lm = ln & 15, g = ln >> 4;
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
                 if (TM::valid(w, i)) {
@@ -566,6 +566,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
         // LDS reads and MFMAs of different tiles can be interleaved freely.
         // The scheduler is fenced between batches: the LDS reads of batch k+1 are issued before the MFMAs of
         // batch k, so one wait covers a whole batch instead of one wait per operand.
+        // per-lane LDS offsets (bf16 elements), derived afresh in every chunk: kept across the loop they would
+        // occupy registers through the staging and gate stages as well
+        const int ln = recompute_per_chunk(lane), lm = ln & 15, g = ln >> 4;
+        // channel group read by this lane in 32-channel step ks; groups beyond dk alias the all-zero group
+        int colk[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) colk[ks] = (4 * ks + g < NDK8) ? 8 * (4 * ks + g) : L::kZeroCol;
+        // transposing reads: this lane supplies row lm/4 (of 4 tokens) and column quad lm%4 (of 16 columns)
+        const int tr_row = lm >> 2, tr_col = 4 * (lm & 3);
         auto contract = [&](auto wave_c) {
             constexpr int W = decltype(wave_c)::value;
             constexpr int IT = W & 3;                       // 16-row output tile of this wave
