@@ -177,10 +177,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     constexpr int NCT = (NDK8 + 1) / 2;         // 16-channel row tiles of the state
     using TM = TileMap<OUT, NW, NCT, NDV16>;
     constexpr int TPW = TM::kPerWave;           // state tiles per wave
-    constexpr int NHALF = NW / 4;               // waves sharing one 16-row output tile
-    constexpr int NH = (NDV16 + NHALF - 1) / NHALF;  // value-column tiles per wave
-    constexpr bool LOWREG = MINW >= 4;          // 128 registers per lane: shallow operand batches in the output pass
-    static_assert(NW == 4 || NW == 8, "4 or 8 waves");
+    static_assert(NW == 4 || (NW == 8 && !OUT), "4 waves, or 8 in the state pass");
     static_assert(16 * NCT <= CHS, "state tiles must fit the operand row");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -577,44 +574,34 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
         const int tr_row = lm >> 2, tr_col = 4 * (lm & 3);
         auto contract = [&](auto wave_c) {
             constexpr int W = decltype(wave_c)::value;
-            constexpr int IT = W & 3;                       // 16-row output tile of this wave
-            constexpr int NT0 = (W >> 2) * NH;              // first value-column tile of this wave
-            constexpr int NX = (NDV16 - NT0 < NH) ? NDV16 - NT0 : NH;
+            constexpr int IT = W & 3;                       // 16-row output tile of this wave (output pass)
             constexpr int NTW = TM::count(W);               // state tiles of this wave
 
-            // ---- state-update operands: K~ (A operand) and V (B operand); contraction slot (g, e) of a 32-token
-            // step is token 32 ks + 8g + e for both.  With row-owned tiles the K~ operand is read once per chunk.
-            const uint16_t *krow_h = s_khi + (8 * g + tr_row) * CHS + tr_col;
-            const uint16_t *krow_l = s_klo + (8 * g + tr_row) * CHS + tr_col;
-            const uint16_t *vrow_s = s_v + (8 * g + tr_row) * VS + tr_col;
+            // Contraction slot (g, e) of the 32-token step q32 is token 32 q32 + 16 (e/4) + 4g + e%4, for every
+            // operand that is contracted over tokens (the layout in which the score tiles leave the MFMA).
+            // ---- state-update operands: K~ (A operand) and V (B operand).  With row-owned tiles the K~ operand
+            // is read once per chunk, and the V operand is the one the output rows were computed with.
+            const uint16_t *krow_h = s_khi + (4 * g + tr_row) * CHS + tr_col;
+            const uint16_t *krow_l = s_klo + (4 * g + tr_row) * CHS + tr_col;
+            const uint16_t *vrow = s_v + (4 * g + tr_row) * VS + tr_col;
             constexpr int KB = OUT ? 1 : 2;                 // K~ buffers: shared, or one per tile in flight
-            u32x2 ukh[KB][2][2], ukl[KB][2][2];             // [buffer][ks][half]
-            u32x2 uv[2][2][2];                              // [buffer][ks][half]
+            u32x2 ukh[KB][2][2], ukl[KB][2][2];             // [buffer][32-token step][half]
             auto load_state_k = [&](int buf, int i) {
                 const int ko = 16 * TM::ct(W, i);
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     ukh[buf][ks][0] = lds_read_tr(krow_h + 32 * ks * CHS + ko);
-                    ukh[buf][ks][1] = lds_read_tr(krow_h + 32 * ks * CHS + ko + 4 * CHS);
+                    ukh[buf][ks][1] = lds_read_tr(krow_h + (32 * ks + 16) * CHS + ko);
                     ukl[buf][ks][0] = lds_read_tr(krow_l + 32 * ks * CHS + ko);
-                    ukl[buf][ks][1] = lds_read_tr(krow_l + 32 * ks * CHS + ko + 4 * CHS);
+                    ukl[buf][ks][1] = lds_read_tr(krow_l + (32 * ks + 16) * CHS + ko);
                 }
             };
-            auto load_state_ops = [&](int buf, int i) {
-                if (!OUT || i == 0) load_state_k(OUT ? 0 : buf, i);
-                const int vo = 16 * TM::nt(W, i);
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    uv[buf][ks][0] = lds_read_tr(vrow_s + 32 * ks * VS + vo);
-                    uv[buf][ks][1] = lds_read_tr(vrow_s + 32 * ks * VS + vo + 4 * VS);
-                }
-            };
-            auto update_state = [&](int buf, int i) {
-                const int kb = OUT ? 0 : buf;
+            // S = diag(exp(b_C)) (S + K~^T V) on state tile i; b0, b1 = V fragments of the two 32-token steps
+            auto update_state = [&](int kb, int i, const u32x4 &b0, const u32x4 &b1) {
                 f32x4 a = acc[i];
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
-                    const u32x4 b = u32x4{uv[buf][ks][0][0], uv[buf][ks][0][1], uv[buf][ks][1][0], uv[buf][ks][1][1]};
+                    const u32x4 b = ks == 0 ? b0 : b1;
                     a = mfma(u32x4{ukh[kb][ks][0][0], ukh[kb][ks][0][1], ukh[kb][ks][1][0], ukh[kb][ks][1][1]}, b, a);
                     a = mfma(u32x4{ukl[kb][ks][0][0], ukl[kb][ks][0][1], ukl[kb][ks][1][0], ukl[kb][ks][1][1]}, b, a);
                 }
@@ -623,15 +610,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 for (int r = 0; r < 4; ++r) a[r] *= gm[r];
                 acc[i] = a;
             };
-            auto load_state_first = [&]() {
-                if constexpr (NTW > 0) load_state_ops(0, 0);
-            };
 
-            if constexpr (OUT && NX > 0) {
+            if constexpr (OUT) {
+                constexpr int NX = NDV16;          // this wave's 16 output rows span all value-column tiles
                 const uint16_t *qrow_h = s_qhi + (16 * IT + lm) * CHS, *qrow_l = s_qlo + (16 * IT + lm) * CHS;
                 u32x4 qfh[KS], qfl[KS];            // Q~ fragments of this wave's 16 output rows
                 u32x4 kfh[2][KS], kfl[2][KS];      // K~ fragments of two score tiles
-                u32x2 vt[NX][2];                   // V fragments of one 32-token step
+                u32x2 vt[2][NX][2];                // V fragments of the two 32-token steps
                 u32x4 sth[2][NX], stl[2][NX];      // S_0 fragments of one 32-channel step, two buffers
                 u32x2 ph[2], pl[2];                // two score tiles as bf16 hi/lo (A operand of O += A V)
                 f32x4 o[NX];
@@ -642,31 +627,32 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                         kfl[u][ks] = *reinterpret_cast<const u32x4 *>(s_klo + (16 * jt + lm) * CHS + colk[ks]);
                     }
                 };
-                // contraction slot (g, e) of the 32-token step q32 is token 32 q32 + 16 (e/4) + 4g + e%4
                 auto load_v = [&](int q32) {
-                    const uint16_t *vrow = s_v + (32 * q32 + 4 * g + tr_row) * VS + tr_col + 16 * NT0;
 #pragma unroll
                     for (int x = 0; x < NX; ++x) {
-                        vt[x][0] = lds_read_tr(vrow + 16 * x);
-                        vt[x][1] = lds_read_tr(vrow + 16 * VS + 16 * x);
+                        vt[q32][x][0] = lds_read_tr(vrow + 32 * q32 * VS + 16 * x);
+                        vt[q32][x][1] = lds_read_tr(vrow + (32 * q32 + 16) * VS + 16 * x);
                     }
+                };
+                auto v_frag = [&](int q32, int x) {
+                    return u32x4{vt[q32][x][0][0], vt[q32][x][0][1], vt[q32][x][1][0], vt[q32][x][1][1]};
                 };
                 auto load_st = [&](int buf, int ks) {
 #pragma unroll
                     for (int x = 0; x < NX; ++x) {
-                        const int srow = (16 * (NT0 + x) + lm) * CHS + colk[ks];
+                        const int srow = (16 * x + lm) * CHS + colk[ks];
                         sth[buf][x] = *reinterpret_cast<const u32x4 *>(s_sthi + srow);
                         stl[buf][x] = *reinterpret_cast<const u32x4 *>(s_stlo + srow);
                     }
                 };
                 // score tile, transposed: lane (lm, g) gets A[i = 16 IT + lm][j = 16 jt + 4g + r]
-                auto score_tile = [&](int ku, int u, int jt) {  // K~ buffer ku -> score operand slot u
+                auto score_tile = [&](int u, int jt) {
                     f32x4 d = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
-                        d = mfma(kfh[ku][ks], qfh[ks], d);
-                        d = mfma(kfh[ku][ks], qfl[ks], d);
-                        d = mfma(kfl[ku][ks], qfh[ks], d);
+                        d = mfma(kfh[u][ks], qfh[ks], d);
+                        d = mfma(kfh[u][ks], qfl[ks], d);
+                        d = mfma(kfl[u][ks], qfh[ks], d);
                     }
                     if (jt == IT) {
 #pragma unroll
@@ -676,13 +662,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     SPLIT_PAIR(d[0], d[1], ph[u][0], pl[u][0]);
                     SPLIT_PAIR(d[2], d[3], ph[u][1], pl[u][1]);
                 };
-                // O^T += V^T A^T : lane (lm, g) accumulates o[x][r] = O[i = 16 IT + lm][n = 16 (NT0 + x) + 4g + r]
-                auto av = [&]() {
+                // O^T += V^T A^T : lane (lm, g) accumulates o[x][r] = O[i = 16 IT + lm][n = 16 x + 4g + r]
+                auto av = [&](int q32) {
                     const u32x4 ah = u32x4{ph[0][0], ph[0][1], ph[1][0], ph[1][1]};
                     const u32x4 al = u32x4{pl[0][0], pl[0][1], pl[1][0], pl[1][1]};
 #pragma unroll
                     for (int x = 0; x < NX; ++x) {
-                        const u32x4 b = u32x4{vt[x][0][0], vt[x][0][1], vt[x][1][0], vt[x][1][1]};
+                        const u32x4 b = v_frag(q32, x);
                         o[x] = mfma(b, ah, o[x]);
                         o[x] = mfma(b, al, o[x]);
                     }
@@ -693,6 +679,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                         o[x] = mfma(sth[buf][x], qfh[ks], o[x]);
                         o[x] = mfma(sth[buf][x], qfl[ks], o[x]);
                         o[x] = mfma(stl[buf][x], qfh[ks], o[x]);
+                    }
+                };
+                // what the state update still has to read: its K~ operand, and the second 32 tokens of V when the
+                // causal part of this wave's rows ended before them
+                auto load_state_first = [&]() {
+                    if constexpr (NTW > 0) {
+                        load_state_k(0, 0);
+                        if constexpr (IT < 2) load_v(1);
                     }
                 };
 
@@ -706,71 +700,27 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     qfh[ks] = *reinterpret_cast<const u32x4 *>(qrow_h + colk[ks]);
                     qfl[ks] = *reinterpret_cast<const u32x4 *>(qrow_l + colk[ks]);
                 }
-                if constexpr (LOWREG) {
-                    // 128-register budget (four waves per SIMD hide the waits instead of deep batches):
-                    // one S_0 step and one K~ tile in registers at a time
-                    load_st(0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                    qs(0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                    if constexpr (KS > 1) {
-                        load_st(0, 1);
-                        __builtin_amdgcn_sched_barrier(0);
-                        qs(0, 1);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    load_ktile(0, 0);
-                    load_v(0);
-                    __builtin_amdgcn_sched_barrier(0);
-                    score_tile(0, 0, 0);
-                    if constexpr (IT >= 1) {
-                        __builtin_amdgcn_sched_barrier(0);
-                        load_ktile(0, 1);
-                        __builtin_amdgcn_sched_barrier(0);
-                        score_tile(0, 1, 1);
-                    }
-                    av();
-                    __builtin_amdgcn_sched_barrier(0);
-                    if constexpr (IT >= 2) {
-                        load_ktile(0, 2);
-                        load_v(1);
-                        ph[1] = u32x2{0, 0};
-                        pl[1] = u32x2{0, 0};
-                        __builtin_amdgcn_sched_barrier(0);
-                        score_tile(0, 0, 2);
-                        if constexpr (IT >= 3) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            load_ktile(0, 3);
-                            __builtin_amdgcn_sched_barrier(0);
-                            score_tile(0, 1, 3);
-                        }
-                        av();
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    load_state_first();
-                    __builtin_amdgcn_sched_barrier(0);
-                } else {
                 load_ktile(0, 0);
                 if constexpr (IT >= 1) load_ktile(1, 1);
                 __builtin_amdgcn_sched_barrier(0);
                 load_v(0);
-                score_tile(0, 0, 0);
-                if constexpr (IT >= 1) score_tile(1, 1, 1);
+                score_tile(0, 0);
+                if constexpr (IT >= 1) score_tile(1, 1);
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (IT >= 2) {
                     load_ktile(0, 2);
                     if constexpr (IT >= 3) load_ktile(1, 3);
-                    av();
+                    av(0);
                     __builtin_amdgcn_sched_barrier(0);
                     load_v(1);
                     ph[1] = u32x2{0, 0};
                     pl[1] = u32x2{0, 0};
-                    score_tile(0, 0, 2);
-                    if constexpr (IT >= 3) score_tile(1, 1, 3);
+                    score_tile(0, 2);
+                    if constexpr (IT >= 3) score_tile(1, 3);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 load_st(0, 0);
-                av();
+                av(IT >= 2 ? 1 : 0);
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (KS > 1) load_st(1, 1);
                 else load_state_first();
@@ -781,10 +731,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     qs(1, 1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                }
                 const int row = 16 * IT + lm;
                 if (row < nvalid) {
-                    const int col0 = 16 * NT0 + 4 * g;
+                    const int col0 = 4 * g;
                     char *orow = gout + ((uint32_t)tok[row] * (uint32_t)dv + (uint32_t)col0) * (uint32_t)sizeof(TOut);
 #pragma unroll
                     for (int x = 0; x < NX; ++x) {
@@ -797,16 +746,30 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                         }
                     }
                 }
-            } else {
-                load_state_first();
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            // S = diag(exp(b_C)) (S + K~^T V) on the tiles this wave owns
 #pragma unroll
-            for (int i = 0; i < NTW; ++i) {
-                if (i + 1 < NTW) load_state_ops((i + 1) & 1, i + 1);
-                update_state(i & 1, i);
+                for (int i = 0; i < NTW; ++i) update_state(0, i, v_frag(0, TM::nt(W, i)), v_frag(1, TM::nt(W, i)));
+            } else {
+                // state pass: operands of tile i+1 are read while tile i is contracted
+                u32x2 uv[2][2][2];                              // [buffer][32-token step][half]
+                auto load_state_ops = [&](int buf, int i) {
+                    load_state_k(buf, i);
+                    const int vo = 16 * TM::nt(W, i);
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        uv[buf][ks][0] = lds_read_tr(vrow + 32 * ks * VS + vo);
+                        uv[buf][ks][1] = lds_read_tr(vrow + (32 * ks + 16) * VS + vo);
+                    }
+                };
+                if constexpr (NTW > 0) load_state_ops(0, 0);
                 __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < NTW; ++i) {
+                    if (i + 1 < NTW) load_state_ops((i + 1) & 1, i + 1);
+                    const int bf = i & 1;
+                    update_state(bf, i, u32x4{uv[bf][0][0][0], uv[bf][0][0][1], uv[bf][0][1][0], uv[bf][0][1][1]},
+                                 u32x4{uv[bf][1][0][0], uv[bf][1][0][1], uv[bf][1][1][0], uv[bf][1][1][1]});
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         };
         switch (w) {
