@@ -614,6 +614,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             if constexpr (OUT) {
                 constexpr int NX = NDV16;          // this wave's 16 output rows span all value-column tiles
                 const uint16_t *qrow_h = s_qhi + (16 * IT + lm) * CHS, *qrow_l = s_qlo + (16 * IT + lm) * CHS;
+                // When the last 32-channel step holds a single 8-channel group (dk = 33..40, or dk <= 8), its three
+                // products hi*hi, hi*lo, lo*hi share one MFMA: lane groups g = 0, 1, 2 of the gated operand and of
+                // S_0 read (hi, hi, lo) of that channel group, those of Q~ read (hi, lo, hi), g = 3 reads zeros.
+                // The "hi" arrays then hold the packed fragment of that step and the "lo" entry is unused.
+                constexpr bool PT = NDK8 % 4 == 1;
+                constexpr int TC = 32 * (KS - 1);  // first channel of the last step
+                const uint16_t *ktail = (g == 2 ? s_klo : s_khi) + (g == 3 ? L::kZeroCol : TC);
+                const uint16_t *qtail = (g == 1 ? s_qlo : s_qhi) + (g == 3 ? L::kZeroCol : TC);
+                const uint16_t *sttail = (g == 2 ? s_stlo : s_sthi) + (g == 3 ? L::kZeroCol : TC);
                 u32x4 qfh[KS], qfl[KS];            // Q~ fragments of this wave's 16 output rows
                 u32x4 kfh[2][KS], kfl[2][KS];      // K~ fragments of two score tiles
                 u32x2 vt[2][NX][2];                // V fragments of the two 32-token steps
@@ -623,8 +632,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 auto load_ktile = [&](int u, int jt) {
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
-                        kfh[u][ks] = *reinterpret_cast<const u32x4 *>(s_khi + (16 * jt + lm) * CHS + colk[ks]);
-                        kfl[u][ks] = *reinterpret_cast<const u32x4 *>(s_klo + (16 * jt + lm) * CHS + colk[ks]);
+                        if (PT && ks == KS - 1) {
+                            kfh[u][ks] = *reinterpret_cast<const u32x4 *>(ktail + (16 * jt + lm) * CHS);
+                        } else {
+                            kfh[u][ks] = *reinterpret_cast<const u32x4 *>(s_khi + (16 * jt + lm) * CHS + colk[ks]);
+                            kfl[u][ks] = *reinterpret_cast<const u32x4 *>(s_klo + (16 * jt + lm) * CHS + colk[ks]);
+                        }
                     }
                 };
                 auto load_v = [&](int q32) {
@@ -640,9 +653,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 auto load_st = [&](int buf, int ks) {
 #pragma unroll
                     for (int x = 0; x < NX; ++x) {
-                        const int srow = (16 * x + lm) * CHS + colk[ks];
-                        sth[buf][x] = *reinterpret_cast<const u32x4 *>(s_sthi + srow);
-                        stl[buf][x] = *reinterpret_cast<const u32x4 *>(s_stlo + srow);
+                        if (PT && ks == KS - 1) {
+                            sth[buf][x] = *reinterpret_cast<const u32x4 *>(sttail + (16 * x + lm) * CHS);
+                        } else {
+                            const int srow = (16 * x + lm) * CHS + colk[ks];
+                            sth[buf][x] = *reinterpret_cast<const u32x4 *>(s_sthi + srow);
+                            stl[buf][x] = *reinterpret_cast<const u32x4 *>(s_stlo + srow);
+                        }
                     }
                 };
                 // score tile, transposed: lane (lm, g) gets A[i = 16 IT + lm][j = 16 jt + 4g + r]
@@ -651,6 +668,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
                         d = mfma(kfh[u][ks], qfh[ks], d);
+                        if (PT && ks == KS - 1) continue;
                         d = mfma(kfh[u][ks], qfl[ks], d);
                         d = mfma(kfl[u][ks], qfh[ks], d);
                     }
@@ -677,6 +695,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
 #pragma unroll
                     for (int x = 0; x < NX; ++x) {
                         o[x] = mfma(sth[buf][x], qfh[ks], o[x]);
+                        if (PT && ks == KS - 1) continue;
                         o[x] = mfma(sth[buf][x], qfl[ks], o[x]);
                         o[x] = mfma(stl[buf][x], qfh[ks], o[x]);
                     }
@@ -697,8 +716,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 // batch 0: Q~ and the first two score tiles' K~
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    qfh[ks] = *reinterpret_cast<const u32x4 *>(qrow_h + colk[ks]);
-                    qfl[ks] = *reinterpret_cast<const u32x4 *>(qrow_l + colk[ks]);
+                    if (PT && ks == KS - 1) {
+                        qfh[ks] = *reinterpret_cast<const u32x4 *>(qtail + (16 * IT + lm) * CHS);
+                    } else {
+                        qfh[ks] = *reinterpret_cast<const u32x4 *>(qrow_h + colk[ks]);
+                        qfl[ks] = *reinterpret_cast<const u32x4 *>(qrow_l + colk[ks]);
+                    }
                 }
                 load_ktile(0, 0);
                 if constexpr (IT >= 1) load_ktile(1, 1);
