@@ -330,7 +330,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     // ---- which HBM pieces this thread stages (the same for every chunk) ----
     // A row of log_alpha is cut into 16-byte pieces (4 channels), a row of q or k into 8-byte pieces (the same
     // 4 channels), a row of v into 16-byte pieces (8 columns).  Slot m of a thread is piece m*PPS + tid%PPS of
-    // row tid/PPS; pieces a row has beyond the last whole slot are dealt, one thread each, to the first waves.
+    // row tid/PPS; pieces a row has beyond the last whole slot are dealt, one thread each, to the last waves.
     // A slot that points past the row repeats an earlier piece (same bytes to the same place).
     constexpr int PPS = NTHR / kChunk;                     // pieces of one row handled per slot
     constexpr int kSlots = (NDK8 * 2) / PPS;               // whole slots at the largest dk of this instantiation
@@ -339,9 +339,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     const int pcs = dk >> 2, vpcs = dv >> 3;
     const int nslots = min(kSlots, pcs / PPS), nvslots = min(kVSlots, vpcs / PPS);
     const int prem = pcs - nslots * PPS, vrem = vpcs - nvslots * PPS;   // left-over pieces per row (< PPS)
-    const bool has_rem = w < prem, has_vrem = w < vrem;                 // 64*rem threads = the first rem waves
-    const int rrow = has_rem ? tid / prem : 0, rch = has_rem ? 4 * (nslots * PPS + tid % prem) : 0;
-    const int vrrow = has_vrem ? tid / vrem : 0, vrcol = has_vrem ? 8 * (nvslots * PPS + tid % vrem) : 0;
+    // 64*rem threads = the last rem waves (in the output pass the first waves also split the state for S_0)
+    const bool has_rem = w >= NW - prem, has_vrem = w >= NW - vrem;
+    const int rid = tid - 64 * (NW - prem), vrid = tid - 64 * (NW - vrem);
+    const int rrow = has_rem ? rid / prem : 0, rch = has_rem ? 4 * (nslots * PPS + rid % prem) : 0;
+    const int vrrow = has_vrem ? vrid / vrem : 0, vrcol = has_vrem ? 8 * (nvslots * PPS + vrid % vrem) : 0;
     const uint32_t dk2 = 2u * (uint32_t)dk, dv2 = 2u * (uint32_t)dv;
 
     f32x4 r_la[kSlots + 1];
@@ -446,9 +448,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 }
             }
         }
-        if (tid < kChunk && chunk + 2 < nch) {  // token map two chunks ahead (three buffers)
-            const int s = s_begin + (chunk + 2) * kChunk + tid;
-            s_tok[((chunk + 2) % 3) * kChunk + tid] =
+        if (w == NW - 1 && chunk + 2 < nch) {  // token map two chunks ahead (three buffers), by the last wave
+            const int s = s_begin + (chunk + 2) * kChunk + lane;
+            s_tok[((chunk + 2) % 3) * kChunk + lane] =
                 scan_token(p.scan_dir, (s < s_end) ? s : s_begin, T, p.grid_h, p.grid_w);
         }
         __syncthreads();
