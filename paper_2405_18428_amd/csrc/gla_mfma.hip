@@ -211,7 +211,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     // pass chains the span states itself (nothing reads that U)
     const int spans_here = (!OUT && p.chain_in_output) ? p.nspans - 1 : p.nspans;
     const int bh = blk / spans_here;
-    const int sp = blk - bh * spans_here;
+    int sp_ = blk - bh * spans_here;
+    // Work-groups i and i + 32 of an XCD's range tend to share a compute unit.  When the output pass chains the
+    // span states itself, the cost of that grows with the span index, so odd heads walk their spans backwards:
+    // a compute unit then hosts a long and a short chain, and the group that ends first leaves it to the other.
+    if (OUT && p.chain_in_output && (bh & 1)) sp_ = spans_here - 1 - sp_;
+    const int sp = sp_;
     const int dk = p.dk, dv = p.dv, T = p.T;
     const int s_begin = sp * p.span_len;
     const int s_end = min(T, s_begin + p.span_len);
