@@ -89,7 +89,7 @@ typedef enum {
 /* Where the states of the spans of one (batch, head) are chained, S_start(r+1) = diag(Gamma_r) S_start(r) + U_r
  * (the recurrence of Eq. (attn_gla) applied span by span). */
 typedef enum {
-    GLA_CARRY_AUTO = 0,          /* in the output pass when the MFMA engine runs with at most 64 spans per head */
+    GLA_CARRY_AUTO = 0,          /* in the output pass when the MFMA engine runs with at most 48 spans per head */
     GLA_CARRY_KERNEL = 1,        /* a kernel of its own between the two passes */
     GLA_CARRY_IN_OUTPUT_PASS = 2 /* each output work-group chains the local states before its span, whatever the
                                     span count (the recurrent engine has no such path and keeps the kernel) */

@@ -16,7 +16,7 @@ int g_opt_carry = GLA_CARRY_AUTO;
 
 // Most spans per (batch, head) that the output pass chains by itself: work-group r reads the r local states
 // before it, so the reads grow with the square of the span count while a carry kernel's grow linearly.
-constexpr int kMaxChainedSpans = 64;
+constexpr int kMaxChainedSpans = 48;  // measured on MI355X with 16 heads: the two ways cost the same near 50 spans
 
 struct Scratch {
     void *ptr = nullptr;

@@ -126,10 +126,11 @@ def test_plans_and_engines_agree_with_oracle(engine, carry, cps):
 
 
 @pytest.mark.parametrize("cps,carry", [(1, gla.CARRY_IN_OUTPUT_PASS), (1, gla.CARRY_AUTO), (2, gla.CARRY_AUTO),
-                                       (4, gla.CARRY_KERNEL), (4, gla.CARRY_AUTO)])
+                                       (4, gla.CARRY_IN_OUTPUT_PASS), (4, gla.CARRY_AUTO), (6, gla.CARRY_AUTO),
+                                       (6, gla.CARRY_KERNEL)])
 def test_many_spans_per_head_at_full_size(cps, carry):
-    """The 2048 px workload cut into 256, 128 and 64 spans per head: long chains in the output pass (forced at
-    256 spans), the carry kernel above 64 spans, and the automatic choice on both sides of that limit."""
+    """The 2048 px workload cut into 256, 128, 64 and 43 spans per head: long chains in the output pass (forced at
+    256 spans), the carry kernel, and the automatic choice on both sides of its limit of 48 spans."""
     name, scan = "dig_xl2_2048", 1
     cfg = gi.CONFIGS[name]
     gla.gla_set_option(gla.OPT_CARRY, carry)
@@ -232,6 +233,21 @@ def test_final_state_is_optional_and_streams_are_honoured():
     s.synchronize()
     assert fin is None
     assert rel_err(out.cpu().numpy(), ref) <= TOL_BF16
+
+
+def test_timed_entry_point_runs_the_same_path():
+    """gla_fwd_timed (HIP events around each kernel, used by the benchmark) leaves the same outputs as gla_fwd_ex."""
+    name = "dig_xl2_512"
+    cfg = gi.CONFIGS[name]
+    q, k, v, la = upload(_config_inputs(name))
+    out, fin = gla.gla_fwd_ex(q, k, v, la, cfg.grid_h, cfg.grid_w, 1)
+    out2, fin2 = torch.zeros_like(out), torch.zeros_like(fin)
+    nbytes = gla.gla_fwd_workspace_bytes(cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv, gla.DT_BF16)
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=q.device)
+    ms = gla.gla_fwd_timed(q, k, v, la, cfg.grid_h, cfg.grid_w, 1, out2, fin2, ws, iters=3)
+    torch.cuda.synchronize()
+    assert len(ms) == 4 and all(m >= 0.0 for m in ms) and ms[3] > 0.0
+    assert torch.equal(out, out2) and torch.equal(fin, fin2)
 
 
 def test_errors_write_nothing():
