@@ -60,12 +60,15 @@ int validate(const void *q, const void *k, const void *v, const float *log_alpha
 // per-work-group prologue; short spans give the 256 compute units more
 // work-groups.  Two resident work-groups per compute unit is the sweet spot
 // measured on MI355X for the output pass.
-int plan_chunks_per_span(int bh, int nchunks) {
+int plan_chunks_per_span(int bh, int nchunks, bool mfma_engine) {
     int cps = g_opt_chunks_per_span;
     if (cps <= 0) {
-        const long long target_groups = 512;
-        cps = (int)(((long long)bh * nchunks) / target_groups);
+        // at most 512 work-groups, so that all of them are resident at once (two per compute unit); sequences of
+        // up to four chunks are walked in one pass (a second kernel costs more than the chunks it would save)
+        const long long resident_groups = 512;
+        cps = (int)(((long long)bh * nchunks + resident_groups - 1) / resident_groups);
         if (cps < 1) cps = 1;
+        if (mfma_engine && nchunks <= 4) cps = nchunks;
     }
     if (cps > nchunks) cps = nchunks;
     return cps;
@@ -91,15 +94,6 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     p.grid_h = grid_h; p.grid_w = grid_w; p.scan_dir = scan_dir;
     p.qkv_dtype = qkv_dtype; p.out_dtype = out_dtype;
 
-    const int nchunks = (T + kChunk - 1) / kChunk;
-    const int cps = plan_chunks_per_span(B * H, nchunks);
-    p.span_len = cps * kChunk;
-    p.nspans = (nchunks + cps - 1) / cps;
-    const size_t bh = (size_t)B * H;
-    p.ws_state = static_cast<float *>(workspace);
-    p.ws_lgam = reinterpret_cast<float *>(static_cast<char *>(workspace) +
-                                          align_up(bh * p.nspans * dk * dv * sizeof(float), 256));
-
     bool use_mfma;
     if (g_opt_engine == GLA_ENGINE_RECURRENT) {
         use_mfma = false;
@@ -109,6 +103,15 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     } else {
         use_mfma = mfma_engine_supports(p);
     }
+
+    const int nchunks = (T + kChunk - 1) / kChunk;
+    const int cps = plan_chunks_per_span(B * H, nchunks, use_mfma);
+    p.span_len = cps * kChunk;
+    p.nspans = (nchunks + cps - 1) / cps;
+    const size_t bh = (size_t)B * H;
+    p.ws_state = static_cast<float *>(workspace);
+    p.ws_lgam = reinterpret_cast<float *>(static_cast<char *>(workspace) +
+                                          align_up(bh * p.nspans * dk * dv * sizeof(float), 256));
     auto span = [&](SpanMode mode) {
         return use_mfma ? launch_mfma_span(p, mode, stream) : launch_recurrent_span(p, mode, stream);
     };
