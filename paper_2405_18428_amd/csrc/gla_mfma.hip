@@ -177,7 +177,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     constexpr int NCT = (NDK8 + 1) / 2;         // 16-channel row tiles of the state
     using TM = TileMap<OUT, NW, NCT, NDV16>;
     constexpr int TPW = TM::kPerWave;           // state tiles per wave
+    constexpr int DEPTH = (OUT || NDK8 > 5 || NDV16 > 5) ? 1 : 2;
+    constexpr int NTB = DEPTH + 2;              // token-map buffers in LDS
     static_assert(NW == 4 || (NW == 8 && !OUT), "4 waves, or 8 in the state pass");
+    static_assert(NTB <= 4 && (DEPTH + 1) * kChunk <= NTHR, "token maps: four buffers, first ones filled in one go");
     static_assert(16 * NCT <= CHS, "state tiles must fit the operand row");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -307,7 +310,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     for (int i = tid; i < L::kBytes / 16; i += NTHR)
         reinterpret_cast<u32x4 *>(smem)[i] = u32x4{0, 0, 0, 0};
     __syncthreads();
-    if (tid < 2 * kChunk) {
+    if (tid < (DEPTH + 1) * kChunk) {
         const int s = s_begin + tid;
         s_tok[tid] = scan_token(p.scan_dir, (s < s_end) ? s : s_begin, T, p.grid_h, p.grid_w);
     }
@@ -351,36 +354,34 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     const int vrrow = has_vrem ? vrid / vrem : 0, vrcol = has_vrem ? 8 * (nvslots * PPS + vrid % vrem) : 0;
     const uint32_t dk2 = 2u * (uint32_t)dk, dv2 = 2u * (uint32_t)dv;
 
-    f32x4 r_la[kSlots + 1];
-    u32x2 r_k[kSlots + 1];
-    u32x2 r_q[OUT ? kSlots + 1 : 1];
-    u32x4 r_v[kVSlots + 1];
+    f32x4 r_la[DEPTH][kSlots + 1];
+    u32x2 r_k[DEPTH][kSlots + 1];
+    u32x2 r_q[DEPTH][OUT ? kSlots + 1 : 1];
+    u32x4 r_v[DEPTH][kVSlots + 1];
 
     // Rows past the end of a ragged last chunk carry the token of a valid row in s_tok (so the loads
     // stay in bounds) and are zeroed when they are written to LDS.
-    auto load_chunk = [&](int chunk) {
-        const int *tok = s_tok + (chunk % 3) * kChunk;
+    auto load_chunk = [&](int chunk, auto set_c) {
+        constexpr int S = decltype(set_c)::value;
+        const int *tok = s_tok + (chunk % NTB) * kChunk;
         const uint32_t row_k = (uint32_t)tok[prow] * dk2, row_v = (uint32_t)tok[prow] * dv2;
 #pragma unroll
         for (int m = 0; m < kSlots; ++m) {
-            if (m < nslots) {
-                const uint32_t e2 = row_k + 8u * (uint32_t)(m * PPS + psub);
-                r_la[m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
-                r_k[m] = *reinterpret_cast<const u32x2 *>(gk + e2);
-                if constexpr (OUT) r_q[m] = *reinterpret_cast<const u32x2 *>(gq + e2);
-            }
+            const uint32_t e2 = row_k + 8u * (uint32_t)min(m * PPS + psub, pcs - 1);
+            r_la[S][m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
+            r_k[S][m] = *reinterpret_cast<const u32x2 *>(gk + e2);
+            if constexpr (OUT) r_q[S][m] = *reinterpret_cast<const u32x2 *>(gq + e2);
         }
-        if (has_rem) {
+        {
             const uint32_t e2 = (uint32_t)tok[rrow] * dk2 + 2u * (uint32_t)rch;
-            r_la[kSlots] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
-            r_k[kSlots] = *reinterpret_cast<const u32x2 *>(gk + e2);
-            if constexpr (OUT) r_q[kSlots] = *reinterpret_cast<const u32x2 *>(gq + e2);
+            r_la[S][kSlots] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
+            r_k[S][kSlots] = *reinterpret_cast<const u32x2 *>(gk + e2);
+            if constexpr (OUT) r_q[S][kSlots] = *reinterpret_cast<const u32x2 *>(gq + e2);
         }
 #pragma unroll
         for (int m = 0; m < kVSlots; ++m)
-            if (m < nvslots) r_v[m] = *reinterpret_cast<const u32x4 *>(gv + row_v + 16u * (uint32_t)(m * PPS + psub));
-        if (has_vrem)
-            r_v[kVSlots] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tok[vrrow] * dv2 + 2u * (uint32_t)vrcol);
+            r_v[S][m] = *reinterpret_cast<const u32x4 *>(gv + row_v + 16u * (uint32_t)min(m * PPS + psub, vpcs - 1));
+        r_v[S][kVSlots] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tok[vrrow] * dv2 + 2u * (uint32_t)vrcol);
     };
 
     // ---- gate work of this wave: whole UW-channel units w, w+NW, ..., then single left-over channels ----
@@ -392,10 +393,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     constexpr int kMaxUnits = kMaxDk / (UW * NW);
     constexpr int kMaxLeft = (UW * NW - 4 + NW - 1) / NW;
 
-    load_chunk(0);
+    load_chunk(0, int_c<0>{});
+    if constexpr (DEPTH == 2) {
+        load_chunk(1, int_c<1>{});
+    }
 
-    for (int chunk = 0; chunk < nch; ++chunk) {
-        const int *tok = s_tok + (chunk % 3) * kChunk;
+    auto process_chunk = [&](int chunk, auto set_c) {
+        constexpr int S = decltype(set_c)::value;       // register set that holds this chunk's rows
+        const int *tok = s_tok + (chunk % NTB) * kChunk;
 
         // ================= (a) registers -> LDS =================
         const int nvalid = min(kChunk, s_end - s_begin - chunk * kChunk);  // rows of this chunk that are tokens
@@ -403,40 +408,40 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             if (prow >= nvalid) {
 #pragma unroll
                 for (int m = 0; m < kSlots; ++m) {
-                    r_la[m] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    r_k[m] = u32x2{0, 0};
-                    if constexpr (OUT) r_q[m] = u32x2{0, 0};
+                    r_la[S][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    r_k[S][m] = u32x2{0, 0};
+                    if constexpr (OUT) r_q[S][m] = u32x2{0, 0};
                 }
 #pragma unroll
-                for (int m = 0; m < kVSlots; ++m) r_v[m] = u32x4{0, 0, 0, 0};
+                for (int m = 0; m < kVSlots; ++m) r_v[S][m] = u32x4{0, 0, 0, 0};
             }
             if (rrow >= nvalid) {
-                r_la[kSlots] = f32x4{0.f, 0.f, 0.f, 0.f};
-                r_k[kSlots] = u32x2{0, 0};
-                if constexpr (OUT) r_q[kSlots] = u32x2{0, 0};
+                r_la[S][kSlots] = f32x4{0.f, 0.f, 0.f, 0.f};
+                r_k[S][kSlots] = u32x2{0, 0};
+                if constexpr (OUT) r_q[S][kSlots] = u32x2{0, 0};
             }
-            if (vrrow >= nvalid) r_v[kVSlots] = u32x4{0, 0, 0, 0};
+            if (vrrow >= nvalid) r_v[S][kVSlots] = u32x4{0, 0, 0, 0};
         }
 #pragma unroll
         for (int m = 0; m < kSlots; ++m) {
             if (m < nslots) {
                 const int ch = 4 * (m * PPS + psub);
-                *reinterpret_cast<f32x4 *>(s_la + prow * LAS + ch) = r_la[m];
-                *reinterpret_cast<u32x2 *>(s_khi + prow * CHS + ch) = r_k[m];
-                if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + prow * CHS + ch) = r_q[m];
+                *reinterpret_cast<f32x4 *>(s_la + prow * LAS + ch) = r_la[S][m];
+                *reinterpret_cast<u32x2 *>(s_khi + prow * CHS + ch) = r_k[S][m];
+                if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + prow * CHS + ch) = r_q[S][m];
             }
         }
         if (has_rem) {
-            *reinterpret_cast<f32x4 *>(s_la + rrow * LAS + rch) = r_la[kSlots];
-            *reinterpret_cast<u32x2 *>(s_khi + rrow * CHS + rch) = r_k[kSlots];
-            if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + rrow * CHS + rch) = r_q[kSlots];
+            *reinterpret_cast<f32x4 *>(s_la + rrow * LAS + rch) = r_la[S][kSlots];
+            *reinterpret_cast<u32x2 *>(s_khi + rrow * CHS + rch) = r_k[S][kSlots];
+            if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + rrow * CHS + rch) = r_q[S][kSlots];
         }
 #pragma unroll
         for (int m = 0; m < kVSlots; ++m)
-            if (m < nvslots) *reinterpret_cast<u32x4 *>(s_v + prow * VS + 8 * (m * PPS + psub)) = r_v[m];
-        if (has_vrem) *reinterpret_cast<u32x4 *>(s_v + vrrow * VS + vrcol) = r_v[kVSlots];
-        // the next chunk's rows start their trip from HBM now and land while this chunk is being computed
-        if (chunk + 1 < nch) load_chunk(chunk + 1);
+            if (m < nvslots) *reinterpret_cast<u32x4 *>(s_v + prow * VS + 8 * (m * PPS + psub)) = r_v[S][m];
+        if (has_vrem) *reinterpret_cast<u32x4 *>(s_v + vrrow * VS + vrcol) = r_v[S][kVSlots];
+        // the rows of a later chunk start their trip from HBM into the set just emptied
+        load_chunk(chunk + DEPTH, set_c);  // past the span: the clamped token map makes every lane read one row
         if constexpr (OUT) {
             // S_0 (state entering the chunk) as bf16 hi/lo, value-column-major for the B operand
             // (state rows past dk are exactly zero and land in the zero padding of the row)
@@ -453,9 +458,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 }
             }
         }
-        if (w == NW - 1 && chunk + 2 < nch) {  // token map two chunks ahead (three buffers), by the last wave
-            const int s = s_begin + (chunk + 2) * kChunk + lane;
-            s_tok[((chunk + 2) % 3) * kChunk + lane] =
+        if (w == NW - 1) {  // token map of the chunk loaded next time, by the last wave
+            const int s = s_begin + (chunk + DEPTH + 1) * kChunk + lane;
+            s_tok[((chunk + DEPTH + 1) % NTB) * kChunk + lane] =
                 scan_token(p.scan_dir, (s < s_end) ? s : s_begin, T, p.grid_h, p.grid_w);
         }
         __syncthreads();
@@ -813,6 +818,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
         default: if constexpr (NW > 4) contract(int_c<7>{}); break;
         }
         __syncthreads();
+    };
+    for (int chunk = 0; chunk < nch; chunk += DEPTH) {
+        process_chunk(chunk, int_c<0>{});
+        // (a span with an odd number of chunks walks one empty chunk: all rows zero, the state does not move;
+        // a conditional call would hide from the compiler which loads are still in flight at the loop head)
+        if constexpr (DEPTH == 2) process_chunk(chunk + 1, int_c<1>{});
     }
 
     // ---- epilogue: the span's state ----
