@@ -165,7 +165,8 @@ struct TileMap {
 };
 
 // MINW = waves per SIMD the register budget must allow (4 -> 128 VGPRs, 2 -> 256 VGPRs).
-template <int MODE, int NDK8, int NDV16, int NW, int MINW, typename TOut>
+// DEPTH = chunks of rows kept in flight from HBM (register sets; 2 only in the state pass).
+template <int MODE, int NDK8, int NDV16, int NW, int MINW, int DEPTH, typename TOut>
 __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     using L = Layout<MODE, NDK8, NDV16>;
     constexpr bool OUT = MODE == kModeOutput;
@@ -177,9 +178,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     constexpr int NCT = (NDK8 + 1) / 2;         // 16-channel row tiles of the state
     using TM = TileMap<OUT, NW, NCT, NDV16>;
     constexpr int TPW = TM::kPerWave;           // state tiles per wave
-    constexpr int DEPTH = (OUT || NDK8 > 5 || NDV16 > 5) ? 1 : 2;
+    // With two sets in flight every row load is issued unconditionally (slots past the row or the span repeat a
+    // valid piece), so that the number of younger loads is a constant and the waits can leave them in flight.
+    constexpr bool UNCOND = OUT || DEPTH > 1;
     constexpr int NTB = DEPTH + 2;              // token-map buffers in LDS
     static_assert(NW == 4 || (NW == 8 && !OUT), "4 waves, or 8 in the state pass");
+    static_assert(DEPTH == 1 || (DEPTH == 2 && !OUT), "two register sets only in the state pass");
     static_assert(NTB <= 4 && (DEPTH + 1) * kChunk <= NTHR, "token maps: four buffers, first ones filled in one go");
     static_assert(16 * NCT <= CHS, "state tiles must fit the operand row");
 
@@ -367,12 +371,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
         const uint32_t row_k = (uint32_t)tok[prow] * dk2, row_v = (uint32_t)tok[prow] * dv2;
 #pragma unroll
         for (int m = 0; m < kSlots; ++m) {
-            const uint32_t e2 = row_k + 8u * (uint32_t)min(m * PPS + psub, pcs - 1);
-            r_la[S][m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
-            r_k[S][m] = *reinterpret_cast<const u32x2 *>(gk + e2);
-            if constexpr (OUT) r_q[S][m] = *reinterpret_cast<const u32x2 *>(gq + e2);
+            if (UNCOND || m < nslots) {
+                const uint32_t e2 = row_k + 8u * (uint32_t)min(m * PPS + psub, pcs - 1);
+                r_la[S][m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
+                r_k[S][m] = *reinterpret_cast<const u32x2 *>(gk + e2);
+                if constexpr (OUT) r_q[S][m] = *reinterpret_cast<const u32x2 *>(gq + e2);
+            }
         }
-        {
+        if (UNCOND || has_rem) {
             const uint32_t e2 = (uint32_t)tok[rrow] * dk2 + 2u * (uint32_t)rch;
             r_la[S][kSlots] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
             r_k[S][kSlots] = *reinterpret_cast<const u32x2 *>(gk + e2);
@@ -380,8 +386,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
         }
 #pragma unroll
         for (int m = 0; m < kVSlots; ++m)
-            r_v[S][m] = *reinterpret_cast<const u32x4 *>(gv + row_v + 16u * (uint32_t)min(m * PPS + psub, vpcs - 1));
-        r_v[S][kVSlots] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tok[vrrow] * dv2 + 2u * (uint32_t)vrcol);
+            if (UNCOND || m < nvslots)
+                r_v[S][m] = *reinterpret_cast<const u32x4 *>(gv + row_v + 16u * (uint32_t)min(m * PPS + psub, vpcs - 1));
+        if (UNCOND || has_vrem)
+            r_v[S][kVSlots] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tok[vrrow] * dv2 + 2u * (uint32_t)vrcol);
     };
 
     // ---- gate work of this wave: whole UW-channel units w, w+NW, ..., then single left-over channels ----
@@ -441,7 +449,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             if (m < nvslots) *reinterpret_cast<u32x4 *>(s_v + prow * VS + 8 * (m * PPS + psub)) = r_v[S][m];
         if (has_vrem) *reinterpret_cast<u32x4 *>(s_v + vrrow * VS + vrcol) = r_v[S][kVSlots];
         // the rows of a later chunk start their trip from HBM into the set just emptied
-        load_chunk(chunk + DEPTH, set_c);  // past the span: the clamped token map makes every lane read one row
+        // (unconditional loads past the span: the clamped token map makes every lane read one row)
+        if (UNCOND || chunk + DEPTH < nch) load_chunk(chunk + DEPTH, set_c);
         if constexpr (OUT) {
             // S_0 (state entering the chunk) as bf16 hi/lo, value-column-major for the B operand
             // (state rows past dk are exactly zero and land in the zero padding of the row)
@@ -458,7 +467,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 }
             }
         }
-        if (w == NW - 1) {  // token map of the chunk loaded next time, by the last wave
+        if (w == NW - 1 && (UNCOND || chunk + DEPTH + 1 < nch)) {  // token map of the chunk loaded next time, by the last wave
             const int s = s_begin + (chunk + DEPTH + 1) * kChunk + lane;
             s_tok[((chunk + DEPTH + 1) % NTB) * kChunk + lane] =
                 scan_token(p.scan_dir, (s < s_end) ? s : s_begin, T, p.grid_h, p.grid_w);
@@ -819,11 +828,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
         }
         __syncthreads();
     };
-    for (int chunk = 0; chunk < nch; chunk += DEPTH) {
+    // Whole groups of DEPTH chunks in the loop, a last odd chunk after it: a conditional call inside the loop
+    // would hide from the compiler which loads are still in flight at the loop head.
+    int chunk = 0;
+    for (; chunk + DEPTH <= nch; chunk += DEPTH) {
         process_chunk(chunk, int_c<0>{});
-        // (a span with an odd number of chunks walks one empty chunk: all rows zero, the state does not move;
-        // a conditional call would hide from the compiler which loads are still in flight at the loop head)
         if constexpr (DEPTH == 2) process_chunk(chunk + 1, int_c<1>{});
+    }
+    if constexpr (DEPTH == 2) {
+        if (chunk < nch) process_chunk(chunk, int_c<0>{});
     }
 
     // ---- epilogue: the span's state ----
@@ -849,8 +862,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     if (!OUT && tid < dk) p.ws_lgam[((size_t)bh * p.nspans + sp) * dk + tid] = s_lg[tid] * kLn2;
 }
 
-template <int MODE, int NDK8, int NDV16, typename TOut>
-hipError_t launch_one(const Params &p, hipStream_t stream) {
+template <int MODE, int NDK8, int NDV16, int DEPTH, typename TOut>
+hipError_t launch_depth(const Params &p, hipStream_t stream) {
     using L = Layout<MODE, NDK8, NDV16>;
     // The state pass is light on registers and runs best with 8 waves (4 per SIMD at two work-groups per compute
     // unit); the output pass needs the 256-register budget of 4-wave groups for its operand batches.
@@ -859,7 +872,7 @@ hipError_t launch_one(const Params &p, hipStream_t stream) {
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int kWavesPerSimd = kGroupsPerCu * NW / 4;
     constexpr int MINW = kWavesPerSimd >= 4 ? 4 : (kWavesPerSimd >= 2 ? 2 : 1);
-    auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, NW, MINW, TOut>;
+    auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, NW, MINW, DEPTH, TOut>;
     static bool configured = false;  // per instantiation; the attribute is per function, set once
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -871,6 +884,16 @@ hipError_t launch_one(const Params &p, hipStream_t stream) {
     dim3 grid((unsigned)(p.B * p.H * spans)), block(NW * 64);
     hipLaunchKernelGGL(kernel, grid, block, L::kBytes, stream, p);
     return hipGetLastError();
+}
+
+template <int MODE, int NDK8, int NDV16, typename TOut>
+hipError_t launch_one(const Params &p, hipStream_t stream) {
+    // Two chunks of rows in flight pay off in the state pass (short chunk period, registers to spare at the
+    // smaller head sizes) once a span is long enough to amortise the second set's start-up.
+    if constexpr (MODE == kModeState && NDK8 <= 5 && NDV16 <= 5) {
+        if (p.span_len >= 4 * kChunk) return launch_depth<MODE, NDK8, NDV16, 2, TOut>(p, stream);
+    }
+    return launch_depth<MODE, NDK8, NDV16, 1, TOut>(p, stream);
 }
 
 template <int MODE, int NDK8, int NDV16>
