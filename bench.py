@@ -112,13 +112,20 @@ def main():
         gla.gla_fwd_ex(s["q"], s["k"], s["v"], s["la"], cfg.grid_h, cfg.grid_w, args.scan,
                        out=s["out"], final_state=s["fin"], workspace=s["ws"])
 
-    if args.copy_calibration:
-        src = torch.empty((256 << 20,), dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(10):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+    # a plain 256 MiB device copy: the known-size reference of the rocprofv3 HBM counters (--copy-calibration keeps
+    # it in the profiled run) and, timed, the bandwidth a streaming kernel reaches on this machine (read + write bytes)
+    src = torch.empty((256 << 20,), dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(10 if args.copy_calibration else 3):
+        dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * (256 << 20) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
 
     for i in range(args.warmup):
         step(i)
@@ -168,6 +175,7 @@ def main():
         "algorithmic_bytes": alg_bytes, "kernel_ms": round(float(phase[dom]), 5),
         "phase_ms": {n: round(float(x), 5) for n, x in zip(names + ["whole_call"], phase)},
         "whole_path_frac": round(alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "measured_copy_gbs": round(copy_gbs, 1),
         "mfma_tflops": round(alg_flops / (ms_per_step * 1e-3) / 1e12, 2),
         "mfma_frac": round(alg_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5),
     }
