@@ -140,6 +140,18 @@ def test_many_spans_per_head_at_full_size(cps, carry):
     check(_config_inputs(name), cfg.grid_h, cfg.grid_w, scan, ref, ref_fin, TOL_BF16)
 
 
+@pytest.mark.parametrize("cps", [4, 5, 7, 9])
+def test_odd_and_even_span_lengths(cps):
+    """Spans of four chunks or more run the state pass with two chunks of rows in flight (a loop over chunk pairs
+    plus a last odd chunk); 1024 px has 64 chunks per head, so these span lengths also leave a shorter last span."""
+    name, scan = "dig_xl2_1024", 2
+    cfg = gi.CONFIGS[name]
+    gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, cps)
+    ref, ref_fin = _oracle(name, scan)
+    print(f"\nchunks_per_span={cps}", flush=True)
+    check(_config_inputs(name), cfg.grid_h, cfg.grid_w, scan, ref, ref_fin, TOL_BF16)
+
+
 def test_bf16_output():
     name, scan = "dig_s2_256", 2
     cfg = gi.CONFIGS[name]
