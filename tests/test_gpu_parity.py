@@ -175,6 +175,10 @@ SHAPES = [
     (1, 2, 10, 13, 4, 8, "bf16"),        # smallest head sizes of the MFMA engine
     (1, 2, 10, 13, 4, 2, "bf16"),        # dv % 8 != 0 -> recurrent engine
     (1, 2, 17, 19, 40, 96, "bf16"),
+    (1, 2, 9, 15, 48, 80, "bf16"),       # two channel groups in the last 32-channel step
+    (1, 1, 8, 17, 56, 104, "bf16"),      # three
+    (2, 1, 7, 11, 24, 40, "bf16"),
+    (1, 2, 6, 11, 8, 16, "bf16"),
     (1, 2, 12, 11, 33, 65, "bf16"),      # odd head sizes -> recurrent engine
     (1, 2, 12, 11, 20, 24, "f32"),
     (2, 1, 20, 20, 64, 128, "f32"),
