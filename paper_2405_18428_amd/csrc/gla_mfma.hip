@@ -17,10 +17,11 @@
 //   (a) registers prefetched from HBM -> LDS: raw log_alpha / q / k / v rows (all
 //       token-major, 16- or 8-byte pieces), S_0 as bf16 hi/lo;
 //   (b) lane = token: DPP wave scan of log_alpha per channel, exp2, gating, hi/lo
-//       split, q~ and k~ written in place over the raw rows; the 8-channel units of
-//       a row are dealt to the waves round-robin, left-over channels one by one;
-//   (c) MFMA: wave w owns output rows 16(w%4)..+15 (with 8 waves: the value-column tiles
-//       of half w/4) and the state tiles of one 16-channel row tile (shared K~ operand).
+//       split, q~ and k~ written in place over the raw rows; the 32/NW-channel units
+//       of a row are dealt to the waves round-robin, left-over channels one by one;
+//   (c) MFMA: in the output pass wave w owns output rows 16w..16w+15 and the state tiles
+//       of one 16-channel row tile (shared K~ operand); the state pass deals its state
+//       tiles round-robin over its 8 waves.
 // Operands whose contraction runs over tokens (V, and K~ in the state update) are
 // fetched from the token-major rows with ds_read_b64_tr_b16, which hands lane i of
 // a 16-lane group element i%4 of the 8 bytes read by lane 4e + i/4 (e = 0..3): 16
