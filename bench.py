@@ -36,7 +36,8 @@ def algorithmic_flops_per_token_head(dk, dv, chunk=64):
 def measured_traffic(config_name, kernel, args):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary (None if absent or if
     this run does not use the configuration the summary was taken with)."""
-    if args.out_dtype != "f32" or args.scan != 0 or args.chunks_per_span != 0 or args.engine != 0:
+    if (args.out_dtype != "f32" or args.scan != 0 or args.chunks_per_span != 0 or args.engine != 0
+            or args.layout != "bhtd"):
         return None
     path = os.path.join(ROOT, "profiles", f"gla_fwd_{config_name}_hbm_traffic.md")
     try:
@@ -60,6 +61,8 @@ def main():
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated over (1 = cache-warm)")
     ap.add_argument("--chunks-per-span", type=int, default=0)
     ap.add_argument("--engine", type=int, default=0)
+    ap.add_argument("--layout", default="bhtd", choices=["bhtd", "bthd"],
+                    help="memory order of q, k, v, log_alpha, out: [B,H,T,d] (the headline) or [B,T,H,d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--no-cache-resident", action="store_true",
@@ -95,6 +98,9 @@ def main():
     else:
         host = [torch.from_numpy(d[n]) for n in ("q", "k", "v")]
     host.append(torch.from_numpy(d["log_alpha"]))
+    bthd = args.layout == "bthd"
+    if bthd:
+        host = [t.permute(0, 2, 1, 3).contiguous() for t in host]
     out_dt = torch.float32 if args.out_dtype == "f32" else torch.bfloat16
     qdt = gla.DT_BF16 if cfg.dtype == "bf16" else gla.DT_F32
     ws_bytes = gla.gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
@@ -103,14 +109,18 @@ def main():
     for _ in range(max(1, args.sets)):
         q, k, v, la = (t.to(dev) for t in host)
         sets.append(dict(q=q, k=k, v=v, la=la,
-                         out=torch.empty((B, H, T, dv), dtype=out_dt, device=dev),
+                         out=torch.empty((B, T, H, dv) if bthd else (B, H, T, dv), dtype=out_dt, device=dev),
                          fin=torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev),
                          ws=torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)))
 
     def step(i):
         s = sets[i % len(sets)]
-        gla.gla_fwd_ex(s["q"], s["k"], s["v"], s["la"], cfg.grid_h, cfg.grid_w, args.scan,
-                       out=s["out"], final_state=s["fin"], workspace=s["ws"])
+        if bthd:
+            gla.gla_fwd_layout(s["q"], s["k"], s["v"], s["la"], cfg.grid_h, cfg.grid_w, args.scan,
+                               layout=gla.LAYOUT_BTHD, out=s["out"], final_state=s["fin"], workspace=s["ws"])
+        else:
+            gla.gla_fwd_ex(s["q"], s["k"], s["v"], s["la"], cfg.grid_h, cfg.grid_w, args.scan,
+                           out=s["out"], final_state=s["fin"], workspace=s["ws"])
 
     # a plain 256 MiB device copy: the known-size reference of the rocprofv3 HBM counters (--copy-calibration keeps
     # it in the profiled run) and, timed, the bandwidth a streaming kernel reaches on this machine (read + write bytes)
@@ -153,7 +163,7 @@ def main():
     # per-kernel durations with HIP events on the launch stream, rotating over the same sets
     phase = np.zeros(4)
     reps = 0
-    for r in range(8):
+    for r in range(0 if bthd else 8):  # (the timing aid covers the headline memory order only)
         for s in sets:
             ms = gla.gla_fwd_timed(s["q"], s["k"], s["v"], s["la"], cfg.grid_h, cfg.grid_w, args.scan,
                                    s["out"], s["fin"], s["ws"], iters=1)
@@ -162,6 +172,9 @@ def main():
                 reps += 1
     phase /= max(reps, 1)
     names = ["span_state", "carry", "output"]
+    if bthd:
+        phase[:] = [0.0, 0.0, ms_per_step, ms_per_step]
+        names = ["span_state", "carry", "whole_call"]
     dom = int(np.argmax(phase[:3]))
     qb = 2 if cfg.dtype == "bf16" else 4
     ob = 4 if args.out_dtype == "f32" else 2
@@ -187,7 +200,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={B} H={H} T={T} ({cfg.grid_h}x{cfg.grid_w}) dk={dk} dv={dv} "
-                               f"{cfg.dtype} q/k/v, fp32 log_alpha, {args.out_dtype} out, scan={args.scan}",
+                               f"{cfg.dtype} q/k/v, fp32 log_alpha, {args.out_dtype} out, scan={args.scan}, layout={args.layout}",
                    "buffer_sets": len(sets), "token_heads_per_s": round(B * H * T / (ms_per_step * 1e-3), 1),
                    "cache_resident_ms_per_step": None if warm_ms is None else round(warm_ms, 5),
                    "engine": gla.gla_get_option(gla.OPT_ENGINE),
@@ -221,7 +234,9 @@ def main():
             step(0)
             torch.cuda.synchronize()
             rms = float(np.sqrt(np.mean(ref ** 2)))
-            err = float(np.abs(s["out"].float().cpu().numpy() - ref).max() / rms)
+            got = s["out"].float().cpu()
+            got = got.permute(0, 2, 1, 3) if bthd else got
+            err = float(np.abs(got.numpy() - ref).max() / rms)
             result["max_err_over_rms"] = round(err, 6)
 
     print(json.dumps(result), flush=True)

@@ -130,7 +130,29 @@ int gla_fwd_ex(const void *q, const void *k, const void *v, const float *log_alp
                int qkv_dtype, int out_dtype, void *out, float *final_state,
                void *workspace, size_t workspace_bytes, gla_stream_t stream);
 
-/* Bytes of workspace gla_fwd_ex needs for this problem (an upper bound over all
+/* Memory order of q, k, log_alpha ([.., dk]) and v, out ([.., dv]); final_state and initial_state are always
+ * [B,H,dk,dv].  BTHD is the (B, T, D) token stream of Algorithm 1 with D = H * d seen per head. */
+typedef enum { GLA_LAYOUT_BHTD = 0, GLA_LAYOUT_BTHD = 1 } gla_layout;
+
+/*
+ * gla_fwd_layout - gla_fwd_ex for either memory order, starting from a given state
+ * (Eq. (attn_gla) row 1 with S_0 = initial_state instead of zero: the recurrence
+ * continued from an earlier call's final_state, e.g. a sequence fed in pieces).
+ *
+ *   layout           gla_layout of q, k, v, log_alpha and out (dense, no padding)
+ *   initial_state    DEVICE, fp32 [B,H,dk,dv], 16-byte aligned, or NULL for a zero state   (read)
+ *
+ * Everything else as gla_fwd_ex; GLA_ERR_SHAPE for an unknown layout.  With the MFMA
+ * engine a (batch, head) view must span less than 2 GiB (T * H * max(dk, dv) * 4 bytes
+ * in BTHD order), otherwise the call falls back to the recurrent engine.
+ */
+int gla_fwd_layout(const void *q, const void *k, const void *v, const float *log_alpha,
+                   int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                   int qkv_dtype, int out_dtype, int layout, const float *initial_state,
+                   void *out, float *final_state,
+                   void *workspace, size_t workspace_bytes, gla_stream_t stream);
+
+/* Bytes of workspace gla_fwd_ex / gla_fwd_layout need for this problem (an upper bound over all
  * launch plans, so it does not depend on tuning options).  0 on invalid sizes. */
 size_t gla_fwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);
 

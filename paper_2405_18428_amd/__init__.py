@@ -6,10 +6,10 @@ only marshals arguments.  Importing the package does not load the library;
 calling any entry point without a built library raises.
 """
 from .binding import (  # noqa: F401
-    GlaError, gla_fwd, gla_fwd_ex, gla_fwd_workspace_bytes, gla_fwd_timed,
+    GlaError, gla_fwd, gla_fwd_ex, gla_fwd_layout, gla_fwd_workspace_bytes, gla_fwd_timed,
     gla_set_option, gla_get_option, gla_status_string, gla_version,
     library_path, load_library, lib_symbols,
     SCAN_ROW_FWD, SCAN_ROW_REV, SCAN_COL_FWD, SCAN_COL_REV, DT_F32, DT_BF16,
     OPT_CHUNKS_PER_SPAN, OPT_ENGINE, OPT_CARRY, ENGINE_AUTO, ENGINE_RECURRENT, ENGINE_MFMA,
-    CARRY_AUTO, CARRY_KERNEL, CARRY_IN_OUTPUT_PASS,
+    CARRY_AUTO, CARRY_KERNEL, CARRY_IN_OUTPUT_PASS, LAYOUT_BHTD, LAYOUT_BTHD,
 )

@@ -15,6 +15,7 @@ SCAN_ROW_FWD, SCAN_ROW_REV, SCAN_COL_FWD, SCAN_COL_REV = 0, 1, 2, 3
 DT_F32, DT_BF16 = 0, 1
 OPT_CHUNKS_PER_SPAN, OPT_ENGINE, OPT_CARRY = 0, 1, 2
 CARRY_AUTO, CARRY_KERNEL, CARRY_IN_OUTPUT_PASS = 0, 1, 2
+LAYOUT_BHTD, LAYOUT_BTHD = 0, 1
 ENGINE_AUTO, ENGINE_RECURRENT, ENGINE_MFMA = 0, 1, 2
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -56,6 +57,8 @@ def load_library():
     lib.gla_fwd.argtypes = [vp, vp, vp, vp] + shape + [vp, vp, vp]
     lib.gla_fwd_ex.restype = i
     lib.gla_fwd_ex.argtypes = [vp, vp, vp, vp] + shape + [i, i, vp, vp, vp, sz, vp]
+    lib.gla_fwd_layout.restype = i
+    lib.gla_fwd_layout.argtypes = [vp, vp, vp, vp] + shape + [i, i, i, vp, vp, vp, vp, sz, vp]
     lib.gla_fwd_timed.restype = i
     lib.gla_fwd_timed.argtypes = [vp, vp, vp, vp] + shape + [i, i, vp, vp, vp, sz, vp, i, fp]
     lib.gla_fwd_workspace_bytes.restype = sz
@@ -177,6 +180,49 @@ def gla_fwd_ex(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD,
                               B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt, _dt(out),
                               out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
                               workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return out, final_state
+
+
+def gla_fwd_layout(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, layout=LAYOUT_BHTD,
+                   initial_state=None, out_dtype=None, want_final_state=True, out=None, final_state=None,
+                   workspace=None, stream=None):
+    """gla_fwd_ex for [B,H,T,d] (LAYOUT_BHTD) or [B,T,H,d] (LAYOUT_BTHD) tensors, starting from
+    ``initial_state`` ([B,H,dk,dv] fp32, or None for zero)."""
+    torch = _torch()
+    lib = load_library()
+    if layout not in (LAYOUT_BHTD, LAYOUT_BTHD):
+        raise ValueError("unknown layout")
+    for name, t in (("q", q), ("k", k), ("v", v), ("log_alpha", log_alpha)):
+        if not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous 4-d GPU tensor")
+    if q.shape != k.shape or q.shape != log_alpha.shape or v.shape[:3] != q.shape[:3]:
+        raise ValueError("q, k, log_alpha must share one shape and v its first three sizes")
+    if q.dtype != k.dtype or q.dtype != v.dtype or log_alpha.dtype != torch.float32:
+        raise TypeError("q, k, v must share one element type and log_alpha must be fp32")
+    if layout == LAYOUT_BHTD:
+        B, H, T, dk = q.shape
+    else:
+        B, T, H, dk = q.shape
+    dv = v.shape[3]
+    qdt = _dt(q)
+    if initial_state is not None:
+        if (initial_state.dtype != torch.float32 or tuple(initial_state.shape) != (B, H, dk, dv)
+                or not initial_state.is_contiguous() or not initial_state.is_cuda):
+            raise ValueError("initial_state must be a contiguous fp32 GPU tensor [B,H,dk,dv]")
+    if out is None:
+        odt = torch.float32 if out_dtype is None else out_dtype
+        out = torch.empty(tuple(v.shape), dtype=odt, device=q.device)
+    if final_state is None and want_final_state:
+        final_state = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        nbytes = gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
+        workspace = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=q.device)
+    with torch.cuda.device(q.device):
+        _check(lib.gla_fwd_layout(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(),
+                                  B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt, _dt(out), layout,
+                                  initial_state.data_ptr() if initial_state is not None else None,
+                                  out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
+                                  workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return out, final_state
 
 

@@ -8,7 +8,7 @@
 namespace gla {
 namespace {
 
-constexpr int kVersion = 100;  // 0.1.0
+constexpr int kVersion = 200;  // 0.2.0
 
 int g_opt_chunks_per_span = 0;
 int g_opt_engine = GLA_ENGINE_AUTO;
@@ -81,10 +81,13 @@ struct PhaseEvents {
 int run(const void *q, const void *k, const void *v, const float *log_alpha,
         int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
         int qkv_dtype, int out_dtype, void *out, float *final_state,
-        void *workspace, size_t ws_bytes, hipStream_t stream, PhaseEvents *events) {
+        void *workspace, size_t ws_bytes, hipStream_t stream, PhaseEvents *events,
+        int layout = GLA_LAYOUT_BHTD, const float *initial_state = nullptr) {
     int st = validate(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir,
                       qkv_dtype, out_dtype, out, final_state);
     if (st != GLA_OK) return st;
+    if (layout != GLA_LAYOUT_BHTD && layout != GLA_LAYOUT_BTHD) return GLA_ERR_SHAPE;
+    if (initial_state && misaligned(initial_state)) return GLA_ERR_ALIGN;
     if (!workspace || misaligned(workspace) || ws_bytes < workspace_bytes(B, H, T, dk, dv))
         return GLA_ERR_WORKSPACE;
 
@@ -93,6 +96,14 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     p.B = B; p.H = H; p.T = T; p.dk = dk; p.dv = dv;
     p.grid_h = grid_h; p.grid_w = grid_w; p.scan_dir = scan_dir;
     p.qkv_dtype = qkv_dtype; p.out_dtype = out_dtype;
+    p.initial_state = initial_state;
+    if (layout == GLA_LAYOUT_BHTD) {
+        p.st_k = dk; p.sh_k = (long long)T * dk; p.sb_k = (long long)H * T * dk;
+        p.st_v = dv; p.sh_v = (long long)T * dv; p.sb_v = (long long)H * T * dv;
+    } else {  // [B,T,H,d]: the heads of one token are neighbours
+        p.st_k = H * dk; p.sh_k = dk; p.sb_k = (long long)T * H * dk;
+        p.st_v = H * dv; p.sh_v = dv; p.sb_v = (long long)T * H * dv;
+    }
 
     bool use_mfma;
     if (g_opt_engine == GLA_ENGINE_RECURRENT) {
@@ -154,6 +165,16 @@ int gla_fwd_ex(const void *q, const void *k, const void *v, const float *log_alp
                void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
     return run(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype, out_dtype,
                out, final_state, workspace, workspace_bytes_, static_cast<hipStream_t>(stream), nullptr);
+}
+
+int gla_fwd_layout(const void *q, const void *k, const void *v, const float *log_alpha,
+                   int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                   int qkv_dtype, int out_dtype, int layout, const float *initial_state,
+                   void *out, float *final_state,
+                   void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
+    return run(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype, out_dtype,
+               out, final_state, workspace, workspace_bytes_, static_cast<hipStream_t>(stream), nullptr,
+               layout, initial_state);
 }
 
 int gla_fwd(const void *q, const void *k, const void *v, const float *log_alpha,

@@ -3,7 +3,7 @@
 // Every span r has produced, from a zero state, its local state U_r and
 // log Gamma_r (the summed log_alpha of its tokens).  Because the recurrence of
 // Sec. 3.1 Eq. (attn_gla) is linear in S, the state entering span r+1 is
-//     S_start(r+1) = diag(Gamma_r) S_start(r) + U_r ,   S_start(0) = 0.
+//     S_start(r+1) = diag(Gamma_r) S_start(r) + U_r ,   S_start(0) = the caller's initial state (or 0).
 // Each of the dk*dv state elements is an independent scalar recurrence over the
 // spans; the buffer is rewritten in place (U_r becomes S_start(r)) and the value
 // after the last span is the final state.
@@ -37,7 +37,8 @@ __global__ __launch_bounds__(kCarryThreads) void carry_kernel(Params p) {
     float *st = p.ws_state + (size_t)bh * p.nspans * ne + e;
     const float *lg = p.ws_lgam + (size_t)bh * p.nspans * p.dk + c;
 
-    float carry = 0.f;  // state entering the current pass of kGroups * kRun spans
+    // state entering the current pass of kGroups * kRun spans; the first pass starts from the caller's state
+    float carry = p.initial_state ? p.initial_state[(size_t)bh * ne + e] : 0.f;
     for (int r0 = 0; r0 < p.nspans; r0 += kGroups * kRun) {
         const int first = r0 + grp * kRun;
         float u[kRun], gam[kRun];

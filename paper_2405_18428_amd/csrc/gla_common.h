@@ -33,6 +33,10 @@ struct Params {
     const float *log_alpha;
     void *out;
     float *final_state;     // may be null
+    const float *initial_state;  // [B*H, dk, dv] state before the first scan step, or null (zero)
+    // element strides of the [B,H,T,d] tensors: q, k, log_alpha (suffix k) and v, out (suffix v)
+    long long sb_k, sh_k, sb_v, sh_v;   // batch, head
+    int st_k, st_v;                     // token (row) stride
     float *ws_state;        // [B*H, nspans, dk, dv]  U_r after phase 1, S_start(r) after phase 2
     float *ws_lgam;         // [B*H, nspans, dk]      log Gamma_r
     int B, H, T, dk, dv, grid_h, grid_w, scan_dir;
@@ -65,6 +69,14 @@ __host__ __device__ inline uint16_t float_to_bf16_bits(float f) {
     if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
+}
+
+// Element offset of the (batch, head) slab `bh` in the dk-sized / dv-sized tensors.
+__host__ __device__ inline size_t slab_k(const Params &p, int bh) {
+    return (size_t)(bh / p.H) * (size_t)p.sb_k + (size_t)(bh % p.H) * (size_t)p.sh_k;
+}
+__host__ __device__ inline size_t slab_v(const Params &p, int bh) {
+    return (size_t)(bh / p.H) * (size_t)p.sb_v + (size_t)(bh % p.H) * (size_t)p.sh_v;
 }
 
 // Launchers (defined in the .hip files); each enqueues on `stream` and returns

@@ -231,11 +231,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     const int nch = (s_end - s_begin + kChunk - 1) / kChunk;
 
     // per-(batch, head) bases; everything below is a 32-bit byte offset from them
-    const char *gq = static_cast<const char *>(p.q) + (size_t)bh * T * dk * 2;
-    const char *gk = static_cast<const char *>(p.k) + (size_t)bh * T * dk * 2;
-    const char *gv = static_cast<const char *>(p.v) + (size_t)bh * T * dv * 2;
-    const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + (size_t)bh * T * dk * 4;
-    char *gout = static_cast<char *>(p.out) + (size_t)bh * T * dv * sizeof(TOut);
+    const size_t base_k = slab_k(p, bh), base_v = slab_v(p, bh);
+    const char *gq = static_cast<const char *>(p.q) + base_k * 2;
+    const char *gk = static_cast<const char *>(p.k) + base_k * 2;
+    const char *gv = static_cast<const char *>(p.v) + base_v * 2;
+    const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + base_k * 4;
+    char *gout = static_cast<char *>(p.out) + base_v * sizeof(TOut);
 
     // ---- state tiles owned by this wave (TileMap) ----
     f32x4 acc[TPW];
@@ -247,7 +248,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     // s <- Gamma_r s + U_r over r on 4 consecutive state elements per thread (one key channel: dv % 4 == 0),
     // kRun spans loaded at a time; the result goes through LDS into the MFMA accumulator layout.
     if constexpr (OUT) {
-        const bool chain = p.chain_in_output && sp > 0;  // uniform over the work-group
+        const bool chain = p.chain_in_output && (sp > 0 || p.initial_state != nullptr);  // uniform over the group
         if (chain) {
             constexpr int kV4 = (L::kDkp * L::kDvp / 4 + NTHR - 1) / NTHR;  // float4 per thread
             constexpr int kBudget = MINW >= 4 ? 16 : 32;                    // float4 in flight: 64 or 128 registers of U
@@ -263,7 +264,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             }
             f32x4 st[kV4];
 #pragma unroll
-            for (int m = 0; m < kV4; ++m) st[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int m = 0; m < kV4; ++m) {
+                st[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (p.initial_state != nullptr)
+                    st[m] = *reinterpret_cast<const f32x4 *>(p.initial_state + (size_t)bh * ne + 4 * e4[m]);
+            }
             for (int r0 = 0; r0 < sp; r0 += kRun) {
                 f32x4 u[kRun][kV4];
                 float lg[kRun][kV4];
@@ -321,9 +326,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     }
     __syncthreads();
 
-    // ---- or the state entering the span as the carry kernel left it ----
-    if (OUT && p.nspans > 1 && !p.chain_in_output) {
-        const float *s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
+    // ---- or the state entering the span as the carry kernel left it (single span: the caller's state) ----
+    const float *s0 = nullptr;
+    if (OUT && p.nspans > 1 && !p.chain_in_output)
+        s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
+    else if (OUT && p.nspans == 1 && p.initial_state != nullptr)
+        s0 = p.initial_state + (size_t)bh * dk * dv;
+    if (s0 != nullptr) {
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             if (TM::valid(w, i)) {
@@ -357,7 +366,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     const int rid = tid - 64 * (NW - prem), vrid = tid - 64 * (NW - vrem);
     const int rrow = has_rem ? rid / prem : 0, rch = has_rem ? 4 * (nslots * PPS + rid % prem) : 0;
     const int vrrow = has_vrem ? vrid / vrem : 0, vrcol = has_vrem ? 8 * (nvslots * PPS + vrid % vrem) : 0;
-    const uint32_t dk2 = 2u * (uint32_t)dk, dv2 = 2u * (uint32_t)dv;
+    const uint32_t dk2 = 2u * (uint32_t)p.st_k, dv2 = 2u * (uint32_t)p.st_v;  // bytes from one bf16 row to the next
 
     f32x4 r_la[DEPTH][kSlots + 1];
     u32x2 r_k[DEPTH][kSlots + 1];
@@ -779,7 +788,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 const int row = 16 * IT + lm;
                 if (row < nvalid) {
                     const int col0 = 4 * g;
-                    char *orow = gout + ((uint32_t)tok[row] * (uint32_t)dv + (uint32_t)col0) * (uint32_t)sizeof(TOut);
+                    char *orow = gout + ((uint32_t)tok[row] * (uint32_t)p.st_v + (uint32_t)col0) * (uint32_t)sizeof(TOut);
 #pragma unroll
                     for (int x = 0; x < NX; ++x) {
                         if (col0 + 16 * x < dv) {  // dv is a multiple of 8: all four columns or none
@@ -915,8 +924,8 @@ hipError_t launch_mode(const Params &p, hipStream_t stream) {
 }  // namespace
 
 bool mfma_engine_supports(const Params &p) {
-    // 32-bit byte offsets inside one (batch, head) slab
-    const long long slab = (long long)p.T * (p.dk > p.dv ? p.dk : p.dv) * 4;
+    // 32-bit byte offsets inside the view of one (batch, head)
+    const long long slab = (long long)p.T * (p.st_k > p.st_v ? p.st_k : p.st_v) * 4;
     return p.qkv_dtype == GLA_DT_BF16 && p.dk % 4 == 0 && p.dv % 8 == 0 && p.dk <= kMaxDk && p.dv <= kMaxDv &&
            slab < (1LL << 31);
 }

@@ -45,15 +45,20 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
     const int dk = p.dk, dv = p.dv, T = p.T;
     const int s_begin = sp * p.span_len;
     const int s_end = min(T, s_begin + p.span_len);
-    const size_t base_k = (size_t)bh * T * dk;
-    const size_t base_v = (size_t)bh * T * dv;
+    const size_t base_k = slab_k(p, bh), base_v = slab_v(p, bh);
+    const size_t st_k = (size_t)p.st_k, st_v = (size_t)p.st_v;
     const bool col_active = tid < dv;
 
     float S[kMaxDk];
 #pragma unroll
     for (int c = 0; c < kMaxDk; ++c) S[c] = 0.f;
-    if (MODE == kModeOutput && p.nspans > 1 && col_active) {
-        const float *s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
+    // state entering the span: from the carry kernel, or (single span) the caller's initial state
+    const float *s0 = nullptr;
+    if (MODE == kModeOutput && p.nspans > 1)
+        s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
+    else if (MODE == kModeOutput && p.initial_state != nullptr)
+        s0 = p.initial_state + (size_t)bh * dk * dv;
+    if (s0 != nullptr && col_active) {
 #pragma unroll
         for (int c = 0; c < kMaxDk; ++c)
             if (c < dk) S[c] = s0[(size_t)c * dv + tid];
@@ -75,7 +80,7 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
             for (int j = sj; j < kTile; j += 2) {
                 int n = s_tok[j];
                 if (n >= 0) {
-                    size_t e = base_k + (size_t)n * dk + sc;
+                    size_t e = base_k + (size_t)n * st_k + sc;
                     float g = p.log_alpha[e];
                     lsum += g;
                     s_a[j][sc] = expf(g);
@@ -87,7 +92,7 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
         for (int idx = tid; idx < kTile * dv; idx += kThreads) {
             int j = idx / dv, n2 = idx - j * dv;
             int n = s_tok[j];
-            if (n >= 0) s_v[j][n2] = load_elem<TIn>(p.v, base_v + (size_t)n * dv + n2);
+            if (n >= 0) s_v[j][n2] = load_elem<TIn>(p.v, base_v + (size_t)n * st_v + n2);
         }
         __syncthreads();
         if (col_active) {
@@ -103,7 +108,7 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
                         if (MODE == kModeOutput) o = fmaf(s_q[j][c], S[c], o);
                     }
                 }
-                if (MODE == kModeOutput) store_elem<TOut>(p.out, base_v + (size_t)n * dv + tid, o);
+                if (MODE == kModeOutput) store_elem<TOut>(p.out, base_v + (size_t)n * st_v + tid, o);
             }
         }
     }

@@ -63,6 +63,10 @@ def test_argument_validation_needs_no_gpu():
     assert call(ok_ptr, 4, 2, 2, 8, 8, 4) == 2        # bad scan order
     assert call(ok_ptr, 4, 2, 2, 65, 8, 0) == 3       # dk too large
     assert call(ok_ptr, 4, 2, 2, 8, 129, 0) == 3      # dv too large
+    lay = lambda layout, init: lib.gla_fwd_layout(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 1, 1, 4, 8, 8, 2, 2, 0, 1, 0,
+                                                  layout, init, ok_ptr, None, ok_ptr, 1 << 20, None)
+    assert lay(2, None) == 2                          # unknown memory order
+    assert lay(1, vp(4100)) == 4                      # initial state not 16-byte aligned
     assert call(vp(4100), 4, 2, 2, 8, 8, 0) == 4      # misaligned
     # gla_fwd_ex: missing / short workspace
     r = lib.gla_fwd_ex(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 1, 1, 4, 8, 8, 2, 2, 0, 1, 0, ok_ptr, None, None, 0, None)
