@@ -1,4 +1,4 @@
-"""CPU fp64 oracle for the GLA token-mixer forward pass of DiG.
+"""CPU fp64 oracle for the GLA token mixer of DiG (forward pass, and its reverse-mode derivative).
 
 TEST INFRASTRUCTURE ONLY.  Only the tests, the smoke check and the
 ``cpu_baseline`` leg of the benchmark may import this module; the product
@@ -34,15 +34,17 @@ SCAN_NAMES = {0: "row_fwd", 1: "row_rev", 2: "col_fwd", 3: "col_rev"}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gla_oracle.c")
+_SRC_BWD = os.path.join(_HERE, "gla_oracle_bwd.c")
 _LIB = os.path.join(_HERE, "libgla_oracle.so")
 _lib = None
 
 
 def build(force: bool = True) -> str:
-    """Compile gla_oracle.c with gcc (-O2, no fast-math, OpenMP over b*h)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    """Compile gla_oracle.c and gla_oracle_bwd.c with gcc (-O2, no fast-math, OpenMP over b*h)."""
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_BWD))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp",
-               "-o", _LIB, _SRC, "-lm"]
+               "-o", _LIB, _SRC, _SRC_BWD, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -55,6 +57,8 @@ def _load():
         dp = ctypes.POINTER(ctypes.c_double)
         lib.gla_oracle_fwd.restype = ctypes.c_int
         lib.gla_oracle_fwd.argtypes = [dp, dp, dp, dp, dp] + [ctypes.c_int] * 8 + [dp, dp, ctypes.c_int]
+        lib.gla_oracle_bwd.restype = ctypes.c_int
+        lib.gla_oracle_bwd.argtypes = [dp] * 5 + [ctypes.c_int] * 8 + [dp] * 4 + [ctypes.c_int]
         lib.gla_oracle_scan_index.restype = ctypes.c_long
         lib.gla_oracle_scan_index.argtypes = [ctypes.c_int, ctypes.c_long, ctypes.c_int, ctypes.c_int]
         lib.gla_oracle_threads.restype = ctypes.c_int
@@ -120,6 +124,33 @@ def gla_fwd(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD,
     if rc != 0:
         raise ValueError("gla_oracle_fwd rejected its arguments")
     return out, fin
+
+
+def gla_bwd(q, k, v, log_alpha, d_out, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, nthreads=0):
+    """fp64 reverse-mode derivative of :func:`gla_fwd` (zero initial state, loss depending on ``out`` only),
+    one scan step at a time (C loop nest of ``gla_oracle_bwd.c``).
+
+    d_out: [B,H,T,dv] = dL/d out.  Returns (dq, dk, dv, dlog_alpha) as float64 arrays shaped like the inputs.
+    """
+    q = np.asarray(q)
+    B, H, T, dk = q.shape
+    dv = np.asarray(v).shape[-1]
+    q = _as_f64(q, (B, H, T, dk))
+    k = _as_f64(k, (B, H, T, dk))
+    g = _as_f64(log_alpha, (B, H, T, dk))
+    v = _as_f64(v, (B, H, T, dv))
+    do = _as_f64(d_out, (B, H, T, dv))
+    dq = np.empty((B, H, T, dk), dtype=np.float64)
+    dk_ = np.empty((B, H, T, dk), dtype=np.float64)
+    dg = np.empty((B, H, T, dk), dtype=np.float64)
+    dv_ = np.empty((B, H, T, dv), dtype=np.float64)
+    dp = ctypes.POINTER(ctypes.c_double)
+    p = lambda a: a.ctypes.data_as(dp)
+    rc = _load().gla_oracle_bwd(p(q), p(k), p(v), p(g), p(do), B, H, T, dk, dv, grid_h, grid_w, scan_dir,
+                                p(dq), p(dk_), p(dv_), p(dg), int(nthreads))
+    if rc != 0:
+        raise ValueError("gla_oracle_bwd rejected its arguments")
+    return dq, dk_, dv_, dg
 
 
 def threads() -> int:
