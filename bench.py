@@ -50,6 +50,76 @@ def measured_traffic(config_name, kernel, args):
     return None
 
 
+def bench_backward(args, cfg, d, gla, gi, torch, np):
+    """gla_bwd on the workload: whole-call timing over rotating buffer sets, oracle timing, parity figure."""
+    dev = torch.device("cuda:0")
+    B, H, T, dk, dv = cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv
+    rng = np.random.Generator(np.random.PCG64(cfg.seed + 1000))
+    w = rng.standard_normal((B, H, T, dv), dtype=np.float32)
+    bf16 = cfg.dtype == "bf16"
+    if bf16:
+        w_bits = gi.round_to_bf16_bits(w)
+        w = gi.bf16_bits_to_f32(w_bits)
+        to = lambda bits: torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16)
+        host = [to(d["q_bits"]), to(d["k_bits"]), to(d["v_bits"]), torch.from_numpy(d["log_alpha"]), to(w_bits)]
+    else:
+        host = [torch.from_numpy(d[n]) for n in ("q", "k", "v", "log_alpha")] + [torch.from_numpy(w)]
+    qdt = gla.DT_BF16 if bf16 else gla.DT_F32
+    ws_bytes = gla.gla_bwd_workspace_bytes(B, H, T, dk, dv, qdt)
+    sets = []
+    for _ in range(max(1, args.sets)):
+        sets.append([t.to(dev) for t in host] + [torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)])
+
+    def step(i):
+        q, k, v, la, do, ws = sets[i % len(sets)]
+        return gla.gla_bwd(q, k, v, la, do, cfg.grid_h, cfg.grid_w, args.scan, workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    qb = 2 if bf16 else 4
+    # q, k, v, d_out and log_alpha read once; dq, dk, dlog_alpha, dv (fp32) written once
+    alg_bytes = (2 * dk * qb + 2 * dv * qb + dk * 4 + 3 * dk * 4 + dv * 4) * B * H * T
+    achieved = alg_bytes / (ms * 1e-3) / 1e9
+    result = {
+        "metric": "GLA bwd tokens/s at DiG-XL/2 shape T=16384", "value": round(B * T / (ms * 1e-3), 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} backward: B={B} H={H} T={T} ({cfg.grid_h}x{cfg.grid_w}) dk={dk} dv={dv} "
+                               f"{cfg.dtype} q/k/v/d_out, fp32 log_alpha, fp32 gradients, scan={args.scan}",
+                   "buffer_sets": len(sets)},
+        "roofline": {"bound": "hbm", "kernel": "whole_call", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes": alg_bytes, "kernel_ms": round(ms, 5)},
+    }
+    if not args.no_check or not args.no_cpu_baseline:
+        from oracle import gla_oracle
+        c0 = time.perf_counter()
+        ref = gla_oracle.gla_bwd(d["q"], d["k"], d["v"], d["log_alpha"], w, cfg.grid_h, cfg.grid_w, args.scan)
+        c1 = time.perf_counter()
+        if not args.no_cpu_baseline:
+            result["cpu_baseline"] = {"value": round(B * T / (c1 - c0), 1), "unit": "tokens/s",
+                                      "cores": min(gla_oracle.threads(), B * H), "kind": "oracle",
+                                      "sample": f"the whole workload ({B * H} sequences of {T} tokens), one run, "
+                                                "fp64 step-by-step reverse-mode C loop, OpenMP over batch*head"}
+        if not args.no_check:
+            got = step(0)
+            torch.cuda.synchronize()
+            floors = [0.0, 0.0, 0.0, float(np.sqrt(np.mean((d["q"].astype(np.float64) * ref[0]) ** 2)))]
+            errs = []
+            for g, r, f in zip(got, ref, floors):
+                rms = max(float(np.sqrt(np.mean(r ** 2))), f)
+                errs.append(float(np.abs(g.cpu().numpy() - r).max() / rms))
+            result["max_err_over_rms"] = round(max(errs), 6)
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +131,8 @@ def main():
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated over (1 = cache-warm)")
     ap.add_argument("--chunks-per-span", type=int, default=0)
     ap.add_argument("--engine", type=int, default=0)
+    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd"],
+                    help="fwd: the forward hot path (the headline); bwd: gla_bwd on the same workload")
     ap.add_argument("--layout", default="bhtd", choices=["bhtd", "bthd"],
                     help="memory order of q, k, v, log_alpha, out: [B,H,T,d] (the headline) or [B,T,H,d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -92,6 +164,9 @@ def main():
     cfg = gi.CONFIGS[args.config]
     dev = torch.device("cuda:0")
     d = gi.make_config_inputs(cfg)
+    if args.which == "bwd":
+        bench_backward(args, cfg, d, gla, gi, torch, np)
+        return
     B, H, T, dk, dv = cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv
     if cfg.dtype == "bf16":
         host = [torch.from_numpy(d[n + "_bits"].view(np.int16)).view(torch.bfloat16) for n in ("q", "k", "v")]

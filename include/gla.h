@@ -152,6 +152,28 @@ int gla_fwd_layout(const void *q, const void *k, const void *v, const float *log
                    void *out, float *final_state,
                    void *workspace, size_t workspace_bytes, gla_stream_t stream);
 
+/*
+ * gla_bwd - gradients of a scalar loss L that depends on `out` of gla_fwd_ex (zero initial
+ * state, [B,H,T,d] order) with respect to q, k, v and log_alpha: Eq. (attn_gla) rows 1-3
+ * differentiated in reverse mode.  With S_s the state after scan step s and
+ * G_s = q_s^T dO_s + diag(alpha_{s+1}) G_{s+1} the gradient that reaches it:
+ *   dq_s = S_s dO_s^T,  dk_s = G_s v_s^T,  dv_s = k_s G_s,
+ *   dlog_alpha_s = sum over scan steps s' >= s of (q_s' * dq_s' - k_s' * dk_s').
+ *
+ *   q, k, v, d_out   DEVICE, qkv_dtype (d_out = dL/d out, shaped like v)              (read)
+ *   log_alpha        DEVICE, fp32                                                     (read)
+ *   dq, dk_grad, dlog_alpha   DEVICE, fp32 [B,H,T,dk];  dv_grad  DEVICE, fp32 [B,H,T,dv]   (written)
+ *   workspace        DEVICE, 16-byte aligned, at least gla_bwd_workspace_bytes(...) bytes
+ *
+ * Same status codes as gla_fwd_ex; GLA_ERR_UNSUPPORTED also for bf16 inputs with an odd dv.
+ * Never allocates.
+ */
+int gla_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const void *d_out,
+            int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir, int qkv_dtype,
+            float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha,
+            void *workspace, size_t workspace_bytes, gla_stream_t stream);
+size_t gla_bwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);
+
 /* Bytes of workspace gla_fwd_ex / gla_fwd_layout need for this problem (an upper bound over all
  * launch plans, so it does not depend on tuning options).  0 on invalid sizes. */
 size_t gla_fwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);

@@ -59,6 +59,10 @@ def load_library():
     lib.gla_fwd_ex.argtypes = [vp, vp, vp, vp] + shape + [i, i, vp, vp, vp, sz, vp]
     lib.gla_fwd_layout.restype = i
     lib.gla_fwd_layout.argtypes = [vp, vp, vp, vp] + shape + [i, i, i, vp, vp, vp, vp, sz, vp]
+    lib.gla_bwd.restype = i
+    lib.gla_bwd.argtypes = [vp] * 5 + shape + [i] + [vp] * 4 + [vp, sz, vp]
+    lib.gla_bwd_workspace_bytes.restype = sz
+    lib.gla_bwd_workspace_bytes.argtypes = [i] * 6
     lib.gla_fwd_timed.restype = i
     lib.gla_fwd_timed.argtypes = [vp, vp, vp, vp] + shape + [i, i, vp, vp, vp, sz, vp, i, fp]
     lib.gla_fwd_workspace_bytes.restype = sz
@@ -224,6 +228,33 @@ def gla_fwd_layout(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, la
                                   out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
                                   workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return out, final_state
+
+
+def gla_bwd_workspace_bytes(B, H, T, dk, dv, qkv_dtype=DT_BF16) -> int:
+    return int(load_library().gla_bwd_workspace_bytes(B, H, T, dk, dv, qkv_dtype))
+
+
+def gla_bwd(q, k, v, log_alpha, d_out, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, workspace=None, stream=None):
+    """Gradients (dq, dk, dv, dlog_alpha), all fp32, of a loss with upstream gradient ``d_out`` = dL/d out.
+    q, k, v, d_out share one element type (bf16 or fp32); [B,H,T,d] order."""
+    torch = _torch()
+    lib = load_library()
+    B, H, T, dk, dv = _prep(q, k, v, log_alpha, grid_h, grid_w)
+    if d_out.shape != v.shape or d_out.dtype != v.dtype or not d_out.is_cuda or not d_out.is_contiguous():
+        raise ValueError("d_out must be a contiguous GPU tensor shaped and typed like v")
+    qdt = _dt(q)
+    f32 = dict(dtype=torch.float32, device=q.device)
+    dq, dk_ = torch.empty((B, H, T, dk), **f32), torch.empty((B, H, T, dk), **f32)
+    dg, dv_ = torch.empty((B, H, T, dk), **f32), torch.empty((B, H, T, dv), **f32)
+    if workspace is None:
+        nbytes = gla_bwd_workspace_bytes(B, H, T, dk, dv, qdt)
+        workspace = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=q.device)
+    with torch.cuda.device(q.device):
+        _check(lib.gla_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(), d_out.data_ptr(),
+                           B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt,
+                           dq.data_ptr(), dk_.data_ptr(), dv_.data_ptr(), dg.data_ptr(),
+                           workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return dq, dk_, dv_, dg
 
 
 def gla_fwd_timed(q, k, v, log_alpha, grid_h, grid_w, scan_dir, out, final_state,

@@ -74,6 +74,95 @@ int plan_chunks_per_span(int bh, int nchunks, bool mfma_engine) {
     return cps;
 }
 
+// Engine for the span passes (p.qkv_dtype, sizes and strides must be set) and the span plan with its workspace.
+int choose_engine_and_plan(Params &p, void *workspace, bool &use_mfma) {
+    if (g_opt_engine == GLA_ENGINE_RECURRENT) {
+        use_mfma = false;
+    } else if (g_opt_engine == GLA_ENGINE_MFMA) {
+        if (!mfma_engine_supports(p)) return GLA_ERR_UNSUPPORTED;
+        use_mfma = true;
+    } else {
+        use_mfma = mfma_engine_supports(p);
+    }
+    const int nchunks = (p.T + kChunk - 1) / kChunk;
+    const int cps = plan_chunks_per_span(p.B * p.H, nchunks, use_mfma);
+    p.span_len = cps * kChunk;
+    p.nspans = (nchunks + cps - 1) / cps;
+    const size_t bh = (size_t)p.B * p.H;
+    p.ws_state = static_cast<float *>(workspace);
+    p.ws_lgam = reinterpret_cast<float *>(static_cast<char *>(workspace) +
+                                          align_up(bh * p.nspans * p.dk * p.dv * sizeof(float), 256));
+    return GLA_OK;
+}
+
+void set_dense_bhtd_strides(Params &p) {
+    p.st_k = p.dk; p.sh_k = (long long)p.T * p.dk; p.sb_k = (long long)p.H * p.T * p.dk;
+    p.st_v = p.dv; p.sh_v = (long long)p.T * p.dv; p.sb_v = (long long)p.H * p.T * p.dv;
+}
+
+size_t bwd_totals_bytes(int B, int H, int T, int dk) {
+    return align_up((size_t)B * H * dg_spans(T) * dk * sizeof(float), 256);
+}
+
+// Backward pass (see gla_bwd_kernels.hip for the formulas): three walks over the sequence on the span plan of
+// the forward pass, then the reverse cumulative sum for the gate gradient.
+int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const void *d_out,
+            int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir, int qkv_dtype,
+            float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha,
+            void *workspace, size_t ws_bytes, hipStream_t stream) {
+    if (!d_out || !dq || !dk_grad || !dv_grad || !dlog_alpha) return GLA_ERR_NULL;
+    int st = validate(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir,
+                      qkv_dtype, GLA_DT_F32, dv_grad, nullptr);
+    if (st != GLA_OK) return st;
+    if (misaligned(d_out) || misaligned(dq) || misaligned(dk_grad) || misaligned(dlog_alpha)) return GLA_ERR_ALIGN;
+    // the row-read kernel fetches rows of v and d_out with scalar dword loads
+    if (qkv_dtype == GLA_DT_BF16 && (dv & 1)) return GLA_ERR_UNSUPPORTED;
+    const size_t state_bytes = workspace_bytes(B, H, T, dk, dv);
+    if (!workspace || misaligned(workspace) || ws_bytes < state_bytes + bwd_totals_bytes(B, H, T, dk))
+        return GLA_ERR_WORKSPACE;
+    float *totals = reinterpret_cast<float *>(static_cast<char *>(workspace) + state_bytes);
+
+    Params base{};
+    base.B = B; base.H = H; base.T = T; base.dk = dk; base.dv = dv;
+    base.grid_h = grid_h; base.grid_w = grid_w;
+    base.qkv_dtype = qkv_dtype; base.out_dtype = GLA_DT_F32;
+    set_dense_bhtd_strides(base);
+    bool use_mfma;
+    st = choose_engine_and_plan(base, workspace, use_mfma);
+    if (st != GLA_OK) return st;
+    base.chain_in_output = 0;   // the row-read kernel takes the state entering its span from the carry kernel
+    auto span = [&](const Params &p, SpanMode mode) {
+        return use_mfma ? launch_mfma_span(p, mode, stream) : launch_recurrent_span(p, mode, stream);
+    };
+    auto states = [&](const Params &p) {   // span-local states, then chained in place
+        if (p.nspans <= 1) return hipSuccess;
+        hipError_t e = span(p, kModeState);
+        if (e != hipSuccess) return e;
+        return launch_carry(p, stream);
+    };
+
+    // 1. states of the forward recurrence (k, v, log_alpha); dq_s = S_s dO_s
+    Params pa = base;
+    pa.k = k; pa.v = v; pa.log_alpha = log_alpha; pa.scan_dir = scan_dir; pa.gate_shift = 0;
+    if (states(pa) != hipSuccess) return GLA_ERR_HIP;
+    if (launch_row_read(pa, d_out, dq, stream) != hipSuccess) return GLA_ERR_HIP;
+
+    // 2. states of the reversed recurrence G_s = q_s^T dO_s + diag(alpha_{s+1}) G_{s+1}: the forward recurrence
+    //    with k, v := q, dO, walked from the last scan step, each step using the previous step's gate
+    Params pb = base;
+    pb.q = k; pb.k = q; pb.v = d_out; pb.log_alpha = log_alpha; pb.scan_dir = scan_dir ^ 1; pb.gate_shift = 1;
+    pb.out = dv_grad;
+    if (states(pb) != hipSuccess) return GLA_ERR_HIP;
+    if (span(pb, kModeOutput) != hipSuccess) return GLA_ERR_HIP;             // dv_s = k_s G_s
+    if (launch_row_read(pb, v, dk_grad, stream) != hipSuccess) return GLA_ERR_HIP;   // dk_s = G_s v_s
+
+    // 3. dlog_alpha = reverse cumulative sum of q * dq - k * dk along the scan
+    Params pc = base;
+    pc.q = q; pc.k = k; pc.scan_dir = scan_dir;
+    if (launch_dlog_alpha(pc, dq, dk_grad, dlog_alpha, totals, stream) != hipSuccess) return GLA_ERR_HIP;
+    return GLA_OK;
+}
+
 struct PhaseEvents {
     hipEvent_t ev[4];
 };
@@ -106,23 +195,8 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     }
 
     bool use_mfma;
-    if (g_opt_engine == GLA_ENGINE_RECURRENT) {
-        use_mfma = false;
-    } else if (g_opt_engine == GLA_ENGINE_MFMA) {
-        if (!mfma_engine_supports(p)) return GLA_ERR_UNSUPPORTED;
-        use_mfma = true;
-    } else {
-        use_mfma = mfma_engine_supports(p);
-    }
-
-    const int nchunks = (T + kChunk - 1) / kChunk;
-    const int cps = plan_chunks_per_span(B * H, nchunks, use_mfma);
-    p.span_len = cps * kChunk;
-    p.nspans = (nchunks + cps - 1) / cps;
-    const size_t bh = (size_t)B * H;
-    p.ws_state = static_cast<float *>(workspace);
-    p.ws_lgam = reinterpret_cast<float *>(static_cast<char *>(workspace) +
-                                          align_up(bh * p.nspans * dk * dv * sizeof(float), 256));
+    st = choose_engine_and_plan(p, workspace, use_mfma);
+    if (st != GLA_OK) return st;
     auto span = [&](SpanMode mode) {
         return use_mfma ? launch_mfma_span(p, mode, stream) : launch_recurrent_span(p, mode, stream);
     };
@@ -175,6 +249,20 @@ int gla_fwd_layout(const void *q, const void *k, const void *v, const float *log
     return run(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype, out_dtype,
                out, final_state, workspace, workspace_bytes_, static_cast<hipStream_t>(stream), nullptr,
                layout, initial_state);
+}
+
+int gla_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const void *d_out,
+            int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir, int qkv_dtype,
+            float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha,
+            void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
+    return run_bwd(q, k, v, log_alpha, d_out, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype,
+                   dq, dk_grad, dv_grad, dlog_alpha, workspace, workspace_bytes_, static_cast<hipStream_t>(stream));
+}
+
+size_t gla_bwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype) {
+    if (B <= 0 || H <= 0 || T <= 0 || dk <= 0 || dv <= 0) return 0;
+    if (qkv_dtype != GLA_DT_F32 && qkv_dtype != GLA_DT_BF16) return 0;
+    return workspace_bytes(B, H, T, dk, dv) + bwd_totals_bytes(B, H, T, dk);
 }
 
 int gla_fwd(const void *q, const void *k, const void *v, const float *log_alpha,

@@ -42,6 +42,8 @@ struct Params {
     int B, H, T, dk, dv, grid_h, grid_w, scan_dir;
     int nspans;             // spans per (batch, head)
     int span_len;           // tokens per span, a multiple of kChunk
+    int gate_shift;         // 1: scan step s uses the log_alpha row of the token visited at step s-1 (the
+                            //    reverse-mode recurrence dS_s = diag(alpha_{s+1}) dS_{s+1} + q_s^T dO_s walked backwards)
     int chain_in_output;    // 1: no phase-2 kernel; the output pass chains U_0..U_{r-1} itself and phase 1
                             //    skips the last span of every (batch, head) (nobody reads its U)
     int qkv_dtype, out_dtype;
@@ -85,5 +87,11 @@ hipError_t launch_recurrent_span(const Params &p, SpanMode mode, hipStream_t str
 hipError_t launch_mfma_span(const Params &p, SpanMode mode, hipStream_t stream);
 hipError_t launch_carry(const Params &p, hipStream_t stream);
 bool mfma_engine_supports(const Params &p);
+// backward-only kernels: r_s[c] = sum_n S_s[c,n] w_s[n] over the states of (p.k, p.v, p.log_alpha); and
+// dlog_alpha = reverse cumulative sum of q * dq - k * dk (totals: [B*H, dg_spans(T), dk] floats of scratch)
+hipError_t launch_row_read(const Params &p, const void *w, float *r, hipStream_t stream);
+hipError_t launch_dlog_alpha(const Params &p, const float *dq, const float *dk_grad, float *dg, float *totals,
+                             hipStream_t stream);
+int dg_spans(int T);
 
 }  // namespace gla

@@ -124,8 +124,9 @@ struct Layout {
     static constexpr int kV = kChunk * kVStride * 2;
     static constexpr int kSt = kDvp * kChStride * 2;
 
-    static constexpr int oTok = 0;                                        // int[3][64] (+ pad)
-    static constexpr int oGam = oTok + 4 * kChunk * 4;                    // float[64]  exp(b_C) of this chunk
+    static constexpr int oTok = 0;                                        // int[4][64] token of each row
+    static constexpr int oTokG = oTok + 4 * kChunk * 4;                   // int[4][64] token whose gate the row uses
+    static constexpr int oGam = oTokG + 4 * kChunk * 4;                   // float[64]  exp(b_C) of this chunk
     static constexpr int oLg = oGam + 64 * 4;                             // float[64]  sum of b_C over the span (base 2)
     static constexpr int oLa = oLg + 64 * 4;                              // raw log_alpha
     static constexpr int oKHi = oLa + kChunk * kLaStride * 4;             // raw k rows, then k~ hi in place
@@ -190,6 +191,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int *s_tok = reinterpret_cast<int *>(smem + L::oTok);
+    int *s_tokg = reinterpret_cast<int *>(smem + L::oTokG);
     float *s_gam = reinterpret_cast<float *>(smem + L::oGam);
     float *s_lg = reinterpret_cast<float *>(smem + L::oLg);
     float *s_la = reinterpret_cast<float *>(smem + L::oLa);
@@ -322,7 +324,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     __syncthreads();
     if (tid < (DEPTH + 1) * kChunk) {
         const int s = s_begin + tid;
-        s_tok[tid] = scan_token(p.scan_dir, (s < s_end) ? s : s_begin, T, p.grid_h, p.grid_w);
+        const int sc = (s < s_end) ? s : s_begin;
+        s_tok[tid] = scan_token(p.scan_dir, sc, T, p.grid_h, p.grid_w);
+        s_tokg[tid] = scan_token(p.scan_dir, max(sc - p.gate_shift, 0), T, p.grid_h, p.grid_w);
     }
     __syncthreads();
 
@@ -378,19 +382,22 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     auto load_chunk = [&](int chunk, auto set_c) {
         constexpr int S = decltype(set_c)::value;
         const int *tok = s_tok + (chunk % NTB) * kChunk;
+        const int *tokg = s_tokg + (chunk % NTB) * kChunk;
         const uint32_t row_k = (uint32_t)tok[prow] * dk2, row_v = (uint32_t)tok[prow] * dv2;
+        const uint32_t row_g = (uint32_t)tokg[prow] * dk2;
 #pragma unroll
         for (int m = 0; m < kSlots; ++m) {
             if (UNCOND || m < nslots) {
-                const uint32_t e2 = row_k + 8u * (uint32_t)min(m * PPS + psub, pcs - 1);
-                r_la[S][m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
+                const uint32_t pc = 8u * (uint32_t)min(m * PPS + psub, pcs - 1);
+                const uint32_t e2 = row_k + pc;
+                r_la[S][m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * (row_g + pc));
                 r_k[S][m] = *reinterpret_cast<const u32x2 *>(gk + e2);
                 if constexpr (OUT) r_q[S][m] = *reinterpret_cast<const u32x2 *>(gq + e2);
             }
         }
         if (UNCOND || has_rem) {
             const uint32_t e2 = (uint32_t)tok[rrow] * dk2 + 2u * (uint32_t)rch;
-            r_la[S][kSlots] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * e2);
+            r_la[S][kSlots] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * ((uint32_t)tokg[rrow] * dk2 + 2u * (uint32_t)rch));
             r_k[S][kSlots] = *reinterpret_cast<const u32x2 *>(gk + e2);
             if constexpr (OUT) r_q[S][kSlots] = *reinterpret_cast<const u32x2 *>(gq + e2);
         }
@@ -479,8 +486,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
         }
         if (w == NW - 1 && (UNCOND || chunk + DEPTH + 1 < nch)) {  // token map of the chunk loaded next time, by the last wave
             const int s = s_begin + (chunk + DEPTH + 1) * kChunk + lane;
-            s_tok[((chunk + DEPTH + 1) % NTB) * kChunk + lane] =
-                scan_token(p.scan_dir, (s < s_end) ? s : s_begin, T, p.grid_h, p.grid_w);
+            const int sc = (s < s_end) ? s : s_begin;
+            s_tok[((chunk + DEPTH + 1) % NTB) * kChunk + lane] = scan_token(p.scan_dir, sc, T, p.grid_h, p.grid_w);
+            s_tokg[((chunk + DEPTH + 1) % NTB) * kChunk + lane] =
+                scan_token(p.scan_dir, max(sc - p.gate_shift, 0), T, p.grid_h, p.grid_w);
         }
         __syncthreads();
 

@@ -38,6 +38,7 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
     __shared__ float s_v[kTile][kMaxDv];
     __shared__ float s_lsum[2][kMaxDk];
     __shared__ int s_tok[kTile];
+    __shared__ int s_tokg[kTile];   // token whose gate the scan step uses (the previous step's with gate_shift)
 
     const int tid = threadIdx.x;
     const int bh = blockIdx.x / p.nspans;
@@ -74,6 +75,7 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
         if (tid < kTile) {
             int s = t0 + tid;
             s_tok[tid] = (s < s_end) ? scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w) : -1;
+            s_tokg[tid] = scan_token(p.scan_dir, max(min(s, s_end - 1) - p.gate_shift, 0), T, p.grid_h, p.grid_w);
         }
         __syncthreads();
         if (sc < dk) {
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
                 int n = s_tok[j];
                 if (n >= 0) {
                     size_t e = base_k + (size_t)n * st_k + sc;
-                    float g = p.log_alpha[e];
+                    float g = p.log_alpha[base_k + (size_t)s_tokg[j] * st_k + sc];
                     lsum += g;
                     s_a[j][sc] = expf(g);
                     s_k[j][sc] = load_elem<TIn>(p.k, e);

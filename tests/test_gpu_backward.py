@@ -1,0 +1,122 @@
+"""GPU parity of gla_bwd against the CPU fp64 backward oracle.  Error metric as for the forward pass: for each
+gradient tensor, max |gpu - oracle| / RMS(oracle) (for the gate gradient RMS(oracle) or RMS(q * dq), whichever is
+larger); bars 2e-2 for bf16 inputs and 1e-4 for fp32 inputs."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import paper_2405_18428_amd as gla
+from paper_2405_18428_amd import inputs as gi
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4
+TOL_BF16 = 2e-2
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    gla.load_library()
+    yield
+    for opt in (gla.OPT_CHUNKS_PER_SPAN, gla.OPT_ENGINE, gla.OPT_CARRY):
+        gla.gla_set_option(opt, 0)
+
+
+@pytest.fixture(autouse=True)
+def _reset_options():
+    for opt in (gla.OPT_CHUNKS_PER_SPAN, gla.OPT_ENGINE, gla.OPT_CARRY):
+        gla.gla_set_option(opt, 0)
+    yield
+
+
+def rel_err(got, ref, floor=0.0):
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = max(np.sqrt(np.mean(ref ** 2)), floor)
+    return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(rms, 1e-300))
+
+
+def make_problem(B, H, gh, gw, dk, dv, dtype, seed):
+    """Forward inputs from the shared generator plus an upstream gradient drawn the same way as v."""
+    T = gh * gw
+    d = gi.make_inputs(B, H, T, dk, dv, dtype, seed=seed)
+    rng = np.random.Generator(np.random.PCG64(seed + 1000))
+    w = rng.standard_normal((B, H, T, dv), dtype=np.float32)
+    if dtype == "bf16":
+        d["w_bits"] = gi.round_to_bf16_bits(w)
+        d["w"] = gi.bf16_bits_to_f32(d["w_bits"])
+    else:
+        d["w"] = w
+    return d
+
+
+def upload(d, name):
+    dev = torch.device("cuda:0")
+    if name != "log_alpha" and d["dtype"] == "bf16":
+        return torch.from_numpy(d[name + "_bits"].view(np.int16)).to(dev).view(torch.bfloat16)
+    return torch.from_numpy(d[name]).to(dev)
+
+
+def check(d, gh, gw, scan, tol):
+    from oracle import gla_oracle
+    ref = gla_oracle.gla_bwd(d["q"], d["k"], d["v"], d["log_alpha"], d["w"], gh, gw, scan)
+    got = gla.gla_bwd(*(upload(d, n) for n in ("q", "k", "v", "log_alpha", "w")), gh, gw, scan)
+    torch.cuda.synchronize()
+    # the gate gradient is a sum of differences q * dq - k * dk that can cancel completely (it is exactly zero at
+    # the first scan step): its error is measured against the size of the terms when the sum itself is smaller
+    floors = [0.0, 0.0, 0.0, float(np.sqrt(np.mean((d["q"].astype(np.float64) * ref[0]) ** 2)))]
+    errs = [rel_err(g.cpu().numpy(), r, f) for g, r, f in zip(got, ref, floors)]
+    print("  scan=%d  err dq=%.3e dk=%.3e dv=%.3e dlog_alpha=%.3e" % (scan, *errs), flush=True)
+    for g in got:
+        assert bool(torch.isfinite(g).all())
+    assert max(errs) <= tol, errs
+
+
+SHAPES = [
+    # B, H, gh, gw, dk, dv, dtype
+    (1, 1, 1, 1, 36, 72, "bf16"),
+    (2, 2, 5, 13, 36, 72, "bf16"),        # one chunk + 1 token
+    (1, 3, 23, 11, 64, 128, "bf16"),      # largest head sizes
+    (2, 2, 9, 21, 32, 64, "bf16"),
+    (1, 2, 17, 19, 40, 96, "bf16"),
+    (1, 2, 12, 11, 33, 66, "bf16"),       # odd dk -> recurrent engine for the span passes
+    (1, 2, 12, 11, 20, 24, "f32"),
+    (2, 1, 20, 20, 64, 128, "f32"),
+    (1, 2, 7, 9, 5, 3, "f32"),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_shapes_all_scans_and_plans(shape):
+    B, H, gh, gw, dk, dv, dtype = shape
+    d = make_problem(B, H, gh, gw, dk, dv, dtype, seed=21)
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16
+    print(f"\nshape={shape}", flush=True)
+    for cps in (0, 1, 2):
+        gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, cps)
+        for scan in range(4):
+            check(d, gh, gw, scan, tol)
+
+
+@pytest.mark.parametrize("name,scan", [("dig_s2_256", 1), ("dig_xl2_512", 2), ("dig_xl2_1024", 0)])
+def test_contract_workloads(name, scan):
+    cfg = gi.CONFIGS[name]
+    d = make_problem(cfg.B, cfg.H, cfg.grid_h, cfg.grid_w, cfg.dk, cfg.dv, cfg.dtype, seed=cfg.seed)
+    print(f"\n{name}", flush=True)
+    check(d, cfg.grid_h, cfg.grid_w, scan, TOL_BF16)
+
+
+def test_headline_shape_long_spans():
+    """DiG-XL/2 at 2048 px: 16384 scan steps, 32 spans per head, 64 spans of the gate-gradient sum."""
+    cfg = gi.CONFIGS["dig_xl2_2048"]
+    d = make_problem(cfg.B, cfg.H, cfg.grid_h, cfg.grid_w, cfg.dk, cfg.dv, cfg.dtype, seed=cfg.seed)
+    check(d, cfg.grid_h, cfg.grid_w, 0, TOL_BF16)
+
+
+def test_odd_value_width_in_bf16_is_refused():
+    d = make_problem(1, 1, 4, 4, 8, 7, "bf16", seed=3)
+    with pytest.raises(gla.GlaError) as ei:
+        gla.gla_bwd(*(upload(d, n) for n in ("q", "k", "v", "log_alpha", "w")), 4, 4, 0)
+    assert ei.value.status == 3
