@@ -165,8 +165,7 @@ int gla_fwd_layout(const void *q, const void *k, const void *v, const float *log
  *   dq, dk_grad, dlog_alpha   DEVICE, fp32 [B,H,T,dk];  dv_grad  DEVICE, fp32 [B,H,T,dv]   (written)
  *   workspace        DEVICE, 16-byte aligned, at least gla_bwd_workspace_bytes(...) bytes
  *
- * Same status codes as gla_fwd_ex; GLA_ERR_UNSUPPORTED also for bf16 inputs with an odd dv.
- * Never allocates.
+ * Same status codes as gla_fwd_ex.  Never allocates.
  */
 int gla_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const void *d_out,
             int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir, int qkv_dtype,

@@ -115,8 +115,6 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
                       qkv_dtype, GLA_DT_F32, dv_grad, nullptr);
     if (st != GLA_OK) return st;
     if (misaligned(d_out) || misaligned(dq) || misaligned(dk_grad) || misaligned(dlog_alpha)) return GLA_ERR_ALIGN;
-    // the row-read kernel fetches rows of v and d_out with scalar dword loads
-    if (qkv_dtype == GLA_DT_BF16 && (dv & 1)) return GLA_ERR_UNSUPPORTED;
     const size_t state_bytes = workspace_bytes(B, H, T, dk, dv);
     if (!workspace || misaligned(workspace) || ws_bytes < state_bytes + bwd_totals_bytes(B, H, T, dk))
         return GLA_ERR_WORKSPACE;

@@ -12,8 +12,7 @@
 // of half of the value columns.  The state entering the span comes from the span
 // plan of the forward pass (span-state pass + carry kernel).
 //
-// The rows v_s and w_s (the vector the state is read with) are the same for all lanes,
-// so they are fetched with scalar loads and feed the vector ALU as scalar operands.
+// (A first, plain-ALU rendering: the chunk form of these reads on the MFMA units is the next step.)
 #include "gla_common.h"
 
 namespace gla {
@@ -22,45 +21,8 @@ namespace {
 constexpr int kTile = 16;          // tokens staged per round
 constexpr int kRowWaves = 2;       // waves per work-group; each owns half of the value columns
 constexpr int kColsPerWave = kMaxDv / kRowWaves;
-constexpr int kColStep = 16;       // value columns whose scalars are in flight at once
 
-typedef const __attribute__((address_space(4))) uint32_t *const_u32;   // constant address space: scalar loads
-typedef const __attribute__((address_space(4))) float *const_f32;
-
-template <typename TIn> struct ScalarRow;
-// 16 neighbouring columns of a bf16 row as 8 uniform dwords
-// (ncols, the number of columns that exist from col0 on, is even for bf16: no dword straddles the row end)
-template <> struct ScalarRow<uint16_t> {
-    uint32_t w[kColStep / 2];
-    __device__ void load(const void *row, int col0, int ncols) {
-        const_u32 p = (const_u32)(uintptr_t)(static_cast<const uint16_t *>(row) + col0);
-        if (ncols >= kColStep) {
-#pragma unroll
-            for (int i = 0; i < kColStep / 2; ++i) w[i] = p[i];
-        } else {
-#pragma unroll
-            for (int i = 0; i < kColStep / 2; ++i) w[i] = (2 * i < ncols) ? p[i] : 0u;
-        }
-    }
-    __device__ float get(int i) const {
-        const uint32_t x = w[i >> 1];
-        return __builtin_bit_cast(float, (i & 1) ? (x & 0xffff0000u) : (x << 16));
-    }
-};
-template <> struct ScalarRow<float> {
-    float w[kColStep];
-    __device__ void load(const void *row, int col0, int ncols) {
-        const_f32 p = (const_f32)(uintptr_t)(static_cast<const float *>(row) + col0);
-        if (ncols >= kColStep) {
-#pragma unroll
-            for (int i = 0; i < kColStep; ++i) w[i] = p[i];
-        } else {
-#pragma unroll
-            for (int i = 0; i < kColStep; ++i) w[i] = (i < ncols) ? p[i] : 0.f;
-        }
-    }
-    __device__ float get(int i) const { return w[i]; }
-};
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 template <typename T> __device__ inline float load_elem(const void *base, size_t idx);
 template <> __device__ inline float load_elem<float>(const void *base, size_t idx) {
@@ -71,12 +33,15 @@ template <> __device__ inline float load_elem<uint16_t>(const void *base, size_t
 }
 
 // r_s[c] = sum_n S_s[c,n] w_s[n] for the scan steps of one span; S follows (p.k, p.v, p.log_alpha).
-// p.q is not used; `w` has the layout of p.v, `r` (fp32) that of p.k.  Scalar loads are dword loads: bf16 rows
-// must start on 4-byte boundaries and have an even number of columns (checked by the host).
+// p.q is not used; `w` has the layout of p.v, `r` (fp32) that of p.k.
+// A tile of kTile tokens is staged in LDS (alpha and k per channel; v and w interleaved in groups of four
+// columns, as fp32), then walked token by token: the rows v_s and w_s are the same for all lanes and are read
+// as broadcasts, 16 bytes of each per ds_read_b128 pair.
 template <typename TIn>
 __global__ __launch_bounds__(kRowWaves * 64) void row_read_kernel(Params p, const void *w, float *r) {
     __shared__ float s_a[kTile][kMaxDk];
     __shared__ float s_k[kTile][kMaxDk];
+    __shared__ __attribute__((aligned(16))) float s_vw[kTile][kMaxDv / 4][8];   // [token][column quad][v0..v3, w0..w3]
     __shared__ float s_r[kRowWaves][kTile][kMaxDk];
     __shared__ int s_tok[kTile];
     __shared__ int s_tokg[kTile];
@@ -91,10 +56,11 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_read_kernel(Params p, cons
     const int s_end = min(T, s_begin + p.span_len);
     const size_t base_k = slab_k(p, bh), base_v = slab_v(p, bh);
     const size_t st_k = (size_t)p.st_k, st_v = (size_t)p.st_v;
-    // columns of this wave: [col_lo, col_hi), walked in steps of kColStep (the last step may be partial)
-    const int per_wave = ((dv + kRowWaves * kColStep - 1) / (kRowWaves * kColStep)) * kColStep;
-    const int col_lo = half * per_wave;
-    const int col_hi = min(dv, col_lo + per_wave);
+    // column quads of this wave: [quad_lo, quad_hi)
+    const int nquads = (dv + 3) / 4;
+    const int per_wave = (nquads + kRowWaves - 1) / kRowWaves;
+    const int quad_lo = half * per_wave;
+    const int quad_hi = min(nquads, quad_lo + per_wave);
     const bool row_active = c < dk;
 
     float S[kColsPerWave];
@@ -104,7 +70,7 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_read_kernel(Params p, cons
         const float *s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv + (size_t)c * dv;
 #pragma unroll
         for (int n = 0; n < kColsPerWave; ++n)
-            if (col_lo + n < col_hi) S[n] = s0[col_lo + n];
+            if (4 * quad_lo + n < dv && n < 4 * (quad_hi - quad_lo)) S[n] = s0[4 * quad_lo + n];
     }
 
     for (int t0 = s_begin; t0 < s_end; t0 += kTile) {
@@ -115,36 +81,39 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_read_kernel(Params p, cons
             s_tokg[tid] = scan_token(p.scan_dir, max(s - p.gate_shift, 0), T, p.grid_h, p.grid_w);
         }
         __syncthreads();
-        // stage alpha and k of the tile: thread (half, c) takes tokens half, half + 2, ...
+        // stage alpha and k of the tile (a step past the span leaves the state alone) ...
         if (row_active) {
             for (int j = half; j < kTile; j += kRowWaves) {
                 const int n = s_tok[j];
-                if (n >= 0) {
-                    s_a[j][c] = expf(p.log_alpha[base_k + (size_t)s_tokg[j] * st_k + c]);
-                    s_k[j][c] = load_elem<TIn>(p.k, base_k + (size_t)n * st_k + c);
-                }
+                s_a[j][c] = n >= 0 ? expf(p.log_alpha[base_k + (size_t)s_tokg[j] * st_k + c]) : 1.f;
+                s_k[j][c] = n >= 0 ? load_elem<TIn>(p.k, base_k + (size_t)n * st_k + c) : 0.f;
             }
+        }
+        // ... and its rows of v and w, zero past dv and past the span
+        for (int idx = tid; idx < kTile * 4 * nquads; idx += kRowWaves * 64) {
+            const int j = idx / (4 * nquads), col = idx - j * 4 * nquads;
+            const int n = s_tok[j];
+            float x = 0.f, y = 0.f;
+            if (n >= 0 && col < dv) {
+                x = load_elem<TIn>(p.v, base_v + (size_t)n * st_v + col);
+                y = load_elem<TIn>(w, base_v + (size_t)n * st_v + col);
+            }
+            s_vw[j][col >> 2][col & 3] = x;
+            s_vw[j][col >> 2][4 + (col & 3)] = y;
         }
         __syncthreads();
         for (int j = 0; j < kTile; ++j) {
-            const int n = __builtin_amdgcn_readfirstlane(s_tok[j]);
-            if (n < 0) break;
             const float a = s_a[j][c], kc = s_k[j][c];
-            const char *vrow = static_cast<const char *>(p.v) + (base_v + (size_t)n * st_v) * sizeof(TIn);
-            const char *wrow = static_cast<const char *>(w) + (base_v + (size_t)n * st_v) * sizeof(TIn);
             float acc = 0.f;
 #pragma unroll
-            for (int n0 = 0; n0 < kColsPerWave; n0 += kColStep) {
-                if (col_lo + n0 < col_hi) {   // uniform
-                    ScalarRow<TIn> vs, ws;
-                    vs.load(vrow, col_lo + n0, col_hi - col_lo - n0);
-                    ws.load(wrow, col_lo + n0, col_hi - col_lo - n0);
+            for (int qd = 0; qd < kColsPerWave / 4; ++qd) {
+                if (quad_lo + qd < quad_hi) {   // uniform
+                    const f32x4 vq = *reinterpret_cast<const f32x4 *>(&s_vw[j][quad_lo + qd][0]);
+                    const f32x4 wq = *reinterpret_cast<const f32x4 *>(&s_vw[j][quad_lo + qd][4]);
 #pragma unroll
-                    for (int i = 0; i < kColStep; ++i) {
-                        if (col_lo + n0 + i < col_hi) {   // uniform
-                            S[n0 + i] = fmaf(a, S[n0 + i], kc * vs.get(i));
-                            acc = fmaf(S[n0 + i], ws.get(i), acc);
-                        }
+                    for (int i = 0; i < 4; ++i) {
+                        S[4 * qd + i] = fmaf(a, S[4 * qd + i], kc * vq[i]);
+                        acc = fmaf(S[4 * qd + i], wq[i], acc);
                     }
                 }
             }
@@ -169,7 +138,7 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_read_kernel(Params p, cons
 // Spans of kDgSpan scan steps.  Kernel 1: inside each span, lane = scan step, a wave scan from the span's last
 // step backwards per channel, written at the canonical token index, and the span's total.  Kernel 2: every
 // span adds the totals of the spans after it.
-constexpr int kDgSpan = 256;       // scan steps per work-group (4 waves of 64 lanes)
+constexpr int kDgSpan = 128;       // scan steps per work-group (2 waves of 64 lanes)
 
 template <int CTRL, int ROW_MASK, bool BOUND>
 __device__ inline float dpp_move(float v) {
@@ -186,38 +155,54 @@ __device__ inline float wave_inclusive_scan(float v) {
     return v;
 }
 
+// Row j of the tile is scan step (span end - 1 - j): prefix sums over j are suffix sums over the scan.
 template <typename TIn>
 __global__ __launch_bounds__(kDgSpan) void dg_local_kernel(Params p, const float *dq, const float *dk_grad,
                                                           float *dg, float *totals, int ndg) {
+    __shared__ float s_x[kDgSpan][kMaxDk + 1];   // odd row length: lane = row accesses hit distinct banks
     __shared__ float s_wave[kDgSpan / 64][kMaxDk];
+    __shared__ int s_tok[kDgSpan];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int bh = blockIdx.x / ndg, sp = blockIdx.x - bh * ndg;
     const int dk = p.dk, T = p.T;
     const size_t base_k = slab_k(p, bh), st_k = (size_t)p.st_k;
-    // thread tid handles scan step s = span end - 1 - tid: prefix sums over tid are suffix sums over s
     const int s_last = min(T, (sp + 1) * kDgSpan) - 1;
-    const int s = s_last - tid;
-    const bool valid = s >= sp * kDgSpan;
-    const int n = scan_token(p.scan_dir, valid ? s : s_last, T, p.grid_h, p.grid_w);
-    const size_t row = base_k + (size_t)n * st_k;
-    for (int c = 0; c < dk; ++c) {
+    {
+        const int s = s_last - tid;
+        s_tok[tid] = s >= sp * kDgSpan ? scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w) : -1;
+    }
+    __syncthreads();
+    // the terms q * dq - k * dk, rows read channel by channel (neighbouring lanes, neighbouring addresses)
+    for (int idx = tid; idx < kDgSpan * dk; idx += kDgSpan) {
+        const int j = idx / dk, c = idx - j * dk;
+        const int n = s_tok[j];
         float x = 0.f;
-        if (valid)
-            x = load_elem<TIn>(p.q, row + c) * dq[row + c] - load_elem<TIn>(p.k, row + c) * dk_grad[row + c];
-        x = wave_inclusive_scan(x);
+        if (n >= 0) {
+            const size_t e = base_k + (size_t)n * st_k + c;
+            x = load_elem<TIn>(p.q, e) * dq[e] - load_elem<TIn>(p.k, e) * dk_grad[e];
+        }
+        s_x[j][c] = x;
+    }
+    __syncthreads();
+    for (int c = 0; c < dk; ++c) {
+        const float x = wave_inclusive_scan(s_x[tid][c]);
+        s_x[tid][c] = x;
         if (lane == 63) s_wave[wv][c] = x;
-        __syncthreads();
-        float before = 0.f;   // the waves that hold later scan steps
-        for (int u = 0; u < wv; ++u) before += s_wave[u][c];
-        x += before;
-        if (valid) dg[row + c] = x;
-        if (tid == kDgSpan - 1) totals[((size_t)bh * ndg + sp) * dk + c] = x;
-        __syncthreads();
+    }
+    __syncthreads();
+    for (int idx = tid; idx < kDgSpan * dk; idx += kDgSpan) {
+        const int j = idx / dk, c = idx - j * dk;
+        float x = s_x[j][c];
+        for (int u = 0; u < (j >> 6); ++u) x += s_wave[u][c];   // the waves that hold later scan steps
+        const int n = s_tok[j];
+        if (n >= 0) dg[base_k + (size_t)n * st_k + c] = x;
+        if (j == kDgSpan - 1) totals[((size_t)bh * ndg + sp) * dk + c] = x;
     }
 }
 
 __global__ __launch_bounds__(kDgSpan) void dg_offset_kernel(Params p, float *dg, const float *totals, int ndg) {
     __shared__ float s_off[kMaxDk];
+    __shared__ int s_tok[kDgSpan];
     const int tid = threadIdx.x;
     const int bh = blockIdx.x / ndg, sp = blockIdx.x - bh * ndg;
     const int dk = p.dk, T = p.T;
@@ -227,12 +212,17 @@ __global__ __launch_bounds__(kDgSpan) void dg_offset_kernel(Params p, float *dg,
         for (int r = sp + 1; r < ndg; ++r) x += totals[((size_t)bh * ndg + r) * dk + tid];
         s_off[tid] = x;
     }
+    {
+        const int s = sp * kDgSpan + tid;
+        s_tok[tid] = s < T ? scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w) : -1;
+    }
     __syncthreads();
-    const int s = sp * kDgSpan + tid;
-    if (s >= T) return;
-    const int n = scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w);
-    float *row = dg + slab_k(p, bh) + (size_t)n * p.st_k;
-    for (int c = 0; c < dk; ++c) row[c] += s_off[c];
+    const size_t base_k = slab_k(p, bh), st_k = (size_t)p.st_k;
+    for (int idx = tid; idx < kDgSpan * dk; idx += kDgSpan) {
+        const int j = idx / dk, c = idx - j * dk;
+        const int n = s_tok[j];
+        if (n >= 0) dg[base_k + (size_t)n * st_k + c] += s_off[c];
+    }
 }
 
 }  // namespace

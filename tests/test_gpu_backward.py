@@ -81,7 +81,7 @@ SHAPES = [
     (1, 3, 23, 11, 64, 128, "bf16"),      # largest head sizes
     (2, 2, 9, 21, 32, 64, "bf16"),
     (1, 2, 17, 19, 40, 96, "bf16"),
-    (1, 2, 12, 11, 33, 66, "bf16"),       # odd dk -> recurrent engine for the span passes
+    (1, 2, 12, 11, 33, 65, "bf16"),       # odd head sizes -> recurrent engine for the span passes
     (1, 2, 12, 11, 20, 24, "f32"),
     (2, 1, 20, 20, 64, 128, "f32"),
     (1, 2, 7, 9, 5, 3, "f32"),
@@ -113,10 +113,3 @@ def test_headline_shape_long_spans():
     cfg = gi.CONFIGS["dig_xl2_2048"]
     d = make_problem(cfg.B, cfg.H, cfg.grid_h, cfg.grid_w, cfg.dk, cfg.dv, cfg.dtype, seed=cfg.seed)
     check(d, cfg.grid_h, cfg.grid_w, 0, TOL_BF16)
-
-
-def test_odd_value_width_in_bf16_is_refused():
-    d = make_problem(1, 1, 4, 4, 8, 7, "bf16", seed=3)
-    with pytest.raises(gla.GlaError) as ei:
-        gla.gla_bwd(*(upload(d, n) for n in ("q", "k", "v", "log_alpha", "w")), 4, 4, 0)
-    assert ei.value.status == 3
