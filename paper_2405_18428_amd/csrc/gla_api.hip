@@ -132,6 +132,9 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
     auto span = [&](const Params &p, SpanMode mode) {
         return use_mfma ? launch_mfma_span(p, mode, stream) : launch_recurrent_span(p, mode, stream);
     };
+    auto row_read = [&](const Params &p, const void *w, float *r) {
+        return use_mfma ? launch_mfma_row_read(p, w, r, stream) : launch_row_read(p, w, r, stream);
+    };
     auto states = [&](const Params &p) {   // span-local states, then chained in place
         if (p.nspans <= 1) return hipSuccess;
         hipError_t e = span(p, kModeState);
@@ -143,7 +146,7 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
     Params pa = base;
     pa.k = k; pa.v = v; pa.log_alpha = log_alpha; pa.scan_dir = scan_dir; pa.gate_shift = 0;
     if (states(pa) != hipSuccess) return GLA_ERR_HIP;
-    if (launch_row_read(pa, d_out, dq, stream) != hipSuccess) return GLA_ERR_HIP;
+    if (row_read(pa, d_out, dq) != hipSuccess) return GLA_ERR_HIP;
 
     // 2. states of the reversed recurrence G_s = q_s^T dO_s + diag(alpha_{s+1}) G_{s+1}: the forward recurrence
     //    with k, v := q, dO, walked from the last scan step, each step using the previous step's gate
@@ -152,7 +155,7 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
     pb.out = dv_grad;
     if (states(pb) != hipSuccess) return GLA_ERR_HIP;
     if (span(pb, kModeOutput) != hipSuccess) return GLA_ERR_HIP;             // dv_s = k_s G_s
-    if (launch_row_read(pb, v, dk_grad, stream) != hipSuccess) return GLA_ERR_HIP;   // dk_s = G_s v_s
+    if (row_read(pb, v, dk_grad) != hipSuccess) return GLA_ERR_HIP;   // dk_s = G_s v_s
 
     // 3. dlog_alpha = reverse cumulative sum of q * dq - k * dk along the scan
     Params pc = base;

@@ -90,6 +90,8 @@ bool mfma_engine_supports(const Params &p);
 // backward-only kernels: r_s[c] = sum_n S_s[c,n] w_s[n] over the states of (p.k, p.v, p.log_alpha); and
 // dlog_alpha = reverse cumulative sum of q * dq - k * dk (totals: [B*H, dg_spans(T), dk] floats of scratch)
 hipError_t launch_row_read(const Params &p, const void *w, float *r, hipStream_t stream);
+// the same on the MFMA units (chunk form); needs what mfma_engine_supports() checks
+hipError_t launch_mfma_row_read(const Params &p, const void *w, float *r, hipStream_t stream);
 hipError_t launch_dlog_alpha(const Params &p, const float *dq, const float *dk_grad, float *dg, float *totals,
                              hipStream_t stream);
 int dg_spans(int T);

@@ -1,0 +1,424 @@
+// bf16 MFMA kernel for the state reads of the backward pass of the GLA recurrence
+// (DiG paper, Sec. 3.1 Eq. (attn_gla) rows 1-3 with beta = 1, differentiated; chunks of M = 64
+// tokens computed on-chip as in Sec. 3.5).
+//
+// It computes r_s[c] = sum_n S_s[c,n] w_s[n] for every scan step s of a span, where S follows
+// S_s = diag(alpha_s) S_{s-1} + k_s^T v_s: with w = dO this is dq, and on the reversed recurrence
+// of G = dL/dS (k, v := q, dO, gates shifted by one step) with w = v it is dk.
+//
+// Chunk form.  With b_j the inclusive sum of log_alpha inside the chunk (per key channel),
+// k~_j = k_j exp(-b_j), E_j = exp(b_j) and S_0 the state entering the chunk,
+//     S_j = diag(E_j) (S_0 + sum_{i<=j} k~_i^T v_i)
+//     r_j = E_j * ( sum_{i<=j} (w_j . v_i) k~_i  +  S_0 w_j )          ("*" elementwise over channels)
+//     S_C = diag(E_C) (S_0 + K~^T V)
+// i.e. per chunk  P = tril(W V^T)  (plain bf16 operands, contraction over the value columns),
+// R = E * (P K~ + W S_0^T),  S += K~^T V then scaled.  P, K~ and S_0 are split into a bf16 "hi" part
+// and a bf16 "lo" remainder (three products where two split operands meet, two otherwise).
+//
+// One work-group of 4 waves walks the chunks of its span; wave i owns the 16 tokens 16i..16i+15 of a
+// chunk (all channels of R) and the state tiles of the value-column tiles i, i+4.  The state is kept
+// transposed, S^T[n][c], in fp32 accumulators: a lane then holds four consecutive value columns of one
+// channel, which is (a) a 16-byte load from the [dk][dv] state the carry kernel left in the workspace,
+// (b) an 8-byte LDS write of the bf16 parts as the channel-major rows that the S_0 term reads as its A
+// operand, and (c) scaled by one exp(b_C) per lane.
+// P is computed transposed (as in the forward kernel) so that its accumulator registers are the B
+// operand of the next contraction: slot (g, e) of a 32-token step is token 32q + 16(e/4) + 4g + e%4,
+// and K~ (contracted over tokens) is fetched in the same order by the transposing LDS read.
+#include <type_traits>
+
+#include "gla_common.h"
+#include "gla_mfma_util.h"
+
+namespace gla {
+namespace {
+
+template <int NDK8, int NDV16>
+struct RLayout {
+    static constexpr int kDkp = NDK8 * 8;
+    static constexpr int kDvp = NDV16 * 16;
+    static constexpr int kNct = (NDK8 + 1) / 2;                           // 16-channel tiles
+    // bf16 per row of K~: whole 16-channel tiles, an odd number of 16-byte units
+    static constexpr int kChStride = (NDK8 % 4 == 0) ? kDkp + 8 : ((kDkp + 8 + 15) / 16) * 16 + 8;
+    // bf16 per row of V, W and S_0: the columns, then an all-zero group of 8 (lanes whose column group lies
+    // beyond the last one read that group); again an odd number of 16-byte units
+    static constexpr int kVStride = kDvp + 8;
+    static constexpr int kZeroCol = kDvp;
+    static constexpr int kLaStride = kDkp + 4;                            // fp32 per row of log_alpha, then E
+    static constexpr int kRowK = kChunk * kChStride * 2;
+    static constexpr int kRowV = kChunk * kVStride * 2;
+    static constexpr int kSt = 16 * kNct * kVStride * 2;
+
+    static constexpr int oTok = 0;                                        // int[3][64]
+    static constexpr int oTokG = oTok + 3 * kChunk * 4;                   // int[3][64]
+    static constexpr int oGam = oTokG + 3 * kChunk * 4;                   // float[64] exp(b_C)
+    static constexpr int oLa = oGam + 64 * 4;
+    static constexpr int oKHi = oLa + kChunk * kLaStride * 4;
+    static constexpr int oKLo = oKHi + kRowK;
+    static constexpr int oV = oKLo + kRowK;
+    static constexpr int oW = oV + kRowV;
+    static constexpr int oStHi = oW + kRowV;
+    static constexpr int oStLo = oStHi + kSt;
+    static constexpr int kBytes = oStLo + kSt;
+};
+
+template <int N>
+using int_c = std::integral_constant<int, N>;
+
+template <int NDK8, int NDV16, int MINW>
+__global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, const void *w_in, float *r_out) {
+    using L = RLayout<NDK8, NDV16>;
+    constexpr int NW = 4, NTHR = 256;
+    constexpr int CHS = L::kChStride, VS = L::kVStride, LAS = L::kLaStride;
+    constexpr int NCT = L::kNct;
+    constexpr int KSV = (NDV16 * 2 + 3) / 4;        // 32-column steps of the contractions over value columns
+    constexpr int TPW = (NDV16 + NW - 1) / NW;      // value-column tiles of the state per wave
+    constexpr int NTB = 3;
+    static_assert(16 * NCT <= CHS, "channel tiles must fit the operand row");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    int *s_tok = reinterpret_cast<int *>(smem + L::oTok);
+    int *s_tokg = reinterpret_cast<int *>(smem + L::oTokG);
+    float *s_gam = reinterpret_cast<float *>(smem + L::oGam);
+    float *s_la = reinterpret_cast<float *>(smem + L::oLa);
+    uint16_t *s_khi = reinterpret_cast<uint16_t *>(smem + L::oKHi);
+    uint16_t *s_klo = reinterpret_cast<uint16_t *>(smem + L::oKLo);
+    uint16_t *s_v = reinterpret_cast<uint16_t *>(smem + L::oV);
+    uint16_t *s_w = reinterpret_cast<uint16_t *>(smem + L::oW);
+    uint16_t *s_sthi = reinterpret_cast<uint16_t *>(smem + L::oStHi);
+    uint16_t *s_stlo = reinterpret_cast<uint16_t *>(smem + L::oStLo);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lm = lane & 15;
+    const int g = lane >> 4;
+
+    // contiguous ranges of spans per XCD (work-groups are dealt round-robin to the 8 XCDs)
+    int blk = blockIdx.x;
+    {
+        const int nb = gridDim.x;
+        if ((nb & 7) == 0) blk = (blk & 7) * (nb >> 3) + (blk >> 3);
+    }
+    const int bh = blk / p.nspans;
+    const int sp = blk - bh * p.nspans;
+    const int dk = p.dk, dv = p.dv, T = p.T;
+    const int s_begin = sp * p.span_len;
+    const int s_end = min(T, s_begin + p.span_len);
+    const int nch = (s_end - s_begin + kChunk - 1) / kChunk;
+
+    const size_t base_k = slab_k(p, bh), base_v = slab_v(p, bh);
+    const char *gk = static_cast<const char *>(p.k) + base_k * 2;
+    const char *gv = static_cast<const char *>(p.v) + base_v * 2;
+    const char *gw = static_cast<const char *>(w_in) + base_v * 2;
+    const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + base_k * 4;
+    char *gr = reinterpret_cast<char *>(r_out) + base_k * 4;
+
+    // ---- prologue: clear LDS (pads must read as zero), token maps of the first two chunks ----
+    for (int i = tid; i < L::kBytes / 16; i += NTHR)
+        reinterpret_cast<u32x4 *>(smem)[i] = u32x4{0, 0, 0, 0};
+    __syncthreads();
+    if (tid < 2 * kChunk) {
+        const int s = s_begin + tid;
+        const int sc = (s < s_end) ? s : s_begin;
+        s_tok[tid] = scan_token(p.scan_dir, sc, T, p.grid_h, p.grid_w);
+        s_tokg[tid] = scan_token(p.scan_dir, max(sc - p.gate_shift, 0), T, p.grid_h, p.grid_w);
+    }
+    __syncthreads();
+
+    // ---- state tiles of this wave, transposed: acc[i][ct][r] = S[c = 16 ct + lm][n = 16 (w + 4 i) + 4 g + r] ----
+    f32x4 acc[TPW][NCT];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i)
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) acc[i][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (p.nspans > 1) {   // the state entering the span, as the carry kernel left it
+        const float *s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            const int n = 16 * (w + NW * i) + 4 * g;
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                const int c = 16 * ct + lm;
+                if (c < dk && n < dv) acc[i][ct] = *reinterpret_cast<const f32x4 *>(s0 + c * dv + n);
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): keeps later reads of acc from waiting on the row prefetch
+
+    // ---- HBM pieces staged by this thread: 4 threads per row, piece m*4 + tid%4 of row tid/4 in slot m;
+    // a slot past the row repeats the row's last piece (same bytes to the same place) ----
+    constexpr int PPS = NTHR / kChunk;
+    constexpr int kSlots = (NDK8 * 2 + PPS - 1) / PPS;      // 16-byte pieces of log_alpha / 8-byte pieces of k
+    constexpr int kVSlots = (NDV16 * 2 + PPS - 1) / PPS;    // 16-byte pieces of v and w
+    const int prow = tid / PPS, psub = tid % PPS;
+    const int pcs = dk >> 2, vpcs = dv >> 3;
+    const uint32_t dk2 = 2u * (uint32_t)p.st_k, dv2 = 2u * (uint32_t)p.st_v;
+
+    f32x4 r_la[kSlots];
+    u32x2 r_k[kSlots];
+    u32x4 r_v[kVSlots], r_w[kVSlots];
+    auto load_chunk = [&](int chunk) {
+        const int *tok = s_tok + (chunk % NTB) * kChunk;
+        const int *tokg = s_tokg + (chunk % NTB) * kChunk;
+        const uint32_t row_k = (uint32_t)tok[prow] * dk2, row_v = (uint32_t)tok[prow] * dv2;
+        const uint32_t row_g = (uint32_t)tokg[prow] * dk2;
+#pragma unroll
+        for (int m = 0; m < kSlots; ++m) {
+            const uint32_t pc = 8u * (uint32_t)min(m * PPS + psub, pcs - 1);
+            r_la[m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * (row_g + pc));
+            r_k[m] = *reinterpret_cast<const u32x2 *>(gk + row_k + pc);
+        }
+#pragma unroll
+        for (int m = 0; m < kVSlots; ++m) {
+            const uint32_t pc = 16u * (uint32_t)min(m * PPS + psub, vpcs - 1);
+            r_v[m] = *reinterpret_cast<const u32x4 *>(gv + row_v + pc);
+            r_w[m] = *reinterpret_cast<const u32x4 *>(gw + row_v + pc);
+        }
+    };
+    load_chunk(0);
+
+    for (int chunk = 0; chunk < nch; ++chunk) {
+        const int *tok = s_tok + (chunk % NTB) * kChunk;
+        // ================= (a) registers -> LDS =================
+        const int nvalid = min(kChunk, s_end - s_begin - chunk * kChunk);
+        if (prow >= nvalid) {   // rows past the span: no decay, no contribution
+#pragma unroll
+            for (int m = 0; m < kSlots; ++m) {
+                r_la[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+                r_k[m] = u32x2{0, 0};
+            }
+#pragma unroll
+            for (int m = 0; m < kVSlots; ++m) {
+                r_v[m] = u32x4{0, 0, 0, 0};
+                r_w[m] = u32x4{0, 0, 0, 0};
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < kSlots; ++m) {
+            const int ch = 4 * min(m * PPS + psub, pcs - 1);
+            *reinterpret_cast<f32x4 *>(s_la + prow * LAS + ch) = r_la[m];
+            *reinterpret_cast<u32x2 *>(s_khi + prow * CHS + ch) = r_k[m];
+        }
+#pragma unroll
+        for (int m = 0; m < kVSlots; ++m) {
+            const int col = 8 * min(m * PPS + psub, vpcs - 1);
+            *reinterpret_cast<u32x4 *>(s_v + prow * VS + col) = r_v[m];
+            *reinterpret_cast<u32x4 *>(s_w + prow * VS + col) = r_w[m];
+        }
+        load_chunk(chunk + 1);   // past the span the clamped token map keeps the loads in bounds
+        {
+            // S_0 as bf16 hi/lo, channel-major
+            const int ln = recompute_per_chunk(lane), lm2 = ln & 15, g2 = ln >> 4;
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                if (w + NW * i < NDV16) {
+#pragma unroll
+                    for (int ct = 0; ct < NCT; ++ct) {
+                        u32x2 hi, lo;
+                        SPLIT_PAIR(acc[i][ct][0], acc[i][ct][1], hi[0], lo[0]);
+                        SPLIT_PAIR(acc[i][ct][2], acc[i][ct][3], hi[1], lo[1]);
+                        const int off = (16 * ct + lm2) * VS + 16 * (w + NW * i) + 4 * g2;
+                        *reinterpret_cast<u32x2 *>(s_sthi + off) = hi;
+                        *reinterpret_cast<u32x2 *>(s_stlo + off) = lo;
+                    }
+                }
+            }
+        }
+        if (w == NW - 1) {   // token map of the chunk loaded next time
+            const int s = s_begin + (chunk + 2) * kChunk + lane;
+            const int sc = (s < s_end) ? s : s_begin;
+            s_tok[((chunk + 2) % NTB) * kChunk + lane] = scan_token(p.scan_dir, sc, T, p.grid_h, p.grid_w);
+            s_tokg[((chunk + 2) % NTB) * kChunk + lane] =
+                scan_token(p.scan_dir, max(sc - p.gate_shift, 0), T, p.grid_h, p.grid_w);
+        }
+        __syncthreads();
+
+        // ================= (b) gates: lane = token, units of 4 channels dealt to the waves =================
+        {
+            const int j = lane;
+            for (int u = w; u < pcs; u += NW) {
+                const int c0 = 4 * u;
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(s_la + j * LAS + c0);
+                const u32x2 kr = *reinterpret_cast<const u32x2 *>(s_khi + j * CHS + c0);
+                float bb[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) bb[i] = wave_inclusive_scan(x[i] * kLog2e);
+                f32x4 e;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) e[i] = exp2_fast(bb[i]);
+                u32x2 khi, klo;
+                SPLIT_PAIR(bf16_lo_as_float(kr[0]) * exp2_fast(fminf(-bb[0], kMaxExp2)),
+                           bf16_hi_as_float(kr[0]) * exp2_fast(fminf(-bb[1], kMaxExp2)), khi[0], klo[0]);
+                SPLIT_PAIR(bf16_lo_as_float(kr[1]) * exp2_fast(fminf(-bb[2], kMaxExp2)),
+                           bf16_hi_as_float(kr[1]) * exp2_fast(fminf(-bb[3], kMaxExp2)), khi[1], klo[1]);
+                *reinterpret_cast<u32x2 *>(s_khi + j * CHS + c0) = khi;
+                *reinterpret_cast<u32x2 *>(s_klo + j * CHS + c0) = klo;
+                *reinterpret_cast<f32x4 *>(s_la + j * LAS + c0) = e;      // E_j in place of the raw gates
+                if (lane == 63) *reinterpret_cast<f32x4 *>(s_gam + c0) = e;
+            }
+        }
+        __syncthreads();
+
+        // ================= (c) contractions =================
+        const int ln = recompute_per_chunk(lane), lm3 = ln & 15, g3 = ln >> 4;
+        int coln[KSV];   // column group of this lane in 32-column step ks; groups past the data alias the zero group
+#pragma unroll
+        for (int ks = 0; ks < KSV; ++ks) coln[ks] = (4 * ks + g3 < 2 * NDV16) ? 8 * (4 * ks + g3) : L::kZeroCol;
+        const int tr_row = lm3 >> 2, tr_col = 4 * (lm3 & 3);
+        auto contract = [&](auto wave_c) {
+            constexpr int IT = decltype(wave_c)::value;   // 16-token tile of this wave
+            constexpr int NQ = IT / 2 + 1;                // 32-token steps that hold tokens <= the tile's
+            const int lm = lm3, g = g3;
+            const uint16_t *krow_h = s_khi + (4 * g + tr_row) * CHS + tr_col;
+            const uint16_t *krow_l = s_klo + (4 * g + tr_row) * CHS + tr_col;
+            const uint16_t *vrow = s_v + (4 * g + tr_row) * VS + tr_col;
+            u32x4 wf[KSV];
+#pragma unroll
+            for (int ks = 0; ks < KSV; ++ks)
+                wf[ks] = *reinterpret_cast<const u32x4 *>(s_w + (16 * IT + lm) * VS + coln[ks]);
+            u32x4 kth[2][NCT], ktl[2][NCT];   // K~ over tokens: [32-token step][channel tile]
+            auto load_k = [&](int q) {
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct) {
+                    const u32x2 h0 = lds_read_tr(krow_h + 32 * q * CHS + 16 * ct);
+                    const u32x2 h1 = lds_read_tr(krow_h + (32 * q + 16) * CHS + 16 * ct);
+                    const u32x2 l0 = lds_read_tr(krow_l + 32 * q * CHS + 16 * ct);
+                    const u32x2 l1 = lds_read_tr(krow_l + (32 * q + 16) * CHS + 16 * ct);
+                    kth[q][ct] = u32x4{h0[0], h0[1], h1[0], h1[1]};
+                    ktl[q][ct] = u32x4{l0[0], l0[1], l1[0], l1[1]};
+                }
+            };
+            f32x4 rr[NCT];
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) rr[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                u32x2 ph[2] = {u32x2{0, 0}, u32x2{0, 0}}, pl[2] = {u32x2{0, 0}, u32x2{0, 0}};
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int jt = 2 * q + u;
+                    if (jt <= IT) {
+                        // P^T tile: lane (lm, g) gets P[i = 16 IT + lm][j = 16 jt + 4 g + r]
+                        f32x4 d = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int ks = 0; ks < KSV; ++ks) {
+                            const u32x4 vf = *reinterpret_cast<const u32x4 *>(s_v + (16 * jt + lm) * VS + coln[ks]);
+                            d = mfma(vf, wf[ks], d);
+                        }
+                        if (jt == IT) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                if (4 * g + r > lm) d[r] = 0.f;
+                        }
+                        SPLIT_PAIR(d[0], d[1], ph[u][0], pl[u][0]);
+                        SPLIT_PAIR(d[2], d[3], ph[u][1], pl[u][1]);
+                    }
+                }
+                load_k(q);
+                const u32x4 bh_ = u32x4{ph[0][0], ph[0][1], ph[1][0], ph[1][1]};
+                const u32x4 bl_ = u32x4{pl[0][0], pl[0][1], pl[1][0], pl[1][1]};
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct) {
+                    rr[ct] = mfma(kth[q][ct], bh_, rr[ct]);
+                    rr[ct] = mfma(kth[q][ct], bl_, rr[ct]);
+                    rr[ct] = mfma(ktl[q][ct], bh_, rr[ct]);
+                }
+            }
+            // + W S_0^T
+#pragma unroll
+            for (int ks = 0; ks < KSV; ++ks) {
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct) {
+                    const int srow = (16 * ct + lm) * VS + coln[ks];
+                    const u32x4 sh = *reinterpret_cast<const u32x4 *>(s_sthi + srow);
+                    const u32x4 sl = *reinterpret_cast<const u32x4 *>(s_stlo + srow);
+                    rr[ct] = mfma(sh, wf[ks], rr[ct]);
+                    rr[ct] = mfma(sl, wf[ks], rr[ct]);
+                }
+            }
+            // scale by E and store: lane (lm, g) holds channels 16 ct + 4 g .. + 3 of token 16 IT + lm
+            const int row = 16 * IT + lm;
+            if (row < nvalid) {
+                char *orow = gr + ((uint32_t)tok[row] * (uint32_t)p.st_k + 4u * (uint32_t)g) * 4u;
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct) {
+                    if (16 * ct + 4 * g < dk) {   // dk is a multiple of 4: all four channels or none
+                        const f32x4 e = *reinterpret_cast<const f32x4 *>(s_la + row * LAS + 16 * ct + 4 * g);
+                        f32x4 o = rr[ct];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) o[r] *= e[r];
+                        *reinterpret_cast<f32x4 *>(orow + 64 * ct) = o;
+                    }
+                }
+            }
+            // state update on this wave's tiles: S^T += V^T K~, then the chunk's decay per channel
+#pragma unroll
+            for (int q = NQ; q < 2; ++q) load_k(q);
+            float gm[NCT];
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) gm[ct] = s_gam[16 * ct + lm];
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                const int nt = IT + NW * i;
+                if (nt < NDV16) {
+                    u32x4 vt[2];
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const u32x2 v0 = lds_read_tr(vrow + 32 * q * VS + 16 * nt);
+                        const u32x2 v1 = lds_read_tr(vrow + (32 * q + 16) * VS + 16 * nt);
+                        vt[q] = u32x4{v0[0], v0[1], v1[0], v1[1]};
+                    }
+#pragma unroll
+                    for (int ct = 0; ct < NCT; ++ct) {
+                        f32x4 a = acc[i][ct];
+#pragma unroll
+                        for (int q = 0; q < 2; ++q) {
+                            a = mfma(vt[q], kth[q][ct], a);
+                            a = mfma(vt[q], ktl[q][ct], a);
+                        }
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) a[r] *= gm[ct];
+                        acc[i][ct] = a;
+                    }
+                }
+            }
+        };
+        switch (w) {
+        case 0: contract(int_c<0>{}); break;
+        case 1: contract(int_c<1>{}); break;
+        case 2: contract(int_c<2>{}); break;
+        default: contract(int_c<3>{}); break;
+        }
+        __syncthreads();
+    }
+}
+
+template <int NDK8, int NDV16>
+hipError_t launch_one(const Params &p, const void *w, float *r, hipStream_t stream) {
+    using L = RLayout<NDK8, NDV16>;
+    constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
+    constexpr int MINW = kGroupsPerCu >= 2 ? 2 : 1;
+    auto kernel = mfma_row_read_kernel<NDK8, NDV16, MINW>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    dim3 grid((unsigned)(p.B * p.H * p.nspans)), block(256);
+    hipLaunchKernelGGL(kernel, grid, block, L::kBytes, stream, p, w, r);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Same conditions as the forward MFMA engine (bf16 rows, dk % 4 == 0, dv % 8 == 0, 32-bit offsets).
+hipError_t launch_mfma_row_read(const Params &p, const void *w, float *r, hipStream_t stream) {
+    const int ndk8 = (p.dk + 7) / 8, ndv16 = (p.dv + 15) / 16;
+    if (ndk8 <= 4 && ndv16 <= 4) return launch_one<4, 4>(p, w, r, stream);
+    if (ndk8 <= 5 && ndv16 <= 5) return launch_one<5, 5>(p, w, r, stream);
+    return launch_one<8, 8>(p, w, r, stream);
+}
+
+}  // namespace gla

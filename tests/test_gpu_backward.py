@@ -81,6 +81,8 @@ SHAPES = [
     (1, 3, 23, 11, 64, 128, "bf16"),      # largest head sizes
     (2, 2, 9, 21, 32, 64, "bf16"),
     (1, 2, 17, 19, 40, 96, "bf16"),
+    (1, 2, 9, 15, 4, 8, "bf16"),          # smallest head sizes of the MFMA engine
+    (1, 1, 16, 16, 12, 40, "bf16"),
     (1, 2, 12, 11, 33, 65, "bf16"),       # odd head sizes -> recurrent engine for the span passes
     (1, 2, 12, 11, 20, 24, "f32"),
     (2, 1, 20, 20, 64, 128, "f32"),
