@@ -135,10 +135,14 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_read_kernel(Params p, cons
 }
 
 // ---- dlog_alpha: reverse cumulative sum over the scan order of (q * dq - k * dk), in two kernels ----
-// Spans of kDgSpan scan steps.  Kernel 1: inside each span, lane = scan step, a wave scan from the span's last
-// step backwards per channel, written at the canonical token index, and the span's total.  Kernel 2: every
-// span adds the totals of the spans after it.
-constexpr int kDgSpan = 128;       // scan steps per work-group (2 waves of 64 lanes)
+// Spans of kDgSpan scan steps, one work-group each.  Kernel 1 stages the span's terms in LDS channel-major
+// (rows read from HBM in pieces of PW channels, neighbouring lanes neighbouring pieces), scans every channel
+// with lane = scan step counted from the span's last step backwards, and writes the sums at the canonical
+// token index together with the span's total.  Kernel 2 adds to every span the totals of the spans after it.
+constexpr int kDgSpan = 256;       // scan steps per work-group
+constexpr int kDgThreads = 256;    // one lane per scan step in the scan stage
+constexpr int kDgBatch = 3;        // pieces per thread whose loads are in flight together
+constexpr int kDgRow = kDgSpan + 1;  // floats per channel row in LDS
 
 template <int CTRL, int ROW_MASK, bool BOUND>
 __device__ inline float dpp_move(float v) {
@@ -155,52 +159,132 @@ __device__ inline float wave_inclusive_scan(float v) {
     return v;
 }
 
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// PW consecutive elements starting at element index e, as floats (PW = 4: e is a multiple of 4 and 16-byte
+// aligned in fp32, 8-byte aligned in bf16)
+template <typename TIn, int PW>
+__device__ inline void load_piece(const void *base, size_t e, float (&x)[PW]) {
+    if constexpr (PW == 1) {
+        x[0] = load_elem<TIn>(base, e);
+    } else if constexpr (sizeof(TIn) == 4) {
+        const f32x4 t = *reinterpret_cast<const f32x4 *>(static_cast<const float *>(base) + e);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = t[i];
+    } else {
+        const u32x2 t = *reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(base) + e);
+        x[0] = __builtin_bit_cast(float, t[0] << 16);
+        x[1] = __builtin_bit_cast(float, t[0] & 0xffff0000u);
+        x[2] = __builtin_bit_cast(float, t[1] << 16);
+        x[3] = __builtin_bit_cast(float, t[1] & 0xffff0000u);
+    }
+}
+template <int PW>
+__device__ inline void store_piece(float *dst, const float (&x)[PW]) {
+    if constexpr (PW == 1) dst[0] = x[0];
+    else *reinterpret_cast<f32x4 *>(dst) = f32x4{x[0], x[1], x[2], x[3]};
+}
+
+// Walks the (row, piece) pairs tid, tid + kDgThreads, ... of a [kDgSpan][pcs] tile without divisions.
+struct PieceWalk {
+    int j, pc, dj, dpc, pcs;
+    __device__ PieceWalk(int tid, int pcs_) : pcs(pcs_) {
+        j = tid / pcs;
+        pc = tid - j * pcs;
+        dj = kDgThreads / pcs;
+        dpc = kDgThreads - dj * pcs;
+    }
+    __device__ void next() {
+        j += dj;
+        pc += dpc;
+        if (pc >= pcs) {
+            pc -= pcs;
+            ++j;
+        }
+    }
+};
+
 // Row j of the tile is scan step (span end - 1 - j): prefix sums over j are suffix sums over the scan.
-template <typename TIn>
-__global__ __launch_bounds__(kDgSpan) void dg_local_kernel(Params p, const float *dq, const float *dk_grad,
-                                                          float *dg, float *totals, int ndg) {
-    __shared__ float s_x[kDgSpan][kMaxDk + 1];   // odd row length: lane = row accesses hit distinct banks
-    __shared__ float s_wave[kDgSpan / 64][kMaxDk];
-    __shared__ int s_tok[kDgSpan];
+template <typename TIn, int PW>
+__global__ __launch_bounds__(kDgThreads) void dg_local_kernel(Params p, const float *dq, const float *dk_grad,
+                                                             float *dg, float *totals, int ndg) {
+    extern __shared__ float s_dyn[];
+    const int dk = p.dk, T = p.T;
+    float *s_x = s_dyn;                                   // [dk][kDgRow]
+    float *s_wave = s_dyn + dk * kDgRow;                  // [4][dk] sums of the waves, then their exclusive prefix
+    int *s_tok = reinterpret_cast<int *>(s_wave + 4 * dk);  // [kDgSpan]
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int bh = blockIdx.x / ndg, sp = blockIdx.x - bh * ndg;
-    const int dk = p.dk, T = p.T;
     const size_t base_k = slab_k(p, bh), st_k = (size_t)p.st_k;
     const int s_last = min(T, (sp + 1) * kDgSpan) - 1;
-    {
-        const int s = s_last - tid;
-        s_tok[tid] = s >= sp * kDgSpan ? scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w) : -1;
-    }
+    const int nrows = s_last - sp * kDgSpan + 1;          // scan steps in this span (>= 1)
+    s_tok[tid] = scan_token(p.scan_dir, max(s_last - tid, sp * kDgSpan), T, p.grid_h, p.grid_w);
     __syncthreads();
-    // the terms q * dq - k * dk, rows read channel by channel (neighbouring lanes, neighbouring addresses)
-    for (int idx = tid; idx < kDgSpan * dk; idx += kDgSpan) {
-        const int j = idx / dk, c = idx - j * dk;
-        const int n = s_tok[j];
-        float x = 0.f;
-        if (n >= 0) {
-            const size_t e = base_k + (size_t)n * st_k + c;
-            x = load_elem<TIn>(p.q, e) * dq[e] - load_elem<TIn>(p.k, e) * dk_grad[e];
+
+    const int pcs = dk / PW, npieces = kDgSpan * pcs;
+    {
+        PieceWalk wk(tid, pcs);
+        for (int idx0 = tid; idx0 < npieces; idx0 += kDgThreads * kDgBatch) {
+            float x[kDgBatch][PW];
+            int jj[kDgBatch], cc[kDgBatch];
+#pragma unroll
+            for (int b = 0; b < kDgBatch; ++b) {   // rows past the span or the tile repeat a valid row
+                jj[b] = wk.j;
+                cc[b] = PW * wk.pc;
+                const size_t e = base_k + (size_t)s_tok[min(wk.j, kDgSpan - 1)] * st_k + cc[b];
+                float xq[PW], xk[PW], xdq[PW], xdk[PW];
+                load_piece<TIn, PW>(p.q, e, xq);
+                load_piece<TIn, PW>(p.k, e, xk);
+                load_piece<float, PW>(dq, e, xdq);
+                load_piece<float, PW>(dk_grad, e, xdk);
+#pragma unroll
+                for (int i = 0; i < PW; ++i) x[b][i] = xq[i] * xdq[i] - xk[i] * xdk[i];
+                wk.next();
+            }
+#pragma unroll
+            for (int b = 0; b < kDgBatch; ++b) {
+                if (jj[b] < kDgSpan) {
+#pragma unroll
+                    for (int i = 0; i < PW; ++i) s_x[(cc[b] + i) * kDgRow + jj[b]] = jj[b] < nrows ? x[b][i] : 0.f;
+                }
+            }
         }
-        s_x[j][c] = x;
     }
     __syncthreads();
     for (int c = 0; c < dk; ++c) {
-        const float x = wave_inclusive_scan(s_x[tid][c]);
-        s_x[tid][c] = x;
-        if (lane == 63) s_wave[wv][c] = x;
+        const float x = wave_inclusive_scan(s_x[c * kDgRow + tid]);
+        s_x[c * kDgRow + tid] = x;
+        if (lane == 63) s_wave[wv * dk + c] = x;
     }
     __syncthreads();
-    for (int idx = tid; idx < kDgSpan * dk; idx += kDgSpan) {
-        const int j = idx / dk, c = idx - j * dk;
-        float x = s_x[j][c];
-        for (int u = 0; u < (j >> 6); ++u) x += s_wave[u][c];   // the waves that hold later scan steps
-        const int n = s_tok[j];
-        if (n >= 0) dg[base_k + (size_t)n * st_k + c] = x;
-        if (j == kDgSpan - 1) totals[((size_t)bh * ndg + sp) * dk + c] = x;
+    if (tid < dk) {   // what the waves holding later scan steps add to a wave; the sum of all is the span's total
+        float run = 0.f;
+#pragma unroll
+        for (int u = 0; u < kDgThreads / 64; ++u) {
+            const float t = s_wave[u * dk + tid];
+            s_wave[u * dk + tid] = run;
+            run += t;
+        }
+        totals[((size_t)bh * ndg + sp) * dk + tid] = run;
+    }
+    __syncthreads();
+    {
+        PieceWalk wk(tid, pcs);
+        for (int idx = tid; idx < npieces; idx += kDgThreads) {
+            const int j = wk.j, c0 = PW * wk.pc;
+            if (j < nrows) {
+                float x[PW];
+#pragma unroll
+                for (int i = 0; i < PW; ++i) x[i] = s_x[(c0 + i) * kDgRow + j] + s_wave[(j >> 6) * dk + c0 + i];
+                store_piece<PW>(dg + base_k + (size_t)s_tok[j] * st_k + c0, x);
+            }
+            wk.next();
+        }
     }
 }
 
-__global__ __launch_bounds__(kDgSpan) void dg_offset_kernel(Params p, float *dg, const float *totals, int ndg) {
+template <int PW>
+__global__ __launch_bounds__(kDgThreads) void dg_offset_kernel(Params p, float *dg, const float *totals, int ndg) {
     __shared__ float s_off[kMaxDk];
     __shared__ int s_tok[kDgSpan];
     const int tid = threadIdx.x;
@@ -212,17 +296,46 @@ __global__ __launch_bounds__(kDgSpan) void dg_offset_kernel(Params p, float *dg,
         for (int r = sp + 1; r < ndg; ++r) x += totals[((size_t)bh * ndg + r) * dk + tid];
         s_off[tid] = x;
     }
-    {
-        const int s = sp * kDgSpan + tid;
-        s_tok[tid] = s < T ? scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w) : -1;
-    }
+    const int nrows = min(T, (sp + 1) * kDgSpan) - sp * kDgSpan;
+    s_tok[tid] = scan_token(p.scan_dir, min(sp * kDgSpan + tid, T - 1), T, p.grid_h, p.grid_w);
     __syncthreads();
     const size_t base_k = slab_k(p, bh), st_k = (size_t)p.st_k;
-    for (int idx = tid; idx < kDgSpan * dk; idx += kDgSpan) {
-        const int j = idx / dk, c = idx - j * dk;
-        const int n = s_tok[j];
-        if (n >= 0) dg[base_k + (size_t)n * st_k + c] += s_off[c];
+    const int pcs = dk / PW, npieces = kDgSpan * pcs;
+    PieceWalk wk(tid, pcs);
+    for (int idx = tid; idx < npieces; idx += kDgThreads) {
+        const int j = wk.j, c0 = PW * wk.pc;
+        if (j < nrows) {
+            float *dst = dg + base_k + (size_t)s_tok[j] * st_k + c0;
+            float x[PW];
+            load_piece<float, PW>(dst, 0, x);
+#pragma unroll
+            for (int i = 0; i < PW; ++i) x[i] += s_off[c0 + i];
+            store_piece<PW>(dst, x);
+        }
+        wk.next();
     }
+}
+
+constexpr size_t kDgLdsMax = ((size_t)kMaxDk * kDgRow + 4 * kMaxDk + kDgSpan) * 4;
+
+template <typename TIn, int PW>
+hipError_t launch_dg(const Params &p, const float *dq, const float *dk_grad, float *dg, float *totals, int ndg,
+                     hipStream_t stream) {
+    auto kernel = dg_local_kernel<TIn, PW>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDgLdsMax);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const size_t lds = ((size_t)p.dk * kDgRow + 4 * p.dk + kDgSpan) * 4;
+    dim3 grid((unsigned)(p.B * p.H * ndg)), block(kDgThreads);
+    hipLaunchKernelGGL(kernel, grid, block, lds, stream, p, dq, dk_grad, dg, totals, ndg);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (ndg > 1) hipLaunchKernelGGL(dg_offset_kernel<PW>, grid, block, 0, stream, p, dg, totals, ndg);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -241,15 +354,13 @@ int dg_spans(int T) { return (T + kDgSpan - 1) / kDgSpan; }
 hipError_t launch_dlog_alpha(const Params &p, const float *dq, const float *dk_grad, float *dg, float *totals,
                              hipStream_t stream) {
     const int ndg = dg_spans(p.T);
-    dim3 grid((unsigned)(p.B * p.H * ndg)), block(kDgSpan);
-    if (p.qkv_dtype == GLA_DT_BF16)
-        hipLaunchKernelGGL((dg_local_kernel<uint16_t>), grid, block, 0, stream, p, dq, dk_grad, dg, totals, ndg);
-    else
-        hipLaunchKernelGGL((dg_local_kernel<float>), grid, block, 0, stream, p, dq, dk_grad, dg, totals, ndg);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (ndg > 1) hipLaunchKernelGGL(dg_offset_kernel, grid, block, 0, stream, p, dg, totals, ndg);
-    return hipGetLastError();
+    const bool bf16 = p.qkv_dtype == GLA_DT_BF16;
+    // rows in 4-channel pieces (16-byte fp32 accesses) when the channel count and the row pitch allow it
+    if (p.dk % 4 == 0 && p.st_k % 4 == 0)
+        return bf16 ? launch_dg<uint16_t, 4>(p, dq, dk_grad, dg, totals, ndg, stream)
+                    : launch_dg<float, 4>(p, dq, dk_grad, dg, totals, ndg, stream);
+    return bf16 ? launch_dg<uint16_t, 1>(p, dq, dk_grad, dg, totals, ndg, stream)
+                : launch_dg<float, 1>(p, dq, dk_grad, dg, totals, ndg, stream);
 }
 
 }  // namespace gla
