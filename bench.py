@@ -117,6 +117,7 @@ def bench_backward(args, cfg, d, gla, gi, torch, np):
                 rms = max(float(np.sqrt(np.mean(r ** 2))), f)
                 errs.append(float(np.abs(g.cpu().numpy() - r).max() / rms))
             result["max_err_over_rms"] = round(max(errs), 6)
+            result["err_over_rms"] = {n: float("%.3g" % e) for n, e in zip(("dq", "dk", "dv", "dlog_alpha"), errs)}
     print(json.dumps(result), flush=True)
 
 
