@@ -50,6 +50,68 @@ def measured_traffic(config_name, kernel, args):
     return None
 
 
+def bench_fused(args, cfg, gla, gi, torch, np):
+    """gla_fwd_fused on the workload (gates from bf16 pre-activations, Swish gate times LayerNorm before a bf16
+    store): whole-call timing over rotating buffer sets, parity figure against the oracle."""
+    dev = torch.device("cuda:0")
+    B, H, T, dk, dv = cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv
+    d = gi.make_fused_inputs(B, H, T, dk, dv, cfg.dtype, seed=cfg.seed, z_mean=cfg.z_mean)
+    bf16 = cfg.dtype == "bf16"
+    if bf16:
+        to = lambda bits: torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16)
+        host = [to(d[n + "_bits"]) for n in ("q", "k", "v", "z", "r")]
+    else:
+        host = [torch.from_numpy(d[n]) for n in ("q", "k", "v", "z", "r")]
+    host += [torch.from_numpy(d["ln_w"]), torch.from_numpy(d["ln_b"])]
+    odt = torch.bfloat16 if args.out_dtype == "bf16" else torch.float32
+    qdt = gla.DT_BF16 if bf16 else gla.DT_F32
+    ws_bytes = gla.gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
+    sets = []
+    for _ in range(max(1, args.sets)):
+        sets.append([t.to(dev) for t in host] + [torch.empty((B, H, T, dv), dtype=odt, device=dev),
+                                                 torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev),
+                                                 torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)])
+
+    def step(i):
+        q, k, v, z, r, lw, lb, out, fin, ws = sets[i % len(sets)]
+        return gla.gla_fwd_fused(q, k, v, z, 16.0, cfg.grid_h, cfg.grid_w, args.scan, r_pre=r, ln_weight=lw,
+                                 ln_bias=lb, ln_eps=1e-5, out=out, final_state=fin, workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    qb = 2 if bf16 else 4
+    ob = 2 if args.out_dtype == "bf16" else 4
+    alg_bytes = (3 * dk * qb + 2 * dv * qb + dv * ob) * B * H * T   # q, k, z, v, r read once; y written once
+    achieved = alg_bytes / (ms * 1e-3) / 1e9
+    result = {
+        "metric": "GLA fwd (gate prologue + Swish/LayerNorm epilogue) tokens/s at DiG-XL/2 shape T=16384",
+        "value": round(B * T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} fused: B={B} H={H} T={T} ({cfg.grid_h}x{cfg.grid_w}) dk={dk} dv={dv} "
+                               f"{cfg.dtype} q/k/v/z/r, {args.out_dtype} out, scan={args.scan}",
+                   "buffer_sets": len(sets)},
+        "roofline": {"bound": "hbm", "kernel": "whole_call", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes": alg_bytes, "kernel_ms": round(ms, 5)},
+    }
+    if not args.no_check:
+        from oracle import gla_oracle_fused as fo
+        ref, ref_fin = fo.gla_fused(d["q"], d["k"], d["v"], d["z"], 16.0, d["r"], d["ln_w"], d["ln_b"], 1e-5,
+                                    cfg.grid_h, cfg.grid_w, args.scan)
+        got, fin = step(0)
+        torch.cuda.synchronize()
+        rms = float(np.sqrt(np.mean(ref ** 2)))
+        result["max_err_over_rms"] = round(float(np.abs(got.float().cpu().numpy() - ref).max() / rms), 6)
+    print(json.dumps(result), flush=True)
+
+
 def bench_backward(args, cfg, d, gla, gi, torch, np):
     """gla_bwd on the workload: whole-call timing over rotating buffer sets, oracle timing, parity figure."""
     dev = torch.device("cuda:0")
@@ -132,8 +194,9 @@ def main():
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated over (1 = cache-warm)")
     ap.add_argument("--chunks-per-span", type=int, default=0)
     ap.add_argument("--engine", type=int, default=0)
-    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd"],
-                    help="fwd: the forward hot path (the headline); bwd: gla_bwd on the same workload")
+    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "fused"],
+                    help="fwd: the forward hot path (the headline); bwd: gla_bwd on the same workload; "
+                         "fused: gla_fwd_fused (gate prologue, Swish/LayerNorm epilogue) on the same workload")
     ap.add_argument("--layout", default="bhtd", choices=["bhtd", "bthd"],
                     help="memory order of q, k, v, log_alpha, out: [B,H,T,d] (the headline) or [B,T,H,d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -167,6 +230,9 @@ def main():
     d = gi.make_config_inputs(cfg)
     if args.which == "bwd":
         bench_backward(args, cfg, d, gla, gi, torch, np)
+        return
+    if args.which == "fused":
+        bench_fused(args, cfg, gla, gi, torch, np)
         return
     B, H, T, dk, dv = cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv
     if cfg.dtype == "bf16":

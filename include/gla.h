@@ -173,6 +173,30 @@ int gla_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
             void *workspace, size_t workspace_bytes, gla_stream_t stream);
 size_t gla_bwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);
 
+/*
+ * gla_fwd_fused - gla_fwd_ex with the gate computed from its pre-activation inside the kernels
+ * and, optionally, the output gate and normalisation applied before the store:
+ *   log alpha_t = logsigmoid(z_t) / tau                  (Eq. (gate_gla), alpha = sigmoid(z)^(1/tau))
+ *   y_t = Swish(r_t) * LN(o_t),  Swish(x) = x sigmoid(x)  (Eq. (attn_gla) rows 4-5, up to the projection W_O)
+ * LN takes mean and (biased) variance over the dv entries of one head's o_t, adds ln_eps
+ * under the square root, and applies weight and bias rows of that head.
+ *
+ *   z_alpha     DEVICE, qkv_dtype [B,H,T,dk]: X W_alpha + b_alpha                         (read)
+ *   tau         temperature, > 0 (the DiG configurations use 16)
+ *   r_pre       DEVICE, qkv_dtype [B,H,T,dv]: X W_r + b_r, or NULL: no epilogue, `out`
+ *               receives o_t as in gla_fwd_ex (the three ln_ arguments are then ignored)    (read)
+ *   ln_weight, ln_bias   DEVICE, fp32 [H,dv], or NULL for all ones / all zeros            (read)
+ *   ln_eps      >= 0
+ *
+ * Everything else as gla_fwd_ex ([B,H,T,d] order, zero initial state); same status codes,
+ * GLA_ERR_SHAPE also for tau <= 0 or ln_eps < 0.  Never allocates.
+ */
+int gla_fwd_fused(const void *q, const void *k, const void *v, const void *z_alpha, float tau,
+                  const void *r_pre, const float *ln_weight, const float *ln_bias, float ln_eps,
+                  int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                  int qkv_dtype, int out_dtype, void *out, float *final_state,
+                  void *workspace, size_t workspace_bytes, gla_stream_t stream);
+
 /* Bytes of workspace gla_fwd_ex / gla_fwd_layout need for this problem (an upper bound over all
  * launch plans, so it does not depend on tuning options).  0 on invalid sizes. */
 size_t gla_fwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);

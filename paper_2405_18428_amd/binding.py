@@ -61,6 +61,9 @@ def load_library():
     lib.gla_fwd_layout.argtypes = [vp, vp, vp, vp] + shape + [i, i, i, vp, vp, vp, vp, sz, vp]
     lib.gla_bwd.restype = i
     lib.gla_bwd.argtypes = [vp] * 5 + shape + [i] + [vp] * 4 + [vp, sz, vp]
+    lib.gla_fwd_fused.restype = i
+    lib.gla_fwd_fused.argtypes = [vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, ctypes.c_float] + shape + \
+        [i, i, vp, vp, vp, sz, vp]
     lib.gla_bwd_workspace_bytes.restype = sz
     lib.gla_bwd_workspace_bytes.argtypes = [i] * 6
     lib.gla_fwd_timed.restype = i
@@ -227,6 +230,49 @@ def gla_fwd_layout(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, la
                                   initial_state.data_ptr() if initial_state is not None else None,
                                   out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
                                   workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return out, final_state
+
+
+def gla_fwd_fused(q, k, v, z_alpha, tau, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, r_pre=None, ln_weight=None,
+                  ln_bias=None, ln_eps=1e-5, out_dtype=None, want_final_state=True, out=None, final_state=None,
+                  workspace=None, stream=None):
+    """Forward pass with the gates taken from their pre-activations (``log_alpha = logsigmoid(z_alpha) / tau``) and,
+    if ``r_pre`` is given, ``Swish(r_pre) * LayerNorm_head(o)`` stored instead of ``o``.  q, k, v, z_alpha, r_pre
+    share one element type; ln_weight / ln_bias are fp32 [H, dv] or None."""
+    torch = _torch()
+    lib = load_library()
+    tensors = [("q", q), ("k", k), ("v", v), ("z_alpha", z_alpha)] + ([("r_pre", r_pre)] if r_pre is not None else [])
+    for name, t in tensors:
+        if not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous 4-d GPU tensor")
+        if t.dtype != q.dtype:
+            raise TypeError("q, k, v, z_alpha and r_pre must share one element type")
+    if q.shape != k.shape or q.shape != z_alpha.shape or v.shape[:3] != q.shape[:3]:
+        raise ValueError("q, k, z_alpha must share one shape and v its first three sizes")
+    if r_pre is not None and r_pre.shape != v.shape:
+        raise ValueError("r_pre must have the shape of v")
+    B, H, T, dk = q.shape
+    dv = v.shape[3]
+    for name, t in (("ln_weight", ln_weight), ("ln_bias", ln_bias)):
+        if t is not None and (t.dtype != torch.float32 or tuple(t.shape) != (H, dv) or not t.is_contiguous()
+                              or not t.is_cuda):
+            raise ValueError(f"{name} must be a contiguous fp32 GPU tensor [H,dv]")
+    qdt = _dt(q)
+    if out is None:
+        odt = torch.float32 if out_dtype is None else out_dtype
+        out = torch.empty(tuple(v.shape), dtype=odt, device=q.device)
+    if final_state is None and want_final_state:
+        final_state = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        nbytes = gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
+        workspace = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=q.device)
+    ptr = lambda t: t.data_ptr() if t is not None else None
+    with torch.cuda.device(q.device):
+        _check(lib.gla_fwd_fused(q.data_ptr(), k.data_ptr(), v.data_ptr(), z_alpha.data_ptr(), float(tau),
+                                 ptr(r_pre), ptr(ln_weight), ptr(ln_bias), float(ln_eps),
+                                 B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt, _dt(out),
+                                 out.data_ptr(), ptr(final_state), workspace.data_ptr(), workspace.numel(),
+                                 _stream_ptr(stream)))
     return out, final_state
 
 

@@ -8,7 +8,7 @@
 namespace gla {
 namespace {
 
-constexpr int kVersion = 200;  // 0.2.0
+constexpr int kVersion = 210;  // 0.2.1
 
 int g_opt_chunks_per_span = 0;
 int g_opt_engine = GLA_ENGINE_AUTO;
@@ -164,6 +164,15 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
     return GLA_OK;
 }
 
+// arguments of the gate prologue and the output epilogue (gla_fwd_fused)
+struct FusedArgs {
+    const void *z;
+    float tau;
+    const void *r_pre;
+    const float *ln_weight, *ln_bias;
+    float ln_eps;
+};
+
 struct PhaseEvents {
     hipEvent_t ev[4];
 };
@@ -172,10 +181,16 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
         int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
         int qkv_dtype, int out_dtype, void *out, float *final_state,
         void *workspace, size_t ws_bytes, hipStream_t stream, PhaseEvents *events,
-        int layout = GLA_LAYOUT_BHTD, const float *initial_state = nullptr) {
-    int st = validate(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir,
-                      qkv_dtype, out_dtype, out, final_state);
+        int layout = GLA_LAYOUT_BHTD, const float *initial_state = nullptr, const FusedArgs *fused = nullptr) {
+    // with the gate prologue the gate rows are z (checked like log_alpha: non-null, aligned)
+    int st = validate(q, k, v, fused ? static_cast<const float *>(fused->z) : log_alpha, B, H, T, dk, dv,
+                      grid_h, grid_w, scan_dir, qkv_dtype, out_dtype, out, final_state);
     if (st != GLA_OK) return st;
+    if (fused) {
+        if (!(fused->tau > 0.f) || !(fused->ln_eps >= 0.f)) return GLA_ERR_SHAPE;
+        if (misaligned(fused->r_pre) || misaligned(fused->ln_weight) || misaligned(fused->ln_bias))
+            return GLA_ERR_ALIGN;
+    }
     if (layout != GLA_LAYOUT_BHTD && layout != GLA_LAYOUT_BTHD) return GLA_ERR_SHAPE;
     if (initial_state && misaligned(initial_state)) return GLA_ERR_ALIGN;
     if (!workspace || misaligned(workspace) || ws_bytes < workspace_bytes(B, H, T, dk, dv))
@@ -187,6 +202,15 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     p.grid_h = grid_h; p.grid_w = grid_w; p.scan_dir = scan_dir;
     p.qkv_dtype = qkv_dtype; p.out_dtype = out_dtype;
     p.initial_state = initial_state;
+    if (fused) {
+        p.log_alpha = nullptr;
+        p.z_gate = fused->z;
+        p.inv_tau = 1.f / fused->tau;
+        p.r_pre = fused->r_pre;
+        p.ln_weight = fused->ln_weight;
+        p.ln_bias = fused->ln_bias;
+        p.ln_eps = fused->ln_eps;
+    }
     if (layout == GLA_LAYOUT_BHTD) {
         p.st_k = dk; p.sh_k = (long long)T * dk; p.sb_k = (long long)H * T * dk;
         p.st_v = dv; p.sh_v = (long long)T * dv; p.sb_v = (long long)H * T * dv;
@@ -250,6 +274,17 @@ int gla_fwd_layout(const void *q, const void *k, const void *v, const float *log
     return run(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype, out_dtype,
                out, final_state, workspace, workspace_bytes_, static_cast<hipStream_t>(stream), nullptr,
                layout, initial_state);
+}
+
+int gla_fwd_fused(const void *q, const void *k, const void *v, const void *z_alpha, float tau,
+                  const void *r_pre, const float *ln_weight, const float *ln_bias, float ln_eps,
+                  int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                  int qkv_dtype, int out_dtype, void *out, float *final_state,
+                  void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
+    const FusedArgs fused{z_alpha, tau, r_pre, ln_weight, ln_bias, ln_eps};
+    return run(q, k, v, nullptr, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype, out_dtype,
+               out, final_state, workspace, workspace_bytes_, static_cast<hipStream_t>(stream), nullptr,
+               GLA_LAYOUT_BHTD, nullptr, &fused);
 }
 
 int gla_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const void *d_out,

@@ -47,6 +47,16 @@ struct Params {
     int chain_in_output;    // 1: no phase-2 kernel; the output pass chains U_0..U_{r-1} itself and phase 1
                             //    skips the last span of every (batch, head) (nobody reads its U)
     int qkv_dtype, out_dtype;
+    // gate prologue (Eq. (gate_gla)): if z_gate is set, log_alpha is not read; the gate of a row is
+    // logsigmoid(z) * inv_tau, z in the element type of q, k, v and laid out like log_alpha
+    const void *z_gate;
+    float inv_tau;
+    // output epilogue (Eq. (attn_gla) rows 4-5 up to the output projection): if r_pre is set, the stored row is
+    // Swish(r_pre) * LN(o) with LN over the dv entries of the head; r_pre in the element type of q, k, v and laid
+    // out like v; ln_weight / ln_bias: [H, dv] fp32 or null (1 and 0)
+    const void *r_pre;
+    const float *ln_weight, *ln_bias;
+    float ln_eps;
 };
 
 // Scan step s -> canonical token index (Sec. 3.3 / Algorithm 1 orders).

@@ -67,7 +67,9 @@ struct Layout {
     static constexpr int oQLo = oQHi + kRowOp;
     static constexpr int oStHi = oQLo + kRowOp;
     static constexpr int oStLo = oStHi + kSt;
-    static constexpr int oEndOut = oStLo + kSt;
+    static constexpr int oLnW = oStLo + kSt;                              // float[kDvp] LayerNorm weight of this head
+    static constexpr int oLnB = oLnW + kDvp * 4;                          // float[kDvp] LayerNorm bias
+    static constexpr int oEndOut = oLnB + kDvp * 4;
     static constexpr int kBytes = kOut ? oEndOut : oEndState;
 };
 
@@ -97,7 +99,8 @@ struct TileMap {
 
 // MINW = waves per SIMD the register budget must allow (4 -> 128 VGPRs, 2 -> 256 VGPRs).
 // DEPTH = chunks of rows kept in flight from HBM (register sets; 2 only in the state pass).
-template <int MODE, int NDK8, int NDV16, int NW, int MINW, int DEPTH, typename TOut>
+// FUSE = the gate prologue (gates from bf16 pre-activations) and, in the output pass, the optional epilogue.
+template <int MODE, int NDK8, int NDV16, int NW, int MINW, int DEPTH, bool FUSE, typename TOut>
 __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     using L = Layout<MODE, NDK8, NDV16>;
     constexpr bool OUT = MODE == kModeOutput;
@@ -131,6 +134,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     uint16_t *s_qlo = reinterpret_cast<uint16_t *>(smem + L::oQLo);
     uint16_t *s_sthi = reinterpret_cast<uint16_t *>(smem + L::oStHi);
     uint16_t *s_stlo = reinterpret_cast<uint16_t *>(smem + L::oStLo);
+    float *s_lnw = reinterpret_cast<float *>(smem + L::oLnW);
+    float *s_lnb = reinterpret_cast<float *>(smem + L::oLnB);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -167,6 +172,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     const char *gk = static_cast<const char *>(p.k) + base_k * 2;
     const char *gv = static_cast<const char *>(p.v) + base_v * 2;
     const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + base_k * 4;
+    const char *gz = static_cast<const char *>(p.z_gate) + base_k * 2;
+    const char *grp = static_cast<const char *>(p.r_pre) + base_v * 2;
+    const bool epilogue = FUSE && OUT && p.r_pre != nullptr;   // uniform
     char *gout = static_cast<char *>(p.out) + base_v * sizeof(TOut);
 
     // ---- state tiles owned by this wave (TileMap) ----
@@ -251,6 +259,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     for (int i = tid; i < L::kBytes / 16; i += NTHR)
         reinterpret_cast<u32x4 *>(smem)[i] = u32x4{0, 0, 0, 0};
     __syncthreads();
+    if constexpr (FUSE && OUT) {
+        if (epilogue) {
+            const int h = bh % p.H;
+            for (int n = tid; n < dv; n += NTHR) {
+                s_lnw[n] = p.ln_weight != nullptr ? p.ln_weight[h * dv + n] : 1.f;
+                s_lnb[n] = p.ln_bias != nullptr ? p.ln_bias[h * dv + n] : 0.f;
+            }
+        }
+    }
     if (tid < (DEPTH + 1) * kChunk) {
         const int s = s_begin + tid;
         const int sc = (s < s_end) ? s : s_begin;
@@ -302,6 +319,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     const uint32_t dk2 = 2u * (uint32_t)p.st_k, dv2 = 2u * (uint32_t)p.st_v;  // bytes from one bf16 row to the next
 
     f32x4 r_la[DEPTH][kSlots + 1];
+    u32x2 r_z[DEPTH][FUSE ? kSlots + 1 : 1];   // gate pre-activations (bf16) in place of log_alpha rows
     u32x2 r_k[DEPTH][kSlots + 1];
     u32x2 r_q[DEPTH][OUT ? kSlots + 1 : 1];
     u32x4 r_v[DEPTH][kVSlots + 1];
@@ -319,14 +337,18 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             if (UNCOND || m < nslots) {
                 const uint32_t pc = 8u * (uint32_t)min(m * PPS + psub, pcs - 1);
                 const uint32_t e2 = row_k + pc;
-                r_la[S][m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * (row_g + pc));
+                if constexpr (FUSE) r_z[S][m] = *reinterpret_cast<const u32x2 *>(gz + row_g + pc);
+                else r_la[S][m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * (row_g + pc));
                 r_k[S][m] = *reinterpret_cast<const u32x2 *>(gk + e2);
                 if constexpr (OUT) r_q[S][m] = *reinterpret_cast<const u32x2 *>(gq + e2);
             }
         }
         if (UNCOND || has_rem) {
             const uint32_t e2 = (uint32_t)tok[rrow] * dk2 + 2u * (uint32_t)rch;
-            r_la[S][kSlots] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * ((uint32_t)tokg[rrow] * dk2 + 2u * (uint32_t)rch));
+            if constexpr (FUSE)
+                r_z[S][kSlots] = *reinterpret_cast<const u32x2 *>(gz + (uint32_t)tokg[rrow] * dk2 + 2u * (uint32_t)rch);
+            else
+                r_la[S][kSlots] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * ((uint32_t)tokg[rrow] * dk2 + 2u * (uint32_t)rch));
             r_k[S][kSlots] = *reinterpret_cast<const u32x2 *>(gk + e2);
             if constexpr (OUT) r_q[S][kSlots] = *reinterpret_cast<const u32x2 *>(gq + e2);
         }
@@ -358,6 +380,23 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
 
         // ================= (a) registers -> LDS =================
         const int nvalid = min(kChunk, s_end - s_begin - chunk * kChunk);  // rows of this chunk that are tokens
+        if constexpr (FUSE) {
+            // log2(alpha) = log2(sigmoid(z)) / tau = (min(t, 0) - log2(1 + 2^-|t|)) / tau with t = z log2(e)
+            auto gate2 = [&](uint32_t pair, float &lo, float &hi) {
+                const float t0 = bf16_lo_as_float(pair) * kLog2e, t1 = bf16_hi_as_float(pair) * kLog2e;
+                lo = (fminf(t0, 0.f) - __builtin_amdgcn_logf(1.f + exp2_fast(-fabsf(t0)))) * p.inv_tau;
+                hi = (fminf(t1, 0.f) - __builtin_amdgcn_logf(1.f + exp2_fast(-fabsf(t1)))) * p.inv_tau;
+            };
+#pragma unroll
+            for (int m = 0; m <= kSlots; ++m) {
+                f32x4 la;
+                float a0, a1, a2, a3;
+                gate2(r_z[S][m][0], a0, a1);
+                gate2(r_z[S][m][1], a2, a3);
+                la = f32x4{a0, a1, a2, a3};
+                r_la[S][m] = la;
+            }
+        }
         if (nvalid < kChunk) {
             if (prow >= nvalid) {
 #pragma unroll
@@ -435,7 +474,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                         const f32x4 x = *reinterpret_cast<const f32x4 *>(s_la + j * LAS + c0 + 4 * v4);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            const float gi = x[i] * kLog2e;
+                            const float gi = FUSE ? x[i] : x[i] * kLog2e;
                             bb[4 * v4 + i] = wave_inclusive_scan(gi);
                         }
                     }
@@ -503,7 +542,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             for (int li = 0; li < kMaxLeft; ++li) {
                 const int c = left0 + w * lpw + li;
                 if (li < lpw && c < dk) {
-                    const float b = wave_inclusive_scan(s_la[j * LAS + c] * kLog2e);
+                    const float b = wave_inclusive_scan(FUSE ? s_la[j * LAS + c] : s_la[j * LAS + c] * kLog2e);
                     const float kx = bf16_bits_to_float(s_khi[j * CHS + c]) * exp2_fast(fminf(-b, kMaxExp2));
                     float qx = 0.f, e = 0.f;
                     if constexpr (OUT) {
@@ -680,6 +719,17 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
 
 #pragma unroll
                 for (int x = 0; x < NX; ++x) o[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+                // epilogue operand: this lane's four columns per tile of the output-gate pre-activations, fetched
+                // now so that they have arrived when the rows are complete (rows past the span repeat a valid token)
+                u32x2 rg[FUSE ? NX : 1];
+                if constexpr (FUSE) {
+                    if (epilogue) {
+                        const char *rrow = grp + ((uint32_t)tok[16 * IT + lm] * (uint32_t)p.st_v + 4u * (uint32_t)g) * 2u;
+#pragma unroll
+                        for (int x = 0; x < NX; ++x)
+                            rg[x] = (4 * g + 16 * x < dv) ? *reinterpret_cast<const u32x2 *>(rrow + 32 * x) : u32x2{0, 0};
+                    }
+                }
                 ph[1] = u32x2{0, 0};
                 pl[1] = u32x2{0, 0};
                 // batch 0: Q~ and the first two score tiles' K~
@@ -722,6 +772,48 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     load_state_first();
                     qs(1, 1);
                     __builtin_amdgcn_sched_barrier(0);
+                }
+                if constexpr (FUSE) {
+                    if (epilogue) {
+                        // Swish(r) * LN(o): a token's row is spread over the four lanes lm, lm+16, lm+32, lm+48
+                        // (columns past dv are exact zeros: they add nothing to the sum and are left out of the
+                        // squares)
+                        const float inv_n = 1.f / (float)dv;
+                        float sum = 0.f;
+#pragma unroll
+                        for (int x = 0; x < NX; ++x) sum += (o[x][0] + o[x][1]) + (o[x][2] + o[x][3]);
+                        sum += __shfl_xor(sum, 16);
+                        sum += __shfl_xor(sum, 32);
+                        const float mean = sum * inv_n;
+                        float sq = 0.f;
+#pragma unroll
+                        for (int x = 0; x < NX; ++x) {
+                            if (4 * g + 16 * x < dv) {
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) {
+                                    const float d = o[x][r] - mean;
+                                    sq = fmaf(d, d, sq);
+                                }
+                            }
+                        }
+                        sq += __shfl_xor(sq, 16);
+                        sq += __shfl_xor(sq, 32);
+                        const float rstd = __builtin_amdgcn_rsqf(sq * inv_n + p.ln_eps);
+#pragma unroll
+                        for (int x = 0; x < NX; ++x) {
+                            if (4 * g + 16 * x < dv) {
+                                const f32x4 lw = *reinterpret_cast<const f32x4 *>(s_lnw + 16 * x + 4 * g);
+                                const f32x4 lb = *reinterpret_cast<const f32x4 *>(s_lnb + 16 * x + 4 * g);
+                                const float rv[4] = {bf16_lo_as_float(rg[x][0]), bf16_hi_as_float(rg[x][0]),
+                                                     bf16_lo_as_float(rg[x][1]), bf16_hi_as_float(rg[x][1])};
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) {
+                                    const float sw = rv[r] * __builtin_amdgcn_rcpf(1.f + exp2_fast(-rv[r] * kLog2e));
+                                    o[x][r] = fmaf((o[x][r] - mean) * rstd, lw[r], lb[r]) * sw;
+                                }
+                            }
+                        }
+                    }
                 }
                 const int row = 16 * IT + lm;
                 if (row < nvalid) {
@@ -810,7 +902,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     if (!OUT && tid < dk) p.ws_lgam[((size_t)bh * p.nspans + sp) * dk + tid] = s_lg[tid] * kLn2;
 }
 
-template <int MODE, int NDK8, int NDV16, int DEPTH, typename TOut>
+template <int MODE, int NDK8, int NDV16, int DEPTH, bool FUSE, typename TOut>
 hipError_t launch_depth(const Params &p, hipStream_t stream) {
     using L = Layout<MODE, NDK8, NDV16>;
     // The state pass is light on registers and runs best with 8 waves (4 per SIMD at two work-groups per compute
@@ -820,7 +912,7 @@ hipError_t launch_depth(const Params &p, hipStream_t stream) {
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int kWavesPerSimd = kGroupsPerCu * NW / 4;
     constexpr int MINW = kWavesPerSimd >= 4 ? 4 : (kWavesPerSimd >= 2 ? 2 : 1);
-    auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, NW, MINW, DEPTH, TOut>;
+    auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, NW, MINW, DEPTH, FUSE, TOut>;
     static bool configured = false;  // per instantiation; the attribute is per function, set once
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -834,21 +926,26 @@ hipError_t launch_depth(const Params &p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int MODE, int NDK8, int NDV16, typename TOut>
+template <int MODE, int NDK8, int NDV16, bool FUSE, typename TOut>
 hipError_t launch_one(const Params &p, hipStream_t stream) {
     // Two chunks of rows in flight pay off in the state pass (short chunk period, registers to spare at the
     // smaller head sizes) once a span is long enough to amortise the second set's start-up.
     if constexpr (MODE == kModeState && NDK8 <= 5 && NDV16 <= 5) {
-        if (p.span_len >= 4 * kChunk) return launch_depth<MODE, NDK8, NDV16, 2, TOut>(p, stream);
+        if (p.span_len >= 4 * kChunk) return launch_depth<MODE, NDK8, NDV16, 2, FUSE, TOut>(p, stream);
     }
-    return launch_depth<MODE, NDK8, NDV16, 1, TOut>(p, stream);
+    return launch_depth<MODE, NDK8, NDV16, 1, FUSE, TOut>(p, stream);
 }
 
 template <int MODE, int NDK8, int NDV16>
 hipError_t launch_dt(const Params &p, hipStream_t stream) {
+    if (p.z_gate != nullptr) {
+        if (MODE == kModeOutput && p.out_dtype == GLA_DT_BF16)
+            return launch_one<MODE, NDK8, NDV16, true, uint16_t>(p, stream);
+        return launch_one<MODE, NDK8, NDV16, true, float>(p, stream);
+    }
     if (MODE == kModeOutput && p.out_dtype == GLA_DT_BF16)
-        return launch_one<MODE, NDK8, NDV16, uint16_t>(p, stream);
-    return launch_one<MODE, NDK8, NDV16, float>(p, stream);
+        return launch_one<MODE, NDK8, NDV16, false, uint16_t>(p, stream);
+    return launch_one<MODE, NDK8, NDV16, false, float>(p, stream);
 }
 
 template <int MODE>

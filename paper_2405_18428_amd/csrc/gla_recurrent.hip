@@ -36,6 +36,7 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
     __shared__ float s_k[kTile][kMaxDk];
     __shared__ float s_a[kTile][kMaxDk];
     __shared__ float s_v[kTile][kMaxDv];
+    __shared__ float s_o[kTile][kMaxDv];   // rows of o awaiting the epilogue
     __shared__ float s_lsum[2][kMaxDk];
     __shared__ int s_tok[kTile];
     __shared__ int s_tokg[kTile];   // token whose gate the scan step uses (the previous step's with gate_shift)
@@ -49,6 +50,9 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
     const size_t base_k = slab_k(p, bh), base_v = slab_v(p, bh);
     const size_t st_k = (size_t)p.st_k, st_v = (size_t)p.st_v;
     const bool col_active = tid < dv;
+    const bool epilogue = MODE == kModeOutput && p.r_pre != nullptr;   // uniform
+    const float *lnw = p.ln_weight != nullptr ? p.ln_weight + (size_t)(bh % p.H) * dv : nullptr;
+    const float *lnb = p.ln_bias != nullptr ? p.ln_bias + (size_t)(bh % p.H) * dv : nullptr;
 
     float S[kMaxDk];
 #pragma unroll
@@ -83,7 +87,13 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
                 int n = s_tok[j];
                 if (n >= 0) {
                     size_t e = base_k + (size_t)n * st_k + sc;
-                    float g = p.log_alpha[base_k + (size_t)s_tokg[j] * st_k + sc];
+                    float g;
+                    if (p.z_gate != nullptr) {   // Eq. (gate_gla): log alpha = logsigmoid(z) / tau
+                        const float z = load_elem<TIn>(p.z_gate, base_k + (size_t)s_tokg[j] * st_k + sc);
+                        g = (fminf(z, 0.f) - log1pf(expf(-fabsf(z)))) * p.inv_tau;
+                    } else {
+                        g = p.log_alpha[base_k + (size_t)s_tokg[j] * st_k + sc];
+                    }
                     lsum += g;
                     s_a[j][sc] = expf(g);
                     s_k[j][sc] = load_elem<TIn>(p.k, e);
@@ -110,7 +120,40 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
                         if (MODE == kModeOutput) o = fmaf(s_q[j][c], S[c], o);
                     }
                 }
-                if (MODE == kModeOutput) store_elem<TOut>(p.out, base_v + (size_t)n * st_v + tid, o);
+                if (MODE == kModeOutput) {
+                    if (epilogue) s_o[j][tid] = o;
+                    else store_elem<TOut>(p.out, base_v + (size_t)n * st_v + tid, o);
+                }
+            }
+        }
+        if (epilogue) {
+            // Eq. (attn_gla) rows 4-5 up to the projection: Swish(r) * LN(o), 8 threads per token of the tile
+            __syncthreads();
+            const int j = tid >> 3, sub = tid & 7;
+            const int n = s_tok[j];
+            const float inv_n = 1.f / (float)dv;
+            float sum = 0.f;
+            for (int c = sub; c < dv; c += 8) sum += s_o[j][c];
+            sum += __shfl_xor(sum, 1);
+            sum += __shfl_xor(sum, 2);
+            sum += __shfl_xor(sum, 4);
+            const float mean = sum * inv_n;
+            float sq = 0.f;
+            for (int c = sub; c < dv; c += 8) {
+                const float d = s_o[j][c] - mean;
+                sq = fmaf(d, d, sq);
+            }
+            sq += __shfl_xor(sq, 1);
+            sq += __shfl_xor(sq, 2);
+            sq += __shfl_xor(sq, 4);
+            const float rstd = 1.f / sqrtf(sq * inv_n + p.ln_eps);
+            if (n >= 0) {
+                for (int c = sub; c < dv; c += 8) {
+                    const size_t e = base_v + (size_t)n * st_v + c;
+                    const float r = load_elem<TIn>(p.r_pre, e);
+                    const float y = (s_o[j][c] - mean) * rstd * (lnw != nullptr ? lnw[c] : 1.f) + (lnb != nullptr ? lnb[c] : 0.f);
+                    store_elem<TOut>(p.out, e, y * (r / (1.f + expf(-r))));
+                }
             }
         }
     }

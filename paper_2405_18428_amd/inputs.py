@@ -115,5 +115,35 @@ def make_inputs(B, H, T, dk, dv, dtype="bf16", seed=0, z_mean=0.0, tau=TAU):
     return d
 
 
+def make_fused_inputs(B, H, T, dk, dv, dtype="bf16", seed=0, z_mean=0.0):
+    """Inputs of the forward pass with gate prologue and output epilogue: q, k, v and the gate pre-activation z
+    drawn exactly as in :func:`make_inputs` (same generator, same order), plus the output-gate pre-activation
+    ``r`` (standard normal, shaped like v) and LayerNorm rows ``ln_w = 1 + 0.1 n``, ``ln_b = 0.1 n`` of shape
+    [H, dv] from a second generator.  For "bf16" q, k, v, z, r hold bf16-representable values and the
+    ``*_bits`` entries their bit patterns."""
+    if dtype not in ("f32", "bf16"):
+        raise ValueError("dtype must be 'f32' or 'bf16'")
+    rng = np.random.Generator(np.random.PCG64(seed))
+    q = rng.standard_normal((B, H, T, dk), dtype=np.float32)
+    k = rng.standard_normal((B, H, T, dk), dtype=np.float32)
+    v = rng.standard_normal((B, H, T, dv), dtype=np.float32)
+    z = rng.standard_normal((B, H, T, dk), dtype=np.float32)
+    q = (q * np.float32(dk ** -0.5)).astype(np.float32)
+    z = (z + np.float32(z_mean)).astype(np.float32)
+    rng2 = np.random.Generator(np.random.PCG64(seed + 2000))
+    r = rng2.standard_normal((B, H, T, dv), dtype=np.float32)
+    ln_w = (np.float32(1) + np.float32(0.1) * rng2.standard_normal((H, dv), dtype=np.float32)).astype(np.float32)
+    ln_b = (np.float32(0.1) * rng2.standard_normal((H, dv), dtype=np.float32)).astype(np.float32)
+    d = {"dtype": dtype, "ln_w": ln_w, "ln_b": ln_b}
+    for name, a in (("q", q), ("k", k), ("v", v), ("z", z), ("r", r)):
+        if dtype == "bf16":
+            bits = round_to_bf16_bits(a)
+            d[name + "_bits"] = bits
+            d[name] = bf16_bits_to_f32(bits)
+        else:
+            d[name] = a
+    return d
+
+
 def make_config_inputs(cfg: GlaConfig):
     return make_inputs(cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv, cfg.dtype, cfg.seed, cfg.z_mean)
