@@ -126,6 +126,20 @@ def gla_fwd(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD,
     return out, fin
 
 
+def gla_fwd_multi(q, k, v, log_alpha, grid_h, grid_w, scan_dirs, nthreads=0):
+    """Multi-directional scanning (supplement, Algorithms 2 and 3): the same mixer applied along several scan
+    orders of the token grid, every result brought back to canonical token order, and the results added.
+    ``scan_dirs`` is an iterable of scan orders, e.g. (0, 1) for the bidirectional and (0, 1, 2, 3) for the
+    4-directional variant.  Returns the sum [B,H,T,dv] in float64."""
+    total = None
+    for d in scan_dirs:
+        o, _ = gla_fwd(q, k, v, log_alpha, grid_h, grid_w, d, nthreads=nthreads)
+        total = o if total is None else total + o
+    if total is None:
+        raise ValueError("no scan order given")
+    return total
+
+
 def gla_bwd(q, k, v, log_alpha, d_out, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, nthreads=0):
     """fp64 reverse-mode derivative of :func:`gla_fwd` (zero initial state, loss depending on ``out`` only),
     one scan step at a time (C loop nest of ``gla_oracle_bwd.c``).

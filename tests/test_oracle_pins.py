@@ -312,3 +312,56 @@ def test_oracle_rejects_bad_grid(oracle):
     x = np.zeros((1, 1, 6, 2))
     with pytest.raises(ValueError):
         oracle.gla_fwd(x, x, x, x, 2, 2, ROW_FWD)
+
+
+# ---------------------------------------------------------------------------
+# multi-directional scanning (supplement, Algorithms 2 and 3) written out with the matrix operators the
+# paper names (flip, reshape2d, transpose, flatten, +) around the row-forward scan only
+# ---------------------------------------------------------------------------
+def _flip(x):
+    return x[:, :, ::-1]
+
+
+def _transpose_tokens(x, gh, gw):
+    """flatten(transpose(reshape2d(x))) for a token axis that is row-major over a gh x gw grid."""
+    B, H, T, D = x.shape
+    return x.reshape(B, H, gh, gw, D).transpose(0, 1, 3, 2, 4).reshape(B, H, T, D)
+
+
+def test_bidirectional_and_four_directional_scanning_written_out(oracle):
+    rng = np.random.default_rng(77)
+    B, H, gh, gw, dk, dv = 2, 2, 3, 5, 4, 6
+    T = gh * gw
+    q, k, g = _rand(rng, B, H, T, dk), _rand(rng, B, H, T, dk), _gates(rng, B, H, T, dk)
+    v = _rand(rng, B, H, T, dv)
+    row = lambda a, b, c, d, h, w: oracle.gla_fwd(a, b, c, d, h, w, ROW_FWD)[0]
+    # Algorithm 2: GLA(z) + flip(GLA(flip(z)))
+    out1 = row(q, k, v, g, gh, gw)
+    out2 = _flip(row(_flip(q), _flip(k), _flip(v), _flip(g), gh, gw))
+    np.testing.assert_allclose(oracle.gla_fwd_multi(q, k, v, g, gh, gw, (ROW_FWD, ROW_REV)), out1 + out2,
+                               rtol=1e-12, atol=1e-12)
+    # Algorithm 3: the third input is the transposed grid flattened, the fourth its flip; each output is
+    # brought back by the inverse operators (the transpose of a gw x gh grid, after un-flipping)
+    tq, tk, tv, tg = (_transpose_tokens(a, gh, gw) for a in (q, k, v, g))
+    o3 = row(tq, tk, tv, tg, gw, gh)
+    out3 = _transpose_tokens(o3, gw, gh)
+    o4 = row(_flip(tq), _flip(tk), _flip(tv), _flip(tg), gw, gh)
+    out4 = _transpose_tokens(_flip(o4), gw, gh)
+    np.testing.assert_allclose(oracle.gla_fwd_multi(q, k, v, g, gh, gw, (0, 1, 2, 3)), out1 + out2 + out3 + out4,
+                               rtol=1e-12, atol=1e-12)
+    # each direction contributes: dropping one changes the sum
+    assert np.abs(oracle.gla_fwd_multi(q, k, v, g, gh, gw, (0, 1, 2)) - (out1 + out2 + out3 + out4)).max() > 1e-3
+    with pytest.raises(ValueError):
+        oracle.gla_fwd_multi(q, k, v, g, gh, gw, ())
+
+
+def test_bidirectional_without_decay_is_full_attention_plus_diagonal(oracle):
+    # with all gates open the forward scan sums over i <= t and the reversed one over i >= t: together every
+    # pair once and the diagonal twice
+    rng = np.random.default_rng(78)
+    B, H, T, dk, dv = 1, 2, 9, 3, 4
+    q, k, v = _rand(rng, B, H, T, dk), _rand(rng, B, H, T, dk), _rand(rng, B, H, T, dv)
+    g = np.zeros((B, H, T, dk))
+    a = np.einsum("bhic,bhjc->bhij", q, k)
+    full = np.einsum("bhij,bhjn->bhin", a, v) + np.einsum("bhii,bhin->bhin", a, v)
+    np.testing.assert_allclose(oracle.gla_fwd_multi(q, k, v, g, 3, 3, (ROW_FWD, ROW_REV)), full, rtol=1e-12, atol=1e-12)
