@@ -112,6 +112,60 @@ def bench_fused(args, cfg, gla, gi, torch, np):
     print(json.dumps(result), flush=True)
 
 
+def bench_multi(args, cfg, d, gla, gi, torch, np, dirs):
+    """gla_fwd_multi (sum over scan orders) on the workload: whole-call timing over rotating buffer sets."""
+    dev = torch.device("cuda:0")
+    B, H, T, dk, dv = cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv
+    bf16 = cfg.dtype == "bf16"
+    if bf16:
+        host = [torch.from_numpy(d[n + "_bits"].view(np.int16)).view(torch.bfloat16) for n in ("q", "k", "v")]
+    else:
+        host = [torch.from_numpy(d[n]) for n in ("q", "k", "v")]
+    host.append(torch.from_numpy(d["log_alpha"]))
+    qdt = gla.DT_BF16 if bf16 else gla.DT_F32
+    ws_bytes = gla.gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
+    sets = []
+    for _ in range(max(1, args.sets)):
+        sets.append([t.to(dev) for t in host] + [torch.empty((B, H, T, dv), dtype=torch.float32, device=dev),
+                                                 torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)])
+
+    def step(i):
+        q, k, v, la, out, ws = sets[i % len(sets)]
+        return gla.gla_fwd_multi(q, k, v, la, cfg.grid_h, cfg.grid_w, dirs, out=out, workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    qb = 2 if bf16 else 4
+    alg_bytes = (2 * dk * qb + dk * 4 + dv * qb + dv * 4) * B * H * T   # inputs read once, the sum written once
+    achieved = alg_bytes / (ms * 1e-3) / 1e9
+    result = {
+        "metric": f"GLA fwd, {len(dirs)} scan orders summed, tokens/s at DiG-XL/2 shape T=16384",
+        "value": round(B * T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} scan orders {list(dirs)}: B={B} H={H} T={T} ({cfg.grid_h}x{cfg.grid_w}) "
+                               f"dk={dk} dv={dv} {cfg.dtype} q/k/v, fp32 log_alpha, fp32 out",
+                   "buffer_sets": len(sets)},
+        "roofline": {"bound": "hbm", "kernel": "whole_call", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes": alg_bytes, "kernel_ms": round(ms, 5)},
+    }
+    if not args.no_check:
+        from oracle import gla_oracle
+        ref = gla_oracle.gla_fwd_multi(d["q"], d["k"], d["v"], d["log_alpha"], cfg.grid_h, cfg.grid_w, dirs)
+        got = step(0)
+        torch.cuda.synchronize()
+        rms = float(np.sqrt(np.mean(ref ** 2)))
+        result["max_err_over_rms"] = round(float(np.abs(got.cpu().numpy() - ref).max() / rms), 6)
+    print(json.dumps(result), flush=True)
+
+
 def bench_backward(args, cfg, d, gla, gi, torch, np):
     """gla_bwd on the workload: whole-call timing over rotating buffer sets, oracle timing, parity figure."""
     dev = torch.device("cuda:0")
@@ -194,9 +248,10 @@ def main():
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated over (1 = cache-warm)")
     ap.add_argument("--chunks-per-span", type=int, default=0)
     ap.add_argument("--engine", type=int, default=0)
-    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "fused"],
+    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "fused", "bidir", "4dir"],
                     help="fwd: the forward hot path (the headline); bwd: gla_bwd on the same workload; "
-                         "fused: gla_fwd_fused (gate prologue, Swish/LayerNorm epilogue) on the same workload")
+                         "fused: gla_fwd_fused (gate prologue, Swish/LayerNorm epilogue) on the same workload; "
+                         "bidir / 4dir: gla_fwd_multi over scan orders (0, 1) / (0, 1, 2, 3)")
     ap.add_argument("--layout", default="bhtd", choices=["bhtd", "bthd"],
                     help="memory order of q, k, v, log_alpha, out: [B,H,T,d] (the headline) or [B,T,H,d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -233,6 +288,9 @@ def main():
         return
     if args.which == "fused":
         bench_fused(args, cfg, gla, gi, torch, np)
+        return
+    if args.which in ("bidir", "4dir"):
+        bench_multi(args, cfg, d, gla, gi, torch, np, (0, 1) if args.which == "bidir" else (0, 1, 2, 3))
         return
     B, H, T, dk, dv = cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv
     if cfg.dtype == "bf16":

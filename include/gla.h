@@ -174,6 +174,24 @@ int gla_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
 size_t gla_bwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);
 
 /*
+ * gla_fwd_multi - multi-directional scanning (supplement, Algorithms 2 and 3): the sum over
+ * several scan orders of the outputs of gla_fwd_ex on the same q, k, v, log_alpha, every
+ * term in canonical token order:  out = sum over d in scan_mask of gla_fwd_ex(..., scan_dir = d).
+ *
+ *   scan_mask   bit d set (d = gla_scan_dir): scan order d takes part; 0x3 is the
+ *               bidirectional variant, 0xF the 4-directional one; 1..15
+ *   out         DEVICE, fp32 [B,H,T,dv]                                              (written)
+ *
+ * q, k, v, log_alpha, sizes, workspace (gla_fwd_workspace_bytes) and stream as gla_fwd_ex;
+ * no final state is returned (each scan order ends in its own).  The scan orders run one
+ * after the other on `stream`; the first writes `out`, the others add to it.  Same status
+ * codes as gla_fwd_ex, GLA_ERR_SHAPE for a mask outside 1..15.  Never allocates.
+ */
+int gla_fwd_multi(const void *q, const void *k, const void *v, const float *log_alpha,
+                  int B, int H, int T, int dk, int dv, int grid_h, int grid_w, unsigned scan_mask,
+                  int qkv_dtype, float *out, void *workspace, size_t workspace_bytes, gla_stream_t stream);
+
+/*
  * gla_fwd_fused - gla_fwd_ex with the gate computed from its pre-activation inside the kernels
  * and, optionally, the output gate and normalisation applied before the store:
  *   log alpha_t = logsigmoid(z_t) / tau                  (Eq. (gate_gla), alpha = sigmoid(z)^(1/tau))

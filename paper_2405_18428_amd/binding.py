@@ -61,6 +61,8 @@ def load_library():
     lib.gla_fwd_layout.argtypes = [vp, vp, vp, vp] + shape + [i, i, i, vp, vp, vp, vp, sz, vp]
     lib.gla_bwd.restype = i
     lib.gla_bwd.argtypes = [vp] * 5 + shape + [i] + [vp] * 4 + [vp, sz, vp]
+    lib.gla_fwd_multi.restype = i
+    lib.gla_fwd_multi.argtypes = [vp, vp, vp, vp] + [i] * 7 + [ctypes.c_uint, i, vp, vp, sz, vp]
     lib.gla_fwd_fused.restype = i
     lib.gla_fwd_fused.argtypes = [vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, ctypes.c_float] + shape + \
         [i, i, vp, vp, vp, sz, vp]
@@ -231,6 +233,38 @@ def gla_fwd_layout(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, la
                                   out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
                                   workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return out, final_state
+
+
+def gla_fwd_multi(q, k, v, log_alpha, grid_h, grid_w, scan_dirs=(SCAN_ROW_FWD, SCAN_ROW_REV), out=None,
+                  workspace=None, stream=None):
+    """Sum over the scan orders in ``scan_dirs`` of the forward outputs (fp32, canonical token order)."""
+    torch = _torch()
+    lib = load_library()
+    for name, t in (("q", q), ("k", k), ("v", v), ("log_alpha", log_alpha)):
+        if not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous 4-d GPU tensor")
+    if q.shape != k.shape or q.shape != log_alpha.shape or v.shape[:3] != q.shape[:3]:
+        raise ValueError("q, k, log_alpha must share one shape and v its first three sizes")
+    if q.dtype != k.dtype or q.dtype != v.dtype or log_alpha.dtype != torch.float32:
+        raise TypeError("q, k, v must share one element type and log_alpha must be fp32")
+    mask = 0
+    for d in scan_dirs:
+        if d not in (0, 1, 2, 3):
+            raise ValueError("scan orders are 0..3")
+        mask |= 1 << d
+    B, H, T, dk = q.shape
+    dv = v.shape[3]
+    qdt = _dt(q)
+    if out is None:
+        out = torch.empty(tuple(v.shape), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        nbytes = gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
+        workspace = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=q.device)
+    with torch.cuda.device(q.device):
+        _check(lib.gla_fwd_multi(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(),
+                                 B, H, T, dk, dv, grid_h, grid_w, mask, qdt, out.data_ptr(),
+                                 workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return out
 
 
 def gla_fwd_fused(q, k, v, z_alpha, tau, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, r_pre=None, ln_weight=None,

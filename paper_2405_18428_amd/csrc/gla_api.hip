@@ -181,7 +181,8 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
         int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
         int qkv_dtype, int out_dtype, void *out, float *final_state,
         void *workspace, size_t ws_bytes, hipStream_t stream, PhaseEvents *events,
-        int layout = GLA_LAYOUT_BHTD, const float *initial_state = nullptr, const FusedArgs *fused = nullptr) {
+        int layout = GLA_LAYOUT_BHTD, const float *initial_state = nullptr, const FusedArgs *fused = nullptr,
+        int accumulate = 0) {
     // with the gate prologue the gate rows are z (checked like log_alpha: non-null, aligned)
     int st = validate(q, k, v, fused ? static_cast<const float *>(fused->z) : log_alpha, B, H, T, dk, dv,
                       grid_h, grid_w, scan_dir, qkv_dtype, out_dtype, out, final_state);
@@ -202,6 +203,8 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     p.grid_h = grid_h; p.grid_w = grid_w; p.scan_dir = scan_dir;
     p.qkv_dtype = qkv_dtype; p.out_dtype = out_dtype;
     p.initial_state = initial_state;
+    if (accumulate && out_dtype != GLA_DT_F32) return GLA_ERR_UNSUPPORTED;
+    p.accumulate = accumulate;
     if (fused) {
         p.log_alpha = nullptr;
         p.z_gate = fused->z;
@@ -285,6 +288,23 @@ int gla_fwd_fused(const void *q, const void *k, const void *v, const void *z_alp
     return run(q, k, v, nullptr, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype, out_dtype,
                out, final_state, workspace, workspace_bytes_, static_cast<hipStream_t>(stream), nullptr,
                GLA_LAYOUT_BHTD, nullptr, &fused);
+}
+
+int gla_fwd_multi(const void *q, const void *k, const void *v, const float *log_alpha,
+                  int B, int H, int T, int dk, int dv, int grid_h, int grid_w, unsigned scan_mask,
+                  int qkv_dtype, float *out, void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
+    if (scan_mask == 0u || scan_mask > 15u) return GLA_ERR_SHAPE;
+    int first = 1;
+    for (int d = 0; d < 4; ++d) {
+        if (!(scan_mask & (1u << d))) continue;
+        // the first scan order writes `out`, the others add to it; the workspace is reused in stream order
+        const int st = run(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, d, qkv_dtype, GLA_DT_F32, out,
+                           nullptr, workspace, workspace_bytes_, static_cast<hipStream_t>(stream), nullptr,
+                           GLA_LAYOUT_BHTD, nullptr, nullptr, first ? 0 : 1);
+        if (st != GLA_OK) return st;   // argument errors show on the first pass, before any launch
+        first = 0;
+    }
+    return GLA_OK;
 }
 
 int gla_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const void *d_out,

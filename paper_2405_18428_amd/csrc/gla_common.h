@@ -47,6 +47,7 @@ struct Params {
     int chain_in_output;    // 1: no phase-2 kernel; the output pass chains U_0..U_{r-1} itself and phase 1
                             //    skips the last span of every (batch, head) (nobody reads its U)
     int qkv_dtype, out_dtype;
+    int accumulate;         // 1: the output pass adds its rows to what `out` (fp32) holds (sums over scan orders)
     // gate prologue (Eq. (gate_gla)): if z_gate is set, log_alpha is not read; the gate of a row is
     // logsigmoid(z) * inv_tau, z in the element type of q, k, v and laid out like log_alpha
     const void *z_gate;

@@ -100,7 +100,8 @@ struct TileMap {
 // MINW = waves per SIMD the register budget must allow (4 -> 128 VGPRs, 2 -> 256 VGPRs).
 // DEPTH = chunks of rows kept in flight from HBM (register sets; 2 only in the state pass).
 // FUSE = the gate prologue (gates from bf16 pre-activations) and, in the output pass, the optional epilogue.
-template <int MODE, int NDK8, int NDV16, int NW, int MINW, int DEPTH, bool FUSE, typename TOut>
+// ACC = the output pass adds its rows to the fp32 rows already in `out`.
+template <int MODE, int NDK8, int NDV16, int NW, int MINW, int DEPTH, bool FUSE, bool ACC, typename TOut>
 __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     using L = Layout<MODE, NDK8, NDV16>;
     constexpr bool OUT = MODE == kModeOutput;
@@ -120,6 +121,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     static_assert(DEPTH == 1 || (DEPTH == 2 && !OUT), "two register sets only in the state pass");
     static_assert(NTB <= 4 && (DEPTH + 1) * kChunk <= NTHR, "token maps: four buffers, first ones filled in one go");
     static_assert(16 * NCT <= CHS, "state tiles must fit the operand row");
+    static_assert(!ACC || (OUT && !FUSE && sizeof(TOut) == 4), "accumulation: plain output pass, fp32 rows");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int *s_tok = reinterpret_cast<int *>(smem + L::oTok);
@@ -730,6 +732,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                             rg[x] = (4 * g + 16 * x < dv) ? *reinterpret_cast<const u32x2 *>(rrow + 32 * x) : u32x2{0, 0};
                     }
                 }
+                // rows to add to, fetched now so that they have arrived when this chunk's rows are complete
+                f32x4 prev[ACC ? NX : 1];
+                if constexpr (ACC) {
+                    const char *prow_ = gout + ((uint32_t)tok[16 * IT + lm] * (uint32_t)p.st_v + 4u * (uint32_t)g) * 4u;
+#pragma unroll
+                    for (int x = 0; x < NX; ++x)
+                        prev[x] = (4 * g + 16 * x < dv) ? *reinterpret_cast<const f32x4 *>(prow_ + 64 * x)
+                                                        : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
                 ph[1] = u32x2{0, 0};
                 pl[1] = u32x2{0, 0};
                 // batch 0: Q~ and the first two score tiles' K~
@@ -814,6 +825,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                             }
                         }
                     }
+                }
+                if constexpr (ACC) {
+#pragma unroll
+                    for (int x = 0; x < NX; ++x) o[x] += prev[x];
                 }
                 const int row = 16 * IT + lm;
                 if (row < nvalid) {
@@ -902,7 +917,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     if (!OUT && tid < dk) p.ws_lgam[((size_t)bh * p.nspans + sp) * dk + tid] = s_lg[tid] * kLn2;
 }
 
-template <int MODE, int NDK8, int NDV16, int DEPTH, bool FUSE, typename TOut>
+template <int MODE, int NDK8, int NDV16, int DEPTH, bool FUSE, bool ACC, typename TOut>
 hipError_t launch_depth(const Params &p, hipStream_t stream) {
     using L = Layout<MODE, NDK8, NDV16>;
     // The state pass is light on registers and runs best with 8 waves (4 per SIMD at two work-groups per compute
@@ -912,7 +927,7 @@ hipError_t launch_depth(const Params &p, hipStream_t stream) {
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int kWavesPerSimd = kGroupsPerCu * NW / 4;
     constexpr int MINW = kWavesPerSimd >= 4 ? 4 : (kWavesPerSimd >= 2 ? 2 : 1);
-    auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, NW, MINW, DEPTH, FUSE, TOut>;
+    auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, NW, MINW, DEPTH, FUSE, ACC, TOut>;
     static bool configured = false;  // per instantiation; the attribute is per function, set once
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -926,26 +941,29 @@ hipError_t launch_depth(const Params &p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int MODE, int NDK8, int NDV16, bool FUSE, typename TOut>
+template <int MODE, int NDK8, int NDV16, bool FUSE, bool ACC, typename TOut>
 hipError_t launch_one(const Params &p, hipStream_t stream) {
     // Two chunks of rows in flight pay off in the state pass (short chunk period, registers to spare at the
     // smaller head sizes) once a span is long enough to amortise the second set's start-up.
     if constexpr (MODE == kModeState && NDK8 <= 5 && NDV16 <= 5) {
-        if (p.span_len >= 4 * kChunk) return launch_depth<MODE, NDK8, NDV16, 2, FUSE, TOut>(p, stream);
+        if (p.span_len >= 4 * kChunk) return launch_depth<MODE, NDK8, NDV16, 2, FUSE, ACC, TOut>(p, stream);
     }
-    return launch_depth<MODE, NDK8, NDV16, 1, FUSE, TOut>(p, stream);
+    return launch_depth<MODE, NDK8, NDV16, 1, FUSE, ACC, TOut>(p, stream);
 }
 
 template <int MODE, int NDK8, int NDV16>
 hipError_t launch_dt(const Params &p, hipStream_t stream) {
     if (p.z_gate != nullptr) {
         if (MODE == kModeOutput && p.out_dtype == GLA_DT_BF16)
-            return launch_one<MODE, NDK8, NDV16, true, uint16_t>(p, stream);
-        return launch_one<MODE, NDK8, NDV16, true, float>(p, stream);
+            return launch_one<MODE, NDK8, NDV16, true, false, uint16_t>(p, stream);
+        return launch_one<MODE, NDK8, NDV16, true, false, float>(p, stream);
+    }
+    if constexpr (MODE == kModeOutput) {
+        if (p.accumulate) return launch_one<MODE, NDK8, NDV16, false, true, float>(p, stream);   // host checks fp32 out
     }
     if (MODE == kModeOutput && p.out_dtype == GLA_DT_BF16)
-        return launch_one<MODE, NDK8, NDV16, false, uint16_t>(p, stream);
-    return launch_one<MODE, NDK8, NDV16, false, float>(p, stream);
+        return launch_one<MODE, NDK8, NDV16, false, false, uint16_t>(p, stream);
+    return launch_one<MODE, NDK8, NDV16, false, false, float>(p, stream);
 }
 
 template <int MODE>

@@ -121,8 +121,13 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
                     }
                 }
                 if (MODE == kModeOutput) {
-                    if (epilogue) s_o[j][tid] = o;
-                    else store_elem<TOut>(p.out, base_v + (size_t)n * st_v + tid, o);
+                    if (epilogue) {
+                        s_o[j][tid] = o;
+                    } else {
+                        const size_t e = base_v + (size_t)n * st_v + tid;
+                        if (p.accumulate) o += static_cast<const float *>(p.out)[e];   // fp32 rows (host checks)
+                        store_elem<TOut>(p.out, e, o);
+                    }
                 }
             }
         }
