@@ -166,6 +166,57 @@ def bench_multi(args, cfg, d, gla, gi, torch, np, dirs):
     print(json.dumps(result), flush=True)
 
 
+def bench_srem(args, cfg, gla, gi, torch, np):
+    """gla_srem_dwconv on the token matrix of the workload ([B, T, H*dv] bf16 in and out)."""
+    dev = torch.device("cuda:0")
+    B, T, D = cfg.B, cfg.T, cfg.H * cfg.dv
+    rng = np.random.Generator(np.random.PCG64(cfg.seed + 3000))
+    x = rng.standard_normal((B, T, D), dtype=np.float32)
+    bits = gi.round_to_bf16_bits(x)
+    x = gi.bf16_bits_to_f32(bits)
+    w = (rng.standard_normal((D, 3, 3), dtype=np.float32) * np.float32(0.3)).astype(np.float32)
+    w[:, 1, 1] += np.float32(1)
+    b = (rng.standard_normal((D,), dtype=np.float32) * np.float32(0.1)).astype(np.float32)
+    wt, bt = torch.from_numpy(w).to(dev), torch.from_numpy(b).to(dev)
+    sets = []
+    for _ in range(max(1, args.sets)):
+        xt = torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        sets.append((xt, torch.empty_like(xt)))
+
+    def step(i):
+        xt, yt = sets[i % len(sets)]
+        return gla.gla_srem_dwconv(xt, wt, bt, cfg.grid_h, cfg.grid_w, args.scan, out=yt)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    alg_bytes = 2 * 2 * B * T * D        # every element read once and written once, bf16
+    achieved = alg_bytes / (ms * 1e-3) / 1e9
+    result = {
+        "metric": "SREM 3x3 depth-wise convolution tokens/s at DiG-XL/2 shape T=16384",
+        "value": round(B * T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} token matrix: B={B} {cfg.grid_h}x{cfg.grid_w} D={D} bf16 in/out, "
+                               f"orient={args.scan}", "buffer_sets": len(sets)},
+        "roofline": {"bound": "hbm", "kernel": "srem_dwconv_kernel", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes": alg_bytes, "kernel_ms": round(ms, 5)},
+    }
+    if not args.no_check:
+        from oracle import srem_oracle as so
+        ref = so.srem_dwconv(x, w, b, cfg.grid_h, cfg.grid_w, args.scan)
+        got = step(0).float().cpu().numpy()
+        rms = float(np.sqrt(np.mean(ref ** 2)))
+        result["max_err_over_rms"] = round(float(np.abs(got - ref).max() / rms), 6)
+    print(json.dumps(result), flush=True)
+
+
 def bench_backward(args, cfg, d, gla, gi, torch, np):
     """gla_bwd on the workload: whole-call timing over rotating buffer sets, oracle timing, parity figure."""
     dev = torch.device("cuda:0")
@@ -248,10 +299,11 @@ def main():
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated over (1 = cache-warm)")
     ap.add_argument("--chunks-per-span", type=int, default=0)
     ap.add_argument("--engine", type=int, default=0)
-    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "fused", "bidir", "4dir"],
+    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "fused", "bidir", "4dir", "srem"],
                     help="fwd: the forward hot path (the headline); bwd: gla_bwd on the same workload; "
                          "fused: gla_fwd_fused (gate prologue, Swish/LayerNorm epilogue) on the same workload; "
-                         "bidir / 4dir: gla_fwd_multi over scan orders (0, 1) / (0, 1, 2, 3)")
+                         "bidir / 4dir: gla_fwd_multi over scan orders (0, 1) / (0, 1, 2, 3); "
+                         "srem: gla_srem_dwconv on the workload's token matrix")
     ap.add_argument("--layout", default="bhtd", choices=["bhtd", "bthd"],
                     help="memory order of q, k, v, log_alpha, out: [B,H,T,d] (the headline) or [B,T,H,d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -288,6 +340,9 @@ def main():
         return
     if args.which == "fused":
         bench_fused(args, cfg, gla, gi, torch, np)
+        return
+    if args.which == "srem":
+        bench_srem(args, cfg, gla, gi, torch, np)
         return
     if args.which in ("bidir", "4dir"):
         bench_multi(args, cfg, d, gla, gi, torch, np, (0, 1) if args.which == "bidir" else (0, 1, 2, 3))

@@ -174,6 +174,25 @@ int gla_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
 size_t gla_bwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);
 
 /*
+ * gla_srem_dwconv - the 3x3 depth-wise convolution of the spatial reorient & enhancement
+ * module (Sec. 3.3, Algorithm 1: DWConv2d on the 2-D token matrix; every channel has its own
+ * 3x3 kernel, zero padding of one token, stride one; the paper initialises it to the identity).
+ *   y[b, r, c, d] = bias[d] + sum over dy, dx in {-1,0,1} of weight[d, dy+1, dx+1] * x[b, r+dy, c+dx, d]
+ * for orient = 0.  The paper permutes the token sequence between blocks; here tensors stay in
+ * canonical row-major order and `orient` (a gla_scan_dir) names the order the paper's sequence
+ * would be in, so that the result equals: permute, reshape to 2-D, convolve, flatten, un-permute.
+ *
+ *   x        DEVICE, x_dtype [B, grid_h*grid_w, D], 16-byte aligned                  (read)
+ *   weight   DEVICE, fp32 [D, 3, 3]                                                  (read)
+ *   bias     DEVICE, fp32 [D], or NULL                                               (read)
+ *   y        DEVICE, y_dtype [B, grid_h*grid_w, D], 16-byte aligned, not x           (written)
+ *
+ * Status codes as gla_fwd_ex.  Needs no workspace and never allocates.
+ */
+int gla_srem_dwconv(const void *x, const float *weight, const float *bias, int B, int grid_h, int grid_w, int D,
+                    int orient, int x_dtype, int y_dtype, void *y, gla_stream_t stream);
+
+/*
  * gla_fwd_multi - multi-directional scanning (supplement, Algorithms 2 and 3): the sum over
  * several scan orders of the outputs of gla_fwd_ex on the same q, k, v, log_alpha, every
  * term in canonical token order:  out = sum over d in scan_mask of gla_fwd_ex(..., scan_dir = d).

@@ -61,6 +61,8 @@ def load_library():
     lib.gla_fwd_layout.argtypes = [vp, vp, vp, vp] + shape + [i, i, i, vp, vp, vp, vp, sz, vp]
     lib.gla_bwd.restype = i
     lib.gla_bwd.argtypes = [vp] * 5 + shape + [i] + [vp] * 4 + [vp, sz, vp]
+    lib.gla_srem_dwconv.restype = i
+    lib.gla_srem_dwconv.argtypes = [vp, vp, vp] + [i] * 7 + [vp, vp]
     lib.gla_fwd_multi.restype = i
     lib.gla_fwd_multi.argtypes = [vp, vp, vp, vp] + [i] * 7 + [ctypes.c_uint, i, vp, vp, sz, vp]
     lib.gla_fwd_fused.restype = i
@@ -233,6 +235,28 @@ def gla_fwd_layout(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, la
                                   out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
                                   workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return out, final_state
+
+
+def gla_srem_dwconv(x, weight, bias, grid_h, grid_w, orient=0, out_dtype=None, out=None, stream=None):
+    """3x3 depth-wise convolution of the SREM on tokens x [B, T, D] (canonical order); weight fp32 [D,3,3], bias
+    fp32 [D] or None; ``orient`` = the scan order the paper's sequence would be in at this block."""
+    torch = _torch()
+    lib = load_library()
+    if not x.is_cuda or not x.is_contiguous() or x.dim() != 3:
+        raise ValueError("x must be a contiguous 3-d GPU tensor [B,T,D]")
+    B, T, D = x.shape
+    if T != grid_h * grid_w:
+        raise ValueError("T != grid_h * grid_w")
+    if weight.dtype != torch.float32 or tuple(weight.shape) != (D, 3, 3) or not weight.is_contiguous() or not weight.is_cuda:
+        raise ValueError("weight must be a contiguous fp32 GPU tensor [D,3,3]")
+    if bias is not None and (bias.dtype != torch.float32 or tuple(bias.shape) != (D,) or not bias.is_cuda):
+        raise ValueError("bias must be a contiguous fp32 GPU tensor [D]")
+    if out is None:
+        out = torch.empty_like(x, dtype=x.dtype if out_dtype is None else out_dtype)
+    with torch.cuda.device(x.device):
+        _check(lib.gla_srem_dwconv(x.data_ptr(), weight.data_ptr(), bias.data_ptr() if bias is not None else None,
+                                   B, grid_h, grid_w, D, orient, _dt(x), _dt(out), out.data_ptr(), _stream_ptr(stream)))
+    return out
 
 
 def gla_fwd_multi(q, k, v, log_alpha, grid_h, grid_w, scan_dirs=(SCAN_ROW_FWD, SCAN_ROW_REV), out=None,

@@ -290,6 +290,23 @@ int gla_fwd_fused(const void *q, const void *k, const void *v, const void *z_alp
                GLA_LAYOUT_BHTD, nullptr, &fused);
 }
 
+int gla_srem_dwconv(const void *x, const float *weight, const float *bias, int B, int grid_h, int grid_w, int D,
+                    int orient, int x_dtype, int y_dtype, void *y, gla_stream_t stream) {
+    if (!x || !weight || !y) return GLA_ERR_NULL;
+    if (B <= 0 || grid_h <= 0 || grid_w <= 0 || D <= 0 || orient < 0 || orient > 3) return GLA_ERR_SHAPE;
+    if ((x_dtype != GLA_DT_F32 && x_dtype != GLA_DT_BF16) || (y_dtype != GLA_DT_F32 && y_dtype != GLA_DT_BF16))
+        return GLA_ERR_SHAPE;
+    // 32-bit byte offsets inside one batch element, 31-bit strip and work-group counts
+    if ((long long)grid_h * grid_w * D * 4 >= (1LL << 32) || (long long)B * grid_h * grid_w >= (1LL << 31))
+        return GLA_ERR_UNSUPPORTED;
+    if (x == y) return GLA_ERR_SHAPE;   // neighbours are read after a token is written: not in place
+    if (misaligned(x) || misaligned(y) || misaligned(weight) || misaligned(bias)) return GLA_ERR_ALIGN;
+    if (launch_srem_dwconv(x, weight, bias, y, B, grid_h, grid_w, D, orient, x_dtype, y_dtype,
+                           static_cast<hipStream_t>(stream)) != hipSuccess)
+        return GLA_ERR_HIP;
+    return GLA_OK;
+}
+
 int gla_fwd_multi(const void *q, const void *k, const void *v, const float *log_alpha,
                   int B, int H, int T, int dk, int dv, int grid_h, int grid_w, unsigned scan_mask,
                   int qkv_dtype, float *out, void *workspace, size_t workspace_bytes_, gla_stream_t stream) {

@@ -106,5 +106,8 @@ hipError_t launch_mfma_row_read(const Params &p, const void *w, float *r, hipStr
 hipError_t launch_dlog_alpha(const Params &p, const float *dq, const float *dk_grad, float *dg, float *totals,
                              hipStream_t stream);
 int dg_spans(int T);
+// 3x3 depth-wise convolution of the SREM on [B, T, D] tokens (gla_srem.hip)
+hipError_t launch_srem_dwconv(const void *x, const float *w, const float *bias, void *y, int B, int gh, int gw, int D,
+                              int orient, int x_dtype, int y_dtype, hipStream_t stream);
 
 }  // namespace gla
