@@ -303,28 +303,33 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
 
     // ---- which HBM pieces this thread stages (the same for every chunk) ----
     // A row of log_alpha is cut into 16-byte pieces (4 channels), a row of q or k into 8-byte pieces (the same
-    // 4 channels), a row of v into 16-byte pieces (8 columns).  Slot m of a thread is piece m*PPS + tid%PPS of
-    // row tid/PPS; pieces a row has beyond the last whole slot are dealt, one thread each, to the last waves.
-    // A slot that points past the row repeats an earlier piece (same bytes to the same place).
-    constexpr int PPS = NTHR / kChunk;                     // pieces of one row handled per slot
-    constexpr int kSlots = (NDK8 * 2) / PPS;               // whole slots at the largest dk of this instantiation
-    constexpr int kVSlots = (NDV16 * 2) / PPS;
-    const int prow = tid / PPS, psub = tid % PPS;
+    // 4 channels), a row of v into 16-byte pieces (8 columns).  The pieces of a chunk are numbered row by row and
+    // slot m of a thread is piece tid + NTHR m: the lanes of a wave then fetch neighbouring pieces of
+    // neighbouring rows (one contiguous kilobyte when the scan visits rows that are neighbours in memory).
+    // Slots past the last piece repeat it (the load stays in bounds; nothing is written to LDS for them).
+    constexpr int kF = (kChunk * NDK8 * 2 + NTHR - 1) / NTHR;
+    constexpr int kVF = (kChunk * NDV16 * 2 + NTHR - 1) / NTHR;
     const int pcs = dk >> 2, vpcs = dv >> 3;
-    const int nslots = min(kSlots, pcs / PPS), nvslots = min(kVSlots, vpcs / PPS);
-    const int prem = pcs - nslots * PPS, vrem = vpcs - nvslots * PPS;   // left-over pieces per row (< PPS)
-    // 64*rem threads = the last rem waves (in the output pass the first waves also split the state for S_0)
-    const bool has_rem = w >= NW - prem, has_vrem = w >= NW - vrem;
-    const int rid = tid - 64 * (NW - prem), vrid = tid - 64 * (NW - vrem);
-    const int rrow = has_rem ? rid / prem : 0, rch = has_rem ? 4 * (nslots * PPS + rid % prem) : 0;
-    const int vrrow = has_vrem ? vrid / vrem : 0, vrcol = has_vrem ? 8 * (nvslots * PPS + vrid % vrem) : 0;
+    int frp[kF], fvrp[kVF];     // row << 8 | piece
+#pragma unroll
+    for (int m = 0; m < kF; ++m) {
+        const int f = min(tid + NTHR * m, kChunk * pcs - 1);
+        const int row = f / pcs;
+        frp[m] = (row << 8) | (f - row * pcs);
+    }
+#pragma unroll
+    for (int m = 0; m < kVF; ++m) {
+        const int f = min(tid + NTHR * m, kChunk * vpcs - 1);
+        const int row = f / vpcs;
+        fvrp[m] = (row << 8) | (f - row * vpcs);
+    }
     const uint32_t dk2 = 2u * (uint32_t)p.st_k, dv2 = 2u * (uint32_t)p.st_v;  // bytes from one bf16 row to the next
 
-    f32x4 r_la[DEPTH][kSlots + 1];
-    u32x2 r_z[DEPTH][FUSE ? kSlots + 1 : 1];   // gate pre-activations (bf16) in place of log_alpha rows
-    u32x2 r_k[DEPTH][kSlots + 1];
-    u32x2 r_q[DEPTH][OUT ? kSlots + 1 : 1];
-    u32x4 r_v[DEPTH][kVSlots + 1];
+    f32x4 r_la[DEPTH][kF];
+    u32x2 r_z[DEPTH][FUSE ? kF : 1];   // gate pre-activations (bf16) in place of log_alpha rows
+    u32x2 r_k[DEPTH][kF];
+    u32x2 r_q[DEPTH][OUT ? kF : 1];
+    u32x4 r_v[DEPTH][kVF];
 
     // Rows past the end of a ragged last chunk carry the token of a valid row in s_tok (so the loads
     // stay in bounds) and are zeroed when they are written to LDS.
@@ -332,34 +337,20 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
         constexpr int S = decltype(set_c)::value;
         const int *tok = s_tok + (chunk % NTB) * kChunk;
         const int *tokg = s_tokg + (chunk % NTB) * kChunk;
-        const uint32_t row_k = (uint32_t)tok[prow] * dk2, row_v = (uint32_t)tok[prow] * dv2;
-        const uint32_t row_g = (uint32_t)tokg[prow] * dk2;
 #pragma unroll
-        for (int m = 0; m < kSlots; ++m) {
-            if (UNCOND || m < nslots) {
-                const uint32_t pc = 8u * (uint32_t)min(m * PPS + psub, pcs - 1);
-                const uint32_t e2 = row_k + pc;
-                if constexpr (FUSE) r_z[S][m] = *reinterpret_cast<const u32x2 *>(gz + row_g + pc);
-                else r_la[S][m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * (row_g + pc));
-                r_k[S][m] = *reinterpret_cast<const u32x2 *>(gk + e2);
-                if constexpr (OUT) r_q[S][m] = *reinterpret_cast<const u32x2 *>(gq + e2);
-            }
-        }
-        if (UNCOND || has_rem) {
-            const uint32_t e2 = (uint32_t)tok[rrow] * dk2 + 2u * (uint32_t)rch;
-            if constexpr (FUSE)
-                r_z[S][kSlots] = *reinterpret_cast<const u32x2 *>(gz + (uint32_t)tokg[rrow] * dk2 + 2u * (uint32_t)rch);
-            else
-                r_la[S][kSlots] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * ((uint32_t)tokg[rrow] * dk2 + 2u * (uint32_t)rch));
-            r_k[S][kSlots] = *reinterpret_cast<const u32x2 *>(gk + e2);
-            if constexpr (OUT) r_q[S][kSlots] = *reinterpret_cast<const u32x2 *>(gq + e2);
+        for (int m = 0; m < kF; ++m) {
+            const int row = frp[m] >> 8;
+            const uint32_t pc = 8u * (uint32_t)(frp[m] & 255);
+            const uint32_t e2 = (uint32_t)tok[row] * dk2 + pc;
+            const uint32_t eg = (uint32_t)tokg[row] * dk2 + pc;
+            if constexpr (FUSE) r_z[S][m] = *reinterpret_cast<const u32x2 *>(gz + eg);
+            else r_la[S][m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * eg);
+            r_k[S][m] = *reinterpret_cast<const u32x2 *>(gk + e2);
+            if constexpr (OUT) r_q[S][m] = *reinterpret_cast<const u32x2 *>(gq + e2);
         }
 #pragma unroll
-        for (int m = 0; m < kVSlots; ++m)
-            if (UNCOND || m < nvslots)
-                r_v[S][m] = *reinterpret_cast<const u32x4 *>(gv + row_v + 16u * (uint32_t)min(m * PPS + psub, vpcs - 1));
-        if (UNCOND || has_vrem)
-            r_v[S][kVSlots] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tok[vrrow] * dv2 + 2u * (uint32_t)vrcol);
+        for (int m = 0; m < kVF; ++m)
+            r_v[S][m] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tok[fvrp[m] >> 8] * dv2 + 16u * (uint32_t)(fvrp[m] & 255));
     };
 
     // ---- gate work of this wave: whole UW-channel units w, w+NW, ..., then single left-over channels ----
@@ -390,7 +381,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 hi = (fminf(t1, 0.f) - __builtin_amdgcn_logf(1.f + exp2_fast(-fabsf(t1)))) * p.inv_tau;
             };
 #pragma unroll
-            for (int m = 0; m <= kSlots; ++m) {
+            for (int m = 0; m < kF; ++m) {
                 f32x4 la;
                 float a0, a1, a2, a3;
                 gate2(r_z[S][m][0], a0, a1);
@@ -400,41 +391,31 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             }
         }
         if (nvalid < kChunk) {
-            if (prow >= nvalid) {
 #pragma unroll
-                for (int m = 0; m < kSlots; ++m) {
+            for (int m = 0; m < kF; ++m) {
+                if ((frp[m] >> 8) >= nvalid) {
                     r_la[S][m] = f32x4{0.f, 0.f, 0.f, 0.f};
                     r_k[S][m] = u32x2{0, 0};
                     if constexpr (OUT) r_q[S][m] = u32x2{0, 0};
                 }
+            }
 #pragma unroll
-                for (int m = 0; m < kVSlots; ++m) r_v[S][m] = u32x4{0, 0, 0, 0};
-            }
-            if (rrow >= nvalid) {
-                r_la[S][kSlots] = f32x4{0.f, 0.f, 0.f, 0.f};
-                r_k[S][kSlots] = u32x2{0, 0};
-                if constexpr (OUT) r_q[S][kSlots] = u32x2{0, 0};
-            }
-            if (vrrow >= nvalid) r_v[S][kVSlots] = u32x4{0, 0, 0, 0};
+            for (int m = 0; m < kVF; ++m)
+                if ((fvrp[m] >> 8) >= nvalid) r_v[S][m] = u32x4{0, 0, 0, 0};
         }
 #pragma unroll
-        for (int m = 0; m < kSlots; ++m) {
-            if (m < nslots) {
-                const int ch = 4 * (m * PPS + psub);
-                *reinterpret_cast<f32x4 *>(s_la + prow * LAS + ch) = r_la[S][m];
-                *reinterpret_cast<u32x2 *>(s_khi + prow * CHS + ch) = r_k[S][m];
-                if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + prow * CHS + ch) = r_q[S][m];
+        for (int m = 0; m < kF; ++m) {
+            if (tid + NTHR * m < kChunk * pcs) {
+                const int row = frp[m] >> 8, ch = 4 * (frp[m] & 255);
+                *reinterpret_cast<f32x4 *>(s_la + row * LAS + ch) = r_la[S][m];
+                *reinterpret_cast<u32x2 *>(s_khi + row * CHS + ch) = r_k[S][m];
+                if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + row * CHS + ch) = r_q[S][m];
             }
         }
-        if (has_rem) {
-            *reinterpret_cast<f32x4 *>(s_la + rrow * LAS + rch) = r_la[S][kSlots];
-            *reinterpret_cast<u32x2 *>(s_khi + rrow * CHS + rch) = r_k[S][kSlots];
-            if constexpr (OUT) *reinterpret_cast<u32x2 *>(s_qhi + rrow * CHS + rch) = r_q[S][kSlots];
-        }
 #pragma unroll
-        for (int m = 0; m < kVSlots; ++m)
-            if (m < nvslots) *reinterpret_cast<u32x4 *>(s_v + prow * VS + 8 * (m * PPS + psub)) = r_v[S][m];
-        if (has_vrem) *reinterpret_cast<u32x4 *>(s_v + vrrow * VS + vrcol) = r_v[S][kVSlots];
+        for (int m = 0; m < kVF; ++m)
+            if (tid + NTHR * m < kChunk * vpcs)
+                *reinterpret_cast<u32x4 *>(s_v + (fvrp[m] >> 8) * VS + 8 * (fvrp[m] & 255)) = r_v[S][m];
         // the rows of a later chunk start their trip from HBM into the set just emptied
         // (unconditional loads past the span: the clamped token map makes every lane read one row)
         if (UNCOND || chunk + DEPTH < nch) load_chunk(chunk + DEPTH, set_c);
