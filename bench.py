@@ -236,10 +236,17 @@ def bench_backward(args, cfg, d, gla, gi, torch, np):
     sets = []
     for _ in range(max(1, args.sets)):
         sets.append([t.to(dev) for t in host] + [torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)])
+    fwd_ws = []
+    if args.reuse_fwd:   # the forward pass of the same step left its span states behind (not timed here)
+        for q, k, v, la, do, ws in sets:
+            fws = torch.empty((gla.gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt),), dtype=torch.uint8, device=dev)
+            gla.gla_fwd_ex(q, k, v, la, cfg.grid_h, cfg.grid_w, args.scan, workspace=fws)
+            fwd_ws.append(fws)
 
     def step(i):
         q, k, v, la, do, ws = sets[i % len(sets)]
-        return gla.gla_bwd(q, k, v, la, do, cfg.grid_h, cfg.grid_w, args.scan, workspace=ws)
+        return gla.gla_bwd(q, k, v, la, do, cfg.grid_h, cfg.grid_w, args.scan, workspace=ws,
+                           fwd_workspace=fwd_ws[i % len(sets)] if fwd_ws else None)
 
     for i in range(args.warmup):
         step(i)
@@ -259,7 +266,8 @@ def bench_backward(args, cfg, d, gla, gi, torch, np):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name} backward: B={B} H={H} T={T} ({cfg.grid_h}x{cfg.grid_w}) dk={dk} dv={dv} "
-                               f"{cfg.dtype} q/k/v/d_out, fp32 log_alpha, fp32 gradients, scan={args.scan}",
+                               f"{cfg.dtype} q/k/v/d_out, fp32 log_alpha, fp32 gradients, scan={args.scan}"
+                               + (", span states of S reused from the forward call" if args.reuse_fwd else ""),
                    "buffer_sets": len(sets)},
         "roofline": {"bound": "hbm", "kernel": "whole_call", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
@@ -306,6 +314,8 @@ def main():
                          "srem: gla_srem_dwconv on the workload's token matrix")
     ap.add_argument("--layout", default="bhtd", choices=["bhtd", "bthd"],
                     help="memory order of q, k, v, log_alpha, out: [B,H,T,d] (the headline) or [B,T,H,d]")
+    ap.add_argument("--reuse-fwd", action="store_true",
+                    help="with --pass bwd: take the span states of S from the forward call's workspace (gla_bwd_reuse)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--no-cache-resident", action="store_true",

@@ -174,6 +174,26 @@ int gla_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
 size_t gla_bwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);
 
 /*
+ * gla_bwd_reuse - gla_bwd that takes the span states of S from the workspace of the forward
+ * call instead of recomputing them (one of the two state passes of the backward pass is the
+ * state pass of the forward pass).
+ *
+ *   fwd_workspace        DEVICE, the workspace that gla_fwd_ex / gla_fwd_layout (BHTD, no
+ *                        initial state) / gla_fwd_multi's last scan order used for the SAME
+ *                        q, k, v, log_alpha, sizes and scan_dir, untouched since that call, and
+ *                        with the same gla_set_option values in force as then               (read)
+ *   fwd_workspace_bytes  its size, at least gla_fwd_workspace_bytes(...)
+ *
+ * Everything else as gla_bwd; `workspace` must be a different buffer.  The library cannot
+ * check that the forward workspace belongs to these tensors: a stale one gives wrong dq.
+ */
+int gla_bwd_reuse(const void *q, const void *k, const void *v, const float *log_alpha, const void *d_out,
+                  int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir, int qkv_dtype,
+                  const void *fwd_workspace, size_t fwd_workspace_bytes,
+                  float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha,
+                  void *workspace, size_t workspace_bytes, gla_stream_t stream);
+
+/*
  * gla_srem_dwconv - the 3x3 depth-wise convolution of the spatial reorient & enhancement
  * module (Sec. 3.3, Algorithm 1: DWConv2d on the 2-D token matrix; every channel has its own
  * 3x3 kernel, zero padding of one token, stride one; the paper initialises it to the identity).

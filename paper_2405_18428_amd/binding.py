@@ -61,6 +61,8 @@ def load_library():
     lib.gla_fwd_layout.argtypes = [vp, vp, vp, vp] + shape + [i, i, i, vp, vp, vp, vp, sz, vp]
     lib.gla_bwd.restype = i
     lib.gla_bwd.argtypes = [vp] * 5 + shape + [i] + [vp] * 4 + [vp, sz, vp]
+    lib.gla_bwd_reuse.restype = i
+    lib.gla_bwd_reuse.argtypes = [vp] * 5 + shape + [i] + [vp, sz] + [vp] * 4 + [vp, sz, vp]
     lib.gla_srem_dwconv.restype = i
     lib.gla_srem_dwconv.argtypes = [vp, vp, vp] + [i] * 7 + [vp, vp]
     lib.gla_fwd_multi.restype = i
@@ -338,9 +340,12 @@ def gla_bwd_workspace_bytes(B, H, T, dk, dv, qkv_dtype=DT_BF16) -> int:
     return int(load_library().gla_bwd_workspace_bytes(B, H, T, dk, dv, qkv_dtype))
 
 
-def gla_bwd(q, k, v, log_alpha, d_out, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, workspace=None, stream=None):
+def gla_bwd(q, k, v, log_alpha, d_out, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, workspace=None, stream=None,
+            fwd_workspace=None):
     """Gradients (dq, dk, dv, dlog_alpha), all fp32, of a loss with upstream gradient ``d_out`` = dL/d out.
-    q, k, v, d_out share one element type (bf16 or fp32); [B,H,T,d] order."""
+    q, k, v, d_out share one element type (bf16 or fp32); [B,H,T,d] order.  ``fwd_workspace``: the workspace
+    tensor of the gla_fwd_ex call on the same tensors and scan order (untouched since, same options): its span
+    states are reused instead of recomputed (gla_bwd_reuse)."""
     torch = _torch()
     lib = load_library()
     B, H, T, dk, dv = _prep(q, k, v, log_alpha, grid_h, grid_w)
@@ -354,10 +359,17 @@ def gla_bwd(q, k, v, log_alpha, d_out, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, wo
         nbytes = gla_bwd_workspace_bytes(B, H, T, dk, dv, qdt)
         workspace = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=q.device)
     with torch.cuda.device(q.device):
-        _check(lib.gla_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(), d_out.data_ptr(),
-                           B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt,
-                           dq.data_ptr(), dk_.data_ptr(), dv_.data_ptr(), dg.data_ptr(),
-                           workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+        if fwd_workspace is None:
+            _check(lib.gla_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(), d_out.data_ptr(),
+                               B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt,
+                               dq.data_ptr(), dk_.data_ptr(), dv_.data_ptr(), dg.data_ptr(),
+                               workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+        else:
+            _check(lib.gla_bwd_reuse(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(), d_out.data_ptr(),
+                                     B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt,
+                                     fwd_workspace.data_ptr(), fwd_workspace.numel(),
+                                     dq.data_ptr(), dk_.data_ptr(), dv_.data_ptr(), dg.data_ptr(),
+                                     workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dq, dk_, dv_, dg
 
 

@@ -109,7 +109,8 @@ size_t bwd_totals_bytes(int B, int H, int T, int dk) {
 int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const void *d_out,
             int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir, int qkv_dtype,
             float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha,
-            void *workspace, size_t ws_bytes, hipStream_t stream) {
+            void *workspace, size_t ws_bytes, hipStream_t stream,
+            const void *fwd_workspace = nullptr, size_t fwd_ws_bytes = 0) {
     if (!d_out || !dq || !dk_grad || !dv_grad || !dlog_alpha) return GLA_ERR_NULL;
     int st = validate(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir,
                       qkv_dtype, GLA_DT_F32, dv_grad, nullptr);
@@ -119,6 +120,8 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
     if (!workspace || misaligned(workspace) || ws_bytes < state_bytes + bwd_totals_bytes(B, H, T, dk))
         return GLA_ERR_WORKSPACE;
     float *totals = reinterpret_cast<float *>(static_cast<char *>(workspace) + state_bytes);
+    if (fwd_workspace && (misaligned(fwd_workspace) || fwd_ws_bytes < state_bytes || fwd_workspace == workspace))
+        return GLA_ERR_WORKSPACE;
 
     Params base{};
     base.B = B; base.H = H; base.T = T; base.dk = dk; base.dv = dv;
@@ -145,7 +148,28 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
     // 1. states of the forward recurrence (k, v, log_alpha); dq_s = S_s dO_s
     Params pa = base;
     pa.k = k; pa.v = v; pa.log_alpha = log_alpha; pa.scan_dir = scan_dir; pa.gate_shift = 0;
-    if (states(pa) != hipSuccess) return GLA_ERR_HIP;
+    if (fwd_workspace && pa.nspans > 1) {
+        // The forward call on the same tensors ran this very state pass.  Its workspace holds either the chained
+        // states S_start(r) (carry kernel) or the local states U_r and log Gamma_r (chained inside its output
+        // pass); the latter are copied here and chained in place, the former are read where they are.
+        Params pf = base;
+        bool same_engine;
+        if (choose_engine_and_plan(pf, const_cast<void *>(fwd_workspace), same_engine) != GLA_OK) return GLA_ERR_HIP;
+        const bool fwd_chained = use_mfma && (g_opt_carry == GLA_CARRY_IN_OUTPUT_PASS ||
+                                              (g_opt_carry == GLA_CARRY_AUTO && pa.nspans <= kMaxChainedSpans));
+        if (fwd_chained) {
+            const size_t used = (size_t)(reinterpret_cast<const char *>(pf.ws_lgam) - static_cast<const char *>(fwd_workspace)) +
+                                (size_t)B * H * pa.nspans * dk * sizeof(float);
+            if (hipMemcpyAsync(workspace, fwd_workspace, used, hipMemcpyDeviceToDevice, stream) != hipSuccess)
+                return GLA_ERR_HIP;
+            if (launch_carry(pa, stream) != hipSuccess) return GLA_ERR_HIP;
+        } else {
+            pa.ws_state = pf.ws_state;
+            pa.ws_lgam = pf.ws_lgam;
+        }
+    } else if (states(pa) != hipSuccess) {
+        return GLA_ERR_HIP;
+    }
     if (row_read(pa, d_out, dq) != hipSuccess) return GLA_ERR_HIP;
 
     // 2. states of the reversed recurrence G_s = q_s^T dO_s + diag(alpha_{s+1}) G_{s+1}: the forward recurrence
@@ -368,6 +392,17 @@ int gla_fwd(const void *q, const void *k, const void *v, const float *log_alpha,
     }
     return run(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir, GLA_DT_BF16, GLA_DT_F32,
                out, final_state, ws, need, static_cast<hipStream_t>(stream), nullptr);
+}
+
+int gla_bwd_reuse(const void *q, const void *k, const void *v, const float *log_alpha, const void *d_out,
+                  int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir, int qkv_dtype,
+                  const void *fwd_workspace, size_t fwd_workspace_bytes,
+                  float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha,
+                  void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
+    if (!fwd_workspace) return GLA_ERR_NULL;
+    return run_bwd(q, k, v, log_alpha, d_out, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype,
+                   dq, dk_grad, dv_grad, dlog_alpha, workspace, workspace_bytes_, static_cast<hipStream_t>(stream),
+                   fwd_workspace, fwd_workspace_bytes);
 }
 
 size_t gla_fwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype) {

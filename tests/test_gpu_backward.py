@@ -115,3 +115,41 @@ def test_headline_shape_long_spans():
     cfg = gi.CONFIGS["dig_xl2_2048"]
     d = make_problem(cfg.B, cfg.H, cfg.grid_h, cfg.grid_w, cfg.dk, cfg.dv, cfg.dtype, seed=cfg.seed)
     check(d, cfg.grid_h, cfg.grid_w, 0, TOL_BF16)
+
+
+def test_span_states_reused_from_the_forward_workspace():
+    """gla_bwd_reuse: the forward call's workspace supplies the span states of S, in every launch plan and with
+    both ways of chaining the span states; the gradients must not change."""
+    from oracle import gla_oracle
+    B, H, gh, gw, dk, dv = 1, 3, 40, 40, 36, 72
+    d = make_problem(B, H, gh, gw, dk, dv, "bf16", seed=21)
+    q, k, v, la, w = (upload(d, n) for n in ("q", "k", "v", "log_alpha", "w"))
+    for scan in (0, 3):
+        ref = gla_oracle.gla_bwd(d["q"], d["k"], d["v"], d["log_alpha"], d["w"], gh, gw, scan)
+        floors = [0.0, 0.0, 0.0, float(np.sqrt(np.mean((d["q"].astype(np.float64) * ref[0]) ** 2)))]
+        for cps, carry in ((0, gla.CARRY_AUTO), (2, gla.CARRY_KERNEL), (2, gla.CARRY_IN_OUTPUT_PASS), (5, gla.CARRY_AUTO),
+                           (1000, gla.CARRY_AUTO)):
+            gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, cps)
+            gla.gla_set_option(gla.OPT_CARRY, carry)
+            nbytes = gla.gla_fwd_workspace_bytes(B, H, gh * gw, dk, dv, gla.DT_BF16)
+            fwd_ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=q.device)   # NaN patterns where nothing is written
+            gla.gla_fwd_ex(q, k, v, la, gh, gw, scan, workspace=fwd_ws)
+            got = gla.gla_bwd(q, k, v, la, w, gh, gw, scan, fwd_workspace=fwd_ws)
+            torch.cuda.synchronize()
+            errs = [rel_err(g.cpu().numpy(), r, f) for g, r, f in zip(got, ref, floors)]
+            print("  scan=%d cps=%d carry=%d  err dq=%.3e dk=%.3e dv=%.3e dlog_alpha=%.3e" % (scan, cps, carry, *errs), flush=True)
+            assert max(errs) <= TOL_BF16, errs
+    # fp32 inputs (recurrent engine, carry kernel)
+    d = make_problem(1, 2, 12, 11, 20, 24, "f32", seed=22)
+    q, k, v, la, w = (upload(d, n) for n in ("q", "k", "v", "log_alpha", "w"))
+    gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 1)
+    gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_AUTO)
+    ref = gla_oracle.gla_bwd(d["q"], d["k"], d["v"], d["log_alpha"], d["w"], 12, 11, 1)
+    nbytes = gla.gla_fwd_workspace_bytes(1, 2, 132, 20, 24, gla.DT_F32)
+    fwd_ws = torch.empty((nbytes,), dtype=torch.uint8, device=q.device)
+    gla.gla_fwd_ex(q, k, v, la, 12, 11, 1, workspace=fwd_ws)
+    got = gla.gla_bwd(q, k, v, la, w, 12, 11, 1, fwd_workspace=fwd_ws)
+    torch.cuda.synchronize()
+    floors = [0.0, 0.0, 0.0, float(np.sqrt(np.mean((d["q"].astype(np.float64) * ref[0]) ** 2)))]
+    errs = [rel_err(g.cpu().numpy(), r, f) for g, r, f in zip(got, ref, floors)]
+    assert max(errs) <= TOL_F32, errs
