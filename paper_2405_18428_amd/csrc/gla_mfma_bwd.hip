@@ -145,34 +145,46 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): keeps later reads of acc from waiting on the row prefetch
 
-    // ---- HBM pieces staged by this thread: 4 threads per row, piece m*4 + tid%4 of row tid/4 in slot m;
-    // a slot past the row repeats the row's last piece (same bytes to the same place) ----
-    constexpr int PPS = NTHR / kChunk;
-    constexpr int kSlots = (NDK8 * 2 + PPS - 1) / PPS;      // 16-byte pieces of log_alpha / 8-byte pieces of k
-    constexpr int kVSlots = (NDV16 * 2 + PPS - 1) / PPS;    // 16-byte pieces of v and w
-    const int prow = tid / PPS, psub = tid % PPS;
+    // ---- HBM pieces staged by this thread: the 16-byte pieces of log_alpha (8-byte pieces of k) of a chunk and the
+    // 16-byte pieces of v and w are numbered row by row; slot m of a thread is piece tid + 256 m, so that a wave's
+    // request covers neighbouring pieces of neighbouring rows.  Slots past the last piece repeat it (the load stays
+    // in bounds; nothing is written to LDS for them) ----
+    constexpr int kF = (kChunk * NDK8 * 2 + NTHR - 1) / NTHR;
+    constexpr int kVF = (kChunk * NDV16 * 2 + NTHR - 1) / NTHR;
     const int pcs = dk >> 2, vpcs = dv >> 3;
+    int frp[kF], fvrp[kVF];     // row << 8 | piece
+#pragma unroll
+    for (int m = 0; m < kF; ++m) {
+        const int f = min(tid + NTHR * m, kChunk * pcs - 1);
+        const int row = f / pcs;
+        frp[m] = (row << 8) | (f - row * pcs);
+    }
+#pragma unroll
+    for (int m = 0; m < kVF; ++m) {
+        const int f = min(tid + NTHR * m, kChunk * vpcs - 1);
+        const int row = f / vpcs;
+        fvrp[m] = (row << 8) | (f - row * vpcs);
+    }
     const uint32_t dk2 = 2u * (uint32_t)p.st_k, dv2 = 2u * (uint32_t)p.st_v;
 
-    f32x4 r_la[kSlots];
-    u32x2 r_k[kSlots];
-    u32x4 r_v[kVSlots], r_w[kVSlots];
+    f32x4 r_la[kF];
+    u32x2 r_k[kF];
+    u32x4 r_v[kVF], r_w[kVF];
     auto load_chunk = [&](int chunk) {
         const int *tok = s_tok + (chunk % NTB) * kChunk;
         const int *tokg = s_tokg + (chunk % NTB) * kChunk;
-        const uint32_t row_k = (uint32_t)tok[prow] * dk2, row_v = (uint32_t)tok[prow] * dv2;
-        const uint32_t row_g = (uint32_t)tokg[prow] * dk2;
 #pragma unroll
-        for (int m = 0; m < kSlots; ++m) {
-            const uint32_t pc = 8u * (uint32_t)min(m * PPS + psub, pcs - 1);
-            r_la[m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * (row_g + pc));
-            r_k[m] = *reinterpret_cast<const u32x2 *>(gk + row_k + pc);
+        for (int m = 0; m < kF; ++m) {
+            const int row = frp[m] >> 8;
+            const uint32_t pc = 8u * (uint32_t)(frp[m] & 255);
+            r_la[m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * ((uint32_t)tokg[row] * dk2 + pc));
+            r_k[m] = *reinterpret_cast<const u32x2 *>(gk + (uint32_t)tok[row] * dk2 + pc);
         }
 #pragma unroll
-        for (int m = 0; m < kVSlots; ++m) {
-            const uint32_t pc = 16u * (uint32_t)min(m * PPS + psub, vpcs - 1);
-            r_v[m] = *reinterpret_cast<const u32x4 *>(gv + row_v + pc);
-            r_w[m] = *reinterpret_cast<const u32x4 *>(gw + row_v + pc);
+        for (int m = 0; m < kVF; ++m) {
+            const uint32_t e2 = (uint32_t)tok[fvrp[m] >> 8] * dv2 + 16u * (uint32_t)(fvrp[m] & 255);
+            r_v[m] = *reinterpret_cast<const u32x4 *>(gv + e2);
+            r_w[m] = *reinterpret_cast<const u32x4 *>(gw + e2);
         }
     };
     load_chunk(0);
@@ -181,29 +193,37 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
         const int *tok = s_tok + (chunk % NTB) * kChunk;
         // ================= (a) registers -> LDS =================
         const int nvalid = min(kChunk, s_end - s_begin - chunk * kChunk);
-        if (prow >= nvalid) {   // rows past the span: no decay, no contribution
+        if (nvalid < kChunk) {   // rows past the span: no decay, no contribution
 #pragma unroll
-            for (int m = 0; m < kSlots; ++m) {
-                r_la[m] = f32x4{0.f, 0.f, 0.f, 0.f};
-                r_k[m] = u32x2{0, 0};
+            for (int m = 0; m < kF; ++m) {
+                if ((frp[m] >> 8) >= nvalid) {
+                    r_la[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    r_k[m] = u32x2{0, 0};
+                }
             }
 #pragma unroll
-            for (int m = 0; m < kVSlots; ++m) {
-                r_v[m] = u32x4{0, 0, 0, 0};
-                r_w[m] = u32x4{0, 0, 0, 0};
+            for (int m = 0; m < kVF; ++m) {
+                if ((fvrp[m] >> 8) >= nvalid) {
+                    r_v[m] = u32x4{0, 0, 0, 0};
+                    r_w[m] = u32x4{0, 0, 0, 0};
+                }
             }
         }
 #pragma unroll
-        for (int m = 0; m < kSlots; ++m) {
-            const int ch = 4 * min(m * PPS + psub, pcs - 1);
-            *reinterpret_cast<f32x4 *>(s_la + prow * LAS + ch) = r_la[m];
-            *reinterpret_cast<u32x2 *>(s_khi + prow * CHS + ch) = r_k[m];
+        for (int m = 0; m < kF; ++m) {
+            if (tid + NTHR * m < kChunk * pcs) {
+                const int row = frp[m] >> 8, ch = 4 * (frp[m] & 255);
+                *reinterpret_cast<f32x4 *>(s_la + row * LAS + ch) = r_la[m];
+                *reinterpret_cast<u32x2 *>(s_khi + row * CHS + ch) = r_k[m];
+            }
         }
 #pragma unroll
-        for (int m = 0; m < kVSlots; ++m) {
-            const int col = 8 * min(m * PPS + psub, vpcs - 1);
-            *reinterpret_cast<u32x4 *>(s_v + prow * VS + col) = r_v[m];
-            *reinterpret_cast<u32x4 *>(s_w + prow * VS + col) = r_w[m];
+        for (int m = 0; m < kVF; ++m) {
+            if (tid + NTHR * m < kChunk * vpcs) {
+                const int row = fvrp[m] >> 8, col = 8 * (fvrp[m] & 255);
+                *reinterpret_cast<u32x4 *>(s_v + row * VS + col) = r_v[m];
+                *reinterpret_cast<u32x4 *>(s_w + row * VS + col) = r_w[m];
+            }
         }
         load_chunk(chunk + 1);   // past the span the clamped token map keeps the loads in bounds
         {
