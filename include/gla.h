@@ -78,7 +78,9 @@ typedef enum { GLA_DT_F32 = 0, GLA_DT_BF16 = 1 } gla_dtype;
 typedef enum {
     GLA_OPT_CHUNKS_PER_SPAN = 0, /* 0 = choose automatically; n > 0 = n 64-token chunks per work-group */
     GLA_OPT_ENGINE = 1,          /* gla_engine */
-    GLA_OPT_CARRY = 2            /* gla_carry */
+    GLA_OPT_CARRY = 2,           /* gla_carry */
+    GLA_OPT_BWD_SPLIT = 3        /* 0 = the backward pass computes dk and dv of a chunk in one kernel (MFMA engine);
+                                    1 = in two kernels (the forward output pass for dv, the row read for dk) */
 } gla_option;
 typedef enum {
     GLA_ENGINE_AUTO = 0,      /* bf16 inputs with dk % 4 == 0 and dv % 8 == 0 -> MFMA, else recurrent */

@@ -13,7 +13,7 @@ from typing import List, Optional
 
 SCAN_ROW_FWD, SCAN_ROW_REV, SCAN_COL_FWD, SCAN_COL_REV = 0, 1, 2, 3
 DT_F32, DT_BF16 = 0, 1
-OPT_CHUNKS_PER_SPAN, OPT_ENGINE, OPT_CARRY = 0, 1, 2
+OPT_CHUNKS_PER_SPAN, OPT_ENGINE, OPT_CARRY, OPT_BWD_SPLIT = 0, 1, 2, 3
 CARRY_AUTO, CARRY_KERNEL, CARRY_IN_OUTPUT_PASS = 0, 1, 2
 LAYOUT_BHTD, LAYOUT_BTHD = 0, 1
 ENGINE_AUTO, ENGINE_RECURRENT, ENGINE_MFMA = 0, 1, 2

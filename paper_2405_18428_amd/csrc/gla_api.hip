@@ -13,6 +13,7 @@ constexpr int kVersion = 210;  // 0.2.1
 int g_opt_chunks_per_span = 0;
 int g_opt_engine = GLA_ENGINE_AUTO;
 int g_opt_carry = GLA_CARRY_AUTO;
+int g_opt_bwd_split = 0;
 
 // Most spans per (batch, head) that the output pass chains by itself: work-group r reads the r local states
 // before it, so the reads grow with the square of the span count while a carry kernel's grow linearly.
@@ -178,8 +179,13 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
     pb.q = k; pb.k = q; pb.v = d_out; pb.log_alpha = log_alpha; pb.scan_dir = scan_dir ^ 1; pb.gate_shift = 1;
     pb.out = dv_grad;
     if (states(pb) != hipSuccess) return GLA_ERR_HIP;
-    if (span(pb, kModeOutput) != hipSuccess) return GLA_ERR_HIP;             // dv_s = k_s G_s
-    if (row_read(pb, v, dk_grad) != hipSuccess) return GLA_ERR_HIP;   // dk_s = G_s v_s
+    if (use_mfma && !g_opt_bwd_split) {
+        // one walk over the chunks of G for both dk_s = G_s v_s (row read) and dv_s = k_s G_s (outputs with q := k)
+        if (launch_mfma_row_read(pb, v, dk_grad, stream, true) != hipSuccess) return GLA_ERR_HIP;
+    } else {
+        if (span(pb, kModeOutput) != hipSuccess) return GLA_ERR_HIP;             // dv_s = k_s G_s
+        if (row_read(pb, v, dk_grad) != hipSuccess) return GLA_ERR_HIP;          // dk_s = G_s v_s
+    }
 
     // 3. dlog_alpha = reverse cumulative sum of q * dq - k * dk along the scan
     Params pc = base;
@@ -467,6 +473,10 @@ int gla_set_option(int option, int value) {
         if (value < GLA_CARRY_AUTO || value > GLA_CARRY_IN_OUTPUT_PASS) return GLA_ERR_SHAPE;
         g_opt_carry = value;
         return GLA_OK;
+    case GLA_OPT_BWD_SPLIT:
+        if (value < 0 || value > 1) return GLA_ERR_SHAPE;
+        g_opt_bwd_split = value;
+        return GLA_OK;
     default:
         return GLA_ERR_SHAPE;
     }
@@ -477,6 +487,7 @@ int gla_get_option(int option) {
     case GLA_OPT_CHUNKS_PER_SPAN: return g_opt_chunks_per_span;
     case GLA_OPT_ENGINE: return g_opt_engine;
     case GLA_OPT_CARRY: return g_opt_carry;
+    case GLA_OPT_BWD_SPLIT: return g_opt_bwd_split;
     default: return -1;
     }
 }

@@ -102,7 +102,8 @@ bool mfma_engine_supports(const Params &p);
 // dlog_alpha = reverse cumulative sum of q * dq - k * dk (totals: [B*H, dg_spans(T), dk] floats of scratch)
 hipError_t launch_row_read(const Params &p, const void *w, float *r, hipStream_t stream);
 // the same on the MFMA units (chunk form); needs what mfma_engine_supports() checks
-hipError_t launch_mfma_row_read(const Params &p, const void *w, float *r, hipStream_t stream);
+hipError_t launch_mfma_row_read(const Params &p, const void *w, float *r, hipStream_t stream,
+                                bool with_outputs = false);   // with_outputs: also o_j = q_j S_j (p.q) to p.out, fp32
 hipError_t launch_dlog_alpha(const Params &p, const float *dq, const float *dk_grad, float *dg, float *totals,
                              hipStream_t stream);
 int dg_spans(int T);

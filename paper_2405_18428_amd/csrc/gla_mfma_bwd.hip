@@ -32,7 +32,7 @@
 namespace gla {
 namespace {
 
-template <int NDK8, int NDV16>
+template <int NDK8, int NDV16, bool DV>
 struct RLayout {
     static constexpr int kDkp = NDK8 * 8;
     static constexpr int kDvp = NDV16 * 16;
@@ -58,15 +58,21 @@ struct RLayout {
     static constexpr int oW = oV + kRowV;
     static constexpr int oStHi = oW + kRowV;
     static constexpr int oStLo = oStHi + kSt;
-    static constexpr int kBytes = oStLo + kSt;
+    static constexpr int oQHi = oStLo + kSt;                              // with DV: raw q rows, then q~ hi / lo
+    static constexpr int oQLo = oQHi + kRowK;
+    static constexpr int kBytes = DV ? oQLo + kRowK : oStLo + kSt;
 };
 
 template <int N>
 using int_c = std::integral_constant<int, N>;
 
-template <int NDK8, int NDV16, int MINW>
+// DV = also compute the outputs o_j = q_j S_j of the same recurrence (fp32 rows to p.out; p.q holds q):
+//     o_j = sum_{i<=j} (q~_j . k~_i) v_i + q~_j S_0 ,   q~_j = q_j E_j
+// as the forward kernel does, on the operands that are already in LDS.  In the backward pass the reversed
+// recurrence of G needs both: dk as the row read against v, and dv = k G as the output with q := k.
+template <int NDK8, int NDV16, int MINW, bool DV>
 __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, const void *w_in, float *r_out) {
-    using L = RLayout<NDK8, NDV16>;
+    using L = RLayout<NDK8, NDV16, DV>;
     constexpr int NW = 4, NTHR = 256;
     constexpr int CHS = L::kChStride, VS = L::kVStride, LAS = L::kLaStride;
     constexpr int NCT = L::kNct;
@@ -86,6 +92,8 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
     uint16_t *s_w = reinterpret_cast<uint16_t *>(smem + L::oW);
     uint16_t *s_sthi = reinterpret_cast<uint16_t *>(smem + L::oStHi);
     uint16_t *s_stlo = reinterpret_cast<uint16_t *>(smem + L::oStLo);
+    uint16_t *s_qhi = reinterpret_cast<uint16_t *>(smem + L::oQHi);
+    uint16_t *s_qlo = reinterpret_cast<uint16_t *>(smem + L::oQLo);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -112,6 +120,8 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
     const char *gw = static_cast<const char *>(w_in) + base_v * 2;
     const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + base_k * 4;
     char *gr = reinterpret_cast<char *>(r_out) + base_k * 4;
+    const char *gq = static_cast<const char *>(p.q) + base_k * 2;
+    char *gout = static_cast<char *>(p.out) + base_v * 4;
 
     // ---- prologue: clear LDS (pads must read as zero), token maps of the first two chunks ----
     for (int i = tid; i < L::kBytes / 16; i += NTHR)
@@ -169,6 +179,7 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
 
     f32x4 r_la[kF];
     u32x2 r_k[kF];
+    u32x2 r_q[DV ? kF : 1];
     u32x4 r_v[kVF], r_w[kVF];
     auto load_chunk = [&](int chunk) {
         const int *tok = s_tok + (chunk % NTB) * kChunk;
@@ -179,6 +190,7 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
             const uint32_t pc = 8u * (uint32_t)(frp[m] & 255);
             r_la[m] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * ((uint32_t)tokg[row] * dk2 + pc));
             r_k[m] = *reinterpret_cast<const u32x2 *>(gk + (uint32_t)tok[row] * dk2 + pc);
+            if constexpr (DV) r_q[m] = *reinterpret_cast<const u32x2 *>(gq + (uint32_t)tok[row] * dk2 + pc);
         }
 #pragma unroll
         for (int m = 0; m < kVF; ++m) {
@@ -199,6 +211,7 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                 if ((frp[m] >> 8) >= nvalid) {
                     r_la[m] = f32x4{0.f, 0.f, 0.f, 0.f};
                     r_k[m] = u32x2{0, 0};
+                    if constexpr (DV) r_q[m] = u32x2{0, 0};
                 }
             }
 #pragma unroll
@@ -215,6 +228,7 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                 const int row = frp[m] >> 8, ch = 4 * (frp[m] & 255);
                 *reinterpret_cast<f32x4 *>(s_la + row * LAS + ch) = r_la[m];
                 *reinterpret_cast<u32x2 *>(s_khi + row * CHS + ch) = r_k[m];
+                if constexpr (DV) *reinterpret_cast<u32x2 *>(s_qhi + row * CHS + ch) = r_q[m];
             }
         }
 #pragma unroll
@@ -273,6 +287,14 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                            bf16_hi_as_float(kr[1]) * exp2_fast(fminf(-bb[3], kMaxExp2)), khi[1], klo[1]);
                 *reinterpret_cast<u32x2 *>(s_khi + j * CHS + c0) = khi;
                 *reinterpret_cast<u32x2 *>(s_klo + j * CHS + c0) = klo;
+                if constexpr (DV) {
+                    const u32x2 qr = *reinterpret_cast<const u32x2 *>(s_qhi + j * CHS + c0);
+                    u32x2 qhi, qlo;
+                    SPLIT_PAIR(bf16_lo_as_float(qr[0]) * e[0], bf16_hi_as_float(qr[0]) * e[1], qhi[0], qlo[0]);
+                    SPLIT_PAIR(bf16_lo_as_float(qr[1]) * e[2], bf16_hi_as_float(qr[1]) * e[3], qhi[1], qlo[1]);
+                    *reinterpret_cast<u32x2 *>(s_qhi + j * CHS + c0) = qhi;
+                    *reinterpret_cast<u32x2 *>(s_qlo + j * CHS + c0) = qlo;
+                }
                 *reinterpret_cast<f32x4 *>(s_la + j * LAS + c0) = e;      // E_j in place of the raw gates
                 if (lane == 63) *reinterpret_cast<f32x4 *>(s_gam + c0) = e;
             }
@@ -371,6 +393,97 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                     }
                 }
             }
+            if constexpr (DV) {
+                // ---- outputs of the wave's 16 tokens: O^T[n][i], lane (lm, g) holds o[x][r] = O[i = 16 IT + lm][n = 16 x + 4 g + r]
+                constexpr int NX = NDV16;
+                constexpr int KS = (NDK8 + 3) / 4;            // 32-channel steps
+                f32x4 o[NX];
+#pragma unroll
+                for (int x = 0; x < NX; ++x) o[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+                int colk[KS];   // channel group of this lane in step ks; groups past the data alias the all-zero group
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) colk[ks] = (4 * ks + g < NDK8) ? 8 * (4 * ks + g) : L::kDkp;
+                u32x4 qfh[KS], qfl[KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    qfh[ks] = *reinterpret_cast<const u32x4 *>(s_qhi + (16 * IT + lm) * CHS + colk[ks]);
+                    qfl[ks] = *reinterpret_cast<const u32x4 *>(s_qlo + (16 * IT + lm) * CHS + colk[ks]);
+                }
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    u32x2 ah[2] = {u32x2{0, 0}, u32x2{0, 0}}, al[2] = {u32x2{0, 0}, u32x2{0, 0}};
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const int jt = 2 * q + u;
+                        if (jt <= IT) {
+                            // score tile, transposed: lane (lm, g) gets A[i = 16 IT + lm][j = 16 jt + 4 g + r]
+                            f32x4 d = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int ks = 0; ks < KS; ++ks) {
+                                const u32x4 kh = *reinterpret_cast<const u32x4 *>(s_khi + (16 * jt + lm) * CHS + colk[ks]);
+                                const u32x4 kl = *reinterpret_cast<const u32x4 *>(s_klo + (16 * jt + lm) * CHS + colk[ks]);
+                                d = mfma(kh, qfh[ks], d);
+                                d = mfma(kh, qfl[ks], d);
+                                d = mfma(kl, qfh[ks], d);
+                            }
+                            if (jt == IT) {
+#pragma unroll
+                                for (int r = 0; r < 4; ++r)
+                                    if (4 * g + r > lm) d[r] = 0.f;
+                            }
+                            SPLIT_PAIR(d[0], d[1], ah[u][0], al[u][0]);
+                            SPLIT_PAIR(d[2], d[3], ah[u][1], al[u][1]);
+                        }
+                    }
+                    const u32x4 bh2 = u32x4{ah[0][0], ah[0][1], ah[1][0], ah[1][1]};
+                    const u32x4 bl2 = u32x4{al[0][0], al[0][1], al[1][0], al[1][1]};
+#pragma unroll
+                    for (int x = 0; x < NX; ++x) {
+                        const u32x2 v0 = lds_read_tr(vrow + 32 * q * VS + 16 * x);
+                        const u32x2 v1 = lds_read_tr(vrow + (32 * q + 16) * VS + 16 * x);
+                        const u32x4 vf = u32x4{v0[0], v0[1], v1[0], v1[1]};
+                        o[x] = mfma(vf, bh2, o[x]);
+                        o[x] = mfma(vf, bl2, o[x]);
+                    }
+                }
+                // + Q~ S_0: the state rows (channel-major in LDS) are read transposed, so the channels of a 32-channel
+                // step come in the slot order 16 (e/4) + 4 g + e%4; the q~ operand is read in that order too
+                const uint16_t *strow_h = s_sthi + (4 * g + tr_row) * VS + tr_col;
+                const uint16_t *strow_l = s_stlo + (4 * g + tr_row) * VS + tr_col;
+#pragma unroll
+                for (int q = 0; q < KS; ++q) {
+                    const bool second = 32 * q + 16 < 16 * NCT;    // the step's upper 16 channels exist in the state rows
+                    const uint16_t *qh = s_qhi + (16 * IT + lm) * CHS + 32 * q + 4 * g;
+                    const uint16_t *ql = s_qlo + (16 * IT + lm) * CHS + 32 * q + 4 * g;
+                    const u32x2 qh0 = *reinterpret_cast<const u32x2 *>(qh), ql0 = *reinterpret_cast<const u32x2 *>(ql);
+                    u32x2 qh1 = u32x2{0, 0}, ql1 = u32x2{0, 0};
+                    if (second) {
+                        qh1 = *reinterpret_cast<const u32x2 *>(qh + 16);
+                        ql1 = *reinterpret_cast<const u32x2 *>(ql + 16);
+                    }
+                    const u32x4 qsh = u32x4{qh0[0], qh0[1], qh1[0], qh1[1]}, qsl = u32x4{ql0[0], ql0[1], ql1[0], ql1[1]};
+#pragma unroll
+                    for (int x = 0; x < NX; ++x) {
+                        const u32x2 h0 = lds_read_tr(strow_h + 32 * q * VS + 16 * x);
+                        const u32x2 l0 = lds_read_tr(strow_l + 32 * q * VS + 16 * x);
+                        u32x2 h1 = u32x2{0, 0}, l1 = u32x2{0, 0};
+                        if (second) {
+                            h1 = lds_read_tr(strow_h + (32 * q + 16) * VS + 16 * x);
+                            l1 = lds_read_tr(strow_l + (32 * q + 16) * VS + 16 * x);
+                        }
+                        const u32x4 sh = u32x4{h0[0], h0[1], h1[0], h1[1]}, sl = u32x4{l0[0], l0[1], l1[0], l1[1]};
+                        o[x] = mfma(sh, qsh, o[x]);
+                        o[x] = mfma(sh, qsl, o[x]);
+                        o[x] = mfma(sl, qsh, o[x]);
+                    }
+                }
+                if (row < nvalid) {
+                    char *orow2 = gout + ((uint32_t)tok[row] * (uint32_t)p.st_v + 4u * (uint32_t)g) * 4u;
+#pragma unroll
+                    for (int x = 0; x < NX; ++x)
+                        if (4 * g + 16 * x < dv) *reinterpret_cast<f32x4 *>(orow2 + 64 * x) = o[x];
+                }
+            }
             // state update on this wave's tiles: S^T += V^T K~, then the chunk's decay per channel
 #pragma unroll
             for (int q = NQ; q < 2; ++q) load_k(q);
@@ -413,12 +526,12 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
     }
 }
 
-template <int NDK8, int NDV16>
+template <int NDK8, int NDV16, bool DV>
 hipError_t launch_one(const Params &p, const void *w, float *r, hipStream_t stream) {
-    using L = RLayout<NDK8, NDV16>;
+    using L = RLayout<NDK8, NDV16, DV>;
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int MINW = kGroupsPerCu >= 2 ? 2 : 1;
-    auto kernel = mfma_row_read_kernel<NDK8, NDV16, MINW>;
+    auto kernel = mfma_row_read_kernel<NDK8, NDV16, MINW, DV>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -431,14 +544,20 @@ hipError_t launch_one(const Params &p, const void *w, float *r, hipStream_t stre
     return hipGetLastError();
 }
 
+template <bool DV>
+hipError_t launch_sizes(const Params &p, const void *w, float *r, hipStream_t stream) {
+    const int ndk8 = (p.dk + 7) / 8, ndv16 = (p.dv + 15) / 16;
+    if (ndk8 <= 4 && ndv16 <= 4) return launch_one<4, 4, DV>(p, w, r, stream);
+    if (ndk8 <= 5 && ndv16 <= 5) return launch_one<5, 5, DV>(p, w, r, stream);
+    return launch_one<8, 8, DV>(p, w, r, stream);
+}
+
 }  // namespace
 
 // Same conditions as the forward MFMA engine (bf16 rows, dk % 4 == 0, dv % 8 == 0, 32-bit offsets).
-hipError_t launch_mfma_row_read(const Params &p, const void *w, float *r, hipStream_t stream) {
-    const int ndk8 = (p.dk + 7) / 8, ndv16 = (p.dv + 15) / 16;
-    if (ndk8 <= 4 && ndv16 <= 4) return launch_one<4, 4>(p, w, r, stream);
-    if (ndk8 <= 5 && ndv16 <= 5) return launch_one<5, 5>(p, w, r, stream);
-    return launch_one<8, 8>(p, w, r, stream);
+// with_outputs: also write o_j = q_j S_j (p.q, fp32 rows to p.out).
+hipError_t launch_mfma_row_read(const Params &p, const void *w, float *r, hipStream_t stream, bool with_outputs) {
+    return with_outputs ? launch_sizes<true>(p, w, r, stream) : launch_sizes<false>(p, w, r, stream);
 }
 
 }  // namespace gla

@@ -21,13 +21,13 @@ def _need_gpu():
         pytest.skip("no GPU")
     gla.load_library()
     yield
-    for opt in (gla.OPT_CHUNKS_PER_SPAN, gla.OPT_ENGINE, gla.OPT_CARRY):
+    for opt in (gla.OPT_CHUNKS_PER_SPAN, gla.OPT_ENGINE, gla.OPT_CARRY, gla.OPT_BWD_SPLIT):
         gla.gla_set_option(opt, 0)
 
 
 @pytest.fixture(autouse=True)
 def _reset_options():
-    for opt in (gla.OPT_CHUNKS_PER_SPAN, gla.OPT_ENGINE, gla.OPT_CARRY):
+    for opt in (gla.OPT_CHUNKS_PER_SPAN, gla.OPT_ENGINE, gla.OPT_CARRY, gla.OPT_BWD_SPLIT):
         gla.gla_set_option(opt, 0)
     yield
 
@@ -153,3 +153,16 @@ def test_span_states_reused_from_the_forward_workspace():
     floors = [0.0, 0.0, 0.0, float(np.sqrt(np.mean((d["q"].astype(np.float64) * ref[0]) ** 2)))]
     errs = [rel_err(g.cpu().numpy(), r, f) for g, r, f in zip(got, ref, floors)]
     assert max(errs) <= TOL_F32, errs
+
+
+def test_dk_and_dv_in_two_kernels():
+    """GLA_OPT_BWD_SPLIT = 1: dv from the forward output pass and dk from the row-read kernel, instead of both from
+    one walk over the chunks; the same gradients either way."""
+    for shape in ((2, 2, 5, 13, 36, 72), (1, 3, 23, 11, 64, 128), (2, 2, 9, 21, 32, 64), (1, 2, 9, 15, 4, 8)):
+        B, H, gh, gw, dk, dv = shape
+        d = make_problem(B, H, gh, gw, dk, dv, "bf16", seed=23)
+        for split in (1, 0):
+            gla.gla_set_option(gla.OPT_BWD_SPLIT, split)
+            for cps in (0, 2):
+                gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, cps)
+                check(d, gh, gw, 2, TOL_BF16)
