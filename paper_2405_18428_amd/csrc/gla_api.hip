@@ -132,7 +132,11 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
     bool use_mfma;
     st = choose_engine_and_plan(base, workspace, use_mfma);
     if (st != GLA_OK) return st;
-    base.chain_in_output = 0;   // the row-read kernel takes the state entering its span from the carry kernel
+    // MFMA engine with few spans per head: every kernel that needs the state entering its span chains the local
+    // states itself (as the forward output pass does); otherwise the carry kernel chains them in place
+    base.chain_in_output = use_mfma && base.nspans > 1 &&
+                           (g_opt_carry == GLA_CARRY_IN_OUTPUT_PASS ||
+                            (g_opt_carry == GLA_CARRY_AUTO && base.nspans <= kMaxChainedSpans));
     auto span = [&](const Params &p, SpanMode mode) {
         return use_mfma ? launch_mfma_span(p, mode, stream) : launch_recurrent_span(p, mode, stream);
     };
@@ -142,7 +146,7 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
     auto states = [&](const Params &p) {   // span-local states, then chained in place
         if (p.nspans <= 1) return hipSuccess;
         hipError_t e = span(p, kModeState);
-        if (e != hipSuccess) return e;
+        if (e != hipSuccess || p.chain_in_output) return e;
         return launch_carry(p, stream);
     };
 
@@ -152,22 +156,14 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
     if (fwd_workspace && pa.nspans > 1) {
         // The forward call on the same tensors ran this very state pass.  Its workspace holds either the chained
         // states S_start(r) (carry kernel) or the local states U_r and log Gamma_r (chained inside its output
-        // pass); the latter are copied here and chained in place, the former are read where they are.
+        // pass), by the rule that also sets base.chain_in_output.
         Params pf = base;
         bool same_engine;
         if (choose_engine_and_plan(pf, const_cast<void *>(fwd_workspace), same_engine) != GLA_OK) return GLA_ERR_HIP;
-        const bool fwd_chained = use_mfma && (g_opt_carry == GLA_CARRY_IN_OUTPUT_PASS ||
-                                              (g_opt_carry == GLA_CARRY_AUTO && pa.nspans <= kMaxChainedSpans));
-        if (fwd_chained) {
-            const size_t used = (size_t)(reinterpret_cast<const char *>(pf.ws_lgam) - static_cast<const char *>(fwd_workspace)) +
-                                (size_t)B * H * pa.nspans * dk * sizeof(float);
-            if (hipMemcpyAsync(workspace, fwd_workspace, used, hipMemcpyDeviceToDevice, stream) != hipSuccess)
-                return GLA_ERR_HIP;
-            if (launch_carry(pa, stream) != hipSuccess) return GLA_ERR_HIP;
-        } else {
-            pa.ws_state = pf.ws_state;
-            pa.ws_lgam = pf.ws_lgam;
-        }
+        // either way the states are read where they are: the row-read kernel chains local states itself
+        // (pa.chain_in_output follows the same rule as the forward call's plan)
+        pa.ws_state = pf.ws_state;
+        pa.ws_lgam = pf.ws_lgam;
     } else if (states(pa) != hipSuccess) {
         return GLA_ERR_HIP;
     }

@@ -108,7 +108,11 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
         if ((nb & 7) == 0) blk = (blk & 7) * (nb >> 3) + (blk >> 3);
     }
     const int bh = blk / p.nspans;
-    const int sp = blk - bh * p.nspans;
+    int sp_ = blk - bh * p.nspans;
+    // when the work-groups chain the span states themselves the cost grows with the span index: odd heads walk
+    // their spans backwards, so that the two groups sharing a compute unit pair a long chain with a short one
+    if (p.chain_in_output && (bh & 1)) sp_ = p.nspans - 1 - sp_;
+    const int sp = sp_;
     const int dk = p.dk, dv = p.dv, T = p.T;
     const int s_begin = sp * p.span_len;
     const int s_end = min(T, s_begin + p.span_len);
@@ -123,6 +127,90 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
     const char *gq = static_cast<const char *>(p.q) + base_k * 2;
     char *gout = static_cast<char *>(p.out) + base_v * 4;
 
+    // ---- state tiles of this wave, transposed: acc[i][ct][r] = S[c = 16 ct + lm][n = 16 (w + 4 i) + 4 g + r] ----
+    f32x4 acc[TPW][NCT];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i)
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) acc[i][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // The state entering the span: what the carry kernel left in the workspace, or (chain_in_output) chained here
+    // from the local states U_0 .. U_{sp-1} of the spans before it, s <- Gamma_r s + U_r on 4 consecutive state
+    // elements per thread, kRun spans loaded at a time; the result goes through LDS into the accumulator layout.
+    {
+        const bool chain = p.chain_in_output && sp > 0;   // uniform over the group
+        if (chain) {
+            constexpr int kV4 = (L::kDkp * L::kDvp / 4 + NTHR - 1) / NTHR;  // float4 per thread
+            constexpr int kBudget = MINW >= 2 ? 32 : 64;                    // float4 in flight
+            constexpr int kRun = kBudget / kV4 > 0 ? kBudget / kV4 : 1;     // spans in flight
+            const int ne = dk * dv, ne4 = ne >> 2;
+            const float *ub = p.ws_state + (size_t)bh * p.nspans * ne;
+            const float *lb = p.ws_lgam + (size_t)bh * p.nspans * dk;
+            int e4[kV4], ch[kV4];
+#pragma unroll
+            for (int m = 0; m < kV4; ++m) {
+                e4[m] = min(tid + NTHR * m, ne4 - 1);  // threads past the end repeat the last piece
+                ch[m] = (4 * e4[m]) / dv;
+            }
+            f32x4 st[kV4];
+#pragma unroll
+            for (int m = 0; m < kV4; ++m) st[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int r0 = 0; r0 < sp; r0 += kRun) {
+                f32x4 u[kRun][kV4];
+                float lg[kRun][kV4];
+#pragma unroll
+                for (int i = 0; i < kRun; ++i) {
+                    const int r = min(r0 + i, sp - 1);  // loads past the run's end repeat a valid span
+#pragma unroll
+                    for (int m = 0; m < kV4; ++m) {
+                        u[i][m] = *reinterpret_cast<const f32x4 *>(ub + (size_t)r * ne + 4 * e4[m]);
+                        lg[i][m] = lb[r * dk + ch[m]];
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < kRun; ++i) {
+                    if (r0 + i < sp) {
+#pragma unroll
+                        for (int m = 0; m < kV4; ++m) {
+                            const float gm = exp2_fast(lg[i][m] * kLog2e);
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) st[m][x] = fmaf(gm, st[m][x], u[i][m][x]);
+                        }
+                    }
+                }
+            }
+            float *s_chain = reinterpret_cast<float *>(smem);
+#pragma unroll
+            for (int m = 0; m < kV4; ++m)
+                if (tid + NTHR * m < ne4) *reinterpret_cast<f32x4 *>(s_chain + 4 * e4[m]) = st[m];
+        }
+        __syncthreads();
+        if (chain) {
+            const float *s_chain = reinterpret_cast<const float *>(smem);
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                const int n = 16 * (w + NW * i) + 4 * g;
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct) {
+                    const int c = 16 * ct + lm;
+                    if (c < dk && n < dv) acc[i][ct] = *reinterpret_cast<const f32x4 *>(s_chain + c * dv + n);
+                }
+            }
+        }
+        __syncthreads();
+        if (!p.chain_in_output && p.nspans > 1) {
+            const float *s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                const int n = 16 * (w + NW * i) + 4 * g;
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct) {
+                    const int c = 16 * ct + lm;
+                    if (c < dk && n < dv) acc[i][ct] = *reinterpret_cast<const f32x4 *>(s0 + c * dv + n);
+                }
+            }
+        }
+    }
+
     // ---- prologue: clear LDS (pads must read as zero), token maps of the first two chunks ----
     for (int i = tid; i < L::kBytes / 16; i += NTHR)
         reinterpret_cast<u32x4 *>(smem)[i] = u32x4{0, 0, 0, 0};
@@ -135,24 +223,6 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
     }
     __syncthreads();
 
-    // ---- state tiles of this wave, transposed: acc[i][ct][r] = S[c = 16 ct + lm][n = 16 (w + 4 i) + 4 g + r] ----
-    f32x4 acc[TPW][NCT];
-#pragma unroll
-    for (int i = 0; i < TPW; ++i)
-#pragma unroll
-        for (int ct = 0; ct < NCT; ++ct) acc[i][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (p.nspans > 1) {   // the state entering the span, as the carry kernel left it
-        const float *s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            const int n = 16 * (w + NW * i) + 4 * g;
-#pragma unroll
-            for (int ct = 0; ct < NCT; ++ct) {
-                const int c = 16 * ct + lm;
-                if (c < dk && n < dv) acc[i][ct] = *reinterpret_cast<const f32x4 *>(s0 + c * dv + n);
-            }
-        }
-    }
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): keeps later reads of acc from waiting on the row prefetch
 
     // ---- HBM pieces staged by this thread: the 16-byte pieces of log_alpha (8-byte pieces of k) of a chunk and the
