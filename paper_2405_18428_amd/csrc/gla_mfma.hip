@@ -185,59 +185,16 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     for (int i = 0; i < TPW; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // ---- state entering the span, chained here from the local states of the spans before it ----
-    // S_start(sp) = sum_{r < sp} diag(prod_{r < r' < sp} Gamma_r') U_r, evaluated as the recurrence
-    // s <- Gamma_r s + U_r over r on 4 consecutive state elements per thread (one key channel: dv % 4 == 0),
-    // kRun spans loaded at a time; the result goes through LDS into the MFMA accumulator layout.
+    // S_start(sp) = sum_{r < sp} diag(prod_{r < r' < sp} Gamma_r') U_r, summed from the nearest span backwards on
+    // 4 consecutive state elements per thread (one key channel: dv % 4 == 0) until the accumulated decay makes the
+    // remaining terms vanish in fp32 (chain_span_states); the result goes through LDS into the accumulator layout.
     if constexpr (OUT) {
         const bool chain = p.chain_in_output && (sp > 0 || p.initial_state != nullptr);  // uniform over the group
         if (chain) {
             constexpr int kV4 = (L::kDkp * L::kDvp / 4 + NTHR - 1) / NTHR;  // float4 per thread
             constexpr int kBudget = MINW >= 4 ? 16 : 32;                    // float4 in flight: 64 or 128 registers of U
             constexpr int kRun = kBudget / kV4 > 0 ? kBudget / kV4 : 1;     // spans in flight
-            const int ne = dk * dv, ne4 = ne >> 2;
-            const float *ub = p.ws_state + (size_t)bh * p.nspans * ne;
-            const float *lb = p.ws_lgam + (size_t)bh * p.nspans * dk;
-            int e4[kV4], ch[kV4];
-#pragma unroll
-            for (int m = 0; m < kV4; ++m) {
-                e4[m] = min(tid + NTHR * m, ne4 - 1);  // threads past the end repeat the last piece
-                ch[m] = (4 * e4[m]) / dv;
-            }
-            f32x4 st[kV4];
-#pragma unroll
-            for (int m = 0; m < kV4; ++m) {
-                st[m] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (p.initial_state != nullptr)
-                    st[m] = *reinterpret_cast<const f32x4 *>(p.initial_state + (size_t)bh * ne + 4 * e4[m]);
-            }
-            for (int r0 = 0; r0 < sp; r0 += kRun) {
-                f32x4 u[kRun][kV4];
-                float lg[kRun][kV4];
-#pragma unroll
-                for (int i = 0; i < kRun; ++i) {
-                    const int r = min(r0 + i, sp - 1);  // loads past the run's end repeat a valid span
-#pragma unroll
-                    for (int m = 0; m < kV4; ++m) {
-                        u[i][m] = *reinterpret_cast<const f32x4 *>(ub + (size_t)r * ne + 4 * e4[m]);
-                        lg[i][m] = lb[r * dk + ch[m]];
-                    }
-                }
-#pragma unroll
-                for (int i = 0; i < kRun; ++i) {
-                    if (r0 + i < sp) {
-#pragma unroll
-                        for (int m = 0; m < kV4; ++m) {
-                            const float gm = exp2_fast(lg[i][m] * kLog2e);
-#pragma unroll
-                            for (int x = 0; x < 4; ++x) st[m][x] = fmaf(gm, st[m][x], u[i][m][x]);
-                        }
-                    }
-                }
-            }
-            float *s_chain = reinterpret_cast<float *>(smem);
-#pragma unroll
-            for (int m = 0; m < kV4; ++m)
-                if (tid + NTHR * m < ne4) *reinterpret_cast<f32x4 *>(s_chain + 4 * e4[m]) = st[m];
+            chain_span_states<NTHR, kV4, kRun>(p, bh, sp, tid, reinterpret_cast<float *>(smem));
         }
         __syncthreads();
         if (chain) {

@@ -134,54 +134,15 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct) acc[i][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
     // The state entering the span: what the carry kernel left in the workspace, or (chain_in_output) chained here
-    // from the local states U_0 .. U_{sp-1} of the spans before it, s <- Gamma_r s + U_r on 4 consecutive state
-    // elements per thread, kRun spans loaded at a time; the result goes through LDS into the accumulator layout.
+    // from the local states of the spans before it (chain_span_states: nearest span first, until the accumulated
+    // decay makes the rest vanish in fp32); the result goes through LDS into the accumulator layout.
     {
         const bool chain = p.chain_in_output && sp > 0;   // uniform over the group
         if (chain) {
             constexpr int kV4 = (L::kDkp * L::kDvp / 4 + NTHR - 1) / NTHR;  // float4 per thread
             constexpr int kBudget = MINW >= 2 ? 32 : 64;                    // float4 in flight
             constexpr int kRun = kBudget / kV4 > 0 ? kBudget / kV4 : 1;     // spans in flight
-            const int ne = dk * dv, ne4 = ne >> 2;
-            const float *ub = p.ws_state + (size_t)bh * p.nspans * ne;
-            const float *lb = p.ws_lgam + (size_t)bh * p.nspans * dk;
-            int e4[kV4], ch[kV4];
-#pragma unroll
-            for (int m = 0; m < kV4; ++m) {
-                e4[m] = min(tid + NTHR * m, ne4 - 1);  // threads past the end repeat the last piece
-                ch[m] = (4 * e4[m]) / dv;
-            }
-            f32x4 st[kV4];
-#pragma unroll
-            for (int m = 0; m < kV4; ++m) st[m] = f32x4{0.f, 0.f, 0.f, 0.f};
-            for (int r0 = 0; r0 < sp; r0 += kRun) {
-                f32x4 u[kRun][kV4];
-                float lg[kRun][kV4];
-#pragma unroll
-                for (int i = 0; i < kRun; ++i) {
-                    const int r = min(r0 + i, sp - 1);  // loads past the run's end repeat a valid span
-#pragma unroll
-                    for (int m = 0; m < kV4; ++m) {
-                        u[i][m] = *reinterpret_cast<const f32x4 *>(ub + (size_t)r * ne + 4 * e4[m]);
-                        lg[i][m] = lb[r * dk + ch[m]];
-                    }
-                }
-#pragma unroll
-                for (int i = 0; i < kRun; ++i) {
-                    if (r0 + i < sp) {
-#pragma unroll
-                        for (int m = 0; m < kV4; ++m) {
-                            const float gm = exp2_fast(lg[i][m] * kLog2e);
-#pragma unroll
-                            for (int x = 0; x < 4; ++x) st[m][x] = fmaf(gm, st[m][x], u[i][m][x]);
-                        }
-                    }
-                }
-            }
-            float *s_chain = reinterpret_cast<float *>(smem);
-#pragma unroll
-            for (int m = 0; m < kV4; ++m)
-                if (tid + NTHR * m < ne4) *reinterpret_cast<f32x4 *>(s_chain + 4 * e4[m]) = st[m];
+            chain_span_states<NTHR, kV4, kRun>(p, bh, sp, tid, reinterpret_cast<float *>(smem));
         }
         __syncthreads();
         if (chain) {

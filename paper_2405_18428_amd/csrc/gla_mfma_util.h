@@ -4,6 +4,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
+#include "gla_common.h"
+
 namespace gla {
 namespace {
 
@@ -77,6 +81,88 @@ __device__ inline float wave_inclusive_scan(float v) {
     v += dpp_move<0x142, 0xA, false>(v); // row_bcast:15 into rows 1 and 3
     v += dpp_move<0x143, 0xC, false>(v); // row_bcast:31 into rows 2 and 3
     return v;
+}
+
+// State entering span `sp` of (batch, head) `bh`, formed from the local states U_r and the log decays of the
+// spans before it (phase 2 of the span plan, done by the work-group that needs the result):
+//     S_start(sp) = U_{sp-1} + Gamma_{sp-1} U_{sp-2} + Gamma_{sp-1} Gamma_{sp-2} U_{sp-3} + ... (+ the decayed initial state)
+// Each thread owns kV4 pieces of 4 consecutive state elements (one key channel each) and walks the spans from the
+// nearest one backwards, 2 spans first, then kRun at a time (loads of a run issued together).  A thread stops
+// when the decay accumulated on all its channels is below 2^-40: a term that much smaller than the ones already
+// summed does not change an fp32 sum.  With the gates of the DiG configurations a span of a few hundred tokens
+// decays by more than that, so one or two spans are read whatever the span count.
+// The result is written to s_chain[dk * dv] (LDS, row-major [dk][dv]).
+template <int NTHR, int kV4, int kRun>
+__device__ inline void chain_span_states(const Params &p, int bh, int sp, int tid, float *s_chain) {
+    const int dk = p.dk, dv = p.dv, ne = dk * dv, ne4 = ne >> 2;
+    const float *ub = p.ws_state + (size_t)bh * p.nspans * ne;
+    const float *lb = p.ws_lgam + (size_t)bh * p.nspans * dk;
+    int e4[kV4], ch[kV4];
+#pragma unroll
+    for (int m = 0; m < kV4; ++m) {
+        e4[m] = min(tid + NTHR * m, ne4 - 1);  // threads past the end repeat the last piece
+        ch[m] = (4 * e4[m]) / dv;
+    }
+    f32x4 st[kV4];
+    float wl[kV4];      // log2 of the weight of the next span to add
+#pragma unroll
+    for (int m = 0; m < kV4; ++m) {
+        st[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+        wl[m] = 0.f;
+    }
+    auto run = [&](auto n_c, int r_hi) {   // spans r_hi, r_hi - 1, ..., r_hi - n + 1 (those below 0 do not exist)
+        constexpr int N = decltype(n_c)::value;
+        f32x4 u[N][kV4];
+        float lg[N][kV4];
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int r = max(r_hi - i, 0);     // loads past the first span repeat it
+#pragma unroll
+            for (int m = 0; m < kV4; ++m) {
+                u[i][m] = *reinterpret_cast<const f32x4 *>(ub + (size_t)r * ne + 4 * e4[m]);
+                lg[i][m] = lb[r * dk + ch[m]];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            if (r_hi - i >= 0) {
+#pragma unroll
+                for (int m = 0; m < kV4; ++m) {
+                    const float wgt = exp2_fast(wl[m]);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) st[m][x] = fmaf(wgt, u[i][m][x], st[m][x]);
+                    wl[m] += lg[i][m] * kLog2e;    // the workspace keeps natural logarithms
+                }
+            }
+        }
+    };
+    auto alive = [&]() {
+        bool a = false;
+#pragma unroll
+        for (int m = 0; m < kV4; ++m) a = a || wl[m] > -40.f;
+        return a;
+    };
+    int r = sp - 1;
+    if (r >= 0) {
+        run(std::integral_constant<int, 2>{}, r);
+        r -= 2;
+    }
+    while (r >= 0 && alive()) {
+        run(std::integral_constant<int, kRun>{}, r);
+        r -= kRun;
+    }
+    if (p.initial_state != nullptr && alive()) {   // every span was walked: the caller's state, decayed by all of them
+#pragma unroll
+        for (int m = 0; m < kV4; ++m) {
+            const f32x4 s0 = *reinterpret_cast<const f32x4 *>(p.initial_state + (size_t)bh * ne + 4 * e4[m]);
+            const float wgt = exp2_fast(wl[m]);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) st[m][x] = fmaf(wgt, s0[x], st[m][x]);
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < kV4; ++m)
+        if (tid + NTHR * m < ne4) *reinterpret_cast<f32x4 *>(s_chain + 4 * e4[m]) = st[m];
 }
 
 }  // namespace
