@@ -17,7 +17,7 @@ int g_opt_bwd_split = 0;
 
 // Most spans per (batch, head) that the output pass chains by itself: work-group r reads the r local states
 // before it, so the reads grow with the square of the span count while a carry kernel's grow linearly.
-constexpr int kMaxChainedSpans = 48;  // measured on MI355X with 16 heads: the two ways cost the same near 50 spans
+constexpr int kMaxChainedSpans = 128; // beyond this the reads of a slowly decaying chain outgrow the carry kernel
 
 struct Scratch {
     void *ptr = nullptr;
