@@ -413,10 +413,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     for (int v4 = 0; v4 < UW / 4; ++v4) {
                         const f32x4 x = *reinterpret_cast<const f32x4 *>(s_la + j * LAS + c0 + 4 * v4);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float gi = FUSE ? x[i] : x[i] * kLog2e;
-                            bb[4 * v4 + i] = wave_inclusive_scan(gi);
-                        }
+                        for (int i = 0; i < 4; ++i) bb[4 * v4 + i] = FUSE ? x[i] : x[i] * kLog2e;
+                        wave_inclusive_scan4(bb[4 * v4], bb[4 * v4 + 1], bb[4 * v4 + 2], bb[4 * v4 + 3]);
                     }
                     uint32_t kr[UW / 2], khi[UW / 2], klo[UW / 2];
 #pragma unroll

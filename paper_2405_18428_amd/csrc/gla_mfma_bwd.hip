@@ -307,7 +307,8 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                 const u32x2 kr = *reinterpret_cast<const u32x2 *>(s_khi + j * CHS + c0);
                 float bb[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) bb[i] = wave_inclusive_scan(x[i] * kLog2e);
+                for (int i = 0; i < 4; ++i) bb[i] = x[i] * kLog2e;
+                wave_inclusive_scan4(bb[0], bb[1], bb[2], bb[3]);
                 f32x4 e;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) e[i] = exp2_fast(bb[i]);
