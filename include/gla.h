@@ -196,6 +196,22 @@ int gla_bwd_reuse(const void *q, const void *k, const void *v, const float *log_
                   void *workspace, size_t workspace_bytes, gla_stream_t stream);
 
 /*
+ * gla_bwd_layout - gla_bwd / gla_bwd_reuse for either memory order: the backward pass of
+ * gla_fwd_layout with a zero initial state (Eq. (attn_gla) rows 1-3 differentiated).
+ *
+ *   layout           gla_layout of q, k, v, log_alpha, d_out and of the four gradients
+ *   fwd_workspace    as in gla_bwd_reuse, or NULL to recompute the span states (then
+ *                    fwd_workspace_bytes is ignored)
+ *
+ * Everything else as gla_bwd; GLA_ERR_SHAPE for an unknown layout.
+ */
+int gla_bwd_layout(const void *q, const void *k, const void *v, const float *log_alpha, const void *d_out,
+                   int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir, int qkv_dtype,
+                   int layout, const void *fwd_workspace, size_t fwd_workspace_bytes,
+                   float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha,
+                   void *workspace, size_t workspace_bytes, gla_stream_t stream);
+
+/*
  * gla_srem_dwconv - the 3x3 depth-wise convolution of the spatial reorient & enhancement
  * module (Sec. 3.3, Algorithm 1: DWConv2d on the 2-D token matrix; every channel has its own
  * 3x3 kernel, zero padding of one token, stride one; the paper initialises it to the identity).

@@ -61,6 +61,8 @@ def load_library():
     lib.gla_fwd_layout.argtypes = [vp, vp, vp, vp] + shape + [i, i, i, vp, vp, vp, vp, sz, vp]
     lib.gla_bwd.restype = i
     lib.gla_bwd.argtypes = [vp] * 5 + shape + [i] + [vp] * 4 + [vp, sz, vp]
+    lib.gla_bwd_layout.restype = i
+    lib.gla_bwd_layout.argtypes = [vp] * 5 + shape + [i, i] + [vp, sz] + [vp] * 4 + [vp, sz, vp]
     lib.gla_bwd_reuse.restype = i
     lib.gla_bwd_reuse.argtypes = [vp] * 5 + shape + [i] + [vp, sz] + [vp] * 4 + [vp, sz, vp]
     lib.gla_srem_dwconv.restype = i
@@ -338,6 +340,42 @@ def gla_fwd_fused(q, k, v, z_alpha, tau, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, 
 
 def gla_bwd_workspace_bytes(B, H, T, dk, dv, qkv_dtype=DT_BF16) -> int:
     return int(load_library().gla_bwd_workspace_bytes(B, H, T, dk, dv, qkv_dtype))
+
+
+def gla_bwd_layout(q, k, v, log_alpha, d_out, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, layout=LAYOUT_BHTD,
+                   fwd_workspace=None, workspace=None, stream=None):
+    """gla_bwd for [B,H,T,d] (LAYOUT_BHTD) or [B,T,H,d] (LAYOUT_BTHD) tensors; the gradients come in the same order."""
+    torch = _torch()
+    lib = load_library()
+    if layout not in (LAYOUT_BHTD, LAYOUT_BTHD):
+        raise ValueError("unknown layout")
+    for name, t in (("q", q), ("k", k), ("v", v), ("log_alpha", log_alpha), ("d_out", d_out)):
+        if not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous 4-d GPU tensor")
+    if q.shape != k.shape or q.shape != log_alpha.shape or v.shape[:3] != q.shape[:3] or d_out.shape != v.shape:
+        raise ValueError("q, k, log_alpha must share one shape, v its first three sizes, d_out the shape of v")
+    if q.dtype != k.dtype or q.dtype != v.dtype or q.dtype != d_out.dtype or log_alpha.dtype != torch.float32:
+        raise TypeError("q, k, v, d_out must share one element type and log_alpha must be fp32")
+    if layout == LAYOUT_BHTD:
+        B, H, T, dk = q.shape
+    else:
+        B, T, H, dk = q.shape
+    dv = v.shape[3]
+    qdt = _dt(q)
+    f32 = dict(dtype=torch.float32, device=q.device)
+    dq, dk_, dg = (torch.empty(tuple(q.shape), **f32) for _ in range(3))
+    dv_ = torch.empty(tuple(v.shape), **f32)
+    if workspace is None:
+        nbytes = gla_bwd_workspace_bytes(B, H, T, dk, dv, qdt)
+        workspace = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=q.device)
+    with torch.cuda.device(q.device):
+        _check(lib.gla_bwd_layout(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(), d_out.data_ptr(),
+                                  B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt, layout,
+                                  fwd_workspace.data_ptr() if fwd_workspace is not None else None,
+                                  fwd_workspace.numel() if fwd_workspace is not None else 0,
+                                  dq.data_ptr(), dk_.data_ptr(), dv_.data_ptr(), dg.data_ptr(),
+                                  workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return dq, dk_, dv_, dg
 
 
 def gla_bwd(q, k, v, log_alpha, d_out, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, workspace=None, stream=None,

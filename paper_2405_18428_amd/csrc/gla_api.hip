@@ -111,8 +111,9 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
             int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir, int qkv_dtype,
             float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha,
             void *workspace, size_t ws_bytes, hipStream_t stream,
-            const void *fwd_workspace = nullptr, size_t fwd_ws_bytes = 0) {
+            const void *fwd_workspace = nullptr, size_t fwd_ws_bytes = 0, int layout = GLA_LAYOUT_BHTD) {
     if (!d_out || !dq || !dk_grad || !dv_grad || !dlog_alpha) return GLA_ERR_NULL;
+    if (layout != GLA_LAYOUT_BHTD && layout != GLA_LAYOUT_BTHD) return GLA_ERR_SHAPE;
     int st = validate(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir,
                       qkv_dtype, GLA_DT_F32, dv_grad, nullptr);
     if (st != GLA_OK) return st;
@@ -128,7 +129,12 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
     base.B = B; base.H = H; base.T = T; base.dk = dk; base.dv = dv;
     base.grid_h = grid_h; base.grid_w = grid_w;
     base.qkv_dtype = qkv_dtype; base.out_dtype = GLA_DT_F32;
-    set_dense_bhtd_strides(base);
+    if (layout == GLA_LAYOUT_BHTD) {
+        set_dense_bhtd_strides(base);
+    } else {  // [B,T,H,d]: the heads of one token are neighbours (gradients in the same order)
+        base.st_k = H * dk; base.sh_k = dk; base.sb_k = (long long)T * H * dk;
+        base.st_v = H * dv; base.sh_v = dv; base.sb_v = (long long)T * H * dv;
+    }
     bool use_mfma;
     st = choose_engine_and_plan(base, workspace, use_mfma);
     if (st != GLA_OK) return st;
@@ -405,6 +411,16 @@ int gla_bwd_reuse(const void *q, const void *k, const void *v, const float *log_
     return run_bwd(q, k, v, log_alpha, d_out, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype,
                    dq, dk_grad, dv_grad, dlog_alpha, workspace, workspace_bytes_, static_cast<hipStream_t>(stream),
                    fwd_workspace, fwd_workspace_bytes);
+}
+
+int gla_bwd_layout(const void *q, const void *k, const void *v, const float *log_alpha, const void *d_out,
+                   int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir, int qkv_dtype,
+                   int layout, const void *fwd_workspace, size_t fwd_workspace_bytes,
+                   float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha,
+                   void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
+    return run_bwd(q, k, v, log_alpha, d_out, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype,
+                   dq, dk_grad, dv_grad, dlog_alpha, workspace, workspace_bytes_, static_cast<hipStream_t>(stream),
+                   fwd_workspace, fwd_workspace_bytes, layout);
 }
 
 size_t gla_fwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype) {

@@ -166,3 +166,28 @@ def test_dk_and_dv_in_two_kernels():
             for cps in (0, 2):
                 gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, cps)
                 check(d, gh, gw, 2, TOL_BF16)
+
+
+def test_token_major_layout():
+    """gla_bwd_layout with [B,T,H,d] tensors: the same gradients, transposed, in every plan; also with the span states
+    taken from the workspace of gla_fwd_layout."""
+    from oracle import gla_oracle
+    for shape, dtype, tol in (((2, 3, 20, 13, 36, 72), "bf16", TOL_BF16), ((1, 2, 9, 15, 4, 8), "bf16", TOL_BF16),
+                              ((1, 2, 12, 11, 20, 24), "f32", TOL_F32)):
+        B, H, gh, gw, dk, dv = shape
+        d = make_problem(B, H, gh, gw, dk, dv, dtype, seed=27)
+        tm = lambda n: upload(d, n).transpose(1, 2).contiguous()       # [B,T,H,d]
+        q, k, v, la, w = (tm(n) for n in ("q", "k", "v", "log_alpha", "w"))
+        for scan in (0, 3):
+            ref = gla_oracle.gla_bwd(d["q"], d["k"], d["v"], d["log_alpha"], d["w"], gh, gw, scan)
+            floors = [0.0, 0.0, 0.0, float(np.sqrt(np.mean((d["q"].astype(np.float64) * ref[0]) ** 2)))]
+            for cps in (0, 1, 3):
+                gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, cps)
+                qdt = gla.DT_BF16 if dtype == "bf16" else gla.DT_F32
+                fws = torch.empty((gla.gla_fwd_workspace_bytes(B, H, gh * gw, dk, dv, qdt),), dtype=torch.uint8, device=q.device)
+                gla.gla_fwd_layout(q, k, v, la, gh, gw, scan, layout=gla.LAYOUT_BTHD, workspace=fws)
+                for reuse in (None, fws):
+                    got = gla.gla_bwd_layout(q, k, v, la, w, gh, gw, scan, layout=gla.LAYOUT_BTHD, fwd_workspace=reuse)
+                    torch.cuda.synchronize()
+                    errs = [rel_err(g.transpose(1, 2).cpu().numpy(), r, f) for g, r, f in zip(got, ref, floors)]
+                    assert max(errs) <= tol, (shape, scan, cps, reuse is not None, errs)
