@@ -322,12 +322,10 @@ template <typename TIn, int PW>
 hipError_t launch_dg(const Params &p, const float *dq, const float *dk_grad, float *dg, float *totals, int ndg,
                      hipStream_t stream) {
     auto kernel = dg_local_kernel<TIn, PW>;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDgLdsMax);
+    static bool configured[kMaxDevices] = {};  // per instantiation and device
+    {
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), (int)kDgLdsMax, configured);
         if (e != hipSuccess) return e;
-        configured = true;
     }
     const size_t lds = ((size_t)p.dk * kDgRow + 4 * p.dk + kDgSpan) * 4;
     dim3 grid((unsigned)(p.B * p.H * ndg)), block(kDgThreads);

@@ -92,6 +92,21 @@ __host__ __device__ inline size_t slab_v(const Params &p, int bh) {
     return (size_t)(bh / p.H) * (size_t)p.sb_v + (size_t)(bh % p.H) * (size_t)p.sh_v;
 }
 
+// Raises a kernel's dynamic-LDS limit once per device and kernel (`done` is the caller's per-kernel flag array,
+// indexed by device ordinal; the attribute is per device).
+constexpr int kMaxDevices = 64;
+inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, bool (&done)[kMaxDevices]) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices || !done[dev]) {
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < kMaxDevices) done[dev] = true;
+    }
+    return hipSuccess;
+}
+
 // Launchers (defined in the .hip files); each enqueues on `stream` and returns
 // hipGetLastError().
 hipError_t launch_recurrent_span(const Params &p, SpanMode mode, hipStream_t stream);

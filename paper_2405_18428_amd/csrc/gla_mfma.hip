@@ -864,12 +864,10 @@ hipError_t launch_depth(const Params &p, hipStream_t stream) {
     constexpr int kWavesPerSimd = kGroupsPerCu * NW / 4;
     constexpr int MINW = kWavesPerSimd >= 4 ? 4 : (kWavesPerSimd >= 2 ? 2 : 1);
     auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, NW, MINW, DEPTH, FUSE, ACC, TOut>;
-    static bool configured = false;  // per instantiation; the attribute is per function, set once
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes);
+    static bool configured[kMaxDevices] = {};  // per instantiation and device
+    {
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), L::kBytes, configured);
         if (e != hipSuccess) return e;
-        configured = true;
     }
     const int spans = (MODE == kModeState && p.chain_in_output) ? p.nspans - 1 : p.nspans;
     dim3 grid((unsigned)(p.B * p.H * spans)), block(NW * 64);

@@ -564,12 +564,10 @@ hipError_t launch_one(const Params &p, const void *w, float *r, hipStream_t stre
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int MINW = kGroupsPerCu >= 2 ? 2 : 1;
     auto kernel = mfma_row_read_kernel<NDK8, NDV16, MINW, DV>;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes);
+    static bool configured[kMaxDevices] = {};  // per instantiation and device
+    {
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), L::kBytes, configured);
         if (e != hipSuccess) return e;
-        configured = true;
     }
     dim3 grid((unsigned)(p.B * p.H * p.nspans)), block(256);
     hipLaunchKernelGGL(kernel, grid, block, L::kBytes, stream, p, w, r);
