@@ -90,7 +90,7 @@ __device__ inline float wave_inclusive_scan(float v) {
 // All 64 lanes must be active.
 __device__ inline void wave_inclusive_scan4(float &a, float &b, float &c, float &d) {
     asm volatile(
-        "s_nop 1\n\t"   // the inputs may come straight from a vector instruction: two wait states before a DPP read
+        "s_nop 4\n\t"   // wait states a DPP read needs after a vector instruction wrote its source (2) or EXEC (5)
         "v_add_f32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
         "v_add_f32_dpp %1, %1, %1 row_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
         "v_add_f32_dpp %2, %2, %2 row_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
