@@ -7,7 +7,7 @@ dk=36, dv=72, bf16 q/k/v, fp32 log_alpha, fp32 out), inputs resident in HBM.
 Steps rotate over several independent buffer sets so that every call streams
 from HBM rather than from the 256 MB last-level cache.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line (metric, value, unit, timing, workload, roofline, cpu_baseline).
 """
 import argparse
 import json
