@@ -141,3 +141,25 @@ def test_sequence_fed_in_two_pieces_matches_one_call():
     pieces = np.concatenate(outs, axis=2)
     assert rel_err(pieces, whole) <= 1e-3
     assert rel_err(state, whole_fin) <= 1e-3
+
+
+@pytest.mark.parametrize("z_mean", [0.0, 3.0, 6.0])
+def test_long_chains_of_span_states(z_mean):
+    """128 spans per head chained inside the output pass, with gates that decay fast (the chain stops after a few
+    spans), slowly, or hardly at all (every span and the initial state are read); the initial state must reach
+    the outputs exactly as far as the gates let it."""
+    from oracle import gla_oracle
+    B, H, gh, gw, dk, dv = 1, 2, 64, 128, 36, 72        # 128 chunks
+    d = gi.make_inputs(B, H, gh * gw, dk, dv, "bf16", seed=13, z_mean=z_mean)
+    init = make_init(B, H, dk, dv, seed=14)
+    gla.gla_set_option(gla.OPT_ENGINE, gla.ENGINE_MFMA)
+    gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 1)
+    for carry in (gla.CARRY_AUTO, gla.CARRY_KERNEL):
+        gla.gla_set_option(gla.OPT_CARRY, carry)
+        for scan, s0 in ((0, None), (3, init)):
+            ref, ref_fin = gla_oracle.gla_fwd(d["q"], d["k"], d["v"], d["log_alpha"], gh, gw, scan,
+                                              initial_state=None if s0 is None else s0.astype(np.float64))
+            out, fin = run(d, gh, gw, scan, gla.LAYOUT_BHTD, s0)
+            e_out, e_fin = rel_err(out, ref), rel_err(fin, ref_fin)
+            print(f"  z_mean={z_mean} carry={carry} scan={scan} err(out)={e_out:.3e} err(state)={e_fin:.3e}", flush=True)
+            assert e_out <= TOL_BF16 and e_fin <= TOL_BF16
