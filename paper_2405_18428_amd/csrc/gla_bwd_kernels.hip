@@ -7,12 +7,13 @@
 //     dv_s    = k_s G_s                        (a forward pass with q, k, v := k, q, dO)
 //     dlog_alpha_s = sum_{s' >= s} (q_s' * dq_s' - k_s' * dk_s')      (reverse cumulative sum)
 // dq and dk read the state along its value axis, which the forward engines (they read
-// it along the key axis) do not do; row_read_kernel does: it walks one span token by
-// token in fp32 with the state rows in registers, thread c of a wave owning row c
-// of half of the value columns.  The state entering the span comes from the span
-// plan of the forward pass (span-state pass + carry kernel).
-//
-// (A first, plain-ALU rendering: the chunk form of these reads on the MFMA units is the next step.)
+// it along the key axis) do not do.  For bf16 inputs with head sizes the MFMA engine
+// takes, that read runs in chunk form on the MFMA units (gla_mfma_bwd.hip).  The
+// row_read_kernel of this file covers everything else (fp32 inputs, odd head sizes):
+// it walks one span token by token in fp32 with the state rows in registers, thread c
+// of a wave owning row c of half of the value columns.  The state entering the span
+// comes from the span plan of the forward pass (span-state pass + carry kernel).
+// The two kernels of the gate gradient (the reverse cumulative sum) serve both paths.
 #include "gla_common.h"
 
 namespace gla {

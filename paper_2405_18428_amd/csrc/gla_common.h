@@ -1,4 +1,4 @@
-// Shared declarations of the GLA forward library (host + gfx950 device code).
+// Shared declarations of the GLA library (host + gfx950 device code).
 //
 // The operation is the gated recurrence of the DiG paper, Sec. 3.1 Eq. (attn_gla)
 // rows 1-3 with beta = 1:  S_t = diag(alpha_t) S_{t-1} + k_t^T v_t,  o_t = q_t S_t,
@@ -8,8 +8,10 @@
 //   phase 2  the spans of one (batch, head) are chained:
 //            S_start(r+1) = diag(Gamma_r) S_start(r) + U_r;
 //   phase 3  every span recomputes its tokens from S_start(r) and writes o_t.
-// Phase 2 is a kernel of its own, or (MFMA engine, few spans per head) the start
+// Phase 2 is a kernel of its own, or (MFMA engine, up to 128 spans per head) the start
 // of phase 3: each work-group then chains the U of the spans before its own.
+// The backward pass, the gate prologue / output epilogue, the sums over scan orders and
+// the SREM convolution reuse this plan and these parameters.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
