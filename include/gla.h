@@ -1,6 +1,9 @@
 /*
- * gla.h - C ABI of the MI355X (gfx950) forward pass of the gated-linear-attention
- * (GLA) token mixer used in the DiG diffusion backbone.
+ * gla.h - C ABI of the MI355X (gfx950) implementation of the gated-linear-attention
+ * (GLA) token mixer used in the DiG diffusion backbone: the forward pass (gla_fwd*),
+ * its variants with the gate prologue and output epilogue (gla_fwd_fused) and with
+ * several scan orders summed (gla_fwd_multi), the backward pass (gla_bwd*), and the
+ * depth-wise convolution of the DiG block's reorientation module (gla_srem_dwconv).
  *
  * Operation (DiG paper, Sec. 3.1 "Gated Linear Attention Transformer",
  * Eq. (attn_gla), rows 1-3, with the gate G_t reduced to its key-side factor

@@ -8,7 +8,7 @@
 namespace gla {
 namespace {
 
-constexpr int kVersion = 210;  // 0.2.1
+constexpr int kVersion = 300;  // 0.3.0
 
 int g_opt_chunks_per_span = 0;
 int g_opt_engine = GLA_ENGINE_AUTO;
