@@ -183,7 +183,7 @@ size_t gla_bwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtyp
  * call instead of recomputing them (one of the two state passes of the backward pass is the
  * state pass of the forward pass).
  *
- *   fwd_workspace        DEVICE, the workspace that gla_fwd_ex / gla_fwd_layout (BHTD, no
+ *   fwd_workspace        DEVICE, the workspace that gla_fwd_ex / gla_fwd_layout (same layout, no
  *                        initial state) / gla_fwd_multi's last scan order used for the SAME
  *                        q, k, v, log_alpha, sizes and scan_dir, untouched since that call, and
  *                        with the same gla_set_option values in force as then               (read)
@@ -293,7 +293,8 @@ int gla_fwd_timed(const void *q, const void *k, const void *v, const float *log_
                   void *workspace, size_t workspace_bytes, gla_stream_t stream,
                   int iters, float *phase_ms);
 
-/* Process-wide tuning knobs; returns GLA_ERR_SHAPE for an unknown option or value. */
+/* Process-wide tuning knobs; returns GLA_ERR_SHAPE for an unknown option or value.  They are plain process
+ * globals read at the start of every call: set them before, not while, other threads call the library. */
 int gla_set_option(int option, int value);
 int gla_get_option(int option);
 
