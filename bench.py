@@ -236,15 +236,22 @@ def bench_backward(args, cfg, d, gla, gi, torch, np):
     sets = []
     for _ in range(max(1, args.sets)):
         sets.append([t.to(dev) for t in host] + [torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)])
+    train = args.which == "train"     # a step = forward call + backward call that reuses its span states
     fwd_ws = []
-    if args.reuse_fwd:   # the forward pass of the same step left its span states behind (not timed here)
+    if args.reuse_fwd or train:   # the forward pass of the same step leaves its span states behind
         for q, k, v, la, do, ws in sets:
             fws = torch.empty((gla.gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt),), dtype=torch.uint8, device=dev)
             gla.gla_fwd_ex(q, k, v, la, cfg.grid_h, cfg.grid_w, args.scan, workspace=fws)
             fwd_ws.append(fws)
 
+    fwd_out = [(torch.empty((B, H, T, dv), device=dev), torch.empty((B, H, dk, dv), device=dev)) for _ in sets] if train else []
+
     def step(i):
         q, k, v, la, do, ws = sets[i % len(sets)]
+        if train:
+            o, f = fwd_out[i % len(sets)]
+            gla.gla_fwd_ex(q, k, v, la, cfg.grid_h, cfg.grid_w, args.scan, out=o, final_state=f,
+                           workspace=fwd_ws[i % len(sets)])
         return gla.gla_bwd(q, k, v, la, do, cfg.grid_h, cfg.grid_w, args.scan, workspace=ws,
                            fwd_workspace=fwd_ws[i % len(sets)] if fwd_ws else None)
 
@@ -259,13 +266,16 @@ def bench_backward(args, cfg, d, gla, gi, torch, np):
     qb = 2 if bf16 else 4
     # q, k, v, d_out and log_alpha read once; dq, dk, dlog_alpha, dv (fp32) written once
     alg_bytes = (2 * dk * qb + 2 * dv * qb + dk * 4 + 3 * dk * 4 + dv * 4) * B * H * T
+    if train:   # plus the forward call: q, k, v, log_alpha read, out written
+        alg_bytes += (2 * dk * qb + dk * 4 + dv * qb + dv * 4) * B * H * T
     achieved = alg_bytes / (ms * 1e-3) / 1e9
     result = {
-        "metric": "GLA bwd tokens/s at DiG-XL/2 shape T=16384", "value": round(B * T / (ms * 1e-3), 1),
+        "metric": ("GLA fwd+bwd tokens/s at DiG-XL/2 shape T=16384" if train else "GLA bwd tokens/s at DiG-XL/2 shape T=16384"),
+        "value": round(B * T / (ms * 1e-3), 1),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name} backward: B={B} H={H} T={T} ({cfg.grid_h}x{cfg.grid_w}) dk={dk} dv={dv} "
+        "config": {"workload": f"{cfg.name} {'forward + backward' if train else 'backward'}: B={B} H={H} T={T} ({cfg.grid_h}x{cfg.grid_w}) dk={dk} dv={dv} "
                                f"{cfg.dtype} q/k/v/d_out, fp32 log_alpha, fp32 gradients, scan={args.scan}"
                                + (", span states of S reused from the forward call" if args.reuse_fwd else ""),
                    "buffer_sets": len(sets)},
@@ -307,8 +317,9 @@ def main():
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated over (1 = cache-warm)")
     ap.add_argument("--chunks-per-span", type=int, default=0)
     ap.add_argument("--engine", type=int, default=0)
-    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "fused", "bidir", "4dir", "srem"],
+    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "train", "fused", "bidir", "4dir", "srem"],
                     help="fwd: the forward hot path (the headline); bwd: gla_bwd on the same workload; "
+                         "train: gla_fwd_ex followed by gla_bwd_reuse; "
                          "fused: gla_fwd_fused (gate prologue, Swish/LayerNorm epilogue) on the same workload; "
                          "bidir / 4dir: gla_fwd_multi over scan orders (0, 1) / (0, 1, 2, 3); "
                          "srem: gla_srem_dwconv on the workload's token matrix")
@@ -345,7 +356,7 @@ def main():
     cfg = gi.CONFIGS[args.config]
     dev = torch.device("cuda:0")
     d = gi.make_config_inputs(cfg)
-    if args.which == "bwd":
+    if args.which in ("bwd", "train"):
         bench_backward(args, cfg, d, gla, gi, torch, np)
         return
     if args.which == "fused":
