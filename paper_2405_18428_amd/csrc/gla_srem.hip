@@ -8,19 +8,21 @@
 //   order 1 (reversed)                                                    (-dy, -dx)
 //   order 2 (column-major)                                                ( dx,  dy)
 //   order 3 (column-major reversed)                                       (-dx, -dy)
-// A thread owns VEC channels (4 when D allows: 8-byte bf16 pieces) of a strip of kStrip tokens along a grid row.
-// The lanes of a wave cover 64 neighbouring channel groups of the same strip (contiguous addresses); the four
-// waves of a work-group take four strips and share the weights of their 64 channel groups, which are fetched
-// once, coalesced, into LDS (a lane's 9 x VEC weights are VEC*36 bytes apart from its neighbour's in memory) and
-// then held in registers.  All 3 x (kStrip + 2) row pieces of the strip's window are requested before the first
-// is used (clamped coordinates, zeroed afterwards where the window leaves the matrix).  HBM-bound: every
-// element is read from HBM once (the other eight uses hit in cache) and written once.
+// A thread owns VEC channels (4 when D allows: 8-byte bf16 pieces) of a strip of kStrip tokens of a grid row and
+// walks kRows rows of that strip from top to bottom.  The lanes of a wave cover 64 neighbouring channel groups of
+// the same tokens (contiguous addresses); the four waves of a work-group take four strips and share the weights
+// of their 64 channel groups, which are fetched once, coalesced, into LDS (a lane's 9 x VEC weights are VEC*36
+// bytes apart from its neighbour's in memory) and then held in registers.  The window is three rows of
+// kStrip + 2 pieces; the row below it is requested before the arithmetic of the current row starts, so loads and
+// arithmetic overlap inside every wave and an input row is fetched once per band of kRows rows.  Coordinates are
+// clamped and pieces outside the matrix cleared by an AND mask (zero padding, no branches).  HBM-bound.
 #include "gla_common.h"
 
 namespace gla {
 namespace {
 
-constexpr int kStrip = 8;      // output tokens per thread
+constexpr int kStrip = 4;      // output tokens per thread and grid row
+constexpr int kRows = 8;       // grid rows a wave walks
 constexpr int kWaves = 4;      // strips per work-group
 constexpr int kThreads = 64 * kWaves;
 
@@ -98,36 +100,42 @@ __global__ __launch_bounds__(kThreads) void srem_dwconv_kernel(const void *x, co
     const int bx = blk % gx, by = blk / gx;
     const int cg0 = bx * 64;
     const int ncg_here = min(64, ncg - cg0);
-    // The window of this thread's strip is requested first (rows r-1..r+1, columns c0-1..c0+kStrip; clamped
-    // coordinates, lanes and waves without work repeat a valid piece), so that it travels while the weights are staged.
+    // A wave walks kRows grid rows of its strip from top to bottom.  Three rows (r-1, r, r+1; columns c0-1..c0+kStrip)
+    // are held as raw pieces; the row after them is requested before the arithmetic of the current output row starts
+    // and has arrived when the window moves down, so that loads and arithmetic overlap inside every wave and each
+    // input row is fetched once per band instead of three times.  Coordinates are clamped (lanes and waves without
+    // work repeat a valid piece) and pieces outside the matrix are cleared afterwards (zero padding).
     // (strip index and everything derived from it are uniform over the wave: scalar arithmetic; addresses are
     // a 64-bit base of the (batch, channel group) plus 32-bit byte offsets, row part + column part)
     const int nstrips = (gw + kStrip - 1) / kStrip;
-    const uint32_t nsid = (uint32_t)B * (uint32_t)gh * (uint32_t)nstrips;              // < 2^31 (host check)
-    const uint32_t sid = (uint32_t)__builtin_amdgcn_readfirstlane(by * kWaves + wv);   // strip of this wave
+    const int nbands = (gh + kRows - 1) / kRows;
+    const uint32_t nsid = (uint32_t)B * (uint32_t)nbands * (uint32_t)nstrips;          // < 2^31 (host check)
+    const uint32_t sid = (uint32_t)__builtin_amdgcn_readfirstlane(by * kWaves + wv);   // (band, strip) of this wave
     const bool active = lane < ncg_here && sid < nsid;
     const uint32_t sidc = sid < nsid ? sid : nsid - 1;
     const uint32_t q1 = sidc / (uint32_t)nstrips;
     const int cs = (int)(sidc - q1 * (uint32_t)nstrips);
-    const int b = (int)(q1 / (uint32_t)gh);
-    const int r = (int)(q1 - (uint32_t)b * (uint32_t)gh);
+    const int b = (int)(q1 / (uint32_t)nbands);
+    const int r0 = (int)(q1 - (uint32_t)b * (uint32_t)nbands) * kRows;
     const int ch = (cg0 + (lane < ncg_here ? lane : 0)) * VEC;
     const int c0 = cs * kStrip;
     const size_t img = (size_t)b * gh * gw * D + ch;                 // element offset of (b, token 0, ch)
     const char *xin = static_cast<const char *>(x) + img * sizeof(TIn);
     char *yout = static_cast<char *>(y) + img * sizeof(TOut);
     const uint32_t pitch = (uint32_t)D * (uint32_t)sizeof(TIn);     // bytes from a token to the next
-    uint32_t rowoff[3], coloff[kStrip + 2];
-#pragma unroll
-    for (int j = 0; j < 3; ++j) rowoff[j] = (uint32_t)(min(max(r + j - 1, 0), gh - 1) * gw) * pitch;
+    const uint32_t opitch = (uint32_t)D * (uint32_t)sizeof(TOut);
+    uint32_t coloff[kStrip + 2];
 #pragma unroll
     for (int t = 0; t < kStrip + 2; ++t) coloff[t] = (uint32_t)min(max(c0 + t - 1, 0), gw - 1) * pitch;
-    Raw<TIn, VEC> win[3][kStrip + 2];
+    auto load_row = [&](int rr, Raw<TIn, VEC> (&dst)[kStrip + 2]) {
+        const uint32_t rowoff = (uint32_t)(min(max(rr, 0), gh - 1) * gw) * pitch;
 #pragma unroll
-    for (int j = 0; j < 3; ++j)
-#pragma unroll
-        for (int t = 0; t < kStrip + 2; ++t)
-            win[j][t] = *reinterpret_cast<const Raw<TIn, VEC> *>(xin + (rowoff[j] + coloff[t]));
+        for (int t = 0; t < kStrip + 2; ++t) dst[t] = *reinterpret_cast<const Raw<TIn, VEC> *>(xin + (rowoff + coloff[t]));
+    };
+    Raw<TIn, VEC> win[4][kStrip + 2];    // rows r-1, r, r+1 and the one in flight, rotating
+    load_row(r0 - 1, win[0]);
+    load_row(r0, win[1]);
+    load_row(r0 + 1, win[2]);
     // weights of the block's channel groups: one contiguous piece of the [D, 3, 3] array
     {
         const float *src = w + (size_t)cg0 * VEC * 9;
@@ -161,43 +169,51 @@ __global__ __launch_bounds__(kThreads) void srem_dwconv_kernel(const void *x, co
 #pragma unroll
     for (int i = 0; i < VEC; ++i) bv[i] = bias != nullptr ? bias[ch + i] : 0.f;
 
-    float acc[kStrip][VEC];
 #pragma unroll
-    for (int t = 0; t < kStrip; ++t)
+    for (int ri = 0; ri < kRows; ++ri) {
+        const int r = r0 + ri;
+        if (r >= gh) break;                                   // uniform: the last band may be short
+        if (ri + 1 < kRows) load_row(r + 2, win[(ri + 3) & 3]);   // in flight during this row's arithmetic
+        float acc[kStrip][VEC];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[t][i] = bv[i];
+        for (int t = 0; t < kStrip; ++t)
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {
-        const bool row_in = (r + j - 1 >= 0) && (r + j - 1 < gh);
+            for (int i = 0; i < VEC; ++i) acc[t][i] = bv[i];
 #pragma unroll
-        for (int t = 0; t < kStrip + 2; ++t) {
-            const int c = c0 + t - 1;
-            // a piece outside the matrix was fetched from a clamped position: clear it (zero padding)
-            and_mask(win[j][t], (row_in && c >= 0 && c < gw) ? 0xffffffffu : 0u);
-            float xv[VEC];
-            to_floats(win[j][t], xv);
-            // this piece is the left / middle / right neighbour of outputs t, t-1, t-2
+        for (int j = 0; j < 3; ++j) {
+            const bool row_in = (r + j - 1 >= 0) && (r + j - 1 < gh);
 #pragma unroll
-            for (int o = 0; o < 3; ++o) {
-                const int tt = t - o;          // output token index in the strip
-                if (tt >= 0 && tt < kStrip) {
+            for (int t = 0; t < kStrip + 2; ++t) {
+                const int c = c0 + t - 1;
+                // a piece outside the matrix was fetched from a clamped position: clear it (zero padding);
+                // the cleared copy is a temporary, the window keeps the fetched bytes (a clamped bottom row is a
+                // real row for the output rows above it)
+                Raw<TIn, VEC> piece = win[(ri + j) & 3][t];
+                and_mask(piece, (row_in && c >= 0 && c < gw) ? 0xffffffffu : 0u);
+                float xv[VEC];
+                to_floats(piece, xv);
+                // this piece is the left / middle / right neighbour of outputs t, t-1, t-2
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) acc[tt][i] = fmaf(wt[j][o][i], xv[i], acc[tt][i]);
+                for (int o = 0; o < 3; ++o) {
+                    const int tt = t - o;          // output token index in the strip
+                    if (tt >= 0 && tt < kStrip) {
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) acc[tt][i] = fmaf(wt[j][o][i], xv[i], acc[tt][i]);
+                    }
                 }
             }
         }
-    }
-    const uint32_t opitch = (uint32_t)D * (uint32_t)sizeof(TOut);
-    char *yrow = yout + (size_t)((uint32_t)(r * gw + c0) * opitch);
+        char *yrow = yout + (size_t)((uint32_t)(r * gw + c0) * opitch);
 #pragma unroll
-    for (int t = 0; t < kStrip; ++t)
-        if (c0 + t < gw) store_vec<TOut, VEC>(yrow + (uint32_t)t * opitch, 0, acc[t]);
+        for (int t = 0; t < kStrip; ++t)
+            if (c0 + t < gw) store_vec<TOut, VEC>(yrow + (uint32_t)t * opitch, 0, acc[t]);
+    }
 }
 
 template <typename TIn, typename TOut, int VEC>
 hipError_t launch_vec(const void *x, const float *w, const float *bias, void *y, int B, int gh, int gw, int D,
                       int orient, hipStream_t stream) {
-    const long long nstrips = (long long)B * gh * ((gw + kStrip - 1) / kStrip);
+    const long long nstrips = (long long)B * ((gh + kRows - 1) / kRows) * ((gw + kStrip - 1) / kStrip);
     const long long nblocks = (long long)((D / VEC + 63) / 64) * ((nstrips + kWaves - 1) / kWaves);
     dim3 grid((unsigned)nblocks), block(kThreads);
     hipLaunchKernelGGL((srem_dwconv_kernel<TIn, TOut, VEC>), grid, block, 0, stream, x, w, bias, y, B, gh, gw, D,
