@@ -45,6 +45,11 @@ def test_options_round_trip():
     gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_IN_OUTPUT_PASS)
     assert gla.gla_get_option(gla.OPT_CARRY) == gla.CARRY_IN_OUTPUT_PASS
     gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_AUTO)
+    gla.gla_set_option(gla.OPT_BWD_SPLIT, 1)
+    assert gla.gla_get_option(gla.OPT_BWD_SPLIT) == 1
+    gla.gla_set_option(gla.OPT_BWD_SPLIT, 0)
+    with pytest.raises(gla.GlaError):
+        gla.gla_set_option(gla.OPT_BWD_SPLIT, 2)
     with pytest.raises(gla.GlaError):
         gla.gla_set_option(gla.OPT_CARRY, 3)
     with pytest.raises(gla.GlaError):
