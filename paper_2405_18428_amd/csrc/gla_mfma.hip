@@ -18,10 +18,9 @@
 //       token-major, 16- or 8-byte pieces), S_0 as bf16 hi/lo;
 //   (b) lane = token: DPP wave scan of log_alpha per channel, exp2, gating, hi/lo
 //       split, q~ and k~ written in place over the raw rows; the 32/NW-channel units
-//       of a row are dealt to the waves round-robin, left-over channels one by one;
-//   (c) MFMA: in the output pass wave w owns output rows 16w..16w+15 and the state tiles
-//       of one 16-channel row tile (shared K~ operand); the state pass deals its state
-//       tiles round-robin over its 8 waves.
+//       of a row are dealt to the waves round-robin, the channels past the last whole unit one by one;
+//   (c) MFMA: in the output pass wave w owns output rows 16w..16w+15; in both passes the state
+//       tiles of a wave lie in one 16-channel row tile (its K~ operand is read once per chunk).
 // Operands whose contraction runs over tokens (V, and K~ in the state update) are
 // fetched from the token-major rows with ds_read_b64_tr_b16, which hands lane i of
 // a 16-lane group element i%4 of the 8 bytes read by lane 4e + i/4 (e = 0..3): 16
@@ -76,19 +75,29 @@ struct Layout {
 template <int N>
 using int_c = std::integral_constant<int, N>;
 
-// Which 16x16 tile of the dk x dv state is the i-th tile of wave w.  The output pass gives a wave the tiles of one
-// 16-channel row tile (its K~ operand is then read once, and the wave with the most score tiles owns none); the
-// state-only pass has nothing else to balance against and deals the tiles round-robin.
+// Which 16x16 tile of the dk x dv state is the i-th tile of wave w.  All tiles of a wave lie in one 16-channel row
+// tile, so that its K~ operand is read once per chunk.  The output pass gives every row tile the same number of
+// waves (the wave with the most score tiles then owns none); the state-only pass has nothing else to balance
+// against and splits its waves over the row tiles as evenly as they divide (row tile ct: waves NW ct / NCT up to
+// NW (ct + 1) / NCT), and the waves of a row tile take its value-column tiles in turn.
 template <bool ROW_OWNED, int NW, int NCT, int NDV16>
 struct TileMap {
-    static constexpr int WPC = (NW / NCT) > 0 ? NW / NCT : 1;  // waves sharing a row tile
-    static constexpr int kPerWave = ROW_OWNED ? (NDV16 + WPC - 1) / WPC : (NCT * NDV16 + NW - 1) / NW;
-    __host__ __device__ static constexpr int ct(int w, int i) { return ROW_OWNED ? w / WPC : (w + NW * i) / NDV16; }
+    static_assert(ROW_OWNED || NW >= NCT, "state pass: at least one wave per row tile");
+    static constexpr int WPC = (NW / NCT) > 0 ? NW / NCT : 1;  // waves sharing a row tile (the fewest, if uneven)
+    static constexpr int kPerWave = (NDV16 + WPC - 1) / WPC;
+    __host__ __device__ static constexpr int first_wave(int ct) { return NW * ct / NCT; }
+    __host__ __device__ static constexpr int ct(int w, int = 0) {
+        if (ROW_OWNED) return w / WPC;
+        int c = 0;
+        while (c + 1 < NCT && first_wave(c + 1) <= w) ++c;
+        return c;
+    }
     __host__ __device__ static constexpr int nt(int w, int i) {
-        return ROW_OWNED ? (w % WPC) + WPC * i : (w + NW * i) % NDV16;
+        if (ROW_OWNED) return (w % WPC) + WPC * i;
+        return (w - first_wave(ct(w))) + (first_wave(ct(w) + 1) - first_wave(ct(w))) * i;
     }
     __host__ __device__ static constexpr bool valid(int w, int i) {
-        return ROW_OWNED ? (w / WPC < NCT && (w % WPC) + WPC * i < NDV16) : (w + NW * i < NCT * NDV16);
+        return ROW_OWNED ? (w / WPC < NCT && (w % WPC) + WPC * i < NDV16) : nt(w, i) < NDV16;
     }
     __host__ __device__ static constexpr int count(int w) {
         int n = 0;
@@ -313,11 +322,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     // ---- gate work of this wave: whole UW-channel units w, w+NW, ..., then single left-over channels ----
     constexpr int UW = 32 / NW;                       // channels per unit: 16-byte LDS rows accesses for 4 waves
     const int nunits = dk / UW;
-    const int upw = nunits / NW;                      // units every wave owns
-    const int left0 = UW * upw * NW;                  // first left-over channel
+    const int upw = (nunits + NW - 1) / NW;           // units of the busiest wave
+    const int left0 = UW * nunits;                    // first left-over channel (none with 4-channel units)
     const int lpw = (dk - left0 + NW - 1) / NW;       // left-over channels per wave
-    constexpr int kMaxUnits = kMaxDk / (UW * NW);
-    constexpr int kMaxLeft = (UW * NW - 4 + NW - 1) / NW;
+    constexpr int kMaxUnits = (kMaxDk / UW + NW - 1) / NW;
+    constexpr int kMaxLeft = (UW - 4 + NW - 1) / NW;
 
     load_chunk(0, int_c<0>{});
     if constexpr (DEPTH == 2) {
@@ -406,7 +415,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             const int j = lane;
 #pragma unroll
             for (int ui = 0; ui < kMaxUnits; ++ui) {
-                if (ui < upw) {
+                if (ui < upw && w + NW * ui < nunits) {
                     const int c0 = UW * (w + NW * ui);
                     float bb[UW];
 #pragma unroll
@@ -530,8 +539,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             const uint16_t *krow_h = s_khi + (4 * g + tr_row) * CHS + tr_col;
             const uint16_t *krow_l = s_klo + (4 * g + tr_row) * CHS + tr_col;
             const uint16_t *vrow = s_v + (4 * g + tr_row) * VS + tr_col;
-            constexpr int KB = OUT ? 1 : 2;                 // K~ buffers: shared, or one per tile in flight
-            u32x2 ukh[KB][2][2], ukl[KB][2][2];             // [buffer][32-token step][half]
+            u32x2 ukh[1][2][2], ukl[1][2][2];               // [0][32-token step][half]: shared by the wave's tiles
             auto load_state_k = [&](int buf, int i) {
                 const int ko = 16 * TM::ct(W, i);
 #pragma unroll
@@ -784,10 +792,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
 #pragma unroll
                 for (int i = 0; i < NTW; ++i) update_state(0, i, v_frag(0, TM::nt(W, i)), v_frag(1, TM::nt(W, i)));
             } else {
-                // state pass: operands of tile i+1 are read while tile i is contracted
+                // state pass: K~ of the wave's row tile once, V of tile i+1 read while tile i is contracted
                 u32x2 uv[2][2][2];                              // [buffer][32-token step][half]
-                auto load_state_ops = [&](int buf, int i) {
-                    load_state_k(buf, i);
+                auto load_state_v = [&](int buf, int i) {
                     const int vo = 16 * TM::nt(W, i);
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks) {
@@ -795,13 +802,16 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                         uv[buf][ks][1] = lds_read_tr(vrow + (32 * ks + 16) * VS + vo);
                     }
                 };
-                if constexpr (NTW > 0) load_state_ops(0, 0);
+                if constexpr (NTW > 0) {
+                    load_state_k(0, 0);
+                    load_state_v(0, 0);
+                }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < NTW; ++i) {
-                    if (i + 1 < NTW) load_state_ops((i + 1) & 1, i + 1);
+                    if (i + 1 < NTW) load_state_v((i + 1) & 1, i + 1);
                     const int bf = i & 1;
-                    update_state(bf, i, u32x4{uv[bf][0][0][0], uv[bf][0][0][1], uv[bf][0][1][0], uv[bf][0][1][1]},
+                    update_state(0, i, u32x4{uv[bf][0][0][0], uv[bf][0][0][1], uv[bf][0][1][0], uv[bf][0][1][1]},
                                  u32x4{uv[bf][1][0][0], uv[bf][1][0][1], uv[bf][1][1][0], uv[bf][1][1][1]});
                     __builtin_amdgcn_sched_barrier(0);
                 }
