@@ -158,6 +158,24 @@ int gla_fwd_layout(const void *q, const void *k, const void *v, const float *log
                    void *workspace, size_t workspace_bytes, gla_stream_t stream);
 
 /*
+ * gla_fwd_gates - the recurrence with the full gate matrix of Sec. 3.1, G_t = alpha_t^T beta_t
+ * (Eq. (gate_gla) for the key side, Eq. (gate_gla_2) for the value side), applied element-wise
+ * in Eq. (attn_gla) row 1:   S_t = (alpha_t^T beta_t) * S_{t-1} + k_t^T v_t ,  o_t = q_t S_t.
+ *
+ *   log_beta         DEVICE, fp32, shaped and laid out like v ([B,H,T,dv] or [B,T,H,dv]), 16-byte
+ *                    aligned; log of the value-side gate, <= 0                                  (read)
+ *
+ * Everything else as gla_fwd_layout (log_beta = 0 gives its result).  Computed by the
+ * token-by-token fp32 engine for every element type and head size (the MFMA engine factorises
+ * the key-side decay only): GLA_ERR_UNSUPPORTED if the engine option forces the MFMA engine,
+ * GLA_ERR_NULL for a NULL log_beta.
+ */
+int gla_fwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,
+                  int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                  int qkv_dtype, int out_dtype, int layout, const float *initial_state,
+                  void *out, float *final_state, void *workspace, size_t workspace_bytes, gla_stream_t stream);
+
+/*
  * gla_bwd - gradients of a scalar loss L that depends on `out` of gla_fwd_ex (zero initial
  * state, [B,H,T,d] order) with respect to q, k, v and log_alpha: Eq. (attn_gla) rows 1-3
  * differentiated in reverse mode.  With S_s the state after scan step s and

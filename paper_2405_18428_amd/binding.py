@@ -59,6 +59,8 @@ def load_library():
     lib.gla_fwd_ex.argtypes = [vp, vp, vp, vp] + shape + [i, i, vp, vp, vp, sz, vp]
     lib.gla_fwd_layout.restype = i
     lib.gla_fwd_layout.argtypes = [vp, vp, vp, vp] + shape + [i, i, i, vp, vp, vp, vp, sz, vp]
+    lib.gla_fwd_gates.restype = i
+    lib.gla_fwd_gates.argtypes = [vp, vp, vp, vp, vp] + shape + [i, i, i, vp, vp, vp, vp, sz, vp]
     lib.gla_bwd.restype = i
     lib.gla_bwd.argtypes = [vp] * 5 + shape + [i] + [vp] * 4 + [vp, sz, vp]
     lib.gla_bwd_layout.restype = i
@@ -238,6 +240,44 @@ def gla_fwd_layout(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, la
                                   initial_state.data_ptr() if initial_state is not None else None,
                                   out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
                                   workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return out, final_state
+
+
+def gla_fwd_gates(q, k, v, log_alpha, log_beta, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, layout=LAYOUT_BHTD,
+                  initial_state=None, out_dtype=None, want_final_state=True, workspace=None, stream=None):
+    """The recurrence with the two-sided gate alpha_t^T beta_t; ``log_beta`` is fp32, shaped like v."""
+    torch = _torch()
+    lib = load_library()
+    if layout not in (LAYOUT_BHTD, LAYOUT_BTHD):
+        raise ValueError("unknown layout")
+    for name, t in (("q", q), ("k", k), ("v", v), ("log_alpha", log_alpha), ("log_beta", log_beta)):
+        if not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous 4-d GPU tensor")
+    if q.shape != k.shape or q.shape != log_alpha.shape or v.shape[:3] != q.shape[:3] or log_beta.shape != v.shape:
+        raise ValueError("q, k, log_alpha must share one shape, v and log_beta another with the same first three sizes")
+    if q.dtype != k.dtype or q.dtype != v.dtype or log_alpha.dtype != torch.float32 or log_beta.dtype != torch.float32:
+        raise TypeError("q, k, v must share one element type and the gates must be fp32")
+    if layout == LAYOUT_BHTD:
+        B, H, T, dk = q.shape
+    else:
+        B, T, H, dk = q.shape
+    dv = v.shape[3]
+    qdt = _dt(q)
+    if initial_state is not None:
+        if (initial_state.dtype != torch.float32 or tuple(initial_state.shape) != (B, H, dk, dv)
+                or not initial_state.is_contiguous() or not initial_state.is_cuda):
+            raise ValueError("initial_state must be a contiguous fp32 GPU tensor [B,H,dk,dv]")
+    out = torch.empty(tuple(v.shape), dtype=torch.float32 if out_dtype is None else out_dtype, device=q.device)
+    final_state = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device) if want_final_state else None
+    if workspace is None:
+        nbytes = gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
+        workspace = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=q.device)
+    with torch.cuda.device(q.device):
+        _check(lib.gla_fwd_gates(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(), log_beta.data_ptr(),
+                                 B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt, _dt(out), layout,
+                                 initial_state.data_ptr() if initial_state is not None else None,
+                                 out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
+                                 workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return out, final_state
 
 

@@ -8,7 +8,7 @@
 namespace gla {
 namespace {
 
-constexpr int kVersion = 300;  // 0.3.0
+constexpr int kVersion = 310;  // 0.3.1
 
 int g_opt_chunks_per_span = 0;
 int g_opt_engine = GLA_ENGINE_AUTO;
@@ -34,7 +34,8 @@ size_t workspace_bytes(int B, int H, int T, int dk, int dv) {
     size_t bh = (size_t)B * H;
     size_t state = align_up(bh * nspans * dk * dv * sizeof(float), 256);
     size_t lgam = align_up(bh * nspans * dk * sizeof(float), 256);
-    return state + lgam;
+    size_t lgam_b = align_up(bh * nspans * dv * sizeof(float), 256);   // value-side gate sums (two-sided gate only)
+    return state + lgam + lgam_b;
 }
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -93,6 +94,8 @@ int choose_engine_and_plan(Params &p, void *workspace, bool &use_mfma) {
     p.ws_state = static_cast<float *>(workspace);
     p.ws_lgam = reinterpret_cast<float *>(static_cast<char *>(workspace) +
                                           align_up(bh * p.nspans * p.dk * p.dv * sizeof(float), 256));
+    p.ws_lgam_b = reinterpret_cast<float *>(reinterpret_cast<char *>(p.ws_lgam) +
+                                            align_up(bh * p.nspans * p.dk * sizeof(float), 256));
     return GLA_OK;
 }
 
@@ -214,7 +217,7 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
         int qkv_dtype, int out_dtype, void *out, float *final_state,
         void *workspace, size_t ws_bytes, hipStream_t stream, PhaseEvents *events,
         int layout = GLA_LAYOUT_BHTD, const float *initial_state = nullptr, const FusedArgs *fused = nullptr,
-        int accumulate = 0) {
+        int accumulate = 0, const float *log_beta = nullptr) {
     // with the gate prologue the gate rows are z (checked like log_alpha: non-null, aligned)
     int st = validate(q, k, v, fused ? static_cast<const float *>(fused->z) : log_alpha, B, H, T, dk, dv,
                       grid_h, grid_w, scan_dir, qkv_dtype, out_dtype, out, final_state);
@@ -226,10 +229,12 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     }
     if (layout != GLA_LAYOUT_BHTD && layout != GLA_LAYOUT_BTHD) return GLA_ERR_SHAPE;
     if (initial_state && misaligned(initial_state)) return GLA_ERR_ALIGN;
+    if (log_beta && misaligned(log_beta)) return GLA_ERR_ALIGN;
     if (!workspace || misaligned(workspace) || ws_bytes < workspace_bytes(B, H, T, dk, dv))
         return GLA_ERR_WORKSPACE;
 
     Params p{};
+    p.log_beta = log_beta;
     p.q = q; p.k = k; p.v = v; p.log_alpha = log_alpha; p.out = out; p.final_state = final_state;
     p.B = B; p.H = H; p.T = T; p.dk = dk; p.dv = dv;
     p.grid_h = grid_h; p.grid_w = grid_w; p.scan_dir = scan_dir;
@@ -292,6 +297,16 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
 using namespace gla;
 
 extern "C" {
+
+int gla_fwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,
+                  int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                  int qkv_dtype, int out_dtype, int layout, const float *initial_state,
+                  void *out, float *final_state, void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
+    if (!log_beta) return GLA_ERR_NULL;
+    return run(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype, out_dtype,
+               out, final_state, workspace, workspace_bytes_, static_cast<hipStream_t>(stream), nullptr,
+               layout, initial_state, nullptr, 0, log_beta);
+}
 
 int gla_fwd_ex(const void *q, const void *k, const void *v, const float *log_alpha,
                int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,

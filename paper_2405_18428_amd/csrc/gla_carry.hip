@@ -3,7 +3,9 @@
 // Every span r has produced, from a zero state, its local state U_r and
 // log Gamma_r (the summed log_alpha of its tokens).  Because the recurrence of
 // Sec. 3.1 Eq. (attn_gla) is linear in S, the state entering span r+1 is
-//     S_start(r+1) = diag(Gamma_r) S_start(r) + U_r ,   S_start(0) = the caller's initial state (or 0).
+//     S_start(r+1) = diag(Gamma_r) S_start(r) + U_r ,   S_start(0) = the caller's initial state (or 0)
+// (with the value-side gate of Eq. (gate_gla_2), element (c, n) decays by Gamma_r[c] times the product of beta[n]
+// over the span, whose logarithm phase 1 left in ws_lgam_b).
 // Each of the dk*dv state elements is an independent scalar recurrence over the
 // spans; the buffer is rewritten in place (U_r becomes S_start(r)) and the value
 // after the last span is the final state.
@@ -36,6 +38,7 @@ __global__ __launch_bounds__(kCarryThreads) void carry_kernel(Params p) {
     const int c = e / p.dv;
     float *st = p.ws_state + (size_t)bh * p.nspans * ne + e;
     const float *lg = p.ws_lgam + (size_t)bh * p.nspans * p.dk + c;
+    const float *lgb = p.log_beta != nullptr ? p.ws_lgam_b + (size_t)bh * p.nspans * p.dv + (e - c * p.dv) : nullptr;
 
     // state entering the current pass of kGroups * kRun spans; the first pass starts from the caller's state
     float carry = p.initial_state ? p.initial_state[(size_t)bh * ne + e] : 0.f;
@@ -47,7 +50,7 @@ __global__ __launch_bounds__(kCarryThreads) void carry_kernel(Params p) {
             const int r = first + i;
             const bool ok = r < p.nspans;
             u[i] = ok ? st[(size_t)r * ne] : 0.f;
-            gam[i] = ok ? expf(lg[(size_t)r * p.dk]) : 1.f;
+            gam[i] = ok ? expf(lg[(size_t)r * p.dk] + (lgb != nullptr ? lgb[(size_t)r * p.dv] : 0.f)) : 1.f;
         }
         // the run composed from a zero state
         float gprod = 1.f, ulocal = 0.f;

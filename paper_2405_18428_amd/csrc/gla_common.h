@@ -60,6 +60,10 @@ struct Params {
     const void *r_pre;
     const float *ln_weight, *ln_bias;
     float ln_eps;
+    // value-side gate (Eq. (gate_gla_2)): if log_beta is set ([B,H,T,dv] fp32, laid out like v), the state element
+    // (c, n) decays by alpha_t[c] * beta_t[n]; token-by-token engine only
+    const float *log_beta;
+    float *ws_lgam_b;       // [B*H, nspans, dv]  summed log_beta of each span (phase 1 -> phase 2)
 };
 
 // Scan step s -> canonical token index (Sec. 3.3 / Algorithm 1 orders).

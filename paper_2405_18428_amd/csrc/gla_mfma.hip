@@ -923,6 +923,7 @@ hipError_t launch_mode(const Params &p, hipStream_t stream) {
 bool mfma_engine_supports(const Params &p) {
     // 32-bit byte offsets inside the view of one (batch, head)
     const long long slab = (long long)p.T * (p.st_k > p.st_v ? p.st_k : p.st_v) * 4;
+    if (p.log_beta != nullptr) return false;   // the chunk form here factorises the key-side decay only
     return p.qkv_dtype == GLA_DT_BF16 && p.dk % 4 == 0 && p.dv % 8 == 0 && p.dk <= kMaxDk && p.dv <= kMaxDv &&
            slab < (1LL << 31);
 }

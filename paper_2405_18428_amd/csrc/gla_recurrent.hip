@@ -1,5 +1,5 @@
 // Token-by-token fp32 engine for one span of the GLA recurrence
-// (DiG paper, Sec. 3.1 Eq. (attn_gla) rows 1-3, beta = 1).
+// (DiG paper, Sec. 3.1 Eq. (attn_gla) rows 1-3; the value-side gate beta of Eq. (gate_gla_2) is optional).
 //
 // One work-group walks the scan steps of its span in order.  Thread n owns
 // column n of the dk x dv state in registers; q, k and alpha = exp(log_alpha) of
@@ -30,8 +30,10 @@ template <> __device__ inline void store_elem<uint16_t>(void *base, size_t idx, 
     static_cast<uint16_t *>(base)[idx] = float_to_bf16_bits(x);
 }
 
-template <int MODE, typename TIn, typename TOut>
+// BETA: the gate is alpha_t^T beta_t (log_beta given); otherwise diag(alpha_t).
+template <int MODE, typename TIn, typename TOut, bool BETA>
 __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
+    __shared__ float s_b[BETA ? kTile : 1][BETA ? kMaxDv : 1];   // log_beta rows of the tile
     __shared__ float s_q[kTile][kMaxDk];
     __shared__ float s_k[kTile][kMaxDk];
     __shared__ float s_a[kTile][kMaxDk];
@@ -73,6 +75,7 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
     const int sc = tid & 63;
     const int sj = tid >> 6;
     float lsum = 0.f;
+    float lsum_b = 0.f;     // BETA: summed log_beta of this thread's column
 
     for (int t0 = s_begin; t0 < s_end; t0 += kTile) {
         __syncthreads();
@@ -104,7 +107,10 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
         for (int idx = tid; idx < kTile * dv; idx += kThreads) {
             int j = idx / dv, n2 = idx - j * dv;
             int n = s_tok[j];
-            if (n >= 0) s_v[j][n2] = load_elem<TIn>(p.v, base_v + (size_t)n * st_v + n2);
+            if (n >= 0) {
+                s_v[j][n2] = load_elem<TIn>(p.v, base_v + (size_t)n * st_v + n2);
+                if constexpr (BETA) s_b[j][n2] = p.log_beta[base_v + (size_t)s_tokg[j] * st_v + n2];
+            }
         }
         __syncthreads();
         if (col_active) {
@@ -113,10 +119,16 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
                 if (n < 0) break;
                 float vn = s_v[j][tid];
                 float o = 0.f;
+                float bn = 1.f;
+                if constexpr (BETA) {
+                    const float lb = s_b[j][tid];
+                    lsum_b += lb;
+                    bn = expf(lb);
+                }
 #pragma unroll
                 for (int c = 0; c < kMaxDk; ++c) {
                     if (c < dk) {
-                        S[c] = fmaf(s_a[j][c], S[c], s_k[j][c] * vn);
+                        S[c] = fmaf(BETA ? s_a[j][c] * bn : s_a[j][c], S[c], s_k[j][c] * vn);
                         if (MODE == kModeOutput) o = fmaf(s_q[j][c], S[c], o);
                     }
                 }
@@ -170,6 +182,7 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
 #pragma unroll
             for (int c = 0; c < kMaxDk; ++c)
                 if (c < dk) u[(size_t)c * dv + tid] = S[c];
+            if constexpr (BETA) p.ws_lgam_b[((size_t)bh * p.nspans + sp) * dv + tid] = lsum_b;
         }
         s_lsum[sj][sc] = lsum;
         __syncthreads();
@@ -183,20 +196,25 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
     }
 }
 
-template <int MODE>
-hipError_t dispatch(const Params &p, hipStream_t stream) {
+template <int MODE, bool BETA>
+hipError_t dispatch_gate(const Params &p, hipStream_t stream) {
     dim3 grid((unsigned)(p.B * p.H * p.nspans)), block(kThreads);
     const bool in_bf16 = p.qkv_dtype == GLA_DT_BF16;
     const bool out_bf16 = p.out_dtype == GLA_DT_BF16;
     if (in_bf16 && out_bf16)
-        hipLaunchKernelGGL((recurrent_span_kernel<MODE, uint16_t, uint16_t>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((recurrent_span_kernel<MODE, uint16_t, uint16_t, BETA>), grid, block, 0, stream, p);
     else if (in_bf16)
-        hipLaunchKernelGGL((recurrent_span_kernel<MODE, uint16_t, float>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((recurrent_span_kernel<MODE, uint16_t, float, BETA>), grid, block, 0, stream, p);
     else if (out_bf16)
-        hipLaunchKernelGGL((recurrent_span_kernel<MODE, float, uint16_t>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((recurrent_span_kernel<MODE, float, uint16_t, BETA>), grid, block, 0, stream, p);
     else
-        hipLaunchKernelGGL((recurrent_span_kernel<MODE, float, float>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((recurrent_span_kernel<MODE, float, float, BETA>), grid, block, 0, stream, p);
     return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t dispatch(const Params &p, hipStream_t stream) {
+    return p.log_beta != nullptr ? dispatch_gate<MODE, true>(p, stream) : dispatch_gate<MODE, false>(p, stream);
 }
 
 }  // namespace

@@ -146,5 +146,15 @@ def make_fused_inputs(B, H, T, dk, dv, dtype="bf16", seed=0, z_mean=0.0):
     return d
 
 
+def make_gate_inputs(B, H, T, dk, dv, dtype="bf16", seed=0, z_mean=0.0, tau=TAU):
+    """:func:`make_inputs` plus ``log_beta`` [B,H,T,dv] (fp32, <= 0) for the value-side gate: logsigmoid of a
+    standard-normal pre-activation (+ z_mean) from a second generator, divided by tau like log_alpha."""
+    d = make_inputs(B, H, T, dk, dv, dtype, seed, z_mean, tau)
+    rng2 = np.random.Generator(np.random.PCG64(seed + 3000))
+    zb = (rng2.standard_normal((B, H, T, dv), dtype=np.float32) + np.float32(z_mean)).astype(np.float32)
+    d["log_beta"] = (log_sigmoid_f32(zb) / np.float32(tau)).astype(np.float32)
+    return d
+
+
 def make_config_inputs(cfg: GlaConfig):
     return make_inputs(cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv, cfg.dtype, cfg.seed, cfg.z_mean)

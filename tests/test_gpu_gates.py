@@ -1,0 +1,94 @@
+"""GPU parity of gla_fwd_gates (two-sided gate alpha_t^T beta_t, Sec. 3.1 Eqs. (gate_gla), (gate_gla_2)) against the
+fp64 oracle, through the C ABI.  Bars: 1e-4 x RMS (fp32 rows), 2e-2 x RMS (bf16 rows), max-norm."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_2405_18428_amd as gla
+from paper_2405_18428_amd import inputs as gi
+from oracle import gla_oracle as orc
+from oracle import gla_oracle_gates as og
+
+TOL_F32, TOL_BF16 = 1e-4, 2e-2
+
+
+def _err(got, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(rms, 1e-300))
+
+
+def _dev(d, dtype):
+    dev = torch.device("cuda:0")
+    if dtype == "bf16":
+        q, k, v = (torch.from_numpy(d[n + "_bits"].view(np.int16)).to(dev).view(torch.bfloat16) for n in "qkv")
+    else:
+        q, k, v = (torch.from_numpy(d[n]).to(dev) for n in "qkv")
+    return q, k, v, torch.from_numpy(d["log_alpha"]).to(dev), torch.from_numpy(d["log_beta"]).to(dev)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("scan_dir", [0, 1, 2, 3])
+def test_gates_parity_several_spans_ragged(dtype, scan_dir):
+    B, H, gh, gw, dk, dv = 2, 3, 19, 23, 20, 33      # T = 437: seven chunks, a ragged last one, odd head sizes
+    d = gi.make_gate_inputs(B, H, gh * gw, dk, dv, dtype, seed=11 + scan_dir)
+    q, k, v, la, lb = _dev(d, dtype)
+    out, fin = gla.gla_fwd_gates(q, k, v, la, lb, gh, gw, scan_dir)
+    torch.cuda.synchronize()
+    ro, rf = og.gla_fwd_gates(d["q"], d["k"], d["v"], d["log_alpha"], d["log_beta"], gh, gw, scan_dir)
+    assert _err(out.cpu().numpy(), ro) < TOL_F32
+    assert _err(fin.cpu().numpy(), rf) < TOL_F32
+
+
+def test_gates_bf16_rows_token_major_initial_state():
+    B, H, gh, gw, dk, dv = 2, 4, 16, 20, 32, 64
+    T = gh * gw
+    d = gi.make_gate_inputs(B, H, T, dk, dv, "bf16", seed=21)
+    q, k, v, la, lb = _dev(d, "bf16")
+    s0 = np.random.default_rng(5).standard_normal((B, H, dk, dv)).astype(np.float32)
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous()      # [B,H,T,d] -> [B,T,H,d]
+    out, fin = gla.gla_fwd_gates(tm(q), tm(k), tm(v), tm(la), tm(lb), gh, gw, 2, layout=gla.LAYOUT_BTHD,
+                                 initial_state=torch.from_numpy(s0).cuda(), out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    ro, rf = og.gla_fwd_gates(d["q"], d["k"], d["v"], d["log_alpha"], d["log_beta"], gh, gw, 2, initial_state=s0)
+    got = out.float().permute(0, 2, 1, 3).cpu().numpy()
+    rms = float(np.sqrt(np.mean(ro * ro)))
+    assert _err(got, ro) < TOL_BF16 + 2.0 ** -9 * float(np.abs(ro).max()) / rms
+    assert _err(fin.cpu().numpy(), rf) < TOL_F32
+
+
+def test_zero_log_beta_gives_the_key_side_result():
+    B, H, gh, gw, dk, dv = 1, 2, 12, 16, 36, 72
+    d = gi.make_gate_inputs(B, H, gh * gw, dk, dv, "bf16", seed=31)
+    q, k, v, la, lb = _dev(d, "bf16")
+    out, fin = gla.gla_fwd_gates(q, k, v, la, torch.zeros_like(lb), gh, gw, 0)
+    torch.cuda.synchronize()
+    ro, rf = orc.gla_fwd(d["q"], d["k"], d["v"], d["log_alpha"], gh, gw, 0)
+    assert _err(out.cpu().numpy(), ro) < TOL_F32
+    assert _err(fin.cpu().numpy(), rf) < TOL_F32
+
+
+def test_gates_headline_shape():
+    """DiG-XL/2 at 2048 x 2048 (T = 16384, H = 16, dk = 36, dv = 72): every output row against the oracle."""
+    cfg = gi.CONFIGS["dig_xl2_2048"]
+    d = gi.make_gate_inputs(cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv, "bf16", seed=cfg.seed)
+    q, k, v, la, lb = _dev(d, "bf16")
+    out, fin = gla.gla_fwd_gates(q, k, v, la, lb, cfg.grid_h, cfg.grid_w, 0)
+    torch.cuda.synchronize()
+    ro, rf = og.gla_fwd_gates(d["q"], d["k"], d["v"], d["log_alpha"], d["log_beta"], cfg.grid_h, cfg.grid_w, 0)
+    assert _err(out.cpu().numpy(), ro) < TOL_F32
+    assert _err(fin.cpu().numpy(), rf) < TOL_F32
+
+
+def test_gates_reject_forced_mfma_engine_and_null():
+    d = gi.make_gate_inputs(1, 1, 64, 32, 64, "bf16", seed=1)
+    q, k, v, la, lb = _dev(d, "bf16")
+    gla.gla_set_option(gla.OPT_ENGINE, gla.ENGINE_MFMA)
+    try:
+        with pytest.raises(gla.GlaError):
+            gla.gla_fwd_gates(q, k, v, la, lb, 8, 8, 0)
+    finally:
+        gla.gla_set_option(gla.OPT_ENGINE, gla.ENGINE_AUTO)
