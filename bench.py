@@ -166,6 +166,61 @@ def bench_multi(args, cfg, d, gla, gi, torch, np, dirs):
     print(json.dumps(result), flush=True)
 
 
+def bench_gates(args, cfg, gla, gi, torch, np):
+    """gla_fwd_gates (two-sided gate alpha_t^T beta_t) at the workload's shape; token-by-token fp32 engine."""
+    dev = torch.device("cuda:0")
+    B, H, T, dk, dv = cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv
+    d = gi.make_gate_inputs(B, H, T, dk, dv, cfg.dtype, cfg.seed, cfg.z_mean)
+    bf16 = cfg.dtype == "bf16"
+    if bf16:
+        host = [torch.from_numpy(d[n + "_bits"].view(np.int16)).view(torch.bfloat16) for n in ("q", "k", "v")]
+    else:
+        host = [torch.from_numpy(d[n]) for n in ("q", "k", "v")]
+    host += [torch.from_numpy(d["log_alpha"]), torch.from_numpy(d["log_beta"])]
+    qdt = gla.DT_BF16 if bf16 else gla.DT_F32
+    ws_bytes = gla.gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
+    sets = []
+    for _ in range(max(1, args.sets)):
+        sets.append([t.to(dev) for t in host] + [torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)])
+
+    def step(i):
+        q, k, v, la, lb, ws = sets[i % len(sets)]
+        return gla.gla_fwd_gates(q, k, v, la, lb, cfg.grid_h, cfg.grid_w, args.scan, workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    qb = 2 if bf16 else 4
+    alg_bytes = (2 * dk * qb + dk * 4 + dv * qb + dv * 4 + dv * 4) * B * H * T   # q, k, log_alpha, v, log_beta, out
+    alg_flops = 5 * dk * dv * B * H * T      # per state element and token: gate product, decay FMA, k*v, read FMA
+    achieved = alg_flops / (ms * 1e-3) / 1e12
+    result = {
+        "metric": "GLA fwd with the two-sided gate, tokens/s at DiG-XL/2 shape T=16384",
+        "value": round(B * T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} + log_beta: B={B} H={H} T={T} ({cfg.grid_h}x{cfg.grid_w}) dk={dk} dv={dv} "
+                               f"{cfg.dtype} q/k/v, fp32 gates, fp32 out, scan {args.scan}", "buffer_sets": len(sets)},
+        "roofline": {"bound": "alu", "kernel": "whole_call", "achieved": round(achieved, 2), "peak": 157.3,
+                     "unit": "TFLOP/s", "frac": round(achieved / 157.3, 4), "traffic": None,
+                     "algorithmic_flops": alg_flops, "algorithmic_bytes": alg_bytes, "kernel_ms": round(ms, 5)},
+    }
+    if not args.no_check:
+        from oracle import gla_oracle_gates
+        ref, _ = gla_oracle_gates.gla_fwd_gates(d["q"], d["k"], d["v"], d["log_alpha"], d["log_beta"],
+                                                cfg.grid_h, cfg.grid_w, args.scan)
+        got, _ = step(0)
+        torch.cuda.synchronize()
+        rms = float(np.sqrt(np.mean(ref ** 2)))
+        result["max_err_over_rms"] = round(float(np.abs(got.cpu().numpy() - ref).max() / rms), 6)
+    print(json.dumps(result), flush=True)
+
+
 def bench_srem(args, cfg, gla, gi, torch, np):
     """gla_srem_dwconv on the token matrix of the workload ([B, T, H*dv] bf16 in and out)."""
     dev = torch.device("cuda:0")
@@ -317,12 +372,13 @@ def main():
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated over (1 = cache-warm)")
     ap.add_argument("--chunks-per-span", type=int, default=0)
     ap.add_argument("--engine", type=int, default=0)
-    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "train", "fused", "bidir", "4dir", "srem"],
+    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "train", "fused", "bidir", "4dir", "srem", "gates"],
                     help="fwd: the forward hot path (the headline); bwd: gla_bwd on the same workload; "
                          "train: gla_fwd_ex followed by gla_bwd_reuse; "
                          "fused: gla_fwd_fused (gate prologue, Swish/LayerNorm epilogue) on the same workload; "
                          "bidir / 4dir: gla_fwd_multi over scan orders (0, 1) / (0, 1, 2, 3); "
-                         "srem: gla_srem_dwconv on the workload's token matrix")
+                         "srem: gla_srem_dwconv on the workload's token matrix; "
+                         "gates: gla_fwd_gates (two-sided gate) on the same workload plus a log_beta tensor")
     ap.add_argument("--layout", default="bhtd", choices=["bhtd", "bthd"],
                     help="memory order of q, k, v, log_alpha, out: [B,H,T,d] (the headline) or [B,T,H,d]")
     ap.add_argument("--reuse-fwd", action="store_true",
@@ -361,6 +417,9 @@ def main():
         return
     if args.which == "fused":
         bench_fused(args, cfg, gla, gi, torch, np)
+        return
+    if args.which == "gates":
+        bench_gates(args, cfg, gla, gi, torch, np)
         return
     if args.which == "srem":
         bench_srem(args, cfg, gla, gi, torch, np)

@@ -165,10 +165,12 @@ int gla_fwd_layout(const void *q, const void *k, const void *v, const float *log
  *   log_beta         DEVICE, fp32, shaped and laid out like v ([B,H,T,dv] or [B,T,H,dv]), 16-byte
  *                    aligned; log of the value-side gate, <= 0                                  (read)
  *
- * Everything else as gla_fwd_layout (log_beta = 0 gives its result).  Computed by the
- * token-by-token fp32 engine for every element type and head size (the MFMA engine factorises
- * the key-side decay only): GLA_ERR_UNSUPPORTED if the engine option forces the MFMA engine,
- * GLA_ERR_NULL for a NULL log_beta.
+ * Everything else as gla_fwd_layout (log_beta = 0 gives its result).  bf16 q, k, v with
+ * dk % 4 == 0, dv % 8 == 0, dk <= 40 and dv <= 80 run on the MFMA engine (chunk form with both
+ * decays factorised: the values are gated like the keys and carried as bf16 hi/lo pairs); every
+ * other element type and head size runs on the token-by-token fp32 engine.  The spans are
+ * chained by the carry kernel.  GLA_ERR_UNSUPPORTED if the engine option forces the MFMA engine
+ * onto a case it does not cover, GLA_ERR_NULL for a NULL log_beta.
  */
 int gla_fwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,
                   int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,

@@ -35,7 +35,7 @@ namespace gla {
 namespace {
 
 // LDS layout (byte offsets), sized by the padded head dimensions.
-template <int MODE, int NDK8, int NDV16>
+template <int MODE, int NDK8, int NDV16, bool BETA = false>
 struct Layout {
     static constexpr int kDkp = NDK8 * 8;                                 // channels incl. padding to 8
     static constexpr int kDvp = NDV16 * 16;                               // value columns incl. padding to 16
@@ -69,7 +69,16 @@ struct Layout {
     static constexpr int oLnW = oStLo + kSt;                              // float[kDvp] LayerNorm weight of this head
     static constexpr int oLnB = oLnW + kDvp * 4;                          // float[kDvp] LayerNorm bias
     static constexpr int oEndOut = oLnB + kDvp * 4;
-    static constexpr int kBytes = kOut ? oEndOut : oEndState;
+    static constexpr int oEndAlpha = kOut ? oEndOut : oEndState;
+    // two-sided gate only: raw log_beta rows (then exp(b^beta_j), the factor of output row j), the bf16 remainder
+    // of the gated values, and per value column the chunk's total beta decay and its log summed over the span
+    static constexpr int kLbStride = kDvp + 4;                            // fp32 per row of log_beta
+    static constexpr int oLb = oEndAlpha;
+    static constexpr int oVLo = oLb + kChunk * kLbStride * 4;
+    static constexpr int oGamB = oVLo + kV;                               // float[kDvp]
+    static constexpr int oLgB = oGamB + kDvp * 4;                         // float[kDvp]
+    static constexpr int oEndBeta = oLgB + kDvp * 4;
+    static constexpr int kBytes = BETA ? oEndBeta : oEndAlpha;
 };
 
 template <int N>
@@ -110,9 +119,13 @@ struct TileMap {
 // DEPTH = chunks of rows kept in flight from HBM (register sets; 2 only in the state pass).
 // FUSE = the gate prologue (gates from bf16 pre-activations) and, in the output pass, the optional epilogue.
 // ACC = the output pass adds its rows to the fp32 rows already in `out`.
-template <int MODE, int NDK8, int NDV16, int NW, int MINW, int DEPTH, bool FUSE, bool ACC, typename TOut>
+// BETA = two-sided gate alpha_t^T beta_t (Eq. (gate_gla_2)): with c_j = sum_{i<=j} log beta_i inside a chunk, the
+//        values are gated like the keys, v~_i = v_i exp(-c_i) (bf16 hi/lo), output row j is scaled by exp(c_j) and
+//        state column n by exp(c_C[n]) per chunk; the spans are chained by the carry kernel.
+template <int MODE, int NDK8, int NDV16, int NW, int MINW, int DEPTH, bool FUSE, bool ACC, typename TOut,
+          bool BETA = false>
 __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
-    using L = Layout<MODE, NDK8, NDV16>;
+    using L = Layout<MODE, NDK8, NDV16, BETA>;
     constexpr bool OUT = MODE == kModeOutput;
     constexpr int NTHR = NW * 64;
     constexpr int CHS = L::kChStride;
@@ -131,6 +144,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     static_assert(NTB <= 4 && (DEPTH + 1) * kChunk <= NTHR, "token maps: four buffers, first ones filled in one go");
     static_assert(16 * NCT <= CHS, "state tiles must fit the operand row");
     static_assert(!ACC || (OUT && !FUSE && sizeof(TOut) == 4), "accumulation: plain output pass, fp32 rows");
+    static_assert(!BETA || (!FUSE && !ACC), "two-sided gate: plain passes only");
+    constexpr int LBS = L::kLbStride;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int *s_tok = reinterpret_cast<int *>(smem + L::oTok);
@@ -147,6 +162,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     uint16_t *s_stlo = reinterpret_cast<uint16_t *>(smem + L::oStLo);
     float *s_lnw = reinterpret_cast<float *>(smem + L::oLnW);
     float *s_lnb = reinterpret_cast<float *>(smem + L::oLnB);
+    float *s_lb = reinterpret_cast<float *>(smem + L::oLb);          // BETA only, like the three below
+    uint16_t *s_vlo = reinterpret_cast<uint16_t *>(smem + L::oVLo);
+    float *s_gamb = reinterpret_cast<float *>(smem + L::oGamB);
+    float *s_lgb = reinterpret_cast<float *>(smem + L::oLgB);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -183,6 +202,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     const char *gk = static_cast<const char *>(p.k) + base_k * 2;
     const char *gv = static_cast<const char *>(p.v) + base_v * 2;
     const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + base_k * 4;
+    const char *glb = reinterpret_cast<const char *>(p.log_beta) + base_v * 4;
     const char *gz = static_cast<const char *>(p.z_gate) + base_k * 2;
     const char *grp = static_cast<const char *>(p.r_pre) + base_v * 2;
     const bool epilogue = FUSE && OUT && p.r_pre != nullptr;   // uniform
@@ -296,6 +316,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     u32x2 r_k[DEPTH][kF];
     u32x2 r_q[DEPTH][OUT ? kF : 1];
     u32x4 r_v[DEPTH][kVF];
+    f32x4 r_lb[DEPTH][BETA ? kVF : 1][2];   // log_beta of the same 8 columns as the v piece
 
     // Rows past the end of a ragged last chunk carry the token of a valid row in s_tok (so the loads
     // stay in bounds) and are zeroed when they are written to LDS.
@@ -315,8 +336,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             if constexpr (OUT) r_q[S][m] = *reinterpret_cast<const u32x2 *>(gq + e2);
         }
 #pragma unroll
-        for (int m = 0; m < kVF; ++m)
+        for (int m = 0; m < kVF; ++m) {
             r_v[S][m] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tok[fvrp[m] >> 8] * dv2 + 16u * (uint32_t)(fvrp[m] & 255));
+            if constexpr (BETA) {
+                const char *lbp = glb + 2u * ((uint32_t)tokg[fvrp[m] >> 8] * dv2 + 16u * (uint32_t)(fvrp[m] & 255));
+                r_lb[S][m][0] = *reinterpret_cast<const f32x4 *>(lbp);
+                r_lb[S][m][1] = *reinterpret_cast<const f32x4 *>(lbp + 16);
+            }
+        }
     };
 
     // ---- gate work of this wave: whole UW-channel units w, w+NW, ..., then single left-over channels ----
@@ -366,8 +393,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 }
             }
 #pragma unroll
-            for (int m = 0; m < kVF; ++m)
-                if ((fvrp[m] >> 8) >= nvalid) r_v[S][m] = u32x4{0, 0, 0, 0};
+            for (int m = 0; m < kVF; ++m) {
+                if ((fvrp[m] >> 8) >= nvalid) {
+                    r_v[S][m] = u32x4{0, 0, 0, 0};
+                    if constexpr (BETA) r_lb[S][m][0] = r_lb[S][m][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            }
         }
 #pragma unroll
         for (int m = 0; m < kF; ++m) {
@@ -379,9 +410,16 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             }
         }
 #pragma unroll
-        for (int m = 0; m < kVF; ++m)
-            if (tid + NTHR * m < kChunk * vpcs)
+        for (int m = 0; m < kVF; ++m) {
+            if (tid + NTHR * m < kChunk * vpcs) {
                 *reinterpret_cast<u32x4 *>(s_v + (fvrp[m] >> 8) * VS + 8 * (fvrp[m] & 255)) = r_v[S][m];
+                if constexpr (BETA) {
+                    float *lrow = s_lb + (fvrp[m] >> 8) * LBS + 8 * (fvrp[m] & 255);
+                    *reinterpret_cast<f32x4 *>(lrow) = r_lb[S][m][0];
+                    *reinterpret_cast<f32x4 *>(lrow + 4) = r_lb[S][m][1];
+                }
+            }
+        }
         // the rows of a later chunk start their trip from HBM into the set just emptied
         // (unconditional loads past the span: the clamped token map makes every lane read one row)
         if (UNCOND || chunk + DEPTH < nch) load_chunk(chunk + DEPTH, set_c);
@@ -510,6 +548,44 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     }
                 }
             }
+            if constexpr (BETA) {
+                // value side: 8-column units dealt round-robin; v~ = v exp(-c) as bf16 hi/lo, exp(c) left in
+                // place of the log_beta row, lane 63 holds the chunk's total
+                for (int c0 = 8 * w; c0 < dv; c0 += 8 * NW) {
+                    float cc[8];
+#pragma unroll
+                    for (int v4 = 0; v4 < 2; ++v4) {
+                        const f32x4 x = *reinterpret_cast<const f32x4 *>(s_lb + j * LBS + c0 + 4 * v4);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) cc[4 * v4 + i] = x[i] * kLog2e;
+                        wave_inclusive_scan4(cc[4 * v4], cc[4 * v4 + 1], cc[4 * v4 + 2], cc[4 * v4 + 3]);
+                    }
+                    const u32x4 vr = *reinterpret_cast<const u32x4 *>(s_v + j * VS + c0);
+                    u32x4 vh, vl;
+                    float ev[8];
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        SPLIT_PAIR(bf16_lo_as_float(vr[h]) * exp2_fast(fminf(-cc[2 * h], kMaxExp2)),
+                                   bf16_hi_as_float(vr[h]) * exp2_fast(fminf(-cc[2 * h + 1], kMaxExp2)),
+                                   vh[h], vl[h]);
+                        ev[2 * h] = exp2_fast(cc[2 * h]);
+                        ev[2 * h + 1] = exp2_fast(cc[2 * h + 1]);
+                    }
+                    *reinterpret_cast<u32x4 *>(s_v + j * VS + c0) = vh;
+                    *reinterpret_cast<u32x4 *>(s_vlo + j * VS + c0) = vl;
+                    if constexpr (OUT) {
+                        *reinterpret_cast<f32x4 *>(s_lb + j * LBS + c0) = f32x4{ev[0], ev[1], ev[2], ev[3]};
+                        *reinterpret_cast<f32x4 *>(s_lb + j * LBS + c0 + 4) = f32x4{ev[4], ev[5], ev[6], ev[7]};
+                    }
+                    if (lane == 63) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            s_gamb[c0 + i] = ev[i];
+                            if constexpr (!OUT) s_lgb[c0 + i] += cc[i];
+                        }
+                    }
+                }
+            }
         }
         __syncthreads();
 
@@ -539,6 +615,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             const uint16_t *krow_h = s_khi + (4 * g + tr_row) * CHS + tr_col;
             const uint16_t *krow_l = s_klo + (4 * g + tr_row) * CHS + tr_col;
             const uint16_t *vrow = s_v + (4 * g + tr_row) * VS + tr_col;
+            const uint16_t *vrow_l = s_vlo + (4 * g + tr_row) * VS + tr_col;   // BETA: remainder of the gated values
             u32x2 ukh[1][2][2], ukl[1][2][2];               // [0][32-token step][half]: shared by the wave's tiles
             auto load_state_k = [&](int buf, int i) {
                 const int ko = 16 * TM::ct(W, i);
@@ -551,15 +628,28 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 }
             };
             // S = diag(exp(b_C)) (S + K~^T V) on state tile i; b0, b1 = V fragments of the two 32-token steps
-            auto update_state = [&](int kb, int i, const u32x4 &b0, const u32x4 &b1) {
+            // (BETA: V~ hi with its remainders b0l, b1l, and column n of the tile also decays by exp(c_C[n]))
+            auto update_state = [&](int kb, int i, const u32x4 &b0, const u32x4 &b1, const u32x4 &b0l,
+                                    const u32x4 &b1l) {
                 f32x4 a = acc[i];
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const u32x4 b = ks == 0 ? b0 : b1;
-                    a = mfma(u32x4{ukh[kb][ks][0][0], ukh[kb][ks][0][1], ukh[kb][ks][1][0], ukh[kb][ks][1][1]}, b, a);
+                    const u32x4 kh = u32x4{ukh[kb][ks][0][0], ukh[kb][ks][0][1], ukh[kb][ks][1][0], ukh[kb][ks][1][1]};
+                    a = mfma(kh, b, a);
                     a = mfma(u32x4{ukl[kb][ks][0][0], ukl[kb][ks][0][1], ukl[kb][ks][1][0], ukl[kb][ks][1][1]}, b, a);
+                    if constexpr (BETA) {
+                        a = mfma(kh, ks == 0 ? b0l : b1l, a);
+                        a = mfma(u32x4{ukl[kb][ks][0][0], ukl[kb][ks][0][1], ukl[kb][ks][1][0], ukl[kb][ks][1][1]},
+                                 ks == 0 ? b0l : b1l, a);
+                    }
                 }
-                const f32x4 gm = *reinterpret_cast<const f32x4 *>(s_gam + 16 * TM::ct(W, i) + 4 * g);
+                f32x4 gm = *reinterpret_cast<const f32x4 *>(s_gam + 16 * TM::ct(W, i) + 4 * g);
+                if constexpr (BETA) {
+                    const float gbn = s_gamb[16 * TM::nt(W, i) + lm];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) gm[r] *= gbn;
+                }
 #pragma unroll
                 for (int r = 0; r < 4; ++r) a[r] *= gm[r];
                 acc[i] = a;
@@ -580,6 +670,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 u32x4 qfh[KS], qfl[KS];            // Q~ fragments of this wave's 16 output rows
                 u32x4 kfh[2][KS], kfl[2][KS];      // K~ fragments of two score tiles
                 u32x2 vt[2][NX][2];                // V fragments of the two 32-token steps
+                u32x2 vtl[2][BETA ? NX : 1][2];    // BETA: their remainders
                 u32x4 sth[2][NX], stl[2][NX];      // S_0 fragments of one 32-channel step, two buffers
                 u32x2 ph[2], pl[2];                // two score tiles as bf16 hi/lo (A operand of O += A V)
                 f32x4 o[NX];
@@ -599,10 +690,20 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     for (int x = 0; x < NX; ++x) {
                         vt[q32][x][0] = lds_read_tr(vrow + 32 * q32 * VS + 16 * x);
                         vt[q32][x][1] = lds_read_tr(vrow + (32 * q32 + 16) * VS + 16 * x);
+                        if constexpr (BETA) {
+                            vtl[q32][x][0] = lds_read_tr(vrow_l + 32 * q32 * VS + 16 * x);
+                            vtl[q32][x][1] = lds_read_tr(vrow_l + (32 * q32 + 16) * VS + 16 * x);
+                        }
                     }
                 };
                 auto v_frag = [&](int q32, int x) {
                     return u32x4{vt[q32][x][0][0], vt[q32][x][0][1], vt[q32][x][1][0], vt[q32][x][1][1]};
+                };
+                auto v_frag_lo = [&](int q32, int x) {   // (without BETA: unused by the callee)
+                    if constexpr (BETA)
+                        return u32x4{vtl[q32][x][0][0], vtl[q32][x][0][1], vtl[q32][x][1][0], vtl[q32][x][1][1]};
+                    else
+                        return v_frag(q32, x);
                 };
                 auto load_st = [&](int buf, int ks) {
 #pragma unroll
@@ -625,6 +726,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                         if (PT && ks == KS - 1) continue;
                         d = mfma(kfh[u][ks], qfl[ks], d);
                         d = mfma(kfl[u][ks], qfh[ks], d);
+                        if constexpr (BETA) d = mfma(kfl[u][ks], qfl[ks], d);
                     }
                     if (jt == IT) {
 #pragma unroll
@@ -643,6 +745,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                         const u32x4 b = v_frag(q32, x);
                         o[x] = mfma(b, ah, o[x]);
                         o[x] = mfma(b, al, o[x]);
+                        if constexpr (BETA) {
+                            o[x] = mfma(v_frag_lo(q32, x), ah, o[x]);
+                            o[x] = mfma(v_frag_lo(q32, x), al, o[x]);
+                        }
                     }
                 };
                 auto qs = [&](int buf, int ks) {
@@ -652,6 +758,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                         if (PT && ks == KS - 1) continue;
                         o[x] = mfma(sth[buf][x], qfl[ks], o[x]);
                         o[x] = mfma(stl[buf][x], qfh[ks], o[x]);
+                        if constexpr (BETA) o[x] = mfma(stl[buf][x], qfl[ks], o[x]);
                     }
                 };
                 // what the state update still has to read: its K~ operand, and the second 32 tokens of V when the
@@ -728,6 +835,18 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     qs(1, 1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                if constexpr (BETA) {
+                    // row j of the output carries exp(c_j) per value column
+                    const float *erow = s_lb + (16 * IT + lm) * LBS + 4 * g;
+#pragma unroll
+                    for (int x = 0; x < NX; ++x) {
+                        if (4 * g + 16 * x < dv) {
+                            const f32x4 e4 = *reinterpret_cast<const f32x4 *>(erow + 16 * x);
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) o[x][r] *= e4[r];
+                        }
+                    }
+                }
                 if constexpr (FUSE) {
                     if (epilogue) {
                         // Swish(r) * LN(o): a token's row is spread over the four lanes lm, lm+16, lm+32, lm+48
@@ -790,16 +909,23 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     }
                 }
 #pragma unroll
-                for (int i = 0; i < NTW; ++i) update_state(0, i, v_frag(0, TM::nt(W, i)), v_frag(1, TM::nt(W, i)));
+                for (int i = 0; i < NTW; ++i)
+                    update_state(0, i, v_frag(0, TM::nt(W, i)), v_frag(1, TM::nt(W, i)), v_frag_lo(0, TM::nt(W, i)),
+                                 v_frag_lo(1, TM::nt(W, i)));
             } else {
                 // state pass: K~ of the wave's row tile once, V of tile i+1 read while tile i is contracted
                 u32x2 uv[2][2][2];                              // [buffer][32-token step][half]
+                u32x2 uvl[BETA ? 2 : 1][2][2];                  // BETA: remainders of the gated values
                 auto load_state_v = [&](int buf, int i) {
                     const int vo = 16 * TM::nt(W, i);
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks) {
                         uv[buf][ks][0] = lds_read_tr(vrow + 32 * ks * VS + vo);
                         uv[buf][ks][1] = lds_read_tr(vrow + (32 * ks + 16) * VS + vo);
+                        if constexpr (BETA) {
+                            uvl[buf][ks][0] = lds_read_tr(vrow_l + 32 * ks * VS + vo);
+                            uvl[buf][ks][1] = lds_read_tr(vrow_l + (32 * ks + 16) * VS + vo);
+                        }
                     }
                 };
                 if constexpr (NTW > 0) {
@@ -811,8 +937,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 for (int i = 0; i < NTW; ++i) {
                     if (i + 1 < NTW) load_state_v((i + 1) & 1, i + 1);
                     const int bf = i & 1;
-                    update_state(0, i, u32x4{uv[bf][0][0][0], uv[bf][0][0][1], uv[bf][0][1][0], uv[bf][0][1][1]},
-                                 u32x4{uv[bf][1][0][0], uv[bf][1][0][1], uv[bf][1][1][0], uv[bf][1][1][1]});
+                    const u32x4 v0 = u32x4{uv[bf][0][0][0], uv[bf][0][0][1], uv[bf][0][1][0], uv[bf][0][1][1]};
+                    const u32x4 v1 = u32x4{uv[bf][1][0][0], uv[bf][1][0][1], uv[bf][1][1][0], uv[bf][1][1][1]};
+                    if constexpr (BETA)
+                        update_state(0, i, v0, v1,
+                                     u32x4{uvl[bf][0][0][0], uvl[bf][0][0][1], uvl[bf][0][1][0], uvl[bf][0][1][1]},
+                                     u32x4{uvl[bf][1][0][0], uvl[bf][1][0][1], uvl[bf][1][1][0], uvl[bf][1][1][1]});
+                    else
+                        update_state(0, i, v0, v1, v0, v1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -861,11 +993,17 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     }
     // the workspace keeps natural logarithms
     if (!OUT && tid < dk) p.ws_lgam[((size_t)bh * p.nspans + sp) * dk + tid] = s_lg[tid] * kLn2;
+    if constexpr (BETA && !OUT) {
+        if (tid < dv) p.ws_lgam_b[((size_t)bh * p.nspans + sp) * dv + tid] = s_lgb[tid] * kLn2;
+    }
 }
 
-template <int MODE, int NDK8, int NDV16, int DEPTH, bool FUSE, bool ACC, typename TOut>
+template <int MODE, int NDK8, int NDV16, int DEPTH, bool FUSE, bool ACC, typename TOut, bool BETA>
 hipError_t launch_depth(const Params &p, hipStream_t stream) {
-    using L = Layout<MODE, NDK8, NDV16>;
+    using L = Layout<MODE, NDK8, NDV16, BETA>;
+    if constexpr (L::kBytes > 160 * 1024) {
+        return hipErrorInvalidConfiguration;   // (two-sided gate at the largest head sizes: mfma_engine_supports says no)
+    } else {
     // The state pass is light on registers and runs best with 8 waves (4 per SIMD at two work-groups per compute
     // unit); the output pass needs the 256-register budget of 4-wave groups for its operand batches.
     constexpr int NW = (MODE == kModeState) ? 8 : 4;
@@ -873,7 +1011,7 @@ hipError_t launch_depth(const Params &p, hipStream_t stream) {
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int kWavesPerSimd = kGroupsPerCu * NW / 4;
     constexpr int MINW = kWavesPerSimd >= 4 ? 4 : (kWavesPerSimd >= 2 ? 2 : 1);
-    auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, NW, MINW, DEPTH, FUSE, ACC, TOut>;
+    auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, NW, MINW, DEPTH, FUSE, ACC, TOut, BETA>;
     static bool configured[kMaxDevices] = {};  // per instantiation and device
     {
         hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), L::kBytes, configured);
@@ -883,20 +1021,27 @@ hipError_t launch_depth(const Params &p, hipStream_t stream) {
     dim3 grid((unsigned)(p.B * p.H * spans)), block(NW * 64);
     hipLaunchKernelGGL(kernel, grid, block, L::kBytes, stream, p);
     return hipGetLastError();
+    }
 }
 
-template <int MODE, int NDK8, int NDV16, bool FUSE, bool ACC, typename TOut>
+template <int MODE, int NDK8, int NDV16, bool FUSE, bool ACC, typename TOut, bool BETA = false>
 hipError_t launch_one(const Params &p, hipStream_t stream) {
     // Two chunks of rows in flight pay off in the state pass (short chunk period, registers to spare at the
     // smaller head sizes) once a span is long enough to amortise the second set's start-up.
     if constexpr (MODE == kModeState && NDK8 <= 5 && NDV16 <= 5) {
-        if (p.span_len >= 4 * kChunk) return launch_depth<MODE, NDK8, NDV16, 2, FUSE, ACC, TOut>(p, stream);
+        if (!BETA && p.span_len >= 4 * kChunk)
+            return launch_depth<MODE, NDK8, NDV16, 2, FUSE, ACC, TOut, false>(p, stream);
     }
-    return launch_depth<MODE, NDK8, NDV16, 1, FUSE, ACC, TOut>(p, stream);
+    return launch_depth<MODE, NDK8, NDV16, 1, FUSE, ACC, TOut, BETA>(p, stream);
 }
 
 template <int MODE, int NDK8, int NDV16>
 hipError_t launch_dt(const Params &p, hipStream_t stream) {
+    if (p.log_beta != nullptr) {   // two-sided gate (the host keeps it apart from the prologue and the accumulation)
+        if (MODE == kModeOutput && p.out_dtype == GLA_DT_BF16)
+            return launch_one<MODE, NDK8, NDV16, false, false, uint16_t, true>(p, stream);
+        return launch_one<MODE, NDK8, NDV16, false, false, float, true>(p, stream);
+    }
     if (p.z_gate != nullptr) {
         if (MODE == kModeOutput && p.out_dtype == GLA_DT_BF16)
             return launch_one<MODE, NDK8, NDV16, true, false, uint16_t>(p, stream);
@@ -921,9 +1066,10 @@ hipError_t launch_mode(const Params &p, hipStream_t stream) {
 }  // namespace
 
 bool mfma_engine_supports(const Params &p) {
+    // two-sided gate: the extra rows (log_beta, remainder of the gated values) fit the LDS up to dk = 40, dv = 80
+    if (p.log_beta != nullptr && (p.dk > 40 || p.dv > 80)) return false;
     // 32-bit byte offsets inside the view of one (batch, head)
     const long long slab = (long long)p.T * (p.st_k > p.st_v ? p.st_k : p.st_v) * 4;
-    if (p.log_beta != nullptr) return false;   // the chunk form here factorises the key-side decay only
     return p.qkv_dtype == GLA_DT_BF16 && p.dk % 4 == 0 && p.dv % 8 == 0 && p.dk <= kMaxDk && p.dv <= kMaxDv &&
            slab < (1LL << 31);
 }

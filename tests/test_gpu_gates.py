@@ -43,6 +43,40 @@ def test_gates_parity_several_spans_ragged(dtype, scan_dir):
     assert _err(fin.cpu().numpy(), rf) < TOL_F32
 
 
+@pytest.mark.parametrize("dk,dv", [(8, 16), (32, 64), (36, 72), (40, 80), (64, 128)])
+@pytest.mark.parametrize("scan_dir", [0, 3])
+def test_gates_mfma_engine_sizes(dk, dv, scan_dir):
+    """bf16 inputs with dk % 4 == 0, dv % 8 == 0, dk <= 40 and dv <= 80 run on the MFMA engine (chunk form with both
+    decays factorised), larger heads on the token-by-token engine; seven chunks with a ragged last one, chained by
+    the carry kernel."""
+    B, H, gh, gw = 2, 2, 19, 23
+    d = gi.make_gate_inputs(B, H, gh * gw, dk, dv, "bf16", seed=41 + dk)
+    q, k, v, la, lb = _dev(d, "bf16")
+    out, fin = gla.gla_fwd_gates(q, k, v, la, lb, gh, gw, scan_dir)
+    torch.cuda.synchronize()
+    ro, rf = og.gla_fwd_gates(d["q"], d["k"], d["v"], d["log_alpha"], d["log_beta"], gh, gw, scan_dir)
+    assert _err(out.cpu().numpy(), ro) < TOL_F32
+    assert _err(fin.cpu().numpy(), rf) < TOL_F32
+
+
+def test_gates_engines_agree_and_single_span():
+    """One span (T <= 256: no carry kernel, final state from the output pass) and the token-by-token engine on the
+    same inputs."""
+    B, H, gh, gw, dk, dv = 1, 3, 10, 20, 36, 72
+    d = gi.make_gate_inputs(B, H, gh * gw, dk, dv, "bf16", seed=51)
+    q, k, v, la, lb = _dev(d, "bf16")
+    ro, rf = og.gla_fwd_gates(d["q"], d["k"], d["v"], d["log_alpha"], d["log_beta"], gh, gw, 1)
+    for engine in (gla.ENGINE_AUTO, gla.ENGINE_RECURRENT, gla.ENGINE_MFMA):
+        gla.gla_set_option(gla.OPT_ENGINE, engine)
+        try:
+            out, fin = gla.gla_fwd_gates(q, k, v, la, lb, gh, gw, 1)
+            torch.cuda.synchronize()
+        finally:
+            gla.gla_set_option(gla.OPT_ENGINE, gla.ENGINE_AUTO)
+        assert _err(out.cpu().numpy(), ro) < TOL_F32
+        assert _err(fin.cpu().numpy(), rf) < TOL_F32
+
+
 def test_gates_bf16_rows_token_major_initial_state():
     B, H, gh, gw, dk, dv = 2, 4, 16, 20, 32, 64
     T = gh * gw
@@ -83,8 +117,8 @@ def test_gates_headline_shape():
     assert _err(fin.cpu().numpy(), rf) < TOL_F32
 
 
-def test_gates_reject_forced_mfma_engine_and_null():
-    d = gi.make_gate_inputs(1, 1, 64, 32, 64, "bf16", seed=1)
+def test_gates_forced_mfma_engine_rejects_what_it_cannot_run():
+    d = gi.make_gate_inputs(1, 1, 64, 20, 33, "bf16", seed=1)      # dv not a multiple of 8
     q, k, v, la, lb = _dev(d, "bf16")
     gla.gla_set_option(gla.OPT_ENGINE, gla.ENGINE_MFMA)
     try:
