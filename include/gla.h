@@ -168,8 +168,8 @@ int gla_fwd_layout(const void *q, const void *k, const void *v, const float *log
  * Everything else as gla_fwd_layout (log_beta = 0 gives its result).  bf16 q, k, v with
  * dk % 4 == 0, dv % 8 == 0, dk <= 40 and dv <= 80 run on the MFMA engine (chunk form with both
  * decays factorised: the values are gated like the keys and carried as bf16 hi/lo pairs); every
- * other element type and head size runs on the token-by-token fp32 engine.  The spans are
- * chained by the carry kernel.  GLA_ERR_UNSUPPORTED if the engine option forces the MFMA engine
+ * other element type and head size runs on the token-by-token fp32 engine.
+ * GLA_ERR_UNSUPPORTED if the engine option forces the MFMA engine
  * onto a case it does not cover, GLA_ERR_NULL for a NULL log_beta.
  */
 int gla_fwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,

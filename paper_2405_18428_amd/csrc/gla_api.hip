@@ -269,8 +269,7 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
         if (events) (void)hipEventRecord(events->ev[i], stream);
     };
 
-    // (the in-pass chaining knows the key-side decay only: with log_beta the carry kernel chains the spans)
-    p.chain_in_output = use_mfma && p.nspans > 1 && p.log_beta == nullptr &&
+    p.chain_in_output = use_mfma && p.nspans > 1 &&
                         (g_opt_carry == GLA_CARRY_IN_OUTPUT_PASS ||
                          (g_opt_carry == GLA_CARRY_AUTO && p.nspans <= kMaxChainedSpans));
 

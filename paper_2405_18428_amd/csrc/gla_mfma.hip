@@ -121,7 +121,7 @@ struct TileMap {
 // ACC = the output pass adds its rows to the fp32 rows already in `out`.
 // BETA = two-sided gate alpha_t^T beta_t (Eq. (gate_gla_2)): with c_j = sum_{i<=j} log beta_i inside a chunk, the
 //        values are gated like the keys, v~_i = v_i exp(-c_i) (bf16 hi/lo), output row j is scaled by exp(c_j) and
-//        state column n by exp(c_C[n]) per chunk; the spans are chained by the carry kernel.
+//        state column n by exp(c_C[n]) per chunk.
 template <int MODE, int NDK8, int NDV16, int NW, int MINW, int DEPTH, bool FUSE, bool ACC, typename TOut,
           bool BETA = false>
 __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             constexpr int kV4 = (L::kDkp * L::kDvp / 4 + NTHR - 1) / NTHR;  // float4 per thread
             constexpr int kBudget = MINW >= 4 ? 16 : 32;                    // float4 in flight: 64 or 128 registers of U
             constexpr int kRun = kBudget / kV4 > 0 ? kBudget / kV4 : 1;     // spans in flight
-            chain_span_states<NTHR, kV4, kRun>(p, bh, sp, tid, reinterpret_cast<float *>(smem));
+            chain_span_states<NTHR, kV4, kRun, BETA>(p, bh, sp, tid, reinterpret_cast<float *>(smem));
         }
         __syncthreads();
         if (chain) {

@@ -128,28 +128,35 @@ __device__ inline void wave_inclusive_scan4(float &a, float &b, float &c, float 
 // summed does not change an fp32 sum.  With the gates of the DiG configurations a span of a few hundred tokens
 // decays by more than that, so one or two spans are read whatever the span count.
 // The result is written to s_chain[dk * dv] (LDS, row-major [dk][dv]).
-template <int NTHR, int kV4, int kRun>
+// BETA (two-sided gate): element (c, n) also decays by the value-side sums of the spans (ws_lgam_b, per column n);
+// the stopping rule stays the key-side one (the value side only makes the skipped terms smaller).
+template <int NTHR, int kV4, int kRun, bool BETA = false>
 __device__ inline void chain_span_states(const Params &p, int bh, int sp, int tid, float *s_chain) {
     const int dk = p.dk, dv = p.dv, ne = dk * dv, ne4 = ne >> 2;
     const float *ub = p.ws_state + (size_t)bh * p.nspans * ne;
     const float *lb = p.ws_lgam + (size_t)bh * p.nspans * dk;
-    int e4[kV4], ch[kV4];
+    const float *lbb = BETA ? p.ws_lgam_b + (size_t)bh * p.nspans * dv : nullptr;
+    int e4[kV4], ch[kV4], col[kV4];
 #pragma unroll
     for (int m = 0; m < kV4; ++m) {
         e4[m] = min(tid + NTHR * m, ne4 - 1);  // threads past the end repeat the last piece
         ch[m] = (4 * e4[m]) / dv;
+        col[m] = 4 * e4[m] - ch[m] * dv;       // first of the piece's four value columns (dv % 4 == 0)
     }
     f32x4 st[kV4];
     float wl[kV4];      // log2 of the weight of the next span to add
+    f32x4 wb[BETA ? kV4 : 1];   // BETA: its value-side part per column
 #pragma unroll
     for (int m = 0; m < kV4; ++m) {
         st[m] = f32x4{0.f, 0.f, 0.f, 0.f};
         wl[m] = 0.f;
+        if constexpr (BETA) wb[m] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     auto run = [&](auto n_c, int r_hi) {   // spans r_hi, r_hi - 1, ..., r_hi - n + 1 (those below 0 do not exist)
         constexpr int N = decltype(n_c)::value;
         f32x4 u[N][kV4];
         float lg[N][kV4];
+        f32x4 lgb[BETA ? N : 1][BETA ? kV4 : 1];
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             const int r = max(r_hi - i, 0);     // loads past the first span repeat it
@@ -157,6 +164,7 @@ __device__ inline void chain_span_states(const Params &p, int bh, int sp, int ti
             for (int m = 0; m < kV4; ++m) {
                 u[i][m] = *reinterpret_cast<const f32x4 *>(ub + (size_t)r * ne + 4 * e4[m]);
                 lg[i][m] = lb[r * dk + ch[m]];
+                if constexpr (BETA) lgb[i][m] = *reinterpret_cast<const f32x4 *>(lbb + r * dv + col[m]);
             }
         }
 #pragma unroll
@@ -164,9 +172,17 @@ __device__ inline void chain_span_states(const Params &p, int bh, int sp, int ti
             if (r_hi - i >= 0) {
 #pragma unroll
                 for (int m = 0; m < kV4; ++m) {
-                    const float wgt = exp2_fast(wl[m]);
+                    if constexpr (BETA) {
 #pragma unroll
-                    for (int x = 0; x < 4; ++x) st[m][x] = fmaf(wgt, u[i][m][x], st[m][x]);
+                        for (int x = 0; x < 4; ++x) {
+                            st[m][x] = fmaf(exp2_fast(wl[m] + wb[m][x]), u[i][m][x], st[m][x]);
+                            wb[m][x] += lgb[i][m][x] * kLog2e;
+                        }
+                    } else {
+                        const float wgt = exp2_fast(wl[m]);
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) st[m][x] = fmaf(wgt, u[i][m][x], st[m][x]);
+                    }
                     wl[m] += lg[i][m] * kLog2e;    // the workspace keeps natural logarithms
                 }
             }
@@ -191,9 +207,12 @@ __device__ inline void chain_span_states(const Params &p, int bh, int sp, int ti
 #pragma unroll
         for (int m = 0; m < kV4; ++m) {
             const f32x4 s0 = *reinterpret_cast<const f32x4 *>(p.initial_state + (size_t)bh * ne + 4 * e4[m]);
-            const float wgt = exp2_fast(wl[m]);
 #pragma unroll
-            for (int x = 0; x < 4; ++x) st[m][x] = fmaf(wgt, s0[x], st[m][x]);
+            for (int x = 0; x < 4; ++x) {
+                float wlx = wl[m];
+                if constexpr (BETA) wlx += wb[m][x];
+                st[m][x] = fmaf(exp2_fast(wlx), s0[x], st[m][x]);
+            }
         }
     }
 #pragma unroll

@@ -59,6 +59,26 @@ def test_gates_mfma_engine_sizes(dk, dv, scan_dir):
     assert _err(fin.cpu().numpy(), rf) < TOL_F32
 
 
+@pytest.mark.parametrize("carry", ["kernel", "in_output"])
+def test_gates_both_ways_of_chaining_the_spans(carry):
+    """The spans are chained by the carry kernel or by the output pass itself; both multiply the two decays."""
+    B, H, gh, gw, dk, dv = 1, 2, 30, 40, 36, 72          # 1200 tokens: 19 chunks
+    d = gi.make_gate_inputs(B, H, gh * gw, dk, dv, "bf16", seed=61)
+    q, k, v, la, lb = _dev(d, "bf16")
+    s0 = np.random.default_rng(7).standard_normal((B, H, dk, dv)).astype(np.float32)
+    ro, rf = og.gla_fwd_gates(d["q"], d["k"], d["v"], d["log_alpha"], d["log_beta"], gh, gw, 2, initial_state=s0)
+    gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_KERNEL if carry == "kernel" else gla.CARRY_IN_OUTPUT_PASS)
+    gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 2)
+    try:
+        out, fin = gla.gla_fwd_gates(q, k, v, la, lb, gh, gw, 2, initial_state=torch.from_numpy(s0).cuda())
+        torch.cuda.synchronize()
+    finally:
+        gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_AUTO)
+        gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 0)
+    assert _err(out.cpu().numpy(), ro) < TOL_F32
+    assert _err(fin.cpu().numpy(), rf) < TOL_F32
+
+
 def test_gates_engines_agree_and_single_span():
     """One span (T <= 256: no carry kernel, final state from the output pass) and the token-by-token engine on the
     same inputs."""
