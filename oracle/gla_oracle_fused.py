@@ -63,3 +63,19 @@ def gla_fused(q, k, v, z, tau, r_pre, ln_weight, ln_bias, ln_eps, grid_h, grid_w
     if r_pre is None:
         return o, fin
     return swish(r_pre) * layer_norm_heads(o, ln_weight, ln_bias, ln_eps), fin
+
+
+def gla_fused_gates(q, k, v, z_alpha, z_beta, tau, r_pre, ln_weight, ln_bias, ln_eps, grid_h, grid_w,
+                    scan_dir=gla_oracle.SCAN_ROW_FWD):
+    """The whole mixer of Sec. 3.1 up to the projection W_O: both gates from their pre-activations
+    (Eq. (gate_gla): alpha = sigmoid(z_alpha)^(1/tau); Eq. (gate_gla_2): beta = sigmoid(z_beta)^(1/tau)), the recurrence
+    with G_t = alpha_t^T beta_t (Eq. (attn_gla) rows 1-3) and, if ``r_pre`` is given, Swish(r) * LN(o) (rows 4-5).
+
+    Returns (y [B,H,T,dv], final_state [B,H,dk,dv]) in float64.
+    """
+    from . import gla_oracle_gates
+    o, fin = gla_oracle_gates.gla_fwd_gates(q, k, v, log_alpha_from_z(z_alpha, tau), log_alpha_from_z(z_beta, tau),
+                                            grid_h, grid_w, scan_dir)
+    if r_pre is None:
+        return o, fin
+    return swish(r_pre) * layer_norm_heads(o, ln_weight, ln_bias, ln_eps), fin

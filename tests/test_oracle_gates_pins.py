@@ -108,3 +108,34 @@ def test_column_scans_are_row_scans_of_the_transposed_grid(d):
     ot, ft = og.gla_fwd_gates(tr(q), tr(k), tr(v), tr(la), tr(lb), gw, gh, d - 2)
     np.testing.assert_allclose(tr(o), ot, rtol=1e-12, atol=1e-12)
     np.testing.assert_allclose(f, ft, rtol=1e-12, atol=1e-12)
+
+
+def test_fused_gates_two_tokens_by_hand():
+    """dk = 1, dv = 2, two tokens, tau = 1, every step written out: gates sigmoid(z), state, output, LayerNorm over
+    the two value columns (mean of two numbers, variance ((a-b)/2)^2), Swish gate."""
+    from oracle import gla_oracle_fused as fo
+    q = np.array([[[[2.0], [3.0]]]]); k = np.array([[[[1.0], [0.5]]]])
+    v = np.array([[[[1.0, -1.0], [2.0, 4.0]]]])
+    za = np.array([[[[0.3], [np.log(3.0)]]]])                 # alpha_2 = 3/4
+    zb = np.array([[[[0.1, 0.2], [0.0, np.log(1.0 / 3.0)]]]])  # beta_2 = (1/2, 1/4)
+    r = np.array([[[[1.0, 2.0], [0.5, -1.0]]]])
+    y, fin = fo.gla_fused_gates(q, k, v, za, zb, 1.0, r, None, None, 0.0, 1, 2, 0)
+    # token 1: S = k v = (1, -1), o = 2 S = (2, -2); token 2: S = 3/4 (1/2, 1/4) * (1, -1) + 0.5 (2, 4)
+    s2 = np.array([0.75 * 0.5 * 1.0 + 1.0, 0.75 * 0.25 * -1.0 + 2.0])
+    np.testing.assert_allclose(fin[0, 0, 0], s2, rtol=1e-14)
+    o1, o2 = np.array([2.0, -2.0]), 3.0 * s2
+    sw = lambda x: x / (1.0 + np.exp(-x))
+    ln = lambda o: (o - o.mean()) / abs((o[0] - o[1]) / 2.0)      # eps = 0: a two-entry row normalises to (+-1)
+    np.testing.assert_allclose(y[0, 0, 0], sw(r[0, 0, 0]) * ln(o1), rtol=1e-13)
+    np.testing.assert_allclose(y[0, 0, 1], sw(r[0, 0, 1]) * ln(o2), rtol=1e-13)
+
+
+def test_fused_gates_large_negative_z_beta_forgets_the_past():
+    """beta -> 0 on every column wipes the previous state: each output is q_t (k_t^T v_t)."""
+    from oracle import gla_oracle_fused as fo
+    q, k, v, la, lb = _rand(1, 1, 2, 3, 3, 2, 9)
+    z_a = np.zeros_like(la)
+    z_b = np.full_like(lb, -800.0)
+    o, _ = fo.gla_fused_gates(q, k, v, z_a, z_b, 1.0, None, None, None, 0.0, 2, 3, 0)
+    expect = np.einsum("bhtc,bhtc->bht", q, k)[..., None] * v
+    np.testing.assert_allclose(o, expect, rtol=1e-12, atol=1e-12)
