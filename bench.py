@@ -167,16 +167,26 @@ def bench_multi(args, cfg, d, gla, gi, torch, np, dirs):
 
 
 def bench_gates(args, cfg, gla, gi, torch, np):
-    """gla_fwd_gates (two-sided gate alpha_t^T beta_t) at the workload's shape; token-by-token fp32 engine."""
+    """gla_fwd_gates (two-sided gate alpha_t^T beta_t) at the workload's shape, or (--pass fusedgates)
+    gla_fwd_fused_gates: both gates from bf16 pre-activations plus the Swish / LayerNorm epilogue."""
     dev = torch.device("cuda:0")
     B, H, T, dk, dv = cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv
-    d = gi.make_gate_inputs(B, H, T, dk, dv, cfg.dtype, cfg.seed, cfg.z_mean)
+    fused = args.which == "fusedgates"
     bf16 = cfg.dtype == "bf16"
-    if bf16:
-        host = [torch.from_numpy(d[n + "_bits"].view(np.int16)).view(torch.bfloat16) for n in ("q", "k", "v")]
+    if fused:
+        d = gi.make_fused_gate_inputs(B, H, T, dk, dv, cfg.dtype, cfg.seed, cfg.z_mean)
+        names = ("q", "k", "v", "z", "zb", "r")
     else:
-        host = [torch.from_numpy(d[n]) for n in ("q", "k", "v")]
-    host += [torch.from_numpy(d["log_alpha"]), torch.from_numpy(d["log_beta"])]
+        d = gi.make_gate_inputs(B, H, T, dk, dv, cfg.dtype, cfg.seed, cfg.z_mean)
+        names = ("q", "k", "v")
+    if bf16:
+        host = [torch.from_numpy(d[n + "_bits"].view(np.int16)).view(torch.bfloat16) for n in names]
+    else:
+        host = [torch.from_numpy(d[n]) for n in names]
+    if fused:
+        lnw, lnb = torch.from_numpy(d["ln_w"]).to(dev), torch.from_numpy(d["ln_b"]).to(dev)
+    else:
+        host += [torch.from_numpy(d["log_alpha"]), torch.from_numpy(d["log_beta"])]
     qdt = gla.DT_BF16 if bf16 else gla.DT_F32
     ws_bytes = gla.gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
     sets = []
@@ -184,6 +194,10 @@ def bench_gates(args, cfg, gla, gi, torch, np):
         sets.append([t.to(dev) for t in host] + [torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)])
 
     def step(i):
+        if fused:
+            q, k, v, z, zb, r, ws = sets[i % len(sets)]
+            return gla.gla_fwd_fused_gates(q, k, v, z, zb, 16.0, cfg.grid_h, cfg.grid_w, args.scan, r_pre=r,
+                                           ln_weight=lnw, ln_bias=lnb, ln_eps=1e-5, workspace=ws)
         q, k, v, la, lb, ws = sets[i % len(sets)]
         return gla.gla_fwd_gates(q, k, v, la, lb, cfg.grid_h, cfg.grid_w, args.scan, workspace=ws)
 
@@ -196,24 +210,33 @@ def bench_gates(args, cfg, gla, gi, torch, np):
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     qb = 2 if bf16 else 4
-    alg_bytes = (2 * dk * qb + dk * 4 + dv * qb + dv * 4 + dv * 4) * B * H * T   # q, k, log_alpha, v, log_beta, out
+    if fused:
+        alg_bytes = (3 * dk * qb + 3 * dv * qb + dv * 4) * B * H * T    # q, k, z_alpha; v, z_beta, r; y
+    else:
+        alg_bytes = (2 * dk * qb + dk * 4 + dv * qb + dv * 4 + dv * 4) * B * H * T   # q, k, log_alpha, v, log_beta, out
     alg_flops = 5 * dk * dv * B * H * T      # per state element and token: gate product, decay FMA, k*v, read FMA
     achieved = alg_flops / (ms * 1e-3) / 1e12
     result = {
-        "metric": "GLA fwd with the two-sided gate, tokens/s at DiG-XL/2 shape T=16384",
+        "metric": ("GLA fwd with both gates from pre-activations and the output epilogue" if fused else
+                   "GLA fwd with the two-sided gate") + ", tokens/s at DiG-XL/2 shape T=16384",
         "value": round(B * T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name} + log_beta: B={B} H={H} T={T} ({cfg.grid_h}x{cfg.grid_w}) dk={dk} dv={dv} "
-                               f"{cfg.dtype} q/k/v, fp32 gates, fp32 out, scan {args.scan}", "buffer_sets": len(sets)},
+        "config": {"workload": f"{cfg.name} + {'z_beta, r' if fused else 'log_beta'}: B={B} H={H} T={T} ({cfg.grid_h}x{cfg.grid_w}) dk={dk} dv={dv} "
+                               f"{cfg.dtype} q/k/v, {cfg.dtype + ' gate pre-activations' if fused else 'fp32 gates'}, fp32 out, "
+                               f"scan {args.scan}", "buffer_sets": len(sets)},
         "roofline": {"bound": "alu", "kernel": "whole_call", "achieved": round(achieved, 2), "peak": 157.3,
                      "unit": "TFLOP/s", "frac": round(achieved / 157.3, 4), "traffic": None,
                      "algorithmic_flops": alg_flops, "algorithmic_bytes": alg_bytes, "kernel_ms": round(ms, 5)},
     }
     if not args.no_check:
-        from oracle import gla_oracle_gates
-        ref, _ = gla_oracle_gates.gla_fwd_gates(d["q"], d["k"], d["v"], d["log_alpha"], d["log_beta"],
-                                                cfg.grid_h, cfg.grid_w, args.scan)
+        from oracle import gla_oracle_gates, gla_oracle_fused
+        if fused:
+            ref, _ = gla_oracle_fused.gla_fused_gates(d["q"], d["k"], d["v"], d["z"], d["zb"], 16.0, d["r"], d["ln_w"],
+                                                      d["ln_b"], 1e-5, cfg.grid_h, cfg.grid_w, args.scan)
+        else:
+            ref, _ = gla_oracle_gates.gla_fwd_gates(d["q"], d["k"], d["v"], d["log_alpha"], d["log_beta"],
+                                                    cfg.grid_h, cfg.grid_w, args.scan)
         got, _ = step(0)
         torch.cuda.synchronize()
         rms = float(np.sqrt(np.mean(ref ** 2)))
@@ -372,13 +395,14 @@ def main():
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated over (1 = cache-warm)")
     ap.add_argument("--chunks-per-span", type=int, default=0)
     ap.add_argument("--engine", type=int, default=0)
-    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "train", "fused", "bidir", "4dir", "srem", "gates"],
+    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "train", "fused", "bidir", "4dir", "srem", "gates", "fusedgates"],
                     help="fwd: the forward hot path (the headline); bwd: gla_bwd on the same workload; "
                          "train: gla_fwd_ex followed by gla_bwd_reuse; "
                          "fused: gla_fwd_fused (gate prologue, Swish/LayerNorm epilogue) on the same workload; "
                          "bidir / 4dir: gla_fwd_multi over scan orders (0, 1) / (0, 1, 2, 3); "
                          "srem: gla_srem_dwconv on the workload's token matrix; "
-                         "gates: gla_fwd_gates (two-sided gate) on the same workload plus a log_beta tensor")
+                         "gates: gla_fwd_gates (two-sided gate) on the same workload plus a log_beta tensor; "
+                         "fusedgates: gla_fwd_fused_gates (both gates from pre-activations, Swish/LayerNorm epilogue)")
     ap.add_argument("--layout", default="bhtd", choices=["bhtd", "bthd"],
                     help="memory order of q, k, v, log_alpha, out: [B,H,T,d] (the headline) or [B,T,H,d]")
     ap.add_argument("--reuse-fwd", action="store_true",
@@ -418,7 +442,7 @@ def main():
     if args.which == "fused":
         bench_fused(args, cfg, gla, gi, torch, np)
         return
-    if args.which == "gates":
+    if args.which in ("gates", "fusedgates"):
         bench_gates(args, cfg, gla, gi, torch, np)
         return
     if args.which == "srem":

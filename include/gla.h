@@ -295,6 +295,21 @@ int gla_fwd_fused(const void *q, const void *k, const void *v, const void *z_alp
                   int qkv_dtype, int out_dtype, void *out, float *final_state,
                   void *workspace, size_t workspace_bytes, gla_stream_t stream);
 
+/*
+ * gla_fwd_fused_gates - gla_fwd_fused with the value-side gate as well, also from its
+ * pre-activation (Eq. (gate_gla_2): beta = sigmoid(z_beta)^(1/tau), same temperature):
+ * the mixer of Sec. 3.1 from the projections' outputs to the input of W_O in one call.
+ *
+ *   z_beta      DEVICE, qkv_dtype [B,H,T,dv]: X W_beta + b_beta, 16-byte aligned          (read)
+ *
+ * Everything else as gla_fwd_fused; engines as gla_fwd_gates.  GLA_ERR_NULL for a NULL z_beta.
+ */
+int gla_fwd_fused_gates(const void *q, const void *k, const void *v, const void *z_alpha, const void *z_beta, float tau,
+                        const void *r_pre, const float *ln_weight, const float *ln_bias, float ln_eps,
+                        int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                        int qkv_dtype, int out_dtype, void *out, float *final_state,
+                        void *workspace, size_t workspace_bytes, gla_stream_t stream);
+
 /* Bytes of workspace gla_fwd_ex / gla_fwd_layout need for this problem (an upper bound over all
  * launch plans, so it does not depend on tuning options).  0 on invalid sizes. */
 size_t gla_fwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);

@@ -74,6 +74,9 @@ def load_library():
     lib.gla_fwd_fused.restype = i
     lib.gla_fwd_fused.argtypes = [vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, ctypes.c_float] + shape + \
         [i, i, vp, vp, vp, sz, vp]
+    lib.gla_fwd_fused_gates.restype = i
+    lib.gla_fwd_fused_gates.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, ctypes.c_float] + shape + \
+        [i, i, vp, vp, vp, sz, vp]
     lib.gla_bwd_workspace_bytes.restype = sz
     lib.gla_bwd_workspace_bytes.argtypes = [i] * 6
     lib.gla_fwd_timed.restype = i
@@ -337,13 +340,17 @@ def gla_fwd_multi(q, k, v, log_alpha, grid_h, grid_w, scan_dirs=(SCAN_ROW_FWD, S
 
 def gla_fwd_fused(q, k, v, z_alpha, tau, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, r_pre=None, ln_weight=None,
                   ln_bias=None, ln_eps=1e-5, out_dtype=None, want_final_state=True, out=None, final_state=None,
-                  workspace=None, stream=None):
+                  workspace=None, stream=None, _z_beta=None):
     """Forward pass with the gates taken from their pre-activations (``log_alpha = logsigmoid(z_alpha) / tau``) and,
     if ``r_pre`` is given, ``Swish(r_pre) * LayerNorm_head(o)`` stored instead of ``o``.  q, k, v, z_alpha, r_pre
     share one element type; ln_weight / ln_bias are fp32 [H, dv] or None."""
     torch = _torch()
     lib = load_library()
     tensors = [("q", q), ("k", k), ("v", v), ("z_alpha", z_alpha)] + ([("r_pre", r_pre)] if r_pre is not None else [])
+    if _z_beta is not None:
+        tensors.append(("z_beta", _z_beta))
+        if _z_beta.shape != v.shape:
+            raise ValueError("z_beta must have the shape of v")
     for name, t in tensors:
         if not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
             raise ValueError(f"{name} must be a contiguous 4-d GPU tensor")
@@ -369,13 +376,23 @@ def gla_fwd_fused(q, k, v, z_alpha, tau, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, 
         nbytes = gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
         workspace = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=q.device)
     ptr = lambda t: t.data_ptr() if t is not None else None
+    tail = (ptr(r_pre), ptr(ln_weight), ptr(ln_bias), float(ln_eps), B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt,
+            _dt(out), out.data_ptr(), ptr(final_state), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
     with torch.cuda.device(q.device):
-        _check(lib.gla_fwd_fused(q.data_ptr(), k.data_ptr(), v.data_ptr(), z_alpha.data_ptr(), float(tau),
-                                 ptr(r_pre), ptr(ln_weight), ptr(ln_bias), float(ln_eps),
-                                 B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt, _dt(out),
-                                 out.data_ptr(), ptr(final_state), workspace.data_ptr(), workspace.numel(),
-                                 _stream_ptr(stream)))
+        if _z_beta is not None:
+            _check(lib.gla_fwd_fused_gates(q.data_ptr(), k.data_ptr(), v.data_ptr(), z_alpha.data_ptr(),
+                                           _z_beta.data_ptr(), float(tau), *tail))
+        else:
+            _check(lib.gla_fwd_fused(q.data_ptr(), k.data_ptr(), v.data_ptr(), z_alpha.data_ptr(), float(tau), *tail))
     return out, final_state
+
+
+def gla_fwd_fused_gates(q, k, v, z_alpha, z_beta, tau, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, **kwargs):
+    """gla_fwd_fused with the value-side gate as well: ``log_beta = logsigmoid(z_beta) / tau``, z_beta shaped like v
+    and of the element type of q, k, v.  Keyword arguments as gla_fwd_fused."""
+    if z_beta is None:
+        raise ValueError("z_beta is required")
+    return gla_fwd_fused(q, k, v, z_alpha, tau, grid_h, grid_w, scan_dir, _z_beta=z_beta, **kwargs)
 
 
 def gla_bwd_workspace_bytes(B, H, T, dk, dv, qkv_dtype=DT_BF16) -> int:

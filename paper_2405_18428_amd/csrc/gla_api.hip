@@ -8,7 +8,7 @@
 namespace gla {
 namespace {
 
-constexpr int kVersion = 310;  // 0.3.1
+constexpr int kVersion = 320;  // 0.3.2
 
 int g_opt_chunks_per_span = 0;
 int g_opt_engine = GLA_ENGINE_AUTO;
@@ -206,6 +206,7 @@ struct FusedArgs {
     const void *r_pre;
     const float *ln_weight, *ln_bias;
     float ln_eps;
+    const void *z_beta;     // pre-activation of the value-side gate, or null (beta = 1)
 };
 
 struct PhaseEvents {
@@ -224,7 +225,8 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     if (st != GLA_OK) return st;
     if (fused) {
         if (!(fused->tau > 0.f) || !(fused->ln_eps >= 0.f)) return GLA_ERR_SHAPE;
-        if (misaligned(fused->r_pre) || misaligned(fused->ln_weight) || misaligned(fused->ln_bias))
+        if (misaligned(fused->r_pre) || misaligned(fused->ln_weight) || misaligned(fused->ln_bias) ||
+            misaligned(fused->z_beta))
             return GLA_ERR_ALIGN;
     }
     if (layout != GLA_LAYOUT_BHTD && layout != GLA_LAYOUT_BTHD) return GLA_ERR_SHAPE;
@@ -241,6 +243,7 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     p.qkv_dtype = qkv_dtype; p.out_dtype = out_dtype;
     p.initial_state = initial_state;
     if (accumulate && out_dtype != GLA_DT_F32) return GLA_ERR_UNSUPPORTED;
+    if (accumulate && (log_beta || (fused && fused->z_beta))) return GLA_ERR_UNSUPPORTED;
     p.accumulate = accumulate;
     if (fused) {
         p.log_alpha = nullptr;
@@ -250,6 +253,7 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
         p.ln_weight = fused->ln_weight;
         p.ln_bias = fused->ln_bias;
         p.ln_eps = fused->ln_eps;
+        p.z_beta = fused->z_beta;
     }
     if (layout == GLA_LAYOUT_BHTD) {
         p.st_k = dk; p.sh_k = (long long)T * dk; p.sb_k = (long long)H * T * dk;
@@ -331,7 +335,19 @@ int gla_fwd_fused(const void *q, const void *k, const void *v, const void *z_alp
                   int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
                   int qkv_dtype, int out_dtype, void *out, float *final_state,
                   void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
-    const FusedArgs fused{z_alpha, tau, r_pre, ln_weight, ln_bias, ln_eps};
+    const FusedArgs fused{z_alpha, tau, r_pre, ln_weight, ln_bias, ln_eps, nullptr};
+    return run(q, k, v, nullptr, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype, out_dtype,
+               out, final_state, workspace, workspace_bytes_, static_cast<hipStream_t>(stream), nullptr,
+               GLA_LAYOUT_BHTD, nullptr, &fused);
+}
+
+int gla_fwd_fused_gates(const void *q, const void *k, const void *v, const void *z_alpha, const void *z_beta, float tau,
+                        const void *r_pre, const float *ln_weight, const float *ln_bias, float ln_eps,
+                        int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                        int qkv_dtype, int out_dtype, void *out, float *final_state,
+                        void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
+    if (!z_beta) return GLA_ERR_NULL;
+    const FusedArgs fused{z_alpha, tau, r_pre, ln_weight, ln_bias, ln_eps, z_beta};
     return run(q, k, v, nullptr, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype, out_dtype,
                out, final_state, workspace, workspace_bytes_, static_cast<hipStream_t>(stream), nullptr,
                GLA_LAYOUT_BHTD, nullptr, &fused);

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kCarryThreads) void carry_kernel(Params p) {
     const int c = e / p.dv;
     float *st = p.ws_state + (size_t)bh * p.nspans * ne + e;
     const float *lg = p.ws_lgam + (size_t)bh * p.nspans * p.dk + c;
-    const float *lgb = p.log_beta != nullptr ? p.ws_lgam_b + (size_t)bh * p.nspans * p.dv + (e - c * p.dv) : nullptr;
+    const float *lgb = two_sided(p) ? p.ws_lgam_b + (size_t)bh * p.nspans * p.dv + (e - c * p.dv) : nullptr;
 
     // state entering the current pass of kGroups * kRun spans; the first pass starts from the caller's state
     float carry = p.initial_state ? p.initial_state[(size_t)bh * ne + e] : 0.f;

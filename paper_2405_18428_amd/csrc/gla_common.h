@@ -63,8 +63,12 @@ struct Params {
     // value-side gate (Eq. (gate_gla_2)): if log_beta is set ([B,H,T,dv] fp32, laid out like v), the state element
     // (c, n) decays by alpha_t[c] * beta_t[n]; token-by-token engine only
     const float *log_beta;
+    const void *z_beta;     // or (with z_gate) its pre-activation: log beta = logsigmoid(z_beta) * inv_tau, like v
     float *ws_lgam_b;       // [B*H, nspans, dv]  summed log_beta of each span (phase 1 -> phase 2)
 };
+
+// the gate has a value-side factor
+__host__ __device__ inline bool two_sided(const Params &p) { return p.log_beta != nullptr || p.z_beta != nullptr; }
 
 // Scan step s -> canonical token index (Sec. 3.3 / Algorithm 1 orders).
 __host__ __device__ inline int scan_token(int scan_dir, int s, int T, int grid_h, int grid_w) {

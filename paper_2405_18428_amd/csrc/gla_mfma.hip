@@ -144,7 +144,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     static_assert(NTB <= 4 && (DEPTH + 1) * kChunk <= NTHR, "token maps: four buffers, first ones filled in one go");
     static_assert(16 * NCT <= CHS, "state tiles must fit the operand row");
     static_assert(!ACC || (OUT && !FUSE && sizeof(TOut) == 4), "accumulation: plain output pass, fp32 rows");
-    static_assert(!BETA || (!FUSE && !ACC), "two-sided gate: plain passes only");
+    static_assert(!BETA || !ACC, "two-sided gate: no accumulation into existing rows");
     constexpr int LBS = L::kLbStride;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -204,6 +204,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + base_k * 4;
     const char *glb = reinterpret_cast<const char *>(p.log_beta) + base_v * 4;
     const char *gz = static_cast<const char *>(p.z_gate) + base_k * 2;
+    const char *gzb = static_cast<const char *>(p.z_beta) + base_v * 2;
     const char *grp = static_cast<const char *>(p.r_pre) + base_v * 2;
     const bool epilogue = FUSE && OUT && p.r_pre != nullptr;   // uniform
     char *gout = static_cast<char *>(p.out) + base_v * sizeof(TOut);
@@ -317,6 +318,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     u32x2 r_q[DEPTH][OUT ? kF : 1];
     u32x4 r_v[DEPTH][kVF];
     f32x4 r_lb[DEPTH][BETA ? kVF : 1][2];   // log_beta of the same 8 columns as the v piece
+    u32x4 r_zb[DEPTH][(BETA && FUSE) ? kVF : 1];   // or their pre-activations (bf16)
 
     // Rows past the end of a ragged last chunk carry the token of a valid row in s_tok (so the loads
     // stay in bounds) and are zeroed when they are written to LDS.
@@ -338,7 +340,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
 #pragma unroll
         for (int m = 0; m < kVF; ++m) {
             r_v[S][m] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tok[fvrp[m] >> 8] * dv2 + 16u * (uint32_t)(fvrp[m] & 255));
-            if constexpr (BETA) {
+            if constexpr (BETA && FUSE) {
+                r_zb[S][m] = *reinterpret_cast<const u32x4 *>(gzb + (uint32_t)tokg[fvrp[m] >> 8] * dv2 + 16u * (uint32_t)(fvrp[m] & 255));
+            } else if constexpr (BETA) {
                 const char *lbp = glb + 2u * ((uint32_t)tokg[fvrp[m] >> 8] * dv2 + 16u * (uint32_t)(fvrp[m] & 255));
                 r_lb[S][m][0] = *reinterpret_cast<const f32x4 *>(lbp);
                 r_lb[S][m][1] = *reinterpret_cast<const f32x4 *>(lbp + 16);
@@ -381,6 +385,18 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                 gate2(r_z[S][m][1], a2, a3);
                 la = f32x4{a0, a1, a2, a3};
                 r_la[S][m] = la;
+            }
+            if constexpr (BETA) {
+#pragma unroll
+                for (int m = 0; m < kVF; ++m) {
+                    float b0, b1, b2, b3, b4, b5, b6, b7;
+                    gate2(r_zb[S][m][0], b0, b1);
+                    gate2(r_zb[S][m][1], b2, b3);
+                    gate2(r_zb[S][m][2], b4, b5);
+                    gate2(r_zb[S][m][3], b6, b7);
+                    r_lb[S][m][0] = f32x4{b0, b1, b2, b3};
+                    r_lb[S][m][1] = f32x4{b4, b5, b6, b7};
+                }
             }
         }
         if (nvalid < kChunk) {
@@ -557,7 +573,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                     for (int v4 = 0; v4 < 2; ++v4) {
                         const f32x4 x = *reinterpret_cast<const f32x4 *>(s_lb + j * LBS + c0 + 4 * v4);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) cc[4 * v4 + i] = x[i] * kLog2e;
+                        for (int i = 0; i < 4; ++i) cc[4 * v4 + i] = FUSE ? x[i] : x[i] * kLog2e;
                         wave_inclusive_scan4(cc[4 * v4], cc[4 * v4 + 1], cc[4 * v4 + 2], cc[4 * v4 + 3]);
                     }
                     const u32x4 vr = *reinterpret_cast<const u32x4 *>(s_v + j * VS + c0);
@@ -1037,7 +1053,12 @@ hipError_t launch_one(const Params &p, hipStream_t stream) {
 
 template <int MODE, int NDK8, int NDV16>
 hipError_t launch_dt(const Params &p, hipStream_t stream) {
-    if (p.log_beta != nullptr) {   // two-sided gate (the host keeps it apart from the prologue and the accumulation)
+    if (p.z_gate != nullptr && p.z_beta != nullptr) {   // both gates from pre-activations (+ optional epilogue)
+        if (MODE == kModeOutput && p.out_dtype == GLA_DT_BF16)
+            return launch_one<MODE, NDK8, NDV16, true, false, uint16_t, true>(p, stream);
+        return launch_one<MODE, NDK8, NDV16, true, false, float, true>(p, stream);
+    }
+    if (p.log_beta != nullptr) {   // two-sided gate from its logarithms (the host keeps it apart from the accumulation)
         if (MODE == kModeOutput && p.out_dtype == GLA_DT_BF16)
             return launch_one<MODE, NDK8, NDV16, false, false, uint16_t, true>(p, stream);
         return launch_one<MODE, NDK8, NDV16, false, false, float, true>(p, stream);
@@ -1067,7 +1088,7 @@ hipError_t launch_mode(const Params &p, hipStream_t stream) {
 
 bool mfma_engine_supports(const Params &p) {
     // two-sided gate: the extra rows (log_beta, remainder of the gated values) fit the LDS up to dk = 40, dv = 80
-    if (p.log_beta != nullptr && (p.dk > 40 || p.dv > 80)) return false;
+    if (two_sided(p) && (p.dk > 40 || p.dv > 80)) return false;
     // 32-bit byte offsets inside the view of one (batch, head)
     const long long slab = (long long)p.T * (p.st_k > p.st_v ? p.st_k : p.st_v) * 4;
     return p.qkv_dtype == GLA_DT_BF16 && p.dk % 4 == 0 && p.dv % 8 == 0 && p.dk <= kMaxDk && p.dv <= kMaxDv &&

@@ -109,7 +109,15 @@ __global__ __launch_bounds__(kThreads) void recurrent_span_kernel(Params p) {
             int n = s_tok[j];
             if (n >= 0) {
                 s_v[j][n2] = load_elem<TIn>(p.v, base_v + (size_t)n * st_v + n2);
-                if constexpr (BETA) s_b[j][n2] = p.log_beta[base_v + (size_t)s_tokg[j] * st_v + n2];
+                if constexpr (BETA) {
+                    const size_t eb = base_v + (size_t)s_tokg[j] * st_v + n2;
+                    if (p.z_beta != nullptr) {   // Eq. (gate_gla_2): log beta = logsigmoid(z) / tau
+                        const float z = load_elem<TIn>(p.z_beta, eb);
+                        s_b[j][n2] = (fminf(z, 0.f) - log1pf(expf(-fabsf(z)))) * p.inv_tau;
+                    } else {
+                        s_b[j][n2] = p.log_beta[eb];
+                    }
+                }
             }
         }
         __syncthreads();
@@ -214,7 +222,7 @@ hipError_t dispatch_gate(const Params &p, hipStream_t stream) {
 
 template <int MODE>
 hipError_t dispatch(const Params &p, hipStream_t stream) {
-    return p.log_beta != nullptr ? dispatch_gate<MODE, true>(p, stream) : dispatch_gate<MODE, false>(p, stream);
+    return two_sided(p) ? dispatch_gate<MODE, true>(p, stream) : dispatch_gate<MODE, false>(p, stream);
 }
 
 }  // namespace

@@ -156,5 +156,19 @@ def make_gate_inputs(B, H, T, dk, dv, dtype="bf16", seed=0, z_mean=0.0, tau=TAU)
     return d
 
 
+def make_fused_gate_inputs(B, H, T, dk, dv, dtype="bf16", seed=0, z_mean=0.0):
+    """:func:`make_fused_inputs` plus ``zb`` [B,H,T,dv], the pre-activation of the value-side gate (standard normal
+    + z_mean, third generator; bf16-representable with its ``zb_bits`` for "bf16")."""
+    d = make_fused_inputs(B, H, T, dk, dv, dtype, seed, z_mean)
+    rng3 = np.random.Generator(np.random.PCG64(seed + 4000))
+    zb = (rng3.standard_normal((B, H, T, dv), dtype=np.float32) + np.float32(z_mean)).astype(np.float32)
+    if dtype == "bf16":
+        d["zb_bits"] = round_to_bf16_bits(zb)
+        d["zb"] = bf16_bits_to_f32(d["zb_bits"])
+    else:
+        d["zb"] = zb
+    return d
+
+
 def make_config_inputs(cfg: GlaConfig):
     return make_inputs(cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv, cfg.dtype, cfg.seed, cfg.z_mean)

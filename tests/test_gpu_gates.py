@@ -146,3 +146,61 @@ def test_gates_forced_mfma_engine_rejects_what_it_cannot_run():
             gla.gla_fwd_gates(q, k, v, la, lb, 8, 8, 0)
     finally:
         gla.gla_set_option(gla.OPT_ENGINE, gla.ENGINE_AUTO)
+
+
+# ---- both gates from their pre-activations, with the output epilogue (gla_fwd_fused_gates) ----
+
+def _dev_fused(d, dtype):
+    dev = torch.device("cuda:0")
+    names = ("q", "k", "v", "z", "zb", "r")
+    if dtype == "bf16":
+        return {n: torch.from_numpy(d[n + "_bits"].view(np.int16)).to(dev).view(torch.bfloat16) for n in names}
+    return {n: torch.from_numpy(d[n]).to(dev) for n in names}
+
+
+def _check_fused_gates(B, H, gh, gw, dk, dv, dtype, scan, seed, epilogue, out_dtype=None, engine=None):
+    from oracle import gla_oracle_fused as fo
+    d = gi.make_fused_gate_inputs(B, H, gh * gw, dk, dv, dtype, seed=seed)
+    t = _dev_fused(d, dtype)
+    ref, rfin = fo.gla_fused_gates(d["q"], d["k"], d["v"], d["z"], d["zb"], 16.0, d["r"] if epilogue else None,
+                                   d["ln_w"], d["ln_b"], 1e-5, gh, gw, scan)
+    if engine is not None:
+        gla.gla_set_option(gla.OPT_ENGINE, engine)
+    try:
+        y, fin = gla.gla_fwd_fused_gates(t["q"], t["k"], t["v"], t["z"], t["zb"], 16.0, gh, gw, scan,
+                                         r_pre=t["r"] if epilogue else None,
+                                         ln_weight=torch.from_numpy(d["ln_w"]).cuda() if epilogue else None,
+                                         ln_bias=torch.from_numpy(d["ln_b"]).cuda() if epilogue else None,
+                                         ln_eps=1e-5, out_dtype=out_dtype)
+        torch.cuda.synchronize()
+    finally:
+        gla.gla_set_option(gla.OPT_ENGINE, gla.ENGINE_AUTO)
+    return _err(y.float().cpu().numpy(), ref), _err(fin.cpu().numpy(), rfin), float(np.abs(ref).max() / np.sqrt(np.mean(ref ** 2)))
+
+
+@pytest.mark.parametrize("dk,dv", [(32, 64), (36, 72), (20, 33), (64, 128)])
+@pytest.mark.parametrize("scan", [0, 2])
+def test_fused_gates_parity(dk, dv, scan):
+    """Same bars as gla_fwd_fused: 2e-2 of the RMS for bf16 inputs with the LayerNorm epilogue (LN divides by the
+    row's spread), 1e-4 for fp32 inputs; the plain rows (no epilogue) of bf16 inputs to 2e-4."""
+    e_y, e_f, _ = _check_fused_gates(2, 2, 19, 23, dk, dv, "bf16", scan, 71, True)
+    assert e_y < TOL_BF16 and e_f < 2e-4
+    e_o, e_f, _ = _check_fused_gates(2, 2, 19, 23, dk, dv, "bf16", scan, 72, False)
+    assert e_o < 2e-4 and e_f < 2e-4
+    if dv % 8:
+        e_y, e_f, _ = _check_fused_gates(1, 2, 19, 23, dk, dv, "f32", scan, 73, True)
+        assert e_y < TOL_F32 and e_f < TOL_F32
+
+
+def test_fused_gates_engines_and_bf16_rows():
+    for engine in (gla.ENGINE_RECURRENT, gla.ENGINE_MFMA):
+        e_y, e_f, _ = _check_fused_gates(1, 3, 30, 40, 36, 72, "bf16", 1, 74, True, engine=engine)
+        assert e_y < TOL_BF16 and e_f < 2e-4
+    e_y, e_f, peak = _check_fused_gates(1, 3, 30, 40, 36, 72, "bf16", 3, 75, True, out_dtype=torch.bfloat16)
+    assert e_y < TOL_BF16 + 2.0 ** -9 * peak
+
+
+def test_fused_gates_headline_shape():
+    cfg = gi.CONFIGS["dig_xl2_2048"]
+    e_y, e_f, _ = _check_fused_gates(cfg.B, cfg.H, cfg.grid_h, cfg.grid_w, cfg.dk, cfg.dv, "bf16", 0, cfg.seed, True)
+    assert e_y < TOL_BF16 and e_f < 2e-4
