@@ -80,3 +80,13 @@ def test_argument_validation_needs_no_gpu():
     assert r == 5
     r = lib.gla_fwd_ex(ok_ptr, ok_ptr, ok_ptr, ok_ptr, 1, 1, 4, 8, 8, 2, 2, 0, 5, 0, ok_ptr, None, ok_ptr, 1 << 20, None)
     assert r == 2
+    # two-sided gate: the value-side tensor is mandatory and must be aligned
+    g = lambda lb: lib.gla_fwd_gates(ok_ptr, ok_ptr, ok_ptr, ok_ptr, lb, 1, 1, 4, 8, 8, 2, 2, 0, 1, 0, 0, None,
+                                     ok_ptr, None, ok_ptr, 1 << 20, None)
+    assert g(None) == 1
+    assert g(vp(4100)) == 4
+    f = ctypes.c_float
+    fg = lambda zb: lib.gla_fwd_fused_gates(ok_ptr, ok_ptr, ok_ptr, ok_ptr, zb, f(16.0), None, None, None, f(1e-5),
+                                            1, 1, 4, 8, 8, 2, 2, 0, 1, 0, ok_ptr, None, ok_ptr, 1 << 20, None)
+    assert fg(None) == 1
+    assert fg(vp(4100)) == 4
