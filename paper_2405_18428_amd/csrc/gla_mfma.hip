@@ -674,15 +674,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
             if constexpr (OUT) {
                 constexpr int NX = NDV16;          // this wave's 16 output rows span all value-column tiles
                 const uint16_t *qrow_h = s_qhi + (16 * IT + lm) * CHS, *qrow_l = s_qlo + (16 * IT + lm) * CHS;
-                // When the last 32-channel step holds a single 8-channel group (dk = 33..40, or dk <= 8), its three
-                // products hi*hi, hi*lo, lo*hi share one MFMA: lane groups g = 0, 1, 2 of the gated operand and of
-                // S_0 read (hi, hi, lo) of that channel group, those of Q~ read (hi, lo, hi), g = 3 reads zeros.
+                // When the last 32-channel step holds a single 8-channel group (dk = 33..40, or dk <= 8), its four
+                // products hi*hi, hi*lo, lo*hi, lo*lo share one MFMA: lane groups g = 0..3 of the gated operand and
+                // of S_0 read (hi, hi, lo, lo) of that channel group, those of Q~ read (hi, lo, hi, lo).
                 // The "hi" arrays then hold the packed fragment of that step and the "lo" entry is unused.
                 constexpr bool PT = NDK8 % 4 == 1;
                 constexpr int TC = 32 * (KS - 1);  // first channel of the last step
-                const uint16_t *ktail = (g == 2 ? s_klo : s_khi) + (g == 3 ? L::kZeroCol : TC);
-                const uint16_t *qtail = (g == 1 ? s_qlo : s_qhi) + (g == 3 ? L::kZeroCol : TC);
-                const uint16_t *sttail = (g == 2 ? s_stlo : s_sthi) + (g == 3 ? L::kZeroCol : TC);
+                const uint16_t *ktail = (g >= 2 ? s_klo : s_khi) + TC;
+                const uint16_t *qtail = ((g & 1) ? s_qlo : s_qhi) + TC;
+                const uint16_t *sttail = (g >= 2 ? s_stlo : s_sthi) + TC;
                 u32x4 qfh[KS], qfl[KS];            // Q~ fragments of this wave's 16 output rows
                 u32x4 kfh[2][KS], kfl[2][KS];      // K~ fragments of two score tiles
                 u32x2 vt[2][NX][2];                // V fragments of the two 32-token steps
@@ -742,7 +742,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                         if (PT && ks == KS - 1) continue;
                         d = mfma(kfh[u][ks], qfl[ks], d);
                         d = mfma(kfl[u][ks], qfh[ks], d);
-                        if constexpr (BETA) d = mfma(kfl[u][ks], qfl[ks], d);
+                        d = mfma(kfl[u][ks], qfl[ks], d);
                     }
                     if (jt == IT) {
 #pragma unroll
@@ -774,7 +774,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
                         if (PT && ks == KS - 1) continue;
                         o[x] = mfma(sth[buf][x], qfl[ks], o[x]);
                         o[x] = mfma(stl[buf][x], qfh[ks], o[x]);
-                        if constexpr (BETA) o[x] = mfma(stl[buf][x], qfl[ks], o[x]);
+                        o[x] = mfma(stl[buf][x], qfl[ks], o[x]);
                     }
                 };
                 // what the state update still has to read: its K~ operand, and the second 32 tokens of V when the
