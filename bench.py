@@ -191,15 +191,19 @@ def bench_gates(args, cfg, gla, gi, torch, np):
     ws_bytes = gla.gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
     sets = []
     for _ in range(max(1, args.sets)):
-        sets.append([t.to(dev) for t in host] + [torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)])
+        sets.append([t.to(dev) for t in host] + [torch.empty((ws_bytes,), dtype=torch.uint8, device=dev),
+                                                 torch.empty((B, H, T, dv), dtype=torch.float32, device=dev),
+                                                 torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev)])
 
     def step(i):
         if fused:
-            q, k, v, z, zb, r, ws = sets[i % len(sets)]
+            q, k, v, z, zb, r, ws, out, fin = sets[i % len(sets)]
             return gla.gla_fwd_fused_gates(q, k, v, z, zb, 16.0, cfg.grid_h, cfg.grid_w, args.scan, r_pre=r,
-                                           ln_weight=lnw, ln_bias=lnb, ln_eps=1e-5, workspace=ws)
-        q, k, v, la, lb, ws = sets[i % len(sets)]
-        return gla.gla_fwd_gates(q, k, v, la, lb, cfg.grid_h, cfg.grid_w, args.scan, workspace=ws)
+                                           ln_weight=lnw, ln_bias=lnb, ln_eps=1e-5, out=out, final_state=fin,
+                                           workspace=ws)
+        q, k, v, la, lb, ws, out, fin = sets[i % len(sets)]
+        return gla.gla_fwd_gates(q, k, v, la, lb, cfg.grid_h, cfg.grid_w, args.scan, out=out, final_state=fin,
+                                 workspace=ws)
 
     for i in range(args.warmup):
         step(i)

@@ -247,7 +247,8 @@ def gla_fwd_layout(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, la
 
 
 def gla_fwd_gates(q, k, v, log_alpha, log_beta, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, layout=LAYOUT_BHTD,
-                  initial_state=None, out_dtype=None, want_final_state=True, workspace=None, stream=None):
+                  initial_state=None, out_dtype=None, want_final_state=True, out=None, final_state=None,
+                  workspace=None, stream=None):
     """The recurrence with the two-sided gate alpha_t^T beta_t; ``log_beta`` is fp32, shaped like v."""
     torch = _torch()
     lib = load_library()
@@ -270,8 +271,10 @@ def gla_fwd_gates(q, k, v, log_alpha, log_beta, grid_h, grid_w, scan_dir=SCAN_RO
         if (initial_state.dtype != torch.float32 or tuple(initial_state.shape) != (B, H, dk, dv)
                 or not initial_state.is_contiguous() or not initial_state.is_cuda):
             raise ValueError("initial_state must be a contiguous fp32 GPU tensor [B,H,dk,dv]")
-    out = torch.empty(tuple(v.shape), dtype=torch.float32 if out_dtype is None else out_dtype, device=q.device)
-    final_state = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device) if want_final_state else None
+    if out is None:
+        out = torch.empty(tuple(v.shape), dtype=torch.float32 if out_dtype is None else out_dtype, device=q.device)
+    if final_state is None and want_final_state:
+        final_state = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device)
     if workspace is None:
         nbytes = gla_fwd_workspace_bytes(B, H, T, dk, dv, qdt)
         workspace = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=q.device)

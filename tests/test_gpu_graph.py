@@ -65,3 +65,41 @@ def test_forward_and_backward_replay_from_a_graph():
         gla.gla_fwd_ex(q, k, v, la, gh, gw, 1, workspace=ws)
         gla.gla_bwd(q, k, v, la, w, gh, gw, 1, workspace=ws_b)
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("carry", ["in_output", "kernel"])
+def test_two_sided_gate_call_replays_from_a_graph(carry):
+    dev = torch.device("cuda:0")
+    B, H, gh, gw, dk, dv = 1, 4, 24, 40, 36, 72
+    T = gh * gw
+    d = gi.make_gate_inputs(B, H, T, dk, dv, "bf16", seed=62)
+    q, k, v = (_bf16(d, n, dev) for n in ("q", "k", "v"))
+    la, lb = torch.from_numpy(d["log_alpha"]).to(dev), torch.from_numpy(d["log_beta"]).to(dev)
+    out = torch.empty((B, H, T, dv), device=dev)
+    fin = torch.empty((B, H, dk, dv), device=dev)
+    ws = torch.empty((gla.gla_fwd_workspace_bytes(B, H, T, dk, dv),), dtype=torch.uint8, device=dev)
+    gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_KERNEL if carry == "kernel" else gla.CARRY_IN_OUTPUT_PASS)
+    gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 3)
+    try:
+        call = lambda scan, stream=None: gla.gla_fwd_gates(q, k, v, la, lb, gh, gw, scan, out=out, final_state=fin,
+                                                           workspace=ws, stream=stream)
+        ref_out, ref_fin = (t.clone() for t in call(3))
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                call(3, side)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            out.fill_(float("nan"))
+            fin.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, ref_out) and torch.equal(fin, ref_fin), rep
+            tmp_o, tmp_f = torch.empty_like(out), torch.empty_like(fin)
+            gla.gla_fwd_gates(q, k, v, la, lb, gh, gw, 0, out=tmp_o, final_state=tmp_f, workspace=ws)  # eager, same workspace
+            torch.cuda.synchronize()
+    finally:
+        gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_AUTO)
+        gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 0)
