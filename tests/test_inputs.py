@@ -39,3 +39,21 @@ def test_contract_configs_present():
     assert gi.CONFIG_ORDER == ["tiny_f32", "dig_s2_256", "dig_xl2_512", "dig_xl2_1024", "dig_xl2_2048"]
     c = gi.CONFIGS["dig_xl2_2048"]
     assert (c.B, c.H, c.T, c.dk, c.dv, c.dtype) == (1, 16, 16384, 36, 72, "bf16")
+
+
+def test_gate_input_recipes_extend_the_plain_ones():
+    """The two-sided-gate generators leave q, k, v and the key-side gate exactly as the plain recipes draw them and
+    add the value-side tensors from generators of their own."""
+    a = gi.make_inputs(1, 2, 40, 8, 16, "bf16", seed=5, z_mean=0.5)
+    g = gi.make_gate_inputs(1, 2, 40, 8, 16, "bf16", seed=5, z_mean=0.5)
+    for name in ("q", "k", "v", "log_alpha", "q_bits"):
+        np.testing.assert_array_equal(a[name], g[name])
+    lb = g["log_beta"]
+    assert lb.shape == (1, 2, 40, 16) and lb.dtype == np.float32 and (lb <= 0).all() and (lb > -2).all()
+    np.testing.assert_array_equal(lb, gi.make_gate_inputs(1, 2, 40, 8, 16, "bf16", seed=5, z_mean=0.5)["log_beta"])
+    f = gi.make_fused_inputs(1, 2, 40, 8, 16, "bf16", seed=5)
+    fg = gi.make_fused_gate_inputs(1, 2, 40, 8, 16, "bf16", seed=5)
+    for name in ("q", "k", "v", "z", "r", "ln_w", "ln_b"):
+        np.testing.assert_array_equal(f[name], fg[name])
+    assert fg["zb"].shape == (1, 2, 40, 16)
+    np.testing.assert_array_equal(gi.bf16_bits_to_f32(fg["zb_bits"]), fg["zb"])   # bf16-representable
