@@ -139,3 +139,62 @@ def test_fused_gates_large_negative_z_beta_forgets_the_past():
     o, _ = fo.gla_fused_gates(q, k, v, z_a, z_b, 1.0, None, None, None, 0.0, 2, 3, 0)
     expect = np.einsum("bhtc,bhtc->bht", q, k)[..., None] * v
     np.testing.assert_allclose(o, expect, rtol=1e-12, atol=1e-12)
+
+
+# ---- reverse mode of the two-sided-gate recurrence ----
+
+def _loss(q, k, v, la, lb, w, gh, gw, d):
+    o, _ = og.gla_fwd_gates(q, k, v, la, lb, gh, gw, d)
+    return float((o * w).sum())
+
+
+@pytest.mark.parametrize("d", [0, 1, 2, 3])
+def test_backward_matches_central_differences(d):
+    """Every gradient entry against (L(x + h) - L(x - h)) / 2h for L = <out, w> (fp64, h = 1e-6)."""
+    gh, gw = 2, 3
+    q, k, v, la, lb = _rand(1, 2, gh, gw, 3, 2, 20 + d)
+    w = np.random.default_rng(30 + d).standard_normal(v.shape)
+    grads = og.gla_bwd_gates(q, k, v, la, lb, w, gh, gw, d)
+    args = [q, k, v, la, lb]
+    h = 1e-6
+    for a_i, g in enumerate(grads):
+        x = args[a_i]
+        num = np.empty_like(x)
+        it = np.nditer(x, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            keep = x[idx]
+            x[idx] = keep + h
+            lp = _loss(*args, w, gh, gw, d)
+            x[idx] = keep - h
+            lm = _loss(*args, w, gh, gw, d)
+            x[idx] = keep
+            num[idx] = (lp - lm) / (2 * h)
+        np.testing.assert_allclose(g, num, rtol=2e-6, atol=2e-8)
+
+
+def test_backward_with_unit_beta_is_the_key_side_backward():
+    q, k, v, la, lb = _rand(2, 2, 4, 5, 3, 4, 41)
+    w = np.random.default_rng(42).standard_normal(v.shape)
+    for d in (0, 3):
+        dq, dk, dvv, dla, dlb = og.gla_bwd_gates(q, k, v, la, np.zeros_like(lb), w, 4, 5, d)
+        r = orc.gla_bwd(q, k, v, la, w, 4, 5, d)
+        for got, ref in zip((dq, dk, dvv, dla), r):
+            np.testing.assert_allclose(got, ref, rtol=1e-11, atol=1e-12)
+
+
+def test_gate_gradients_are_reverse_cumulative_sums():
+    """d log alpha = reverse cumulative sum over the scan of (q * dq - k * dk); d log beta likewise of
+    (o * dO - v * dv): the identities the GPU path evaluates, checked on the oracle's direct formulas."""
+    gh, gw, d = 3, 4, 2
+    q, k, v, la, lb = _rand(1, 2, gh, gw, 3, 4, 43)
+    w = np.random.default_rng(44).standard_normal(v.shape)
+    dq, dk, dvv, dla, dlb = og.gla_bwd_gates(q, k, v, la, lb, w, gh, gw, d)
+    o, _ = og.gla_fwd_gates(q, k, v, la, lb, gh, gw, d)
+    pi = orc.scan_order(d, gh, gw)
+    ta = (q * dq - k * dk)[:, :, pi, :]
+    tb = (o * w - v * dvv)[:, :, pi, :]
+    ra = np.flip(np.cumsum(np.flip(ta, 2), 2), 2)
+    rb = np.flip(np.cumsum(np.flip(tb, 2), 2), 2)
+    np.testing.assert_allclose(dla[:, :, pi, :], ra, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dlb[:, :, pi, :], rb, rtol=1e-10, atol=1e-12)
