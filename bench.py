@@ -248,6 +248,70 @@ def bench_gates(args, cfg, gla, gi, torch, np):
     print(json.dumps(result), flush=True)
 
 
+def bench_bwd_gates(args, cfg, gla, gi, torch, np):
+    """gla_bwd_gates (backward of the two-sided-gate recurrence) at the workload's shape."""
+    dev = torch.device("cuda:0")
+    B, H, T, dk, dv = cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv
+    d = gi.make_gate_inputs(B, H, T, dk, dv, cfg.dtype, cfg.seed, cfg.z_mean)
+    w = np.random.Generator(np.random.PCG64(cfg.seed + 1000)).standard_normal((B, H, T, dv), dtype=np.float32)
+    bf16 = cfg.dtype == "bf16"
+    if bf16:
+        wb = gi.round_to_bf16_bits(w)
+        w = gi.bf16_bits_to_f32(wb)
+        host = [torch.from_numpy(d[n + "_bits"].view(np.int16)).view(torch.bfloat16) for n in ("q", "k", "v")]
+        host.append(torch.from_numpy(wb.view(np.int16)).view(torch.bfloat16))
+    else:
+        host = [torch.from_numpy(d[n]) for n in ("q", "k", "v")] + [torch.from_numpy(w)]
+    host += [torch.from_numpy(d["log_alpha"]), torch.from_numpy(d["log_beta"])]
+    qdt = gla.DT_BF16 if bf16 else gla.DT_F32
+    ws_bytes = gla.gla_bwd_gates_workspace_bytes(B, H, T, dk, dv, qdt)
+    sets = [[t.to(dev) for t in host] + [torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)]
+            for _ in range(max(1, min(args.sets, 2)))]
+
+    def step(i):
+        q, k, v, wt, la, lb, ws = sets[i % len(sets)]
+        return gla.gla_bwd_gates(q, k, v, la, lb, wt, cfg.grid_h, cfg.grid_w, args.scan, workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    qb = 2 if bf16 else 4
+    # q, k, v, dO, both gates read once; five gradients written once
+    alg_bytes = ((2 * dk + 2 * dv) * qb + (dk + dv) * 4 + (3 * dk + 2 * dv) * 4) * B * H * T
+    achieved = alg_bytes / (ms * 1e-3) / 1e9
+    result = {
+        "metric": "GLA bwd with the two-sided gate, tokens/s at DiG-XL/2 shape T=16384",
+        "value": round(B * T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} + log_beta, backward: B={B} H={H} T={T} ({cfg.grid_h}x{cfg.grid_w}) dk={dk} "
+                               f"dv={dv} {cfg.dtype} q/k/v/dO, fp32 gates and gradients, scan {args.scan}",
+                   "buffer_sets": len(sets)},
+        "roofline": {"bound": "hbm", "kernel": "whole_call", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes": alg_bytes, "kernel_ms": round(ms, 5)},
+    }
+    if not args.no_check:
+        # the oracle keeps every state of a sequence: check the first two heads (heads are independent)
+        from oracle import gla_oracle_gates
+        hs = slice(0, min(H, 2))
+        ref = gla_oracle_gates.gla_bwd_gates(d["q"][:1, hs], d["k"][:1, hs], d["v"][:1, hs], d["log_alpha"][:1, hs],
+                                             d["log_beta"][:1, hs], w[:1, hs], cfg.grid_h, cfg.grid_w, args.scan)
+        got = step(0)
+        torch.cuda.synchronize()
+        errs = {}
+        for name, g, r in zip(("dq", "dk", "dv", "dlog_alpha", "dlog_beta"), got, ref):
+            rms = float(np.sqrt(np.mean(r ** 2)))
+            errs[name] = round(float(np.abs(g[:1, hs].cpu().numpy() - r).max() / rms), 6)
+        result["err_over_rms_first_two_heads"] = errs
+    print(json.dumps(result), flush=True)
+
+
 def bench_srem(args, cfg, gla, gi, torch, np):
     """gla_srem_dwconv on the token matrix of the workload ([B, T, H*dv] bf16 in and out)."""
     dev = torch.device("cuda:0")
@@ -399,14 +463,15 @@ def main():
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated over (1 = cache-warm)")
     ap.add_argument("--chunks-per-span", type=int, default=0)
     ap.add_argument("--engine", type=int, default=0)
-    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "train", "fused", "bidir", "4dir", "srem", "gates", "fusedgates"],
+    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "train", "fused", "bidir", "4dir", "srem", "gates", "fusedgates", "bwdgates"],
                     help="fwd: the forward hot path (the headline); bwd: gla_bwd on the same workload; "
                          "train: gla_fwd_ex followed by gla_bwd_reuse; "
                          "fused: gla_fwd_fused (gate prologue, Swish/LayerNorm epilogue) on the same workload; "
                          "bidir / 4dir: gla_fwd_multi over scan orders (0, 1) / (0, 1, 2, 3); "
                          "srem: gla_srem_dwconv on the workload's token matrix; "
                          "gates: gla_fwd_gates (two-sided gate) on the same workload plus a log_beta tensor; "
-                         "fusedgates: gla_fwd_fused_gates (both gates from pre-activations, Swish/LayerNorm epilogue)")
+                         "fusedgates: gla_fwd_fused_gates (both gates from pre-activations, Swish/LayerNorm epilogue); "
+                         "bwdgates: gla_bwd_gates (backward of the two-sided-gate recurrence)")
     ap.add_argument("--layout", default="bhtd", choices=["bhtd", "bthd"],
                     help="memory order of q, k, v, log_alpha, out: [B,H,T,d] (the headline) or [B,T,H,d]")
     ap.add_argument("--reuse-fwd", action="store_true",
@@ -445,6 +510,9 @@ def main():
         return
     if args.which == "fused":
         bench_fused(args, cfg, gla, gi, torch, np)
+        return
+    if args.which == "bwdgates":
+        bench_bwd_gates(args, cfg, gla, gi, torch, np)
         return
     if args.which in ("gates", "fusedgates"):
         bench_gates(args, cfg, gla, gi, torch, np)

@@ -199,6 +199,28 @@ int gla_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
 size_t gla_bwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);
 
 /*
+ * gla_bwd_gates - gla_bwd for the recurrence of gla_fwd_gates (two-sided gate alpha_t^T beta_t,
+ * zero initial state, [B,H,T,d] order).  The gradient that reaches the state obeys
+ * G_s = q_s^T dO_s + (alpha_{s+1}^T beta_{s+1}) * G_{s+1}; dq, dk, dv as in gla_bwd, and
+ *   dlog_alpha_s = sum over s' >= s of (q_s' * dq_s' - k_s' * dk_s'),
+ *   dlog_beta_s  = sum over s' >= s of (o_s' * dO_s' - v_s' * dv_s')      (o = the forward outputs,
+ *                                                                           recomputed in the workspace).
+ *
+ *   log_beta         DEVICE, fp32 [B,H,T,dv]                                           (read)
+ *   dlog_beta        DEVICE, fp32 [B,H,T,dv]                                           (written)
+ *   workspace        DEVICE, 16-byte aligned, at least gla_bwd_gates_workspace_bytes(...) bytes
+ *
+ * Everything else as gla_bwd.  The span passes run on the engine gla_fwd_gates would take; the
+ * reads of the state along its value axis run token by token in fp32 for every case (the MFMA
+ * row-read kernels of gla_bwd know the key-side decay only).  Never allocates.
+ */
+int gla_bwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,
+                  const void *d_out, int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                  int qkv_dtype, float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha, float *dlog_beta,
+                  void *workspace, size_t workspace_bytes, gla_stream_t stream);
+size_t gla_bwd_gates_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);
+
+/*
  * gla_bwd_reuse - gla_bwd that takes the span states of S from the workspace of the forward
  * call instead of recomputing them (one of the two state passes of the backward pass is the
  * state pass of the forward pass).

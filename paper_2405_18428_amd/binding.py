@@ -77,6 +77,10 @@ def load_library():
     lib.gla_fwd_fused_gates.restype = i
     lib.gla_fwd_fused_gates.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, ctypes.c_float] + shape + \
         [i, i, vp, vp, vp, sz, vp]
+    lib.gla_bwd_gates.restype = i
+    lib.gla_bwd_gates.argtypes = [vp] * 6 + shape + [i] + [vp] * 5 + [vp, sz, vp]
+    lib.gla_bwd_gates_workspace_bytes.restype = sz
+    lib.gla_bwd_gates_workspace_bytes.argtypes = [i] * 6
     lib.gla_bwd_workspace_bytes.restype = sz
     lib.gla_bwd_workspace_bytes.argtypes = [i] * 6
     lib.gla_fwd_timed.restype = i
@@ -396,6 +400,42 @@ def gla_fwd_fused_gates(q, k, v, z_alpha, z_beta, tau, grid_h, grid_w, scan_dir=
     if z_beta is None:
         raise ValueError("z_beta is required")
     return gla_fwd_fused(q, k, v, z_alpha, tau, grid_h, grid_w, scan_dir, _z_beta=z_beta, **kwargs)
+
+
+def gla_bwd_gates(q, k, v, log_alpha, log_beta, d_out, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, workspace=None,
+                  stream=None):
+    """Gradients of the two-sided-gate recurrence: returns (dq, dk, dv, dlog_alpha, dlog_beta), all fp32."""
+    torch = _torch()
+    lib = load_library()
+    for name, t in (("q", q), ("k", k), ("v", v), ("log_alpha", log_alpha), ("log_beta", log_beta), ("d_out", d_out)):
+        if not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous 4-d GPU tensor")
+    if (q.shape != k.shape or q.shape != log_alpha.shape or v.shape[:3] != q.shape[:3] or log_beta.shape != v.shape
+            or d_out.shape != v.shape):
+        raise ValueError("q, k, log_alpha must share one shape; v, log_beta, d_out another with the same first three sizes")
+    if q.dtype != k.dtype or q.dtype != v.dtype or d_out.dtype != q.dtype:
+        raise TypeError("q, k, v, d_out must share one element type")
+    if log_alpha.dtype != torch.float32 or log_beta.dtype != torch.float32:
+        raise TypeError("the gates must be fp32")
+    B, H, T, dk = q.shape
+    dv = v.shape[3]
+    qdt = _dt(q)
+    f32 = dict(dtype=torch.float32, device=q.device)
+    dq, dk_g, dla = (torch.empty((B, H, T, dk), **f32) for _ in range(3))
+    dv_g, dlb = (torch.empty((B, H, T, dv), **f32) for _ in range(2))
+    if workspace is None:
+        nbytes = int(lib.gla_bwd_gates_workspace_bytes(B, H, T, dk, dv, qdt))
+        workspace = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=q.device)
+    with torch.cuda.device(q.device):
+        _check(lib.gla_bwd_gates(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(), log_beta.data_ptr(),
+                                 d_out.data_ptr(), B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt,
+                                 dq.data_ptr(), dk_g.data_ptr(), dv_g.data_ptr(), dla.data_ptr(), dlb.data_ptr(),
+                                 workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return dq, dk_g, dv_g, dla, dlb
+
+
+def gla_bwd_gates_workspace_bytes(B, H, T, dk, dv, qkv_dtype=DT_BF16) -> int:
+    return int(load_library().gla_bwd_gates_workspace_bytes(B, H, T, dk, dv, qkv_dtype))
 
 
 def gla_bwd_workspace_bytes(B, H, T, dk, dv, qkv_dtype=DT_BF16) -> int:

@@ -8,7 +8,7 @@
 namespace gla {
 namespace {
 
-constexpr int kVersion = 320;  // 0.3.2
+constexpr int kVersion = 330;  // 0.3.3
 
 int g_opt_chunks_per_span = 0;
 int g_opt_engine = GLA_ENGINE_AUTO;
@@ -196,6 +196,79 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
     Params pc = base;
     pc.q = q; pc.k = k; pc.scan_dir = scan_dir;
     if (launch_dlog_alpha(pc, dq, dk_grad, dlog_alpha, totals, stream) != hipSuccess) return GLA_ERR_HIP;
+    return GLA_OK;
+}
+
+// Backward pass with the two-sided gate alpha_t^T beta_t.  Same walks as run_bwd; the adjoint state obeys
+// G_s = q_s^T dO_s + (alpha_{s+1}^T beta_{s+1}) * G_{s+1}.  The span passes run on the engine the forward call would
+// take (MFMA where it covers the case), the value-axis reads of the state on the token-by-token kernel, which
+// needs the states entering the spans in memory: the carry kernel chains them.  The value-side gate gradient is
+// the reverse cumulative sum of o * dO - v * dv, so the outputs o are recomputed first (fp32, in the workspace).
+size_t bwd_gates_out_bytes(int B, int H, int T, int dv) { return align_up((size_t)B * H * T * dv * sizeof(float), 256); }
+
+int run_bwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,
+                  const void *d_out, int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                  int qkv_dtype, float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha, float *dlog_beta,
+                  void *workspace, size_t ws_bytes, hipStream_t stream) {
+    if (!log_beta || !d_out || !dq || !dk_grad || !dv_grad || !dlog_alpha || !dlog_beta) return GLA_ERR_NULL;
+    int st = validate(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir,
+                      qkv_dtype, GLA_DT_F32, dv_grad, nullptr);
+    if (st != GLA_OK) return st;
+    if (misaligned(log_beta) || misaligned(d_out) || misaligned(dq) || misaligned(dk_grad) || misaligned(dlog_alpha) ||
+        misaligned(dlog_beta))
+        return GLA_ERR_ALIGN;
+    const size_t state_bytes = workspace_bytes(B, H, T, dk, dv);
+    const size_t totals_bytes = bwd_totals_bytes(B, H, T, dk > dv ? dk : dv);
+    if (!workspace || misaligned(workspace) ||
+        ws_bytes < state_bytes + totals_bytes + bwd_gates_out_bytes(B, H, T, dv))
+        return GLA_ERR_WORKSPACE;
+    float *totals = reinterpret_cast<float *>(static_cast<char *>(workspace) + state_bytes);
+    float *o_buf = reinterpret_cast<float *>(static_cast<char *>(workspace) + state_bytes + totals_bytes);
+
+    Params base{};
+    base.B = B; base.H = H; base.T = T; base.dk = dk; base.dv = dv;
+    base.grid_h = grid_h; base.grid_w = grid_w;
+    base.qkv_dtype = qkv_dtype; base.out_dtype = GLA_DT_F32;
+    base.log_alpha = log_alpha; base.log_beta = log_beta;
+    set_dense_bhtd_strides(base);
+    bool use_mfma;
+    st = choose_engine_and_plan(base, workspace, use_mfma);
+    if (st != GLA_OK) return st;
+    base.chain_in_output = 0;
+    auto span = [&](const Params &p, SpanMode mode) {
+        return use_mfma ? launch_mfma_span(p, mode, stream) : launch_recurrent_span(p, mode, stream);
+    };
+    auto states = [&](const Params &p) {
+        if (p.nspans <= 1) return hipSuccess;
+        hipError_t e = span(p, kModeState);
+        return e != hipSuccess ? e : launch_carry(p, stream);
+    };
+
+    // 1. forward recurrence: states entering the spans, the outputs o (for the value-side gate gradient),
+    //    dq_s = S_s dO_s
+    Params pa = base;
+    pa.q = q; pa.k = k; pa.v = v; pa.scan_dir = scan_dir; pa.gate_shift = 0; pa.out = o_buf;
+    if (states(pa) != hipSuccess) return GLA_ERR_HIP;
+    if (span(pa, kModeOutput) != hipSuccess) return GLA_ERR_HIP;
+    if (launch_row_read(pa, d_out, dq, stream) != hipSuccess) return GLA_ERR_HIP;
+
+    // 2. adjoint recurrence (k, v := q, dO; walked from the last scan step, each step with the previous step's
+    //    gates): dv_s = k_s G_s (outputs with q := k), dk_s = G_s v_s
+    Params pb = base;
+    pb.q = k; pb.k = q; pb.v = d_out; pb.scan_dir = scan_dir ^ 1; pb.gate_shift = 1; pb.out = dv_grad;
+    if (states(pb) != hipSuccess) return GLA_ERR_HIP;
+    if (span(pb, kModeOutput) != hipSuccess) return GLA_ERR_HIP;
+    if (launch_row_read(pb, v, dk_grad, stream) != hipSuccess) return GLA_ERR_HIP;
+
+    // 3. gate gradients: reverse cumulative sums of q * dq - k * dk (key side) and of dO * o - v * dv (value
+    //    side: the same kernels over the dv columns, with dO, v in the places of q, k)
+    Params pc = base;
+    pc.q = q; pc.k = k; pc.scan_dir = scan_dir;
+    if (launch_dlog_alpha(pc, dq, dk_grad, dlog_alpha, totals, stream) != hipSuccess) return GLA_ERR_HIP;
+    Params pd = base;
+    pd.q = d_out; pd.k = v; pd.scan_dir = scan_dir;
+    pd.dk = dv; pd.st_k = base.st_v; pd.sh_k = base.sh_v; pd.sb_k = base.sb_v;
+    if (launch_dlog_alpha(pd, o_buf, dv_grad, dlog_beta, totals, stream) != hipSuccess) return GLA_ERR_HIP;
     return GLA_OK;
 }
 
@@ -393,6 +466,22 @@ int gla_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
             void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
     return run_bwd(q, k, v, log_alpha, d_out, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype,
                    dq, dk_grad, dv_grad, dlog_alpha, workspace, workspace_bytes_, static_cast<hipStream_t>(stream));
+}
+
+size_t gla_bwd_gates_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype) {
+    (void)qkv_dtype;
+    if (B <= 0 || H <= 0 || T <= 0 || dk <= 0 || dv <= 0) return 0;
+    return workspace_bytes(B, H, T, dk, dv) + bwd_totals_bytes(B, H, T, dk > dv ? dk : dv) +
+           bwd_gates_out_bytes(B, H, T, dv);
+}
+
+int gla_bwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,
+                  const void *d_out, int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                  int qkv_dtype, float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha, float *dlog_beta,
+                  void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
+    return run_bwd_gates(q, k, v, log_alpha, log_beta, d_out, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype,
+                         dq, dk_grad, dv_grad, dlog_alpha, dlog_beta, workspace, workspace_bytes_,
+                         static_cast<hipStream_t>(stream));
 }
 
 size_t gla_bwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype) {

@@ -38,8 +38,10 @@ template <> __device__ inline float load_elem<uint16_t>(const void *base, size_t
 // A tile of kTile tokens is staged in LDS (alpha and k per channel; v and w interleaved in groups of four
 // columns, as fp32), then walked token by token: the rows v_s and w_s are the same for all lanes and are read
 // as broadcasts, 16 bytes of each per ds_read_b128 pair.
-template <typename TIn>
+// BETA: the state element (c, n) decays by alpha[c] * beta[n] (two-sided gate, p.log_beta).
+template <typename TIn, bool BETA>
 __global__ __launch_bounds__(kRowWaves * 64) void row_read_kernel(Params p, const void *w, float *r) {
+    __shared__ __attribute__((aligned(16))) float s_bq[BETA ? kTile : 1][BETA ? kMaxDv / 4 : 1][4];   // beta per column
     __shared__ float s_a[kTile][kMaxDk];
     __shared__ float s_k[kTile][kMaxDk];
     __shared__ __attribute__((aligned(16))) float s_vw[kTile][kMaxDv / 4][8];   // [token][column quad][v0..v3, w0..w3]
@@ -101,6 +103,9 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_read_kernel(Params p, cons
             }
             s_vw[j][col >> 2][col & 3] = x;
             s_vw[j][col >> 2][4 + (col & 3)] = y;
+            if constexpr (BETA)
+                s_bq[j][col >> 2][col & 3] =
+                    (n >= 0 && col < dv) ? expf(p.log_beta[base_v + (size_t)s_tokg[j] * st_v + col]) : 1.f;
         }
         __syncthreads();
         for (int j = 0; j < kTile; ++j) {
@@ -111,9 +116,11 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_read_kernel(Params p, cons
                 if (quad_lo + qd < quad_hi) {   // uniform
                     const f32x4 vq = *reinterpret_cast<const f32x4 *>(&s_vw[j][quad_lo + qd][0]);
                     const f32x4 wq = *reinterpret_cast<const f32x4 *>(&s_vw[j][quad_lo + qd][4]);
+                    f32x4 bq = f32x4{1.f, 1.f, 1.f, 1.f};
+                    if constexpr (BETA) bq = *reinterpret_cast<const f32x4 *>(&s_bq[j][quad_lo + qd][0]);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        S[4 * qd + i] = fmaf(a, S[4 * qd + i], kc * vq[i]);
+                        S[4 * qd + i] = fmaf(BETA ? a * bq[i] : a, S[4 * qd + i], kc * vq[i]);
                         acc = fmaf(S[4 * qd + i], wq[i], acc);
                     }
                 }
@@ -286,7 +293,7 @@ __global__ __launch_bounds__(kDgThreads) void dg_local_kernel(Params p, const fl
 
 template <int PW>
 __global__ __launch_bounds__(kDgThreads) void dg_offset_kernel(Params p, float *dg, const float *totals, int ndg) {
-    __shared__ float s_off[kMaxDk];
+    __shared__ float s_off[kMaxDv];   // (the value-side gate gradient runs this kernel over dv columns)
     __shared__ int s_tok[kDgSpan];
     const int tid = threadIdx.x;
     const int bh = blockIdx.x / ndg, sp = blockIdx.x - bh * ndg;
@@ -317,7 +324,7 @@ __global__ __launch_bounds__(kDgThreads) void dg_offset_kernel(Params p, float *
     }
 }
 
-constexpr size_t kDgLdsMax = ((size_t)kMaxDk * kDgRow + 4 * kMaxDk + kDgSpan) * 4;
+constexpr size_t kDgLdsMax = ((size_t)kMaxDv * kDgRow + 4 * kMaxDv + kDgSpan) * 4;   // up to dv columns (log_beta)
 
 template <typename TIn, int PW>
 hipError_t launch_dg(const Params &p, const float *dq, const float *dk_grad, float *dg, float *totals, int ndg,
@@ -341,10 +348,14 @@ hipError_t launch_dg(const Params &p, const float *dq, const float *dk_grad, flo
 
 hipError_t launch_row_read(const Params &p, const void *w, float *r, hipStream_t stream) {
     dim3 grid((unsigned)(p.B * p.H * p.nspans)), block(kRowWaves * 64);
-    if (p.qkv_dtype == GLA_DT_BF16)
-        hipLaunchKernelGGL((row_read_kernel<uint16_t>), grid, block, 0, stream, p, w, r);
-    else
-        hipLaunchKernelGGL((row_read_kernel<float>), grid, block, 0, stream, p, w, r);
+    const bool bf16 = p.qkv_dtype == GLA_DT_BF16;
+    if (p.log_beta != nullptr) {
+        if (bf16) hipLaunchKernelGGL((row_read_kernel<uint16_t, true>), grid, block, 0, stream, p, w, r);
+        else hipLaunchKernelGGL((row_read_kernel<float, true>), grid, block, 0, stream, p, w, r);
+    } else {
+        if (bf16) hipLaunchKernelGGL((row_read_kernel<uint16_t, false>), grid, block, 0, stream, p, w, r);
+        else hipLaunchKernelGGL((row_read_kernel<float, false>), grid, block, 0, stream, p, w, r);
+    }
     return hipGetLastError();
 }
 

@@ -204,3 +204,52 @@ def test_fused_gates_headline_shape():
     cfg = gi.CONFIGS["dig_xl2_2048"]
     e_y, e_f, _ = _check_fused_gates(cfg.B, cfg.H, cfg.grid_h, cfg.grid_w, cfg.dk, cfg.dv, "bf16", 0, cfg.seed, True)
     assert e_y < TOL_BF16 and e_f < 2e-4
+
+
+# ---- backward pass of the two-sided-gate recurrence (gla_bwd_gates) ----
+
+def _bwd_problem(B, H, gh, gw, dk, dv, dtype, seed):
+    d = gi.make_gate_inputs(B, H, gh * gw, dk, dv, dtype, seed=seed)
+    w = np.random.Generator(np.random.PCG64(seed + 1000)).standard_normal((B, H, gh * gw, dv), dtype=np.float32)
+    if dtype == "bf16":
+        d["w_bits"] = gi.round_to_bf16_bits(w)
+        d["w"] = gi.bf16_bits_to_f32(d["w_bits"])
+    else:
+        d["w"] = w
+    return d
+
+
+def _check_bwd_gates(B, H, gh, gw, dk, dv, dtype, scan, seed, tol):
+    """Bars as for gla_bwd: per gradient tensor max |gpu - oracle| / RMS(oracle), the gate gradients against
+    RMS(oracle) or the RMS of their summands (q * dq, o * dO), whichever is larger."""
+    d = _bwd_problem(B, H, gh, gw, dk, dv, dtype, seed)
+    q, k, v, la, lb = _dev(d, dtype)
+    dev = torch.device("cuda:0")
+    if dtype == "bf16":
+        w = torch.from_numpy(d["w_bits"].view(np.int16)).to(dev).view(torch.bfloat16)
+    else:
+        w = torch.from_numpy(d["w"]).to(dev)
+    got = gla.gla_bwd_gates(q, k, v, la, lb, w, gh, gw, scan)
+    torch.cuda.synchronize()
+    ref = og.gla_bwd_gates(d["q"], d["k"], d["v"], d["log_alpha"], d["log_beta"], d["w"], gh, gw, scan)
+    o, _ = og.gla_fwd_gates(d["q"], d["k"], d["v"], d["log_alpha"], d["log_beta"], gh, gw, scan)
+    floors = [0.0, 0.0, 0.0, float(np.sqrt(np.mean((d["q"].astype(np.float64) * ref[0]) ** 2))),
+              float(np.sqrt(np.mean((o * d["w"].astype(np.float64)) ** 2)))]
+    names = ("dq", "dk", "dv", "dlog_alpha", "dlog_beta")
+    for name, g, r, fl in zip(names, got, ref, floors):
+        r = np.asarray(r)
+        rms = max(float(np.sqrt(np.mean(r * r))), fl)
+        err = float(np.abs(g.cpu().numpy().astype(np.float64) - r).max() / rms)
+        assert err < tol, (name, err)
+
+
+@pytest.mark.parametrize("dk,dv,dtype", [(36, 72, "bf16"), (32, 64, "bf16"), (20, 33, "bf16"), (64, 128, "bf16"),
+                                         (20, 33, "f32"), (36, 72, "f32")])
+@pytest.mark.parametrize("scan", [0, 3])
+def test_bwd_gates_parity(dk, dv, dtype, scan):
+    _check_bwd_gates(2, 2, 19, 23, dk, dv, dtype, scan, 81 + dk, TOL_BF16 if dtype == "bf16" else TOL_F32)
+
+
+def test_bwd_gates_single_span_and_column_scan():
+    _check_bwd_gates(1, 3, 10, 20, 36, 72, "bf16", 2, 91, TOL_BF16)
+    _check_bwd_gates(1, 2, 30, 40, 36, 72, "bf16", 1, 92, TOL_BF16)
