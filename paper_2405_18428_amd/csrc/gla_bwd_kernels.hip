@@ -36,7 +36,7 @@ template <> __device__ inline float load_elem<uint16_t>(const void *base, size_t
 // r_s[c] = sum_n S_s[c,n] w_s[n] for the scan steps of one span; S follows (p.k, p.v, p.log_alpha).
 // p.q is not used; `w` has the layout of p.v, `r` (fp32) that of p.k.
 // A tile of kTile tokens is staged in LDS (alpha and k per channel; v and w interleaved in groups of four
-// columns, as fp32), then walked token by token: the rows v_s and w_s are the same for all lanes and are read
+// columns, as fp32; fetched one tile ahead), then walked token by token: the rows v_s and w_s are the same for all lanes and are read
 // as broadcasts, 16 bytes of each per ds_read_b128 pair.
 // BETA: the state element (c, n) decays by alpha[c] * beta[n] (two-sided gate, p.log_beta).
 template <typename TIn, bool BETA>
@@ -47,7 +47,6 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_read_kernel(Params p, cons
     __shared__ __attribute__((aligned(16))) float s_vw[kTile][kMaxDv / 4][8];   // [token][column quad][v0..v3, w0..w3]
     __shared__ float s_r[kRowWaves][kTile][kMaxDk];
     __shared__ int s_tok[kTile];
-    __shared__ int s_tokg[kTile];
 
     const int tid = threadIdx.x;
     const int c = tid & 63;                                     // state row (key channel) of this lane
@@ -76,37 +75,93 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_read_kernel(Params p, cons
             if (4 * quad_lo + n < dv && n < 4 * (quad_hi - quad_lo)) S[n] = s0[4 * quad_lo + n];
     }
 
+    // The rows of a tile are fetched into registers one tile ahead (the loads of tile t + 1 are in flight while
+    // tile t is walked) and reach LDS, gates exponentiated, at the start of their own round.  Slots: the key side
+    // has token rows half, half + 2, ... of channel c; the value side has (token row, column quad) pairs
+    // tid, tid + 128, ... as 8- or 16-byte pieces when the row pitch allows it, element by element otherwise.
+    constexpr int kKSlots = kTile / kRowWaves;
+    constexpr int kVSlots = kTile * (kMaxDv / 4) / (kRowWaves * 64);
+    const bool vec = (dv % 4 == 0) && (st_v % 4 == 0) && (base_v % 4 == 0);   // uniform
+    float ra[kKSlots], rk[kKSlots];
+    f32x4 rv[kVSlots], rw[kVSlots], rb[kVSlots];
+    auto fetch = [&](int t0) {
+#pragma unroll
+        for (int m = 0; m < kKSlots; ++m) {
+            const int j = half + kRowWaves * m;
+            const bool valid = t0 + j < s_end;
+            const int sc = min(t0 + j, s_end - 1);
+            ra[m] = 0.f;      // a step past the span leaves the state alone: alpha = 1, k = 0
+            rk[m] = 0.f;
+            if (valid && row_active) {
+                const int n = scan_token(p.scan_dir, sc, T, p.grid_h, p.grid_w);
+                const int ng = scan_token(p.scan_dir, max(sc - p.gate_shift, 0), T, p.grid_h, p.grid_w);
+                ra[m] = p.log_alpha[base_k + (size_t)ng * st_k + c];
+                rk[m] = load_elem<TIn>(p.k, base_k + (size_t)n * st_k + c);
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < kVSlots; ++m) {
+            const int idx = tid + kRowWaves * 64 * m;
+            const int j = idx / nquads, col = 4 * (idx - j * nquads);
+            rv[m] = rw[m] = rb[m] = f32x4{0.f, 0.f, 0.f, 0.f};     // zero past dv and past the span (beta = 1)
+            if (j < kTile && t0 + j < s_end) {
+                const int sc = t0 + j;
+                const int n = scan_token(p.scan_dir, sc, T, p.grid_h, p.grid_w);
+                const size_t e = base_v + (size_t)n * st_v + col;
+                size_t eg = e;
+                if (BETA) eg = base_v + (size_t)scan_token(p.scan_dir, max(sc - p.gate_shift, 0), T, p.grid_h, p.grid_w) * st_v + col;
+                if (vec) {
+                    if constexpr (sizeof(TIn) == 4) {
+                        rv[m] = *reinterpret_cast<const f32x4 *>(static_cast<const float *>(p.v) + e);
+                        rw[m] = *reinterpret_cast<const f32x4 *>(static_cast<const float *>(w) + e);
+                    } else {
+                        const uint2 tv = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(p.v) + e);
+                        const uint2 tw = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(w) + e);
+                        rv[m] = f32x4{__builtin_bit_cast(float, tv.x << 16), __builtin_bit_cast(float, tv.x & 0xffff0000u),
+                                      __builtin_bit_cast(float, tv.y << 16), __builtin_bit_cast(float, tv.y & 0xffff0000u)};
+                        rw[m] = f32x4{__builtin_bit_cast(float, tw.x << 16), __builtin_bit_cast(float, tw.x & 0xffff0000u),
+                                      __builtin_bit_cast(float, tw.y << 16), __builtin_bit_cast(float, tw.y & 0xffff0000u)};
+                    }
+                    if constexpr (BETA) rb[m] = *reinterpret_cast<const f32x4 *>(p.log_beta + eg);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (col + i < dv) {
+                            rv[m][i] = load_elem<TIn>(p.v, e + i);
+                            rw[m][i] = load_elem<TIn>(w, e + i);
+                            if constexpr (BETA) rb[m][i] = p.log_beta[eg + i];
+                        }
+                    }
+                }
+            }
+        }
+    };
+    fetch(s_begin);
+
     for (int t0 = s_begin; t0 < s_end; t0 += kTile) {
         __syncthreads();
-        if (tid < kTile) {
-            const int s = min(t0 + tid, s_end - 1);
-            s_tok[tid] = (t0 + tid < s_end) ? scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w) : -1;
-            s_tokg[tid] = scan_token(p.scan_dir, max(s - p.gate_shift, 0), T, p.grid_h, p.grid_w);
-        }
-        __syncthreads();
-        // stage alpha and k of the tile (a step past the span leaves the state alone) ...
+        if (tid < kTile)
+            s_tok[tid] = (t0 + tid < s_end) ? scan_token(p.scan_dir, t0 + tid, T, p.grid_h, p.grid_w) : -1;
         if (row_active) {
-            for (int j = half; j < kTile; j += kRowWaves) {
-                const int n = s_tok[j];
-                s_a[j][c] = n >= 0 ? expf(p.log_alpha[base_k + (size_t)s_tokg[j] * st_k + c]) : 1.f;
-                s_k[j][c] = n >= 0 ? load_elem<TIn>(p.k, base_k + (size_t)n * st_k + c) : 0.f;
+#pragma unroll
+            for (int m = 0; m < kKSlots; ++m) {
+                s_a[half + kRowWaves * m][c] = expf(ra[m]);
+                s_k[half + kRowWaves * m][c] = rk[m];
             }
         }
-        // ... and its rows of v and w, zero past dv and past the span
-        for (int idx = tid; idx < kTile * 4 * nquads; idx += kRowWaves * 64) {
-            const int j = idx / (4 * nquads), col = idx - j * 4 * nquads;
-            const int n = s_tok[j];
-            float x = 0.f, y = 0.f;
-            if (n >= 0 && col < dv) {
-                x = load_elem<TIn>(p.v, base_v + (size_t)n * st_v + col);
-                y = load_elem<TIn>(w, base_v + (size_t)n * st_v + col);
+#pragma unroll
+        for (int m = 0; m < kVSlots; ++m) {
+            const int idx = tid + kRowWaves * 64 * m;
+            const int j = idx / nquads, qd = idx - j * nquads;
+            if (j < kTile) {
+                *reinterpret_cast<f32x4 *>(&s_vw[j][qd][0]) = rv[m];
+                *reinterpret_cast<f32x4 *>(&s_vw[j][qd][4]) = rw[m];
+                if constexpr (BETA)
+                    *reinterpret_cast<f32x4 *>(&s_bq[j][qd][0]) =
+                        f32x4{expf(rb[m][0]), expf(rb[m][1]), expf(rb[m][2]), expf(rb[m][3])};
             }
-            s_vw[j][col >> 2][col & 3] = x;
-            s_vw[j][col >> 2][4 + (col & 3)] = y;
-            if constexpr (BETA)
-                s_bq[j][col >> 2][col & 3] =
-                    (n >= 0 && col < dv) ? expf(p.log_beta[base_v + (size_t)s_tokg[j] * st_v + col]) : 1.f;
         }
+        if (t0 + kTile < s_end) fetch(t0 + kTile);
         __syncthreads();
         for (int j = 0; j < kTile; ++j) {
             const float a = s_a[j][c], kc = s_k[j][c];
