@@ -210,9 +210,8 @@ size_t gla_bwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtyp
  *   dlog_beta        DEVICE, fp32 [B,H,T,dv]                                           (written)
  *   workspace        DEVICE, 16-byte aligned, at least gla_bwd_gates_workspace_bytes(...) bytes
  *
- * Everything else as gla_bwd.  The span passes run on the engine gla_fwd_gates would take; the
- * reads of the state along its value axis run token by token in fp32 for every case (the MFMA
- * row-read kernels of gla_bwd know the key-side decay only).  Never allocates.
+ * Everything else as gla_bwd.  Engines as gla_fwd_gates (MFMA chunk form for bf16 rows with
+ * dk % 4 == 0, dv % 8 == 0, dk <= 40, dv <= 80; token by token in fp32 otherwise).  Never allocates.
  */
 int gla_bwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,
                   const void *d_out, int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,

@@ -200,10 +200,9 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
 }
 
 // Backward pass with the two-sided gate alpha_t^T beta_t.  Same walks as run_bwd; the adjoint state obeys
-// G_s = q_s^T dO_s + (alpha_{s+1}^T beta_{s+1}) * G_{s+1}.  The span passes run on the engine the forward call would
-// take (MFMA where it covers the case), the value-axis reads of the state on the token-by-token kernel, which
-// needs the states entering the spans in memory: the carry kernel chains them.  The value-side gate gradient is
-// the reverse cumulative sum of o * dO - v * dv, so the outputs o are recomputed first (fp32, in the workspace).
+// G_s = q_s^T dO_s + (alpha_{s+1}^T beta_{s+1}) * G_{s+1}.  Every kernel runs on the engine the forward call would
+// take.  The value-side gate gradient is the reverse cumulative sum of o * dO - v * dv, so the outputs o are
+// recomputed first (fp32, in the workspace).
 size_t bwd_gates_out_bytes(int B, int H, int T, int dv) { return align_up((size_t)B * H * T * dv * sizeof(float), 256); }
 
 int run_bwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,
@@ -234,14 +233,22 @@ int run_bwd_gates(const void *q, const void *k, const void *v, const float *log_
     bool use_mfma;
     st = choose_engine_and_plan(base, workspace, use_mfma);
     if (st != GLA_OK) return st;
-    base.chain_in_output = 0;
+    // as in run_bwd: with the MFMA engine and few spans every kernel chains the span states it needs itself
+    base.chain_in_output = use_mfma && base.nspans > 1 &&
+                           (g_opt_carry == GLA_CARRY_IN_OUTPUT_PASS ||
+                            (g_opt_carry == GLA_CARRY_AUTO && base.nspans <= kMaxChainedSpans));
     auto span = [&](const Params &p, SpanMode mode) {
         return use_mfma ? launch_mfma_span(p, mode, stream) : launch_recurrent_span(p, mode, stream);
     };
     auto states = [&](const Params &p) {
         if (p.nspans <= 1) return hipSuccess;
         hipError_t e = span(p, kModeState);
-        return e != hipSuccess ? e : launch_carry(p, stream);
+        if (e != hipSuccess || p.chain_in_output) return e;
+        return launch_carry(p, stream);
+    };
+    // value-axis reads of the state: chunk form on the MFMA units where the engine covers the case
+    auto row_read = [&](const Params &p, const void *w, float *r) {
+        return use_mfma ? launch_mfma_row_read(p, w, r, stream) : launch_row_read(p, w, r, stream);
     };
 
     // 1. forward recurrence: states entering the spans, the outputs o (for the value-side gate gradient),
@@ -250,7 +257,7 @@ int run_bwd_gates(const void *q, const void *k, const void *v, const float *log_
     pa.q = q; pa.k = k; pa.v = v; pa.scan_dir = scan_dir; pa.gate_shift = 0; pa.out = o_buf;
     if (states(pa) != hipSuccess) return GLA_ERR_HIP;
     if (span(pa, kModeOutput) != hipSuccess) return GLA_ERR_HIP;
-    if (launch_row_read(pa, d_out, dq, stream) != hipSuccess) return GLA_ERR_HIP;
+    if (row_read(pa, d_out, dq) != hipSuccess) return GLA_ERR_HIP;
 
     // 2. adjoint recurrence (k, v := q, dO; walked from the last scan step, each step with the previous step's
     //    gates): dv_s = k_s G_s (outputs with q := k), dk_s = G_s v_s
@@ -258,7 +265,7 @@ int run_bwd_gates(const void *q, const void *k, const void *v, const float *log_
     pb.q = k; pb.k = q; pb.v = d_out; pb.scan_dir = scan_dir ^ 1; pb.gate_shift = 1; pb.out = dv_grad;
     if (states(pb) != hipSuccess) return GLA_ERR_HIP;
     if (span(pb, kModeOutput) != hipSuccess) return GLA_ERR_HIP;
-    if (launch_row_read(pb, v, dk_grad, stream) != hipSuccess) return GLA_ERR_HIP;
+    if (row_read(pb, v, dk_grad) != hipSuccess) return GLA_ERR_HIP;
 
     // 3. gate gradients: reverse cumulative sums of q * dq - k * dk (key side) and of dO * o - v * dv (value
     //    side: the same kernels over the dv columns, with dO, v in the places of q, k)

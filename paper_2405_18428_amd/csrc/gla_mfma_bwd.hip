@@ -32,7 +32,7 @@
 namespace gla {
 namespace {
 
-template <int NDK8, int NDV16, bool DV>
+template <int NDK8, int NDV16, bool DV, bool BETA = false>
 struct RLayout {
     static constexpr int kDkp = NDK8 * 8;
     static constexpr int kDvp = NDV16 * 16;
@@ -60,7 +60,14 @@ struct RLayout {
     static constexpr int oStLo = oStHi + kSt;
     static constexpr int oQHi = oStLo + kSt;                              // with DV: raw q rows, then q~ hi / lo
     static constexpr int oQLo = oQHi + kRowK;
-    static constexpr int kBytes = DV ? oQLo + kRowK : oStLo + kSt;
+    static constexpr int oEndAlpha = DV ? oQLo + kRowK : oStLo + kSt;
+    // two-sided gate: raw log_beta rows, the bf16 remainders of the gated v and w rows, exp(c_C) per value column
+    static constexpr int kLbStride = kDvp + 4;
+    static constexpr int oLb = oEndAlpha;
+    static constexpr int oVLo = oLb + kChunk * kLbStride * 4;
+    static constexpr int oWLo = oVLo + kRowV;
+    static constexpr int oGamB = oWLo + kRowV;                            // float[kDvp]
+    static constexpr int kBytes = BETA ? oGamB + kDvp * 4 : oEndAlpha;
 };
 
 template <int N>
@@ -70,9 +77,15 @@ using int_c = std::integral_constant<int, N>;
 //     o_j = sum_{i<=j} (q~_j . k~_i) v_i + q~_j S_0 ,   q~_j = q_j E_j
 // as the forward kernel does, on the operands that are already in LDS.  In the backward pass the reversed
 // recurrence of G needs both: dk as the row read against v, and dv = k G as the output with q := k.
-template <int NDK8, int NDV16, int MINW, bool DV>
+// BETA = two-sided gate (p.log_beta): with c_j the inclusive sum of log_beta inside the chunk (per value column),
+// F_j = exp(c_j), v~_i = v_i / F_i and w~_j = w_j * F_j,
+//     r_j = E_j * ( sum_{i<=j} (w~_j . v~_i) k~_i + S_0 w~_j ),   S_C = diag(E_C) (S_0 + K~^T V~) diag(F_C):
+// the same contractions with v~ and w~ (bf16 hi/lo pairs, all four products) in the places of v and w.
+template <int NDK8, int NDV16, int MINW, bool DV, bool BETA = false>
 __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, const void *w_in, float *r_out) {
-    using L = RLayout<NDK8, NDV16, DV>;
+    using L = RLayout<NDK8, NDV16, DV, BETA>;
+    static_assert(!(DV && BETA), "two-sided gate: row read only");
+    constexpr int LBS = L::kLbStride;
     constexpr int NW = 4, NTHR = 256;
     constexpr int CHS = L::kChStride, VS = L::kVStride, LAS = L::kLaStride;
     constexpr int NCT = L::kNct;
@@ -94,6 +107,10 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
     uint16_t *s_stlo = reinterpret_cast<uint16_t *>(smem + L::oStLo);
     uint16_t *s_qhi = reinterpret_cast<uint16_t *>(smem + L::oQHi);
     uint16_t *s_qlo = reinterpret_cast<uint16_t *>(smem + L::oQLo);
+    float *s_lb = reinterpret_cast<float *>(smem + L::oLb);            // BETA only, like the three below
+    uint16_t *s_vlo = reinterpret_cast<uint16_t *>(smem + L::oVLo);
+    uint16_t *s_wlo = reinterpret_cast<uint16_t *>(smem + L::oWLo);
+    float *s_gamb = reinterpret_cast<float *>(smem + L::oGamB);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -125,6 +142,7 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
     const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + base_k * 4;
     char *gr = reinterpret_cast<char *>(r_out) + base_k * 4;
     const char *gq = static_cast<const char *>(p.q) + base_k * 2;
+    const char *glb = reinterpret_cast<const char *>(p.log_beta) + base_v * 4;
     char *gout = static_cast<char *>(p.out) + base_v * 4;
 
     // ---- state tiles of this wave, transposed: acc[i][ct][r] = S[c = 16 ct + lm][n = 16 (w + 4 i) + 4 g + r] ----
@@ -142,7 +160,7 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
             constexpr int kV4 = (L::kDkp * L::kDvp / 4 + NTHR - 1) / NTHR;  // float4 per thread
             constexpr int kBudget = MINW >= 2 ? 32 : 64;                    // float4 in flight
             constexpr int kRun = kBudget / kV4 > 0 ? kBudget / kV4 : 1;     // spans in flight
-            chain_span_states<NTHR, kV4, kRun>(p, bh, sp, tid, reinterpret_cast<float *>(smem));
+            chain_span_states<NTHR, kV4, kRun, BETA>(p, bh, sp, tid, reinterpret_cast<float *>(smem));
         }
         __syncthreads();
         if (chain) {
@@ -212,6 +230,7 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
     u32x2 r_k[kF];
     u32x2 r_q[DV ? kF : 1];
     u32x4 r_v[kVF], r_w[kVF];
+    f32x4 r_lb[BETA ? kVF : 1][2];   // log_beta of the same 8 columns as the v piece
     auto load_chunk = [&](int chunk) {
         const int *tok = s_tok + (chunk % NTB) * kChunk;
         const int *tokg = s_tokg + (chunk % NTB) * kChunk;
@@ -228,6 +247,11 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
             const uint32_t e2 = (uint32_t)tok[fvrp[m] >> 8] * dv2 + 16u * (uint32_t)(fvrp[m] & 255);
             r_v[m] = *reinterpret_cast<const u32x4 *>(gv + e2);
             r_w[m] = *reinterpret_cast<const u32x4 *>(gw + e2);
+            if constexpr (BETA) {
+                const char *lbp = glb + 2u * ((uint32_t)tokg[fvrp[m] >> 8] * dv2 + 16u * (uint32_t)(fvrp[m] & 255));
+                r_lb[m][0] = *reinterpret_cast<const f32x4 *>(lbp);
+                r_lb[m][1] = *reinterpret_cast<const f32x4 *>(lbp + 16);
+            }
         }
     };
     load_chunk(0);
@@ -250,6 +274,7 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                 if ((fvrp[m] >> 8) >= nvalid) {
                     r_v[m] = u32x4{0, 0, 0, 0};
                     r_w[m] = u32x4{0, 0, 0, 0};
+                    if constexpr (BETA) r_lb[m][0] = r_lb[m][1] = f32x4{0.f, 0.f, 0.f, 0.f};
                 }
             }
         }
@@ -268,6 +293,10 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                 const int row = fvrp[m] >> 8, col = 8 * (fvrp[m] & 255);
                 *reinterpret_cast<u32x4 *>(s_v + row * VS + col) = r_v[m];
                 *reinterpret_cast<u32x4 *>(s_w + row * VS + col) = r_w[m];
+                if constexpr (BETA) {
+                    *reinterpret_cast<f32x4 *>(s_lb + row * LBS + col) = r_lb[m][0];
+                    *reinterpret_cast<f32x4 *>(s_lb + row * LBS + col + 4) = r_lb[m][1];
+                }
             }
         }
         load_chunk(chunk + 1);   // past the span the clamped token map keeps the loads in bounds
@@ -330,6 +359,39 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                 *reinterpret_cast<f32x4 *>(s_la + j * LAS + c0) = e;      // E_j in place of the raw gates
                 if (lane == 63) *reinterpret_cast<f32x4 *>(s_gam + c0) = e;
             }
+            if constexpr (BETA) {
+                // value side, 8-column units dealt from the last wave: v~ = v / F and w~ = w F as bf16 hi/lo
+                for (int c0 = 8 * (NW - 1 - w); c0 < dv; c0 += 8 * NW) {
+                    float cc[8];
+#pragma unroll
+                    for (int v4 = 0; v4 < 2; ++v4) {
+                        const f32x4 x = *reinterpret_cast<const f32x4 *>(s_lb + j * LBS + c0 + 4 * v4);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) cc[4 * v4 + i] = x[i] * kLog2e;
+                        wave_inclusive_scan4(cc[4 * v4], cc[4 * v4 + 1], cc[4 * v4 + 2], cc[4 * v4 + 3]);
+                    }
+                    const u32x4 vr = *reinterpret_cast<const u32x4 *>(s_v + j * VS + c0);
+                    const u32x4 wr = *reinterpret_cast<const u32x4 *>(s_w + j * VS + c0);
+                    u32x4 vh, vl, wh, wl;
+                    float f[8];
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        f[2 * h] = exp2_fast(cc[2 * h]);
+                        f[2 * h + 1] = exp2_fast(cc[2 * h + 1]);
+                        SPLIT_PAIR(bf16_lo_as_float(vr[h]) * exp2_fast(fminf(-cc[2 * h], kMaxExp2)),
+                                   bf16_hi_as_float(vr[h]) * exp2_fast(fminf(-cc[2 * h + 1], kMaxExp2)), vh[h], vl[h]);
+                        SPLIT_PAIR(bf16_lo_as_float(wr[h]) * f[2 * h], bf16_hi_as_float(wr[h]) * f[2 * h + 1], wh[h], wl[h]);
+                    }
+                    *reinterpret_cast<u32x4 *>(s_v + j * VS + c0) = vh;
+                    *reinterpret_cast<u32x4 *>(s_vlo + j * VS + c0) = vl;
+                    *reinterpret_cast<u32x4 *>(s_w + j * VS + c0) = wh;
+                    *reinterpret_cast<u32x4 *>(s_wlo + j * VS + c0) = wl;
+                    if (lane == 63) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) s_gamb[c0 + i] = f[i];
+                    }
+                }
+            }
         }
         __syncthreads();
 
@@ -346,10 +408,13 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
             const uint16_t *krow_h = s_khi + (4 * g + tr_row) * CHS + tr_col;
             const uint16_t *krow_l = s_klo + (4 * g + tr_row) * CHS + tr_col;
             const uint16_t *vrow = s_v + (4 * g + tr_row) * VS + tr_col;
-            u32x4 wf[KSV];
+            const uint16_t *vrow_l = s_vlo + (4 * g + tr_row) * VS + tr_col;   // BETA
+            u32x4 wf[KSV], wfl[BETA ? KSV : 1];
 #pragma unroll
-            for (int ks = 0; ks < KSV; ++ks)
+            for (int ks = 0; ks < KSV; ++ks) {
                 wf[ks] = *reinterpret_cast<const u32x4 *>(s_w + (16 * IT + lm) * VS + coln[ks]);
+                if constexpr (BETA) wfl[ks] = *reinterpret_cast<const u32x4 *>(s_wlo + (16 * IT + lm) * VS + coln[ks]);
+            }
             u32x4 kth[2][NCT], ktl[2][NCT];   // K~ over tokens: [32-token step][channel tile]
             auto load_k = [&](int q) {
 #pragma unroll
@@ -378,6 +443,12 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                         for (int ks = 0; ks < KSV; ++ks) {
                             const u32x4 vf = *reinterpret_cast<const u32x4 *>(s_v + (16 * jt + lm) * VS + coln[ks]);
                             d = mfma(vf, wf[ks], d);
+                            if constexpr (BETA) {
+                                const u32x4 vfl = *reinterpret_cast<const u32x4 *>(s_vlo + (16 * jt + lm) * VS + coln[ks]);
+                                d = mfma(vf, wfl[ks], d);
+                                d = mfma(vfl, wf[ks], d);
+                                d = mfma(vfl, wfl[ks], d);
+                            }
                         }
                         if (jt == IT) {
 #pragma unroll
@@ -408,6 +479,10 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                     const u32x4 sl = *reinterpret_cast<const u32x4 *>(s_stlo + srow);
                     rr[ct] = mfma(sh, wf[ks], rr[ct]);
                     rr[ct] = mfma(sl, wf[ks], rr[ct]);
+                    if constexpr (BETA) {
+                        rr[ct] = mfma(sh, wfl[ks], rr[ct]);
+                        rr[ct] = mfma(sl, wfl[ks], rr[ct]);
+                    }
                 }
             }
             // scale by E and store: lane (lm, g) holds channels 16 ct + 4 g .. + 3 of token 16 IT + lm
@@ -526,13 +601,20 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
             for (int i = 0; i < TPW; ++i) {
                 const int nt = IT + NW * i;
                 if (nt < NDV16) {
-                    u32x4 vt[2];
+                    u32x4 vt[2], vtl[BETA ? 2 : 1];
 #pragma unroll
                     for (int q = 0; q < 2; ++q) {
                         const u32x2 v0 = lds_read_tr(vrow + 32 * q * VS + 16 * nt);
                         const u32x2 v1 = lds_read_tr(vrow + (32 * q + 16) * VS + 16 * nt);
                         vt[q] = u32x4{v0[0], v0[1], v1[0], v1[1]};
+                        if constexpr (BETA) {
+                            const u32x2 l0 = lds_read_tr(vrow_l + 32 * q * VS + 16 * nt);
+                            const u32x2 l1 = lds_read_tr(vrow_l + (32 * q + 16) * VS + 16 * nt);
+                            vtl[q] = u32x4{l0[0], l0[1], l1[0], l1[1]};
+                        }
                     }
+                    f32x4 gb = f32x4{1.f, 1.f, 1.f, 1.f};     // BETA: decay of this lane's four value columns
+                    if constexpr (BETA) gb = *reinterpret_cast<const f32x4 *>(s_gamb + 16 * nt + 4 * g);
 #pragma unroll
                     for (int ct = 0; ct < NCT; ++ct) {
                         f32x4 a = acc[i][ct];
@@ -540,9 +622,13 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                         for (int q = 0; q < 2; ++q) {
                             a = mfma(vt[q], kth[q][ct], a);
                             a = mfma(vt[q], ktl[q][ct], a);
+                            if constexpr (BETA) {
+                                a = mfma(vtl[q], kth[q][ct], a);
+                                a = mfma(vtl[q], ktl[q][ct], a);
+                            }
                         }
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) a[r] *= gm[ct];
+                        for (int r = 0; r < 4; ++r) a[r] *= BETA ? gm[ct] * gb[r] : gm[ct];
                         acc[i][ct] = a;
                     }
                 }
@@ -558,12 +644,12 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
     }
 }
 
-template <int NDK8, int NDV16, bool DV>
+template <int NDK8, int NDV16, bool DV, bool BETA = false>
 hipError_t launch_one(const Params &p, const void *w, float *r, hipStream_t stream) {
-    using L = RLayout<NDK8, NDV16, DV>;
+    using L = RLayout<NDK8, NDV16, DV, BETA>;
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int MINW = kGroupsPerCu >= 2 ? 2 : 1;
-    auto kernel = mfma_row_read_kernel<NDK8, NDV16, MINW, DV>;
+    auto kernel = mfma_row_read_kernel<NDK8, NDV16, MINW, DV, BETA>;
     static bool configured[kMaxDevices] = {};  // per instantiation and device
     {
         hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), L::kBytes, configured);
@@ -577,6 +663,13 @@ hipError_t launch_one(const Params &p, const void *w, float *r, hipStream_t stre
 template <bool DV>
 hipError_t launch_sizes(const Params &p, const void *w, float *r, hipStream_t stream) {
     const int ndk8 = (p.dk + 7) / 8, ndv16 = (p.dv + 15) / 16;
+    if constexpr (!DV) {
+        if (p.log_beta != nullptr) {   // two-sided gate: the head sizes whose extra rows fit the LDS (dk <= 40, dv <= 80)
+            if (ndk8 <= 4 && ndv16 <= 4) return launch_one<4, 4, false, true>(p, w, r, stream);
+            if (ndk8 <= 5 && ndv16 <= 5) return launch_one<5, 5, false, true>(p, w, r, stream);
+            return hipErrorInvalidConfiguration;
+        }
+    }
     if (ndk8 <= 4 && ndv16 <= 4) return launch_one<4, 4, DV>(p, w, r, stream);
     if (ndk8 <= 5 && ndv16 <= 5) return launch_one<5, 5, DV>(p, w, r, stream);
     return launch_one<8, 8, DV>(p, w, r, stream);
