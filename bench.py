@@ -268,9 +268,14 @@ def bench_bwd_gates(args, cfg, gla, gi, torch, np):
     sets = [[t.to(dev) for t in host] + [torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)]
             for _ in range(max(1, min(args.sets, 2)))]
 
+    outs = None
+    if args.reuse_fwd:      # the fp32 outputs of the forward call are handed over instead of being recomputed
+        outs = [gla.gla_fwd_gates(s_[0], s_[1], s_[2], s_[4], s_[5], cfg.grid_h, cfg.grid_w, args.scan)[0] for s_ in sets]
+
     def step(i):
         q, k, v, wt, la, lb, ws = sets[i % len(sets)]
-        return gla.gla_bwd_gates(q, k, v, la, lb, wt, cfg.grid_h, cfg.grid_w, args.scan, workspace=ws)
+        return gla.gla_bwd_gates(q, k, v, la, lb, wt, cfg.grid_h, cfg.grid_w, args.scan, workspace=ws,
+                                 out_fwd=outs[i % len(sets)] if outs else None)
 
     for i in range(args.warmup):
         step(i)
@@ -475,7 +480,8 @@ def main():
     ap.add_argument("--layout", default="bhtd", choices=["bhtd", "bthd"],
                     help="memory order of q, k, v, log_alpha, out: [B,H,T,d] (the headline) or [B,T,H,d]")
     ap.add_argument("--reuse-fwd", action="store_true",
-                    help="with --pass bwd: take the span states of S from the forward call's workspace (gla_bwd_reuse)")
+                    help="with --pass bwd: take the span states of S from the forward call's workspace (gla_bwd_reuse); "
+                         "with --pass bwdgates: hand the forward outputs to gla_bwd_gates")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--no-cache-resident", action="store_true",

@@ -207,6 +207,8 @@ size_t gla_bwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtyp
  *                                                                           recomputed in the workspace).
  *
  *   log_beta         DEVICE, fp32 [B,H,T,dv]                                           (read)
+ *   out_fwd          DEVICE, fp32 [B,H,T,dv]: `out` of gla_fwd_gates on the same inputs, or NULL
+ *                    (the outputs are then recomputed, one more pass over the sequence)          (read)
  *   dlog_beta        DEVICE, fp32 [B,H,T,dv]                                           (written)
  *   workspace        DEVICE, 16-byte aligned, at least gla_bwd_gates_workspace_bytes(...) bytes
  *
@@ -214,7 +216,7 @@ size_t gla_bwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtyp
  * dk % 4 == 0, dv % 8 == 0, dk <= 40, dv <= 80; token by token in fp32 otherwise).  Never allocates.
  */
 int gla_bwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,
-                  const void *d_out, int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                  const void *d_out, const float *out_fwd, int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
                   int qkv_dtype, float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha, float *dlog_beta,
                   void *workspace, size_t workspace_bytes, gla_stream_t stream);
 size_t gla_bwd_gates_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtype);

@@ -78,7 +78,7 @@ def load_library():
     lib.gla_fwd_fused_gates.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, ctypes.c_float] + shape + \
         [i, i, vp, vp, vp, sz, vp]
     lib.gla_bwd_gates.restype = i
-    lib.gla_bwd_gates.argtypes = [vp] * 6 + shape + [i] + [vp] * 5 + [vp, sz, vp]
+    lib.gla_bwd_gates.argtypes = [vp] * 7 + shape + [i] + [vp] * 5 + [vp, sz, vp]
     lib.gla_bwd_gates_workspace_bytes.restype = sz
     lib.gla_bwd_gates_workspace_bytes.argtypes = [i] * 6
     lib.gla_bwd_workspace_bytes.restype = sz
@@ -402,9 +402,10 @@ def gla_fwd_fused_gates(q, k, v, z_alpha, z_beta, tau, grid_h, grid_w, scan_dir=
     return gla_fwd_fused(q, k, v, z_alpha, tau, grid_h, grid_w, scan_dir, _z_beta=z_beta, **kwargs)
 
 
-def gla_bwd_gates(q, k, v, log_alpha, log_beta, d_out, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, workspace=None,
-                  stream=None):
-    """Gradients of the two-sided-gate recurrence: returns (dq, dk, dv, dlog_alpha, dlog_beta), all fp32."""
+def gla_bwd_gates(q, k, v, log_alpha, log_beta, d_out, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, out_fwd=None,
+                  workspace=None, stream=None):
+    """Gradients of the two-sided-gate recurrence: returns (dq, dk, dv, dlog_alpha, dlog_beta), all fp32.
+    ``out_fwd``: the fp32 outputs of gla_fwd_gates on the same inputs, if the caller still holds them."""
     torch = _torch()
     lib = load_library()
     for name, t in (("q", q), ("k", k), ("v", v), ("log_alpha", log_alpha), ("log_beta", log_beta), ("d_out", d_out)):
@@ -420,6 +421,9 @@ def gla_bwd_gates(q, k, v, log_alpha, log_beta, d_out, grid_h, grid_w, scan_dir=
     B, H, T, dk = q.shape
     dv = v.shape[3]
     qdt = _dt(q)
+    if out_fwd is not None and (out_fwd.dtype != torch.float32 or out_fwd.shape != v.shape or not out_fwd.is_cuda
+                                or not out_fwd.is_contiguous()):
+        raise ValueError("out_fwd must be a contiguous fp32 GPU tensor shaped like v")
     f32 = dict(dtype=torch.float32, device=q.device)
     dq, dk_g, dla = (torch.empty((B, H, T, dk), **f32) for _ in range(3))
     dv_g, dlb = (torch.empty((B, H, T, dv), **f32) for _ in range(2))
@@ -428,7 +432,8 @@ def gla_bwd_gates(q, k, v, log_alpha, log_beta, d_out, grid_h, grid_w, scan_dir=
         workspace = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=q.device)
     with torch.cuda.device(q.device):
         _check(lib.gla_bwd_gates(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(), log_beta.data_ptr(),
-                                 d_out.data_ptr(), B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt,
+                                 d_out.data_ptr(), out_fwd.data_ptr() if out_fwd is not None else None,
+                                 B, H, T, dk, dv, grid_h, grid_w, scan_dir, qdt,
                                  dq.data_ptr(), dk_g.data_ptr(), dv_g.data_ptr(), dla.data_ptr(), dlb.data_ptr(),
                                  workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dq, dk_g, dv_g, dla, dlb

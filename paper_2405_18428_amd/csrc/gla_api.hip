@@ -206,14 +206,14 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
 size_t bwd_gates_out_bytes(int B, int H, int T, int dv) { return align_up((size_t)B * H * T * dv * sizeof(float), 256); }
 
 int run_bwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,
-                  const void *d_out, int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                  const void *d_out, const float *out_fwd, int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
                   int qkv_dtype, float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha, float *dlog_beta,
                   void *workspace, size_t ws_bytes, hipStream_t stream) {
     if (!log_beta || !d_out || !dq || !dk_grad || !dv_grad || !dlog_alpha || !dlog_beta) return GLA_ERR_NULL;
     int st = validate(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir,
                       qkv_dtype, GLA_DT_F32, dv_grad, nullptr);
     if (st != GLA_OK) return st;
-    if (misaligned(log_beta) || misaligned(d_out) || misaligned(dq) || misaligned(dk_grad) || misaligned(dlog_alpha) ||
+    if (misaligned(log_beta) || misaligned(d_out) || misaligned(out_fwd) || misaligned(dq) || misaligned(dk_grad) || misaligned(dlog_alpha) ||
         misaligned(dlog_beta))
         return GLA_ERR_ALIGN;
     const size_t state_bytes = workspace_bytes(B, H, T, dk, dv);
@@ -256,7 +256,7 @@ int run_bwd_gates(const void *q, const void *k, const void *v, const float *log_
     Params pa = base;
     pa.q = q; pa.k = k; pa.v = v; pa.scan_dir = scan_dir; pa.gate_shift = 0; pa.out = o_buf;
     if (states(pa) != hipSuccess) return GLA_ERR_HIP;
-    if (span(pa, kModeOutput) != hipSuccess) return GLA_ERR_HIP;
+    if (!out_fwd && span(pa, kModeOutput) != hipSuccess) return GLA_ERR_HIP;   // (the caller may still hold o)
     if (row_read(pa, d_out, dq) != hipSuccess) return GLA_ERR_HIP;
 
     // 2. adjoint recurrence (k, v := q, dO; walked from the last scan step, each step with the previous step's
@@ -275,7 +275,8 @@ int run_bwd_gates(const void *q, const void *k, const void *v, const float *log_
     Params pd = base;
     pd.q = d_out; pd.k = v; pd.scan_dir = scan_dir;
     pd.dk = dv; pd.st_k = base.st_v; pd.sh_k = base.sh_v; pd.sb_k = base.sb_v;
-    if (launch_dlog_alpha(pd, o_buf, dv_grad, dlog_beta, totals, stream) != hipSuccess) return GLA_ERR_HIP;
+    if (launch_dlog_alpha(pd, out_fwd ? out_fwd : o_buf, dv_grad, dlog_beta, totals, stream) != hipSuccess)
+        return GLA_ERR_HIP;
     return GLA_OK;
 }
 
@@ -483,10 +484,10 @@ size_t gla_bwd_gates_workspace_bytes(int B, int H, int T, int dk, int dv, int qk
 }
 
 int gla_bwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,
-                  const void *d_out, int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                  const void *d_out, const float *out_fwd, int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
                   int qkv_dtype, float *dq, float *dk_grad, float *dv_grad, float *dlog_alpha, float *dlog_beta,
                   void *workspace, size_t workspace_bytes_, gla_stream_t stream) {
-    return run_bwd_gates(q, k, v, log_alpha, log_beta, d_out, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype,
+    return run_bwd_gates(q, k, v, log_alpha, log_beta, d_out, out_fwd, B, H, T, dk, dv, grid_h, grid_w, scan_dir, qkv_dtype,
                          dq, dk_grad, dv_grad, dlog_alpha, dlog_beta, workspace, workspace_bytes_,
                          static_cast<hipStream_t>(stream));
 }

@@ -250,6 +250,19 @@ def test_bwd_gates_parity(dk, dv, dtype, scan):
     _check_bwd_gates(2, 2, 19, 23, dk, dv, dtype, scan, 81 + dk, TOL_BF16 if dtype == "bf16" else TOL_F32)
 
 
+def test_bwd_gates_with_the_forward_outputs_given():
+    """The caller may pass the outputs of gla_fwd_gates instead of having them recomputed: same gradients."""
+    d = _bwd_problem(1, 2, 30, 40, 36, 72, "bf16", 97)
+    q, k, v, la, lb = _dev(d, "bf16")
+    w = torch.from_numpy(d["w_bits"].view(np.int16)).cuda().view(torch.bfloat16)
+    out, _ = gla.gla_fwd_gates(q, k, v, la, lb, 30, 40, 1)
+    a = gla.gla_bwd_gates(q, k, v, la, lb, w, 30, 40, 1)
+    b = gla.gla_bwd_gates(q, k, v, la, lb, w, 30, 40, 1, out_fwd=out)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
 def test_bwd_gates_single_span_and_column_scan():
     _check_bwd_gates(1, 3, 10, 20, 36, 72, "bf16", 2, 91, TOL_BF16)
     _check_bwd_gates(1, 2, 30, 40, 36, 72, "bf16", 1, 92, TOL_BF16)
