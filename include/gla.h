@@ -2,12 +2,14 @@
  * gla.h - C ABI of the MI355X (gfx950) implementation of the gated-linear-attention
  * (GLA) token mixer used in the DiG diffusion backbone: the forward pass (gla_fwd*),
  * its variants with the gate prologue and output epilogue (gla_fwd_fused) and with
- * several scan orders summed (gla_fwd_multi), the backward pass (gla_bwd*), and the
- * depth-wise convolution of the DiG block's reorientation module (gla_srem_dwconv).
+ * several scan orders summed (gla_fwd_multi), the backward pass (gla_bwd*), the same
+ * with the full gate matrix alpha_t^T beta_t (gla_fwd_gates, gla_fwd_fused_gates,
+ * gla_bwd_gates), and the depth-wise convolution of the DiG block's reorientation
+ * module (gla_srem_dwconv).
  *
  * Operation (DiG paper, Sec. 3.1 "Gated Linear Attention Transformer",
  * Eq. (attn_gla), rows 1-3, with the gate G_t reduced to its key-side factor
- * alpha_t, i.e. beta_t = 1):
+ * alpha_t, i.e. beta_t = 1, except in the *_gates entry points):
  *
  *     S_t = diag(alpha_t) S_{t-1} + k_t^T v_t ,     o_t = q_t S_t ,     S_0 = 0
  *
