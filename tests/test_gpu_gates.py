@@ -283,3 +283,21 @@ def test_bwd_gates_engines_and_span_chaining(engine, carry):
         gla.gla_set_option(gla.OPT_ENGINE, gla.ENGINE_AUTO)
         gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_AUTO)
         gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 0)
+
+
+def test_bwd_gates_headline_shape_first_two_heads():
+    """The launch configuration the benchmark times (B = 1, H = 16, T = 16384); the oracle keeps every state of a
+    sequence, so it is run on the first two heads only (heads are independent) and those are compared."""
+    cfg = gi.CONFIGS["dig_xl2_2048"]
+    d = _bwd_problem(cfg.B, cfg.H, cfg.grid_h, cfg.grid_w, cfg.dk, cfg.dv, "bf16", cfg.seed)
+    q, k, v, la, lb = _dev(d, "bf16")
+    w = torch.from_numpy(d["w_bits"].view(np.int16)).cuda().view(torch.bfloat16)
+    got = gla.gla_bwd_gates(q, k, v, la, lb, w, cfg.grid_h, cfg.grid_w, 0)
+    torch.cuda.synchronize()
+    hs = slice(0, 2)
+    ref = og.gla_bwd_gates(d["q"][:, hs], d["k"][:, hs], d["v"][:, hs], d["log_alpha"][:, hs], d["log_beta"][:, hs],
+                           d["w"][:, hs], cfg.grid_h, cfg.grid_w, 0)
+    for name, g, r in zip(("dq", "dk", "dv", "dlog_alpha", "dlog_beta"), got, ref):
+        rms = float(np.sqrt(np.mean(r * r)))
+        err = float(np.abs(g[:, hs].cpu().numpy().astype(np.float64) - r).max() / rms)
+        assert err < TOL_BF16, (name, err)
