@@ -264,8 +264,13 @@ int run_bwd_gates(const void *q, const void *k, const void *v, const float *log_
     Params pb = base;
     pb.q = k; pb.k = q; pb.v = d_out; pb.scan_dir = scan_dir ^ 1; pb.gate_shift = 1; pb.out = dv_grad;
     if (states(pb) != hipSuccess) return GLA_ERR_HIP;
-    if (span(pb, kModeOutput) != hipSuccess) return GLA_ERR_HIP;
-    if (row_read(pb, v, dk_grad) != hipSuccess) return GLA_ERR_HIP;
+    if (use_mfma && !g_opt_bwd_split) {
+        // one walk over the chunks of G for both dk (row read) and dv (outputs with q := k)
+        if (launch_mfma_row_read(pb, v, dk_grad, stream, true) != hipSuccess) return GLA_ERR_HIP;
+    } else {
+        if (span(pb, kModeOutput) != hipSuccess) return GLA_ERR_HIP;
+        if (row_read(pb, v, dk_grad) != hipSuccess) return GLA_ERR_HIP;
+    }
 
     // 3. gate gradients: reverse cumulative sums of q * dq - k * dk (key side) and of dO * o - v * dv (value
     //    side: the same kernels over the dv columns, with dO, v in the places of q, k)

@@ -80,11 +80,11 @@ using int_c = std::integral_constant<int, N>;
 // BETA = two-sided gate (p.log_beta): with c_j the inclusive sum of log_beta inside the chunk (per value column),
 // F_j = exp(c_j), v~_i = v_i / F_i and w~_j = w_j * F_j,
 //     r_j = E_j * ( sum_{i<=j} (w~_j . v~_i) k~_i + S_0 w~_j ),   S_C = diag(E_C) (S_0 + K~^T V~) diag(F_C):
-// the same contractions with v~ and w~ (bf16 hi/lo pairs, all four products) in the places of v and w.
+// the same contractions with v~ and w~ (bf16 hi/lo pairs, all four products) in the places of v and w; with DV the
+// outputs are o_j = F_j * (sum_{i<=j} (q~_j . k~_i) v~_i + q~_j S_0) (F_j is left in place of the raw log_beta row).
 template <int NDK8, int NDV16, int MINW, bool DV, bool BETA = false>
 __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, const void *w_in, float *r_out) {
     using L = RLayout<NDK8, NDV16, DV, BETA>;
-    static_assert(!(DV && BETA), "two-sided gate: row read only");
     constexpr int LBS = L::kLbStride;
     constexpr int NW = 4, NTHR = 256;
     constexpr int CHS = L::kChStride, VS = L::kVStride, LAS = L::kLaStride;
@@ -386,6 +386,10 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                     *reinterpret_cast<u32x4 *>(s_vlo + j * VS + c0) = vl;
                     *reinterpret_cast<u32x4 *>(s_w + j * VS + c0) = wh;
                     *reinterpret_cast<u32x4 *>(s_wlo + j * VS + c0) = wl;
+                    if constexpr (DV) {
+                        *reinterpret_cast<f32x4 *>(s_lb + j * LBS + c0) = f32x4{f[0], f[1], f[2], f[3]};
+                        *reinterpret_cast<f32x4 *>(s_lb + j * LBS + c0 + 4) = f32x4{f[4], f[5], f[6], f[7]};
+                    }
                     if (lane == 63) {
 #pragma unroll
                         for (int i = 0; i < 8; ++i) s_gamb[c0 + i] = f[i];
@@ -551,6 +555,13 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                         const u32x4 vf = u32x4{v0[0], v0[1], v1[0], v1[1]};
                         o[x] = mfma(vf, bh2, o[x]);
                         o[x] = mfma(vf, bl2, o[x]);
+                        if constexpr (BETA) {
+                            const u32x2 l0 = lds_read_tr(vrow_l + 32 * q * VS + 16 * x);
+                            const u32x2 l1 = lds_read_tr(vrow_l + (32 * q + 16) * VS + 16 * x);
+                            const u32x4 vfl = u32x4{l0[0], l0[1], l1[0], l1[1]};
+                            o[x] = mfma(vfl, bh2, o[x]);
+                            o[x] = mfma(vfl, bl2, o[x]);
+                        }
                     }
                 }
                 // + Q~ S_0: the state rows (channel-major in LDS) are read transposed, so the channels of a 32-channel
@@ -587,8 +598,16 @@ __global__ __launch_bounds__(256, MINW) void mfma_row_read_kernel(Params p, cons
                 if (row < nvalid) {
                     char *orow2 = gout + ((uint32_t)tok[row] * (uint32_t)p.st_v + 4u * (uint32_t)g) * 4u;
 #pragma unroll
-                    for (int x = 0; x < NX; ++x)
-                        if (4 * g + 16 * x < dv) *reinterpret_cast<f32x4 *>(orow2 + 64 * x) = o[x];
+                    for (int x = 0; x < NX; ++x) {
+                        if (4 * g + 16 * x < dv) {
+                            if constexpr (BETA) {   // row j of the outputs carries F_j per value column
+                                const f32x4 f4 = *reinterpret_cast<const f32x4 *>(s_lb + row * LBS + 16 * x + 4 * g);
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) o[x][r] *= f4[r];
+                            }
+                            *reinterpret_cast<f32x4 *>(orow2 + 64 * x) = o[x];
+                        }
+                    }
                 }
             }
             // state update on this wave's tiles: S^T += V^T K~, then the chunk's decay per channel
@@ -663,12 +682,10 @@ hipError_t launch_one(const Params &p, const void *w, float *r, hipStream_t stre
 template <bool DV>
 hipError_t launch_sizes(const Params &p, const void *w, float *r, hipStream_t stream) {
     const int ndk8 = (p.dk + 7) / 8, ndv16 = (p.dv + 15) / 16;
-    if constexpr (!DV) {
-        if (p.log_beta != nullptr) {   // two-sided gate: the head sizes whose extra rows fit the LDS (dk <= 40, dv <= 80)
-            if (ndk8 <= 4 && ndv16 <= 4) return launch_one<4, 4, false, true>(p, w, r, stream);
-            if (ndk8 <= 5 && ndv16 <= 5) return launch_one<5, 5, false, true>(p, w, r, stream);
-            return hipErrorInvalidConfiguration;
-        }
+    if (p.log_beta != nullptr) {   // two-sided gate: the head sizes whose extra rows fit the LDS (dk <= 40, dv <= 80)
+        if (ndk8 <= 4 && ndv16 <= 4) return launch_one<4, 4, DV, true>(p, w, r, stream);
+        if (ndk8 <= 5 && ndv16 <= 5) return launch_one<5, 5, DV, true>(p, w, r, stream);
+        return hipErrorInvalidConfiguration;
     }
     if (ndk8 <= 4 && ndv16 <= 4) return launch_one<4, 4, DV>(p, w, r, stream);
     if (ndk8 <= 5 && ndv16 <= 5) return launch_one<5, 5, DV>(p, w, r, stream);

@@ -268,11 +268,13 @@ def test_bwd_gates_single_span_and_column_scan():
     _check_bwd_gates(1, 2, 30, 40, 36, 72, "bf16", 1, 92, TOL_BF16)
 
 
-@pytest.mark.parametrize("engine,carry", [("auto", "in_output"), ("auto", "kernel"), ("recurrent", "auto")])
-def test_bwd_gates_engines_and_span_chaining(engine, carry):
-    """The value-axis reads run in chunk form on the MFMA units or token by token; the span states are chained by
-    the kernels themselves or by the carry kernel."""
+@pytest.mark.parametrize("engine,carry,split", [("auto", "in_output", 0), ("auto", "kernel", 0), ("auto", "auto", 1),
+                                                ("recurrent", "auto", 0)])
+def test_bwd_gates_engines_and_span_chaining(engine, carry, split):
+    """The value-axis reads run in chunk form on the MFMA units (dk and dv in one walk, or split) or token by token;
+    the span states are chained by the kernels themselves or by the carry kernel."""
     gla.gla_set_option(gla.OPT_ENGINE, gla.ENGINE_RECURRENT if engine == "recurrent" else gla.ENGINE_AUTO)
+    gla.gla_set_option(gla.OPT_BWD_SPLIT, split)
     gla.gla_set_option(gla.OPT_CARRY, {"in_output": gla.CARRY_IN_OUTPUT_PASS, "kernel": gla.CARRY_KERNEL,
                                        "auto": gla.CARRY_AUTO}[carry])
     gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 3)
@@ -283,6 +285,7 @@ def test_bwd_gates_engines_and_span_chaining(engine, carry):
         gla.gla_set_option(gla.OPT_ENGINE, gla.ENGINE_AUTO)
         gla.gla_set_option(gla.OPT_CARRY, gla.CARRY_AUTO)
         gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 0)
+        gla.gla_set_option(gla.OPT_BWD_SPLIT, 0)
 
 
 def test_bwd_gates_headline_shape_first_two_heads():
