@@ -124,6 +124,28 @@ int gla_fwd(const void *q, const void *k, const void *v, const float *log_alpha,
             float *out, float *final_state, gla_stream_t stream);
 
 /*
+ * gla_fwd_static - gla_fwd for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and status codes as gla_fwd; the span states live in a static
+ * device array of GLA_STATIC_SCRATCH_BYTES that every GPU the library runs on holds
+ * until the process ends.  The call itself makes no hipMalloc / hipFree and uses no
+ * allocating library routine; the kernels it launches are gla_fwd's.
+ *
+ * GLA_ERR_WORKSPACE if the launch plan of the problem needs more than the array holds
+ * (B * H * spans * (dk * dv + dk + dv) floats, spans = 64-token chunks / chunks per
+ * work-group; the DiG-XL/2 shape at 2048 px uses about 7 MiB); nothing is enqueued then.
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (different
+ * streams or threads) race.  Nothing in it needs clearing between calls: every call
+ * writes the span states before it reads them.  As for every entry point that takes a
+ * workspace, the first call of a kernel variant in the process configures it
+ * (hipFuncSetAttribute); make one call outside graph capture before capturing.
+ */
+#define GLA_STATIC_SCRATCH_BYTES (16u << 20)
+int gla_fwd_static(const void *q, const void *k, const void *v, const float *log_alpha,
+                   int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                   float *out, float *final_state, gla_stream_t stream);
+
+/*
  * gla_fwd_ex - the same operation with explicit element types and a caller-owned
  * workspace; never allocates.
  *

@@ -55,6 +55,8 @@ def load_library():
     shape = [i] * 8
     lib.gla_fwd.restype = i
     lib.gla_fwd.argtypes = [vp, vp, vp, vp] + shape + [vp, vp, vp]
+    lib.gla_fwd_static.restype = i
+    lib.gla_fwd_static.argtypes = [vp, vp, vp, vp] + shape + [vp, vp, vp]
     lib.gla_fwd_ex.restype = i
     lib.gla_fwd_ex.argtypes = [vp, vp, vp, vp] + shape + [i, i, vp, vp, vp, sz, vp]
     lib.gla_fwd_layout.restype = i
@@ -180,6 +182,25 @@ def gla_fwd(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD,
                            B, H, T, dk, dv, grid_h, grid_w, scan_dir,
                            out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
                            _stream_ptr(stream)))
+    return out, final_state
+
+
+def gla_fwd_static(q, k, v, log_alpha, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, out=None, final_state=None,
+                   stream=None):
+    """gla_fwd with the span states in the library's static device array (no allocation inside the call):
+    the caller passes ``out`` (fp32 [B,H,T,dv]) and, if wanted, ``final_state`` (fp32 [B,H,dk,dv])."""
+    torch = _torch()
+    lib = load_library()
+    B, H, T, dk, dv = _prep(q, k, v, log_alpha, grid_h, grid_w)
+    if q.dtype != torch.bfloat16:
+        raise TypeError("gla_fwd_static takes bf16 q/k/v")
+    if out is None or out.dtype != torch.float32 or tuple(out.shape) != (B, H, T, dv) or not out.is_contiguous():
+        raise ValueError("out must be a contiguous fp32 GPU tensor [B,H,T,dv]")
+    with torch.cuda.device(q.device):
+        _check(lib.gla_fwd_static(q.data_ptr(), k.data_ptr(), v.data_ptr(), log_alpha.data_ptr(),
+                                  B, H, T, dk, dv, grid_h, grid_w, scan_dir,
+                                  out.data_ptr(), final_state.data_ptr() if final_state is not None else None,
+                                  _stream_ptr(stream)))
     return out, final_state
 
 

@@ -38,6 +38,12 @@ size_t workspace_bytes(int B, int H, int T, int dk, int dv) {
     return state + lgam + lgam_b;
 }
 
+// what a plan of `nspans` spans per (batch, head) really uses (the three arrays that choose_engine_and_plan lays out)
+size_t plan_workspace_bytes(size_t bh, size_t nspans, int dk, int dv) {
+    return align_up(bh * nspans * dk * dv * sizeof(float), 256) + align_up(bh * nspans * dk * sizeof(float), 256) +
+           align_up(bh * nspans * dv * sizeof(float), 256);
+}
+
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 int validate(const void *q, const void *k, const void *v, const float *log_alpha,
@@ -304,7 +310,7 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
         int qkv_dtype, int out_dtype, void *out, float *final_state,
         void *workspace, size_t ws_bytes, hipStream_t stream, PhaseEvents *events,
         int layout = GLA_LAYOUT_BHTD, const float *initial_state = nullptr, const FusedArgs *fused = nullptr,
-        int accumulate = 0, const float *log_beta = nullptr) {
+        int accumulate = 0, const float *log_beta = nullptr, bool plan_sized_workspace = false) {
     // with the gate prologue the gate rows are z (checked like log_alpha: non-null, aligned)
     int st = validate(q, k, v, fused ? static_cast<const float *>(fused->z) : log_alpha, B, H, T, dk, dv,
                       grid_h, grid_w, scan_dir, qkv_dtype, out_dtype, out, final_state);
@@ -318,7 +324,10 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     if (layout != GLA_LAYOUT_BHTD && layout != GLA_LAYOUT_BTHD) return GLA_ERR_SHAPE;
     if (initial_state && misaligned(initial_state)) return GLA_ERR_ALIGN;
     if (log_beta && misaligned(log_beta)) return GLA_ERR_ALIGN;
-    if (!workspace || misaligned(workspace) || ws_bytes < workspace_bytes(B, H, T, dk, dv))
+    // plan_sized_workspace: the buffer is checked against what the launch plan of this call uses (below)
+    // instead of the bound over all plans
+    if (!workspace || misaligned(workspace) ||
+        (!plan_sized_workspace && ws_bytes < workspace_bytes(B, H, T, dk, dv)))
         return GLA_ERR_WORKSPACE;
 
     Params p{};
@@ -352,6 +361,8 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     bool use_mfma;
     st = choose_engine_and_plan(p, workspace, use_mfma);
     if (st != GLA_OK) return st;
+    if (plan_sized_workspace && ws_bytes < plan_workspace_bytes((size_t)B * H, (size_t)p.nspans, dk, dv))
+        return GLA_ERR_WORKSPACE;
     auto span = [&](SpanMode mode) {
         return use_mfma ? launch_mfma_span(p, mode, stream) : launch_recurrent_span(p, mode, stream);
     };
@@ -381,12 +392,56 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     return GLA_OK;
 }
 
+// ---- gla_fwd_static: the workspace of the span plan in a file-scope device array ----
+// Host code never uses the array's name as an address: the device address is asked for once per device
+// (hipGetSymbolAddress with that device current) and kept; every GPU holds its own copy of the array.
+constexpr size_t kStaticScratchBytes = GLA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_static_mutex;
+void *g_static_ptr[kMaxDevices] = {};
+
+// bytes the launch plan of a dense [B,H,T,d] bf16 -> fp32 call uses (host arithmetic only)
+size_t static_plan_bytes(int B, int H, int T, int dk, int dv) {
+    Params p{};
+    p.B = B; p.H = H; p.T = T; p.dk = dk; p.dv = dv;
+    p.qkv_dtype = GLA_DT_BF16; p.out_dtype = GLA_DT_F32;
+    set_dense_bhtd_strides(p);
+    bool use_mfma;
+    alignas(256) static unsigned char layout_base[256];   // only offsets from it are formed, nothing is accessed
+    if (choose_engine_and_plan(p, layout_base, use_mfma) != GLA_OK) return ~(size_t)0;
+    return plan_workspace_bytes((size_t)B * H, (size_t)p.nspans, dk, dv);
+}
+
 }  // namespace
 }  // namespace gla
 
 using namespace gla;
 
 extern "C" {
+
+int gla_fwd_static(const void *q, const void *k, const void *v, const float *log_alpha,
+                   int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
+                   float *out, float *final_state, gla_stream_t stream) {
+    int st = validate(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir,
+                      GLA_DT_BF16, GLA_DT_F32, out, final_state);
+    if (st != GLA_OK) return st;
+    if (static_plan_bytes(B, H, T, dk, dv) > kStaticScratchBytes) return GLA_ERR_WORKSPACE;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GLA_ERR_HIP;
+    void *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        if (!g_static_ptr[dev]) {
+            void *sym = nullptr;
+            if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return GLA_ERR_HIP;
+            g_static_ptr[dev] = sym;
+        }
+        ws = g_static_ptr[dev];
+    }
+    return run(q, k, v, log_alpha, B, H, T, dk, dv, grid_h, grid_w, scan_dir, GLA_DT_BF16, GLA_DT_F32,
+               out, final_state, ws, kStaticScratchBytes, static_cast<hipStream_t>(stream), nullptr,
+               GLA_LAYOUT_BHTD, nullptr, nullptr, 0, nullptr, /*plan_sized_workspace=*/true);
+}
 
 int gla_fwd_gates(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta,
                   int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,

@@ -90,3 +90,12 @@ def test_argument_validation_needs_no_gpu():
                                             1, 1, 4, 8, 8, 2, 2, 0, 1, 0, ok_ptr, None, ok_ptr, 1 << 20, None)
     assert fg(None) == 1
     assert fg(vp(4100)) == 4
+
+
+def test_static_scratch_rejects_oversize_on_the_host():
+    """gla_fwd_static: a plan that needs more than the static array is refused before any HIP call."""
+    lib = gla.load_library()
+    ok = ctypes.c_void_p(4096)
+    # 4096 sequences of 1024 chunks, one span each: 4096 * (64 * 128 + 64 + 128) floats, far beyond 16 MiB
+    assert lib.gla_fwd_static(ok, ok, ok, ok, 64, 64, 65536, 64, 128, 256, 256, 0, ok, None, None) == 5
+    assert lib.gla_fwd_static(None, ok, ok, ok, 1, 1, 4, 8, 8, 2, 2, 0, ok, None, None) == 1
