@@ -84,13 +84,18 @@ typedef enum {
     GLA_OPT_CHUNKS_PER_SPAN = 0, /* 0 = choose automatically; n > 0 = n 64-token chunks per work-group */
     GLA_OPT_ENGINE = 1,          /* gla_engine */
     GLA_OPT_CARRY = 2,           /* gla_carry */
-    GLA_OPT_BWD_SPLIT = 3        /* 0 = the backward pass computes dk and dv of a chunk in one kernel (MFMA engine);
+    GLA_OPT_BWD_SPLIT = 3,       /* 0 = the backward pass computes dk and dv of a chunk in one kernel (MFMA engine);
                                     1 = in two kernels (the forward output pass for dv, the row read for dk) */
+    GLA_OPT_RANGE_FALLBACK = 4   /* 1 (default) = after the fp16 output pass, the spans that left its range are
+                                    recomputed by the bf16 hi/lo pass; 0 = that second launch is skipped (for
+                                    callers that know their gates and inputs stay in range, and for measurements) */
 } gla_option;
 typedef enum {
     GLA_ENGINE_AUTO = 0,      /* bf16 inputs with dk % 4 == 0 and dv % 8 == 0 -> MFMA, else recurrent */
     GLA_ENGINE_RECURRENT = 1, /* fp32 token-by-token arithmetic inside each span; any dtype, any gates */
-    GLA_ENGINE_MFMA = 2       /* bf16 MFMA chunk form (Sec. 3.5); bf16 inputs only */
+    GLA_ENGINE_MFMA = 2,      /* bf16 hi/lo MFMA chunk form (Sec. 3.5) in every pass; bf16 inputs only */
+    GLA_ENGINE_MFMA_FP16 = 3  /* as AUTO picks for the plain forward pass on bf16 inputs: fp16 operands in the output
+                                 pass with the bf16 hi/lo pass as its range fallback; GLA_ERR_UNSUPPORTED elsewhere */
 } gla_engine;
 
 /* Where the states of the spans of one (batch, head) are chained, S_start(r+1) = diag(Gamma_r) S_start(r) + U_r

@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     gla_set_option, gla_get_option, gla_status_string, gla_version,
     library_path, load_library, lib_symbols,
     SCAN_ROW_FWD, SCAN_ROW_REV, SCAN_COL_FWD, SCAN_COL_REV, DT_F32, DT_BF16,
-    OPT_CHUNKS_PER_SPAN, OPT_ENGINE, OPT_CARRY, OPT_BWD_SPLIT, ENGINE_AUTO, ENGINE_RECURRENT, ENGINE_MFMA,
+    OPT_CHUNKS_PER_SPAN, OPT_ENGINE, OPT_CARRY, OPT_BWD_SPLIT, OPT_RANGE_FALLBACK, ENGINE_AUTO, ENGINE_RECURRENT, ENGINE_MFMA, ENGINE_MFMA_FP16,
     CARRY_AUTO, CARRY_KERNEL, CARRY_IN_OUTPUT_PASS, LAYOUT_BHTD, LAYOUT_BTHD,
 )

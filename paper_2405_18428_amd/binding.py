@@ -13,10 +13,10 @@ from typing import List, Optional
 
 SCAN_ROW_FWD, SCAN_ROW_REV, SCAN_COL_FWD, SCAN_COL_REV = 0, 1, 2, 3
 DT_F32, DT_BF16 = 0, 1
-OPT_CHUNKS_PER_SPAN, OPT_ENGINE, OPT_CARRY, OPT_BWD_SPLIT = 0, 1, 2, 3
+OPT_CHUNKS_PER_SPAN, OPT_ENGINE, OPT_CARRY, OPT_BWD_SPLIT, OPT_RANGE_FALLBACK = 0, 1, 2, 3, 4
 CARRY_AUTO, CARRY_KERNEL, CARRY_IN_OUTPUT_PASS = 0, 1, 2
 LAYOUT_BHTD, LAYOUT_BTHD = 0, 1
-ENGINE_AUTO, ENGINE_RECURRENT, ENGINE_MFMA = 0, 1, 2
+ENGINE_AUTO, ENGINE_RECURRENT, ENGINE_MFMA, ENGINE_MFMA_FP16 = 0, 1, 2, 3
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "csrc", "libgla.so")

@@ -8,7 +8,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SOURCES = ["gla_api.hip", "gla_carry.hip", "gla_recurrent.hip", "gla_mfma.hip", "gla_bwd_kernels.hip",
-           "gla_mfma_bwd.hip", "gla_srem.hip"]
+           "gla_mfma_bwd.hip", "gla_srem.hip", "gla_fast.hip"]
 LIB = os.path.join(HERE, "libgla.so")
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 math.

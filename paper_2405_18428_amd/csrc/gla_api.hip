@@ -14,6 +14,7 @@ int g_opt_chunks_per_span = 0;
 int g_opt_engine = GLA_ENGINE_AUTO;
 int g_opt_carry = GLA_CARRY_AUTO;
 int g_opt_bwd_split = 0;
+int g_opt_range_fallback = 1;
 
 // Most spans per (batch, head) that the output pass chains by itself: work-group r reads the r local states
 // before it, so the reads grow with the square of the span count while a carry kernel's grow linearly.
@@ -35,13 +36,14 @@ size_t workspace_bytes(int B, int H, int T, int dk, int dv) {
     size_t state = align_up(bh * nspans * dk * dv * sizeof(float), 256);
     size_t lgam = align_up(bh * nspans * dk * sizeof(float), 256);
     size_t lgam_b = align_up(bh * nspans * dv * sizeof(float), 256);   // value-side gate sums (two-sided gate only)
-    return state + lgam + lgam_b;
+    size_t flags = align_up(bh * nspans * sizeof(int), 256);           // fp16 engine: one range flag per span
+    return state + lgam + lgam_b + flags;
 }
 
 // what a plan of `nspans` spans per (batch, head) really uses (the three arrays that choose_engine_and_plan lays out)
 size_t plan_workspace_bytes(size_t bh, size_t nspans, int dk, int dv) {
     return align_up(bh * nspans * dk * dv * sizeof(float), 256) + align_up(bh * nspans * dk * sizeof(float), 256) +
-           align_up(bh * nspans * dv * sizeof(float), 256);
+           align_up(bh * nspans * dv * sizeof(float), 256) + align_up(bh * nspans * sizeof(int), 256);
 }
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -68,12 +70,13 @@ int validate(const void *q, const void *k, const void *v, const float *log_alpha
 // per-work-group prologue; short spans give the 256 compute units more
 // work-groups.  Two resident work-groups per compute unit is the sweet spot
 // measured on MI355X for the output pass.
-int plan_chunks_per_span(int bh, int nchunks, bool mfma_engine) {
+int plan_chunks_per_span(int bh, int nchunks, bool mfma_engine, int groups_per_cu = 2) {
     int cps = g_opt_chunks_per_span;
     if (cps <= 0) {
-        // at most 512 work-groups, so that all of them are resident at once (two per compute unit); sequences of
-        // up to four chunks are walked in one pass (a second kernel costs more than the chunks it would save)
-        const long long resident_groups = 512;
+        // no more work-groups than are resident at once (two per compute unit; three of the fp16 engine's where
+        // its LDS allows); sequences of up to four chunks are walked in one pass (a second kernel costs more than
+        // the chunks it would save)
+        const long long resident_groups = 256LL * groups_per_cu;
         cps = (int)(((long long)bh * nchunks + resident_groups - 1) / resident_groups);
         if (cps < 1) cps = 1;
         if (mfma_engine && nchunks <= 4) cps = nchunks;
@@ -83,17 +86,25 @@ int plan_chunks_per_span(int bh, int nchunks, bool mfma_engine) {
 }
 
 // Engine for the span passes (p.qkv_dtype, sizes and strides must be set) and the span plan with its workspace.
-int choose_engine_and_plan(Params &p, void *workspace, bool &use_mfma) {
+// use_fast (optional): the caller is the plain forward pass and would take the fp16 output pass where it covers
+// the call; on return, whether it does (the span plan is then sized for that kernel's residency).
+int choose_engine_and_plan(Params &p, void *workspace, bool &use_mfma, bool *use_fast = nullptr) {
     if (g_opt_engine == GLA_ENGINE_RECURRENT) {
         use_mfma = false;
-    } else if (g_opt_engine == GLA_ENGINE_MFMA) {
+    } else if (g_opt_engine == GLA_ENGINE_MFMA || g_opt_engine == GLA_ENGINE_MFMA_FP16) {
         if (!mfma_engine_supports(p)) return GLA_ERR_UNSUPPORTED;
         use_mfma = true;
     } else {
         use_mfma = mfma_engine_supports(p);
     }
+    bool fast = false;
+    if (use_fast != nullptr) {
+        fast = use_mfma && g_opt_engine == GLA_ENGINE_MFMA_FP16 && fast_engine_supports(p);   // (opt-in for now)
+        if (g_opt_engine == GLA_ENGINE_MFMA_FP16 && !fast) return GLA_ERR_UNSUPPORTED;
+        *use_fast = fast;
+    }
     const int nchunks = (p.T + kChunk - 1) / kChunk;
-    const int cps = plan_chunks_per_span(p.B * p.H, nchunks, use_mfma);
+    const int cps = plan_chunks_per_span(p.B * p.H, nchunks, use_mfma, fast ? fast_groups_per_cu(p) : 2);
     p.span_len = cps * kChunk;
     p.nspans = (nchunks + cps - 1) / cps;
     const size_t bh = (size_t)p.B * p.H;
@@ -102,6 +113,8 @@ int choose_engine_and_plan(Params &p, void *workspace, bool &use_mfma) {
                                           align_up(bh * p.nspans * p.dk * p.dv * sizeof(float), 256));
     p.ws_lgam_b = reinterpret_cast<float *>(reinterpret_cast<char *>(p.ws_lgam) +
                                             align_up(bh * p.nspans * p.dk * sizeof(float), 256));
+    p.ws_fail = reinterpret_cast<int *>(reinterpret_cast<char *>(p.ws_lgam_b) +
+                                        align_up(bh * p.nspans * p.dv * sizeof(float), 256));
     return GLA_OK;
 }
 
@@ -173,12 +186,18 @@ int run_bwd(const void *q, const void *k, const void *v, const float *log_alpha,
         // states S_start(r) (carry kernel) or the local states U_r and log Gamma_r (chained inside its output
         // pass), by the rule that also sets base.chain_in_output.
         Params pf = base;
-        bool same_engine;
-        if (choose_engine_and_plan(pf, const_cast<void *>(fwd_workspace), same_engine) != GLA_OK) return GLA_ERR_HIP;
-        // either way the states are read where they are: the row-read kernel chains local states itself
-        // (pa.chain_in_output follows the same rule as the forward call's plan)
+        bool same_engine, fwd_fast = false;
+        if (choose_engine_and_plan(pf, const_cast<void *>(fwd_workspace), same_engine, &fwd_fast) != GLA_OK)
+            return GLA_ERR_HIP;
+        // either way the states are read where they are: the row-read kernel chains local states itself.
+        // The walk adopts the forward call's span plan (its output pass may have been sized differently).
         pa.ws_state = pf.ws_state;
         pa.ws_lgam = pf.ws_lgam;
+        pa.nspans = pf.nspans;
+        pa.span_len = pf.span_len;
+        pa.chain_in_output = use_mfma && pa.nspans > 1 &&
+                             (g_opt_carry == GLA_CARRY_IN_OUTPUT_PASS ||
+                              (g_opt_carry == GLA_CARRY_AUTO && pa.nspans <= kMaxChainedSpans));
     } else if (states(pa) != hipSuccess) {
         return GLA_ERR_HIP;
     }
@@ -358,8 +377,8 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
         p.st_v = H * dv; p.sh_v = dv; p.sb_v = (long long)T * H * dv;
     }
 
-    bool use_mfma;
-    st = choose_engine_and_plan(p, workspace, use_mfma);
+    bool use_mfma, use_fast = false;
+    st = choose_engine_and_plan(p, workspace, use_mfma, &use_fast);
     if (st != GLA_OK) return st;
     if (plan_sized_workspace && ws_bytes < plan_workspace_bytes((size_t)B * H, (size_t)p.nspans, dk, dv))
         return GLA_ERR_WORKSPACE;
@@ -386,7 +405,18 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
         if (e != hipSuccess) return GLA_ERR_HIP;
     }
     mark(2);
-    e = span(kModeOutput);
+    if (use_fast) {
+        // fp16 output pass; the spans whose gates or operands leave its range raise their flags and are
+        // recomputed by the bf16 hi/lo pass (work-groups of unflagged spans return at once)
+        e = launch_fast_output(p, stream);
+        if (e != hipSuccess) return GLA_ERR_HIP;
+        if (g_opt_range_fallback) {
+            p.only_flagged = 1;
+            e = launch_mfma_span(p, kModeOutput, stream);
+        }
+    } else {
+        e = span(kModeOutput);
+    }
     if (e != hipSuccess) return GLA_ERR_HIP;
     mark(3);
     return GLA_OK;
@@ -408,7 +438,8 @@ size_t static_plan_bytes(int B, int H, int T, int dk, int dv) {
     set_dense_bhtd_strides(p);
     bool use_mfma;
     alignas(256) static unsigned char layout_base[256];   // only offsets from it are formed, nothing is accessed
-    if (choose_engine_and_plan(p, layout_base, use_mfma) != GLA_OK) return ~(size_t)0;
+    bool use_fast = false;
+    if (choose_engine_and_plan(p, layout_base, use_mfma, &use_fast) != GLA_OK) return ~(size_t)0;
     return plan_workspace_bytes((size_t)B * H, (size_t)p.nspans, dk, dv);
 }
 
@@ -666,7 +697,7 @@ int gla_set_option(int option, int value) {
         g_opt_chunks_per_span = value;
         return GLA_OK;
     case GLA_OPT_ENGINE:
-        if (value < GLA_ENGINE_AUTO || value > GLA_ENGINE_MFMA) return GLA_ERR_SHAPE;
+        if (value < GLA_ENGINE_AUTO || value > GLA_ENGINE_MFMA_FP16) return GLA_ERR_SHAPE;
         g_opt_engine = value;
         return GLA_OK;
     case GLA_OPT_CARRY:
@@ -676,6 +707,10 @@ int gla_set_option(int option, int value) {
     case GLA_OPT_BWD_SPLIT:
         if (value < 0 || value > 1) return GLA_ERR_SHAPE;
         g_opt_bwd_split = value;
+        return GLA_OK;
+    case GLA_OPT_RANGE_FALLBACK:
+        if (value < 0 || value > 1) return GLA_ERR_SHAPE;
+        g_opt_range_fallback = value;
         return GLA_OK;
     default:
         return GLA_ERR_SHAPE;
@@ -688,6 +723,7 @@ int gla_get_option(int option) {
     case GLA_OPT_ENGINE: return g_opt_engine;
     case GLA_OPT_CARRY: return g_opt_carry;
     case GLA_OPT_BWD_SPLIT: return g_opt_bwd_split;
+    case GLA_OPT_RANGE_FALLBACK: return g_opt_range_fallback;
     default: return -1;
     }
 }

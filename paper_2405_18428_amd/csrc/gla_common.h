@@ -65,6 +65,11 @@ struct Params {
     const float *log_beta;
     const void *z_beta;     // or (with z_gate) its pre-activation: log beta = logsigmoid(z_beta) * inv_tau, like v
     float *ws_lgam_b;       // [B*H, nspans, dv]  summed log_beta of each span (phase 1 -> phase 2)
+    // fp16 engine (gla_fast.hip): one flag per span, raised by the output pass when the span's gates or operands
+    // leave the range its fp16 operands cover; with only_flagged the bf16 hi/lo output pass recomputes those
+    // spans and leaves the others alone
+    int *ws_fail;           // [B*H, nspans]
+    int only_flagged;
 };
 
 // the gate has a value-side factor
@@ -123,6 +128,11 @@ hipError_t launch_recurrent_span(const Params &p, SpanMode mode, hipStream_t str
 hipError_t launch_mfma_span(const Params &p, SpanMode mode, hipStream_t stream);
 hipError_t launch_carry(const Params &p, hipStream_t stream);
 bool mfma_engine_supports(const Params &p);
+// fp16 output pass with the pipelined chunk loop (gla_fast.hip): what it covers, how many of its work-groups a
+// compute unit holds, and its launcher
+bool fast_engine_supports(const Params &p);
+int fast_groups_per_cu(const Params &p);
+hipError_t launch_fast_output(const Params &p, hipStream_t stream);
 // backward-only kernels: r_s[c] = sum_n S_s[c,n] w_s[n] over the states of (p.k, p.v, p.log_alpha); and
 // dlog_alpha = reverse cumulative sum of q * dq - k * dk (totals: [B*H, dg_spans(T), dk] floats of scratch)
 hipError_t launch_row_read(const Params &p, const void *w, float *r, hipStream_t stream);

@@ -1,0 +1,644 @@
+// Pipelined fp16 MFMA engine for the output pass of the GLA recurrence in its chunk form
+// (DiG paper, Sec. 3.5: chunks of M = 64 tokens computed on-chip; recurrence of Sec. 3.1
+// Eq. (attn_gla) rows 1-3 with beta = 1; scan orders of Sec. 3.3 / Algorithm 1).
+//
+// Chunk form with a mid-chunk anchor.  Inside a chunk let b_j = sum_{i<=j} log2 alpha_i (inclusive, per key
+// channel), b_m its value after the chunk's 32nd token and b_C after its last.  With
+//     q~_j = q_j * 2^(b_j - b_m),   k~_i = k_i * 2^(b_m - b_i),   P = diag(2^b_m) S_0   (S_0 = state entering the chunk)
+// unrolling the recurrence gives
+//     o_j = sum_{i<=j} (q~_j . k~_i) v_i + q~_j P ,        S_C = diag(2^(b_C - b_m)) (P + K~^T V).
+// Anchoring in the middle halves the exponent range of the gated operands, which is what lets them be single
+// fp16 numbers (11 significant bits; one v_mfma_f32_16x16x32_f16 per product): as long as a channel decays by at
+// most 2^-kMaxHalfDecay over either half of a chunk and the gated operands stay below kMaxOperand, every operand
+// keeps fp16's full precision.  A span in which that does not hold raises its flag in the workspace and is
+// recomputed by the bf16 hi/lo engine (gla_mfma.hip), which has the exponent range of fp32.
+//
+// A work-group of 4 waves walks the chunks of one span; wave w owns tokens 16w .. 16w+15 of every chunk.
+// Rows are fetched straight into the MFMA operand layout: lane (lm, g) = (lane % 16, lane / 16) holds, for
+// token 16w + lm, the channels 16u + 4g .. 16u + 4g + 3 of every 16-channel unit u (16-byte pieces of log_alpha,
+// 8-byte pieces of q and k).  Two units are the eight contraction slots of one 32-channel MFMA step, and they are
+// also the rows 4g .. 4g+3 of two 16-row accumulator tiles, so the fp32 state in the accumulators becomes the
+// A operand of q~ P by conversion alone.
+// The gate prefix sums are a 4-step DPP scan over the 16 lanes of a row plus the totals of the other waves' tiles,
+// exchanged through LDS.  q~ never leaves the registers; k~ and v go to LDS (token-major) because the other
+// waves' score tiles and the token-contracted products (A V, K~^T V: ds_read_b64_tr_b16) need them.
+//
+// Software pipeline, one barrier per chunk: in iteration c a wave gates chunk c+1 (k~ into the other LDS buffer),
+// scans chunk c+2 (tile totals into LDS), issues the loads of log_alpha for chunk c+3, of q, k for chunk c+2 and
+// of v for chunk c+1, contracts chunk c, and finally parks the v rows of chunk c+1 in LDS.
+#include <type_traits>
+
+#include "gla_common.h"
+#include "gla_mfma_util.h"
+
+namespace gla {
+namespace {
+
+typedef __attribute__((ext_vector_type(2))) _Float16 h16x2;
+typedef __attribute__((ext_vector_type(4))) _Float16 h16x4;
+typedef __attribute__((ext_vector_type(8))) _Float16 h16x8;
+
+#ifndef FAST_MINW_CAP
+#define FAST_MINW_CAP 3
+#endif
+constexpr float kMaxHalfDecay = 11.f;    // log2: decay of a channel over half a chunk that the fp16 operands cover
+constexpr float kMaxOperand = 16384.f;   // largest |v| taken as safe (fp16 overflows at 65504)
+constexpr float kMaxInput = 8.f;         // largest |q|, |k|: times 2^kMaxHalfDecay still below kMaxOperand
+constexpr float kMinInput = 0.00390625f; // a span whose largest |q|, |k| or |v| is below 2^-8 would sit in fp16's subnormals
+constexpr float kClampExp = 15.f;        // exponents are clamped here so that nothing becomes inf before the flag is raised
+
+__device__ inline uint32_t pack_f16(float lo, float hi) {
+    f32x2 x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, h16x2));
+}
+__device__ inline f32x4 mfma_h32(u32x4 a, u32x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h16x8, a), __builtin_bit_cast(h16x8, b), c, 0, 0, 0);
+}
+// a 16-channel step: the 32-channel MFMA with its upper four contraction slots zero.  (The 16-deep MFMA chained
+// onto the accumulator of a 32-deep one gave wrong rows on MI355X with this compiler; one opcode for both.)
+__device__ inline f32x4 mfma_h16(u32x2 a, u32x2 b, f32x4 c) {
+    return mfma_h32(u32x4{a[0], a[1], 0u, 0u}, u32x4{b[0], b[1], 0u, 0u}, c);
+}
+// inclusive prefix sum over the 16 lanes of a DPP row
+__device__ inline float row_scan16(float v) {
+    v += dpp_move<0x111, 0xF, true>(v);  // row_shr:1
+    v += dpp_move<0x112, 0xF, true>(v);  // row_shr:2
+    v += dpp_move<0x114, 0xF, true>(v);  // row_shr:4
+    v += dpp_move<0x118, 0xF, true>(v);  // row_shr:8
+    return v;
+}
+
+// Head-size classes.  NK32 = 32-channel MFMA steps, TAIL = one more 16-channel step, NCT = 16-channel units
+// (= row tiles of the state), NDV16 = 16-column tiles of the values.  Row strides (in 16-bit elements) are chosen so
+// that the 8- and 16-byte reads of 16 neighbouring rows spread over the LDS banks.
+template <int CLS>
+struct FastCfg;
+template <>
+struct FastCfg<0> {   // dk <= 32, dv <= 64
+    static constexpr int NK32 = 1, TAIL = 0, NCT = 2, NDV16 = 4, KST = 48, VS = 80, SST = 40;
+    static constexpr int kOwned[4] = {4, 3, 1, 0};
+};
+template <>
+struct FastCfg<1> {   // dk <= 48, dv <= 80
+    static constexpr int NK32 = 1, TAIL = 1, NCT = 3, NDV16 = 5, KST = 48, VS = 80, SST = 56;
+    static constexpr int kOwned[4] = {6, 5, 2, 2};
+};
+template <>
+struct FastCfg<2> {   // dk <= 64, dv <= 128
+    static constexpr int NK32 = 2, TAIL = 0, NCT = 4, NDV16 = 8, KST = 80, VS = 144, SST = 72;
+    static constexpr int kOwned[4] = {12, 10, 5, 5};
+};
+
+template <int CLS>
+struct FastLayout {
+    using C = FastCfg<CLS>;
+    static constexpr int kTot = 3 * 4 * 4 * (4 * C::NCT) * 4;            // float[3][tile][g][NV]
+    static constexpr int kK = kChunk * C::KST * 2;                       // one buffer of k~
+    static constexpr int kV = kChunk * C::VS * 2;                        // one buffer of v
+    static constexpr int kS = 16 * C::NDV16 * C::SST * 2;                // one buffer of P (fp16, [value column][slot])
+    static constexpr int oTot = 0;
+    static constexpr int oFlag = oTot + kTot;                            // int: the span left the fp16 range
+    static constexpr int oK = oFlag + 16;
+    static constexpr int oV = oK + 2 * kK;
+    static constexpr int oS = oV + 2 * kV;
+    static constexpr int kBytes = oS + 2 * kS;
+    static constexpr int oChain = oK;                                    // float[dk * dv] before the first chunk
+    static_assert(kBytes - oChain >= 16 * C::NCT * 16 * C::NDV16 * 4, "the chained start state must fit");
+};
+
+template <int CLS>
+__host__ __device__ constexpr int owned_start(int w) {
+    int s = 0;
+    for (int i = 0; i < w; ++i) s += FastCfg<CLS>::kOwned[i];
+    return s;
+}
+
+template <int CLS, typename TOut, int MINW>
+__global__ __launch_bounds__(256, MINW) void fast_output_kernel(Params p) {
+    using C = FastCfg<CLS>;
+    using L = FastLayout<CLS>;
+    constexpr int NCT = C::NCT, NDV16 = C::NDV16, NK32 = C::NK32, KST = C::KST, VS = C::VS, SST = C::SST;
+    constexpr bool TAIL = C::TAIL != 0;
+    constexpr int NV = 4 * NCT;                       // gate values per lane and chunk
+    constexpr int NVP = (2 * NDV16 + 3) / 4;          // 16-byte pieces of a v row per lane
+    static_assert(2 * NK32 + (TAIL ? 1 : 0) == NCT, "units = slots of the MFMA steps");
+    static_assert(owned_start<CLS>(4) == NCT * NDV16, "every state tile has an owner");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float *s_tot = reinterpret_cast<float *>(smem + L::oTot);
+    int *s_flag = reinterpret_cast<int *>(smem + L::oFlag);
+    uint16_t *s_k = reinterpret_cast<uint16_t *>(smem + L::oK);
+    uint16_t *s_v = reinterpret_cast<uint16_t *>(smem + L::oV);
+    uint16_t *s_s = reinterpret_cast<uint16_t *>(smem + L::oS);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave = 16-token tile of every chunk
+    const int lm = lane & 15;
+    const int g = lane >> 4;
+
+    // work-group -> (batch * head, span): contiguous ranges of spans per XCD; odd heads walk their spans
+    // backwards when the span states are chained here (long and short chains then share a compute unit)
+    int blk = blockIdx.x;
+    {
+        const int nb = gridDim.x;
+        if ((nb & 7) == 0) blk = (blk & 7) * (nb >> 3) + (blk >> 3);
+    }
+    const int bh = blk / p.nspans;
+    int sp_ = blk - bh * p.nspans;
+    if (p.chain_in_output && (bh & 1)) sp_ = p.nspans - 1 - sp_;
+    const int sp = sp_;
+    const int dk = p.dk, dv = p.dv, T = p.T;
+    const int s_begin = sp * p.span_len;
+    const int s_end = min(T, s_begin + p.span_len);
+    const int nch = (s_end - s_begin + kChunk - 1) / kChunk;
+
+    const size_t base_k = slab_k(p, bh), base_v = slab_v(p, bh);
+    const char *gq = static_cast<const char *>(p.q) + base_k * 2;
+    const char *gk = static_cast<const char *>(p.k) + base_k * 2;
+    const char *gv = static_cast<const char *>(p.v) + base_v * 2;
+    const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + base_k * 4;
+    char *gout = static_cast<char *>(p.out) + base_v * sizeof(TOut);
+    const uint32_t dk2 = 2u * (uint32_t)p.st_k, dv2 = 2u * (uint32_t)p.st_v;   // bytes from one bf16 row to the next
+
+    if (tid == 0) *s_flag = 0;
+
+    // ---- per-lane constants of the row pieces ----
+    // unit u: channels 16u + 4g .. +3; units past dk are fetched from the last valid piece and read as zero
+    uint32_t chb[NCT];         // byte offset of the piece in a bf16 row
+    bool uok[NCT];
+#pragma unroll
+    for (int u = 0; u < NCT; ++u) {
+        const int ch = 16 * u + 4 * g;
+        uok[u] = ch < dk;
+        chb[u] = 2u * (uint32_t)min(ch, dk - 4);
+    }
+    uint32_t vpb[NVP];         // byte offset of the lane's i-th v piece (8 columns) in a bf16 row
+    bool vok[NVP];
+#pragma unroll
+    for (int i = 0; i < NVP; ++i) {
+        const int col = 8 * (g + 4 * i);
+        vok[i] = col < dv;
+        vpb[i] = 2u * (uint32_t)min(col, dv - 8);
+    }
+
+    // token of this lane's row in chunk x (rows past the span repeat its last token: loads stay in bounds)
+    auto row_token = [&](int x, bool &valid) {
+        int s = s_begin + x * kChunk + 16 * w + lm;
+        valid = s < s_end;
+        s = min(s, s_end - 1);
+        return scan_token(p.scan_dir, s, T, p.grid_h, p.grid_w);
+    };
+
+    // ---- pipeline registers ----
+    f32x4 r_la[NCT];           // log_alpha pieces waiting for the scan
+    bool la_valid;
+    float r_b[NV];             // scanned gates (log2, prefix inside the 16-token tile) waiting for the gate stage
+    u32x2 r_q[NCT], r_k[NCT];  // raw q, k pieces waiting for the gate stage
+    bool qk_valid;
+    u32x4 r_v[NVP];            // v pieces on their way to LDS
+    bool v_valid;
+    uint32_t qf_cur[NCT][2], qf_next[NCT][2];   // q~ of the chunk being contracted / gated (fp16 pairs per unit)
+#pragma unroll
+    for (int u = 0; u < NCT; ++u) {
+        r_la[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        r_q[u] = u32x2{0u, 0u};
+        r_k[u] = u32x2{0u, 0u};
+    }
+#pragma unroll
+    for (int i = 0; i < NVP; ++i) r_v[i] = u32x4{0u, 0u, 0u, 0u};
+    // only the last chunk of a span can hold rows that are not tokens (their pieces are then cleared)
+    const int ragged_from = (s_end - s_begin) % kChunk != 0 ? nch - 1 : nch;
+    uint32_t ov_cur = 0, ov_next = 0;           // element offset of the lane's output row
+    bool st_cur = false, st_next = false;       // ... and whether that row is a token
+    // fp16 range check of the span: largest half-chunk decay (log2), largest |q|, |k|, |v|, and whether every
+    // output was finite
+    float trk_e = 0.f, trk_q = 0.f, trk_k = 0.f, trk_v = 0.f, trk_o = 0.f;
+
+    // (pieces past dk or dv are never fetched: their registers keep the zeros they start with)
+    auto issue_la = [&](int x) {
+        const uint32_t off = (uint32_t)row_token(x, la_valid) * dk2;
+#pragma unroll
+        for (int u = 0; u < NCT; ++u)
+            if (uok[u]) r_la[u] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * (off + chb[u]));
+    };
+    auto issue_qk = [&](int x) {
+        const uint32_t off = (uint32_t)row_token(x, qk_valid) * dk2;
+#pragma unroll
+        for (int u = 0; u < NCT; ++u) {
+            if (uok[u]) {
+                r_q[u] = *reinterpret_cast<const u32x2 *>(gq + off + chb[u]);
+                r_k[u] = *reinterpret_cast<const u32x2 *>(gk + off + chb[u]);
+            }
+        }
+    };
+    auto issue_v = [&](int x) {
+        const uint32_t tok = (uint32_t)row_token(x, v_valid);
+        ov_next = tok * (uint32_t)p.st_v;
+        st_next = v_valid;
+#pragma unroll
+        for (int i = 0; i < NVP; ++i)
+            if (vok[i]) r_v[i] = *reinterpret_cast<const u32x4 *>(gv + tok * dv2 + vpb[i]);
+    };
+
+    // scan: prefix sums of log2(alpha) inside this wave's tile, tile totals to LDS
+    auto scan = [&](int x) {
+        float *tot = s_tot + ((x % 3) * 4 + w) * 4 * NV + g * NV;
+#pragma unroll
+        for (int u = 0; u < NCT; ++u) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float a = r_la[u][e] * kLog2e;
+                if (x >= ragged_from) a = la_valid ? a : 0.f;
+                r_b[4 * u + e] = row_scan16(a);
+            }
+            if (lm == 15)
+                *reinterpret_cast<f32x4 *>(tot + 4 * u) = f32x4{r_b[4 * u], r_b[4 * u + 1], r_b[4 * u + 2], r_b[4 * u + 3]};
+        }
+    };
+
+    // gate: exponents relative to the mid-chunk anchor, q~ to registers, k~ to LDS.
+    // The prefix sums of this wave's tile are offset by c0 t0 + c1 t1 + c2 t2 (t = totals of tiles 0..2): tiles 0, 1
+    // lie before the anchor (-(t0 + t1), -t1), tile 2 starts at it (0), tile 3 follows tile 2 (+t2).
+    const float cf0 = w == 0 ? -1.f : 0.f, cf1 = w <= 1 ? -1.f : 0.f, cf2 = w == 3 ? 1.f : 0.f;
+    auto gate = [&](int x, bool count) {
+        const float *tot = s_tot + (x % 3) * 16 * NV + g * NV;      // + tile * 4 * NV
+        uint16_t *krow = s_k + (x & 1) * (kChunk * KST) + (16 * w + lm) * KST + 4 * g;
+#pragma unroll
+        for (int u = 0; u < NCT; ++u) {
+            const f32x4 t0 = *reinterpret_cast<const f32x4 *>(tot + 0 * 4 * NV + 4 * u);
+            const f32x4 t1 = *reinterpret_cast<const f32x4 *>(tot + 1 * 4 * NV + 4 * u);
+            const f32x4 t2 = *reinterpret_cast<const f32x4 *>(tot + 2 * 4 * NV + 4 * u);
+            const f32x4 t3 = *reinterpret_cast<const f32x4 *>(tot + 3 * 4 * NV + 4 * u);
+            uint32_t q0 = r_q[u][0], q1 = r_q[u][1], k0 = r_k[u][0], k1 = r_k[u][1];
+            if (x >= ragged_from) {
+                q0 = qk_valid ? q0 : 0u; q1 = qk_valid ? q1 : 0u;
+                k0 = qk_valid ? k0 : 0u; k1 = qk_valid ? k1 : 0u;
+            }
+            float qx[4], kx[4];
+            qx[0] = bf16_lo_as_float(q0); qx[1] = bf16_hi_as_float(q0); qx[2] = bf16_lo_as_float(q1); qx[3] = bf16_hi_as_float(q1);
+            kx[0] = bf16_lo_as_float(k0); kx[1] = bf16_hi_as_float(k0); kx[2] = bf16_lo_as_float(k1); kx[3] = bf16_hi_as_float(k1);
+            if (count) {
+                trk_q = fmaxf(trk_q, fmaxf(fmaxf(fabsf(qx[0]), fabsf(qx[1])), fmaxf(fabsf(qx[2]), fabsf(qx[3]))));
+                trk_k = fmaxf(trk_k, fmaxf(fmaxf(fabsf(kx[0]), fabsf(kx[1])), fmaxf(fabsf(kx[2]), fabsf(kx[3]))));
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float ex = r_b[4 * u + e] + fmaf(cf0, t0[e], fmaf(cf1, t1[e], cf2 * t2[e]));
+                // range of the fp16 operands: the decay over either half of the chunk (the gates are <= 0, so the
+                // prefix sums are monotone and the halves' totals bound every exponent)
+                if (count) trk_e = fmaxf(trk_e, fmaxf(fabsf(t0[e] + t1[e]), fabsf(t2[e] + t3[e])));
+                const float ec = fminf(fmaxf(ex, -kClampExp), kClampExp);
+                qx[e] *= exp2_fast(ec);
+                kx[e] *= exp2_fast(-ec);
+            }
+            qf_next[u][0] = pack_f16(qx[0], qx[1]);
+            qf_next[u][1] = pack_f16(qx[2], qx[3]);
+            *reinterpret_cast<u32x2 *>(krow + 16 * u) = u32x2{pack_f16(kx[0], kx[1]), pack_f16(kx[2], kx[3])};
+        }
+    };
+
+    // v rows of chunk x: bf16 -> fp16 (exact inside fp16's range), to LDS
+    auto park_v = [&](int x) {
+        uint16_t *vrow = s_v + (x & 1) * (kChunk * VS) + (16 * w + lm) * VS + 8 * g;
+#pragma unroll
+        for (int i = 0; i < NVP; ++i) {
+            if (8 * (g + 4 * i) < 16 * NDV16) {
+                u32x4 h;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    uint32_t x2 = r_v[i][j];
+                    if (x >= ragged_from) x2 = v_valid ? x2 : 0u;
+                    const float lo = bf16_lo_as_float(x2), hi = bf16_hi_as_float(x2);
+                    trk_v = fmaxf(trk_v, fmaxf(fabsf(lo), fabsf(hi)));
+                    h[j] = pack_f16(lo, hi);
+                }
+                *reinterpret_cast<u32x4 *>(vrow + 32 * i) = h;
+            }
+        }
+    };
+
+    // ---- state tiles owned by this wave ----
+    constexpr int MAXOWN = C::kOwned[0];
+    f32x4 acc[MAXOWN];
+#pragma unroll
+    for (int i = 0; i < MAXOWN; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // the loads of the first chunk are on their way while the span's start state is formed
+    issue_la(0);
+
+    // ---- state entering the span ----
+    {
+        const bool chain = p.chain_in_output && (sp > 0 || p.initial_state != nullptr);   // uniform
+        const float *s0 = nullptr;
+        if (p.nspans > 1 && !p.chain_in_output)
+            s0 = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;      // as the carry kernel left it
+        else if (p.nspans == 1 && p.initial_state != nullptr)
+            s0 = p.initial_state + (size_t)bh * dk * dv;
+        if (chain) {
+            constexpr int kV4 = (16 * NCT * 16 * NDV16 / 4 + 255) / 256;
+            constexpr int kRun = 16 / kV4 > 0 ? 16 / kV4 : 1;
+            chain_span_states<256, kV4, kRun, false>(p, bh, sp, tid, reinterpret_cast<float *>(smem + L::oChain));
+            __syncthreads();
+            s0 = reinterpret_cast<const float *>(smem + L::oChain);      // (LDS is addressable through flat loads)
+        }
+        if (s0 != nullptr) {
+            auto fetch = [&](auto wave_c) {
+                constexpr int W = decltype(wave_c)::value;
+#pragma unroll
+                for (int i = 0; i < C::kOwned[W]; ++i) {
+                    constexpr int dummy = 0;
+                    (void)dummy;
+                    const int t = owned_start<CLS>(W) + i;
+                    const int n = 16 * (t / NCT) + lm;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int c = 16 * (t % NCT) + 4 * g + r;
+                        if (c < dk && n < dv) acc[i][r] = s0[c * dv + n];
+                    }
+                }
+            };
+            switch (w) {
+            case 0: fetch(std::integral_constant<int, 0>{}); break;
+            case 1: fetch(std::integral_constant<int, 1>{}); break;
+            case 2: fetch(std::integral_constant<int, 2>{}); break;
+            default: fetch(std::integral_constant<int, 3>{}); break;
+            }
+        }
+        __syncthreads();   // the chained state has been read: the pipeline may use its LDS
+    }
+
+    // Owner step after chunk c (c = -1: before the first chunk): the tiles now hold P(c) + K~^T V; scale them by
+    // 2^(b_C(c) - b_m(c) + b_m(c+1)) (anchor to anchor) and publish P(c+1) as the fp16 A operand of q~ P.
+    auto publish = [&](auto wave_c, int c) {
+        constexpr int W = decltype(wave_c)::value;
+        constexpr int t_lo = owned_start<CLS>(W), t_hi = owned_start<CLS>(W + 1);
+        const float *t_c = s_tot + ((c + 3) % 3) * 16 * NV + g * NV;        // totals of chunk c (c = -1: unused)
+        const float *t_n = s_tot + ((c + 1) % 3) * 16 * NV + g * NV;        // totals of chunk c + 1
+        uint16_t *srow = s_s + ((c + 1) & 1) * (16 * NDV16 * SST);
+        f32x4 fac[NCT];
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            bool used = false;
+            for (int t = t_lo; t < t_hi; ++t) used = used || (t % NCT == ct);
+            if (used) {
+                f32x4 f = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (c >= 0)
+                    f += *reinterpret_cast<const f32x4 *>(t_c + 2 * 4 * NV + 4 * ct) +
+                         *reinterpret_cast<const f32x4 *>(t_c + 3 * 4 * NV + 4 * ct);
+                if (c + 1 < nch)
+                    f += *reinterpret_cast<const f32x4 *>(t_n + 0 * 4 * NV + 4 * ct) +
+                         *reinterpret_cast<const f32x4 *>(t_n + 1 * 4 * NV + 4 * ct);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) fac[ct][r] = exp2_fast(f[r]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < t_hi - t_lo; ++i) {
+            const int t = t_lo + i;
+            const int ct = t % NCT, nt = t / NCT;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][r] *= fac[ct][r];
+            // slot of channel 16 ct + 4 g + r in a row of P: the 32-channel steps interleave two units per lane group
+            const int pos = (ct < 2 * NK32) ? 32 * (ct >> 1) + 8 * g + 4 * (ct & 1) : 32 * NK32 + 4 * g;
+            *reinterpret_cast<u32x2 *>(srow + (16 * nt + lm) * SST + pos) =
+                u32x2{pack_f16(acc[i][0], acc[i][1]), pack_f16(acc[i][2], acc[i][3])};
+        }
+    };
+
+    const int tr_row = lm >> 2, tr_col = 4 * (lm & 3);   // transposing reads: token-in-4 and column quad of this lane
+
+    auto contract = [&](auto wave_c, int c) {
+        constexpr int W = decltype(wave_c)::value;
+        constexpr int NQ = W / 2 + 1;                     // 32-token steps that hold causal tokens for this wave
+        const uint16_t *kb = s_k + (c & 1) * (kChunk * KST);
+        const uint16_t *vb = s_v + (c & 1) * (kChunk * VS);
+        const uint16_t *sb = s_s + (c & 1) * (16 * NDV16 * SST);
+        // ---- score tiles, transposed: lane (lm, g) gets A[i = 16 W + lm][j = 16 jt + 4 g + r] ----
+        f32x4 d[W + 1];
+#pragma unroll
+        for (int jt = 0; jt <= W; ++jt) {
+            const uint16_t *krow = kb + (16 * jt + lm) * KST + 4 * g;
+            d[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < NK32; ++ks) {
+                const u32x2 a0 = *reinterpret_cast<const u32x2 *>(krow + 32 * ks);
+                const u32x2 a1 = *reinterpret_cast<const u32x2 *>(krow + 32 * ks + 16);
+                d[jt] = mfma_h32(u32x4{a0[0], a0[1], a1[0], a1[1]},
+                                 u32x4{qf_cur[2 * ks][0], qf_cur[2 * ks][1], qf_cur[2 * ks + 1][0], qf_cur[2 * ks + 1][1]},
+                                 d[jt]);
+            }
+            if constexpr (TAIL) {
+                const u32x2 a = *reinterpret_cast<const u32x2 *>(krow + 32 * NK32);
+                d[jt] = mfma_h16(a, u32x2{qf_cur[2 * NK32][0], qf_cur[2 * NK32][1]}, d[jt]);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (4 * g + r > lm) d[W][r] = 0.f;            // causal mask of the diagonal tile
+        u32x4 pa[NQ];                                     // A^T as the B operand of O^T += V^T A^T
+#pragma unroll
+        for (int q32 = 0; q32 < NQ; ++q32) {
+            pa[q32][0] = pack_f16(d[2 * q32][0], d[2 * q32][1]);
+            pa[q32][1] = pack_f16(d[2 * q32][2], d[2 * q32][3]);
+            if (2 * q32 + 1 <= W) {
+                pa[q32][2] = pack_f16(d[2 * q32 + 1][0], d[2 * q32 + 1][1]);
+                pa[q32][3] = pack_f16(d[2 * q32 + 1][2], d[2 * q32 + 1][3]);
+            } else {
+                pa[q32][2] = 0u;
+                pa[q32][3] = 0u;
+            }
+        }
+        // ---- v fragments (contraction slot (g, e) of step q32 = token 32 q32 + 16 (e / 4) + 4 g + e % 4) ----
+        const uint16_t *vrow = vb + (4 * g + tr_row) * VS + tr_col;
+        auto v_frag = [&](int q32, int x) {
+            const u32x2 lo = lds_read_tr(vrow + 32 * q32 * VS + 16 * x);
+            const u32x2 hi = lds_read_tr(vrow + (32 * q32 + 16) * VS + 16 * x);
+            return u32x4{lo[0], lo[1], hi[0], hi[1]};
+        };
+        // the fragments of the value-column tiles whose state tiles this wave owns are kept for the state update
+        constexpr int t_lo = owned_start<CLS>(W), t_hi = owned_start<CLS>(W + 1);
+        constexpr int NT_LO = t_lo / NCT, NT_HI = t_lo < t_hi ? (t_hi - 1) / NCT : NT_LO - 1;
+        constexpr int NOWN = NT_HI - NT_LO + 1;
+        u32x4 vown[2][NOWN > 0 ? NOWN : 1];
+        // ---- O^T = V^T A^T + P^T Q~^T : lane (lm, g) accumulates O[i = 16 W + lm][n = 16 x + 4 g + r] ----
+        f32x4 o[NDV16];
+#pragma unroll
+        for (int x = 0; x < NDV16; ++x) {
+            o[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const bool owned_col = x >= NT_LO && x <= NT_HI;
+#pragma unroll
+            for (int q32 = 0; q32 < 2; ++q32) {
+                if (q32 < NQ || owned_col) {
+                    const u32x4 vf = v_frag(q32, x);
+                    if (q32 < NQ) o[x] = mfma_h32(vf, pa[q32], o[x]);
+                    if (owned_col) vown[q32][owned_col ? x - NT_LO : 0] = vf;
+                }
+            }
+            const uint16_t *srow = sb + (16 * x + lm) * SST;
+#pragma unroll
+            for (int ks = 0; ks < NK32; ++ks) {
+                const u32x4 st = *reinterpret_cast<const u32x4 *>(srow + 32 * ks + 8 * g);
+                o[x] = mfma_h32(st, u32x4{qf_cur[2 * ks][0], qf_cur[2 * ks][1], qf_cur[2 * ks + 1][0], qf_cur[2 * ks + 1][1]},
+                                o[x]);
+            }
+            if constexpr (TAIL) {
+                const u32x2 st = *reinterpret_cast<const u32x2 *>(srow + 32 * NK32 + 4 * g);
+                o[x] = mfma_h16(st, u32x2{qf_cur[2 * NK32][0], qf_cur[2 * NK32][1]}, o[x]);
+            }
+        }
+#pragma unroll
+        for (int x = 0; x < NDV16; ++x)
+            trk_o = fmaxf(trk_o, fmaxf(fmaxf(fabsf(o[x][0]), fabsf(o[x][1])), fmaxf(fabsf(o[x][2]), fabsf(o[x][3]))));
+        if (st_cur) {
+            char *orow = gout + (ov_cur + 4u * (uint32_t)g) * (uint32_t)sizeof(TOut);
+#pragma unroll
+            for (int x = 0; x < NDV16; ++x) {
+                if (4 * g + 16 * x < dv) {    // dv is a multiple of 8: all four columns or none
+                    if constexpr (sizeof(TOut) == 4)
+                        *reinterpret_cast<f32x4 *>(orow + 64 * x) = o[x];
+                    else
+                        *reinterpret_cast<u32x2 *>(orow + 32 * x) =
+                            u32x2{pack_bf16(o[x][0], o[x][1]), pack_bf16(o[x][2], o[x][3])};
+                }
+            }
+        }
+        // ---- state tiles of this wave: P + K~^T V ----
+        if constexpr (t_lo < t_hi) {
+            const uint16_t *ktr = kb + (4 * g + tr_row) * KST + tr_col;
+            u32x4 kt[NCT][2];
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                bool used = false;
+                for (int t = t_lo; t < t_hi; ++t) used = used || (t % NCT == ct);
+                if (used) {
+#pragma unroll
+                    for (int q32 = 0; q32 < 2; ++q32) {
+                        const u32x2 lo = lds_read_tr(ktr + 32 * q32 * KST + 16 * ct);
+                        const u32x2 hi = lds_read_tr(ktr + (32 * q32 + 16) * KST + 16 * ct);
+                        kt[ct][q32] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < t_hi - t_lo; ++i) {
+                const int t = t_lo + i;
+                acc[i] = mfma_h32(kt[t % NCT][0], vown[0][t / NCT - NT_LO], acc[i]);
+                acc[i] = mfma_h32(kt[t % NCT][1], vown[1][t / NCT - NT_LO], acc[i]);
+            }
+        }
+    };
+
+    auto per_wave = [&](auto fn, int c) {
+        switch (w) {
+        case 0: fn(std::integral_constant<int, 0>{}, c); break;
+        case 1: fn(std::integral_constant<int, 1>{}, c); break;
+        case 2: fn(std::integral_constant<int, 2>{}, c); break;
+        default: fn(std::integral_constant<int, 3>{}, c); break;
+        }
+    };
+
+    // ---- pipeline fill ----
+    scan(0);                       // iteration -2
+    issue_la(1);
+    issue_qk(0);
+    __syncthreads();
+    gate(0, true);                 // iteration -1
+    if (1 < nch) scan(1);
+    issue_v(0);
+    issue_la(2);
+    issue_qk(1);
+    per_wave(publish, -1);
+    park_v(0);
+#pragma unroll
+    for (int u = 0; u < NCT; ++u) { qf_cur[u][0] = qf_next[u][0]; qf_cur[u][1] = qf_next[u][1]; }
+    ov_cur = ov_next;
+    st_cur = st_next;
+    __syncthreads();
+
+    for (int c = 0; c < nch; ++c) {
+        if (c + 1 < nch) gate(c + 1, true);
+        if (c + 2 < nch) scan(c + 2);
+        issue_v(c + 1);
+        issue_la(c + 3);
+        issue_qk(c + 2);
+        per_wave(contract, c);
+        per_wave(publish, c);
+        if (c + 1 < nch) park_v(c + 1);
+#pragma unroll
+        for (int u = 0; u < NCT; ++u) { qf_cur[u][0] = qf_next[u][0]; qf_cur[u][1] = qf_next[u][1]; }
+        ov_cur = ov_next;
+        st_cur = st_next;
+        __syncthreads();
+    }
+
+    // ---- epilogue: fp16 range flag of the span, final state ----
+    // Outside the range: a half-chunk decay beyond what fp16's exponent covers around the anchor; inputs so large
+    // or so small that the gated operands (within 2^kMaxHalfDecay of them) overflow or lose their leading bits;
+    // a non-finite output (an operand overflowed after all).  (Comparisons are written so that NaN fails them.)
+    const bool bad = !(trk_e <= kMaxHalfDecay) || !(trk_q <= kMaxInput) || !(trk_k <= kMaxInput) ||
+                     !(trk_v <= kMaxOperand) || !(trk_q >= kMinInput) || !(trk_k >= kMinInput) ||
+                     !(trk_v >= kMinInput) || !(trk_o <= 3.0e38f);
+    if (__any(bad) && lane == 0) atomicOr(s_flag, 1);
+    __syncthreads();
+    if (tid == 0) p.ws_fail[(size_t)bh * p.nspans + sp] = *s_flag;
+
+    if ((p.nspans == 1 || p.chain_in_output) && sp == p.nspans - 1 && p.final_state != nullptr) {
+        float *dst = p.final_state + (size_t)bh * dk * dv;
+        auto put = [&](auto wave_c, int) {
+            constexpr int W = decltype(wave_c)::value;
+#pragma unroll
+            for (int i = 0; i < C::kOwned[W]; ++i) {
+                const int t = owned_start<CLS>(W) + i;
+                const int n = 16 * (t / NCT) + lm;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int cch = 16 * (t % NCT) + 4 * g + r;
+                    if (cch < dk && n < dv) dst[cch * dv + n] = acc[i][r];
+                }
+            }
+        };
+        per_wave(put, 0);
+    }
+}
+
+template <int CLS, typename TOut>
+hipError_t launch_cls(const Params &p, hipStream_t stream) {
+    using L = FastLayout<CLS>;
+    constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
+    constexpr int MINW = kGroupsPerCu >= 3 ? FAST_MINW_CAP : (kGroupsPerCu >= 2 ? 2 : 1);
+    auto kernel = fast_output_kernel<CLS, TOut, MINW>;
+    static bool configured[kMaxDevices] = {};
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), L::kBytes, configured);
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned)(p.B * p.H * p.nspans)), block(256);
+    hipLaunchKernelGGL(kernel, grid, block, L::kBytes, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool fast_engine_supports(const Params &p) {
+    if (!mfma_engine_supports(p)) return false;
+    // plain key-side recurrence only: no gate prologue / epilogue, no value-side gate, no accumulation, no gate shift
+    return !two_sided(p) && p.z_gate == nullptr && p.r_pre == nullptr && !p.accumulate && p.gate_shift == 0;
+}
+
+int fast_groups_per_cu(const Params &p) {
+    const int ndk16 = (p.dk + 15) / 16, ndv16 = (p.dv + 15) / 16;
+    if (ndk16 <= 2 && ndv16 <= 4) return (160 * 1024) / FastLayout<0>::kBytes >= 3 ? 3 : 2;
+    if (ndk16 <= 3 && ndv16 <= 5) return (160 * 1024) / FastLayout<1>::kBytes >= 3 ? 3 : 2;
+    return (160 * 1024) / FastLayout<2>::kBytes >= 3 ? 3 : ((160 * 1024) / FastLayout<2>::kBytes >= 2 ? 2 : 1);
+}
+
+hipError_t launch_fast_output(const Params &p, hipStream_t stream) {
+    const int ndk16 = (p.dk + 15) / 16, ndv16 = (p.dv + 15) / 16;
+    const bool bf16_out = p.out_dtype == GLA_DT_BF16;
+    if (ndk16 <= 2 && ndv16 <= 4)
+        return bf16_out ? launch_cls<0, uint16_t>(p, stream) : launch_cls<0, float>(p, stream);
+    if (ndk16 <= 3 && ndv16 <= 5)
+        return bf16_out ? launch_cls<1, uint16_t>(p, stream) : launch_cls<1, float>(p, stream);
+    return bf16_out ? launch_cls<2, uint16_t>(p, stream) : launch_cls<2, float>(p, stream);
+}
+
+}  // namespace gla

@@ -191,6 +191,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     // a compute unit then hosts a long and a short chain, and the group that ends first leaves it to the other.
     if (OUT && p.chain_in_output && (bh & 1)) sp_ = spans_here - 1 - sp_;
     const int sp = sp_;
+    if constexpr (OUT) {
+        // second opinion for the fp16 engine: only the spans it flagged are recomputed (uniform over the group)
+        if (p.only_flagged && p.ws_fail[(size_t)bh * p.nspans + sp] == 0) return;
+    }
     const int dk = p.dk, dv = p.dv, T = p.T;
     const int s_begin = sp * p.span_len;
     const int s_end = min(T, s_begin + p.span_len);
