@@ -15,6 +15,7 @@ int g_opt_engine = GLA_ENGINE_AUTO;
 int g_opt_carry = GLA_CARRY_AUTO;
 int g_opt_bwd_split = 0;
 int g_opt_range_fallback = 1;
+int g_opt_fast_state = 1;   // (experiment switch)
 
 // Most spans per (batch, head) that the output pass chains by itself: work-group r reads the r local states
 // before it, so the reads grow with the square of the span count while a carry kernel's grow linearly.
@@ -99,7 +100,7 @@ int choose_engine_and_plan(Params &p, void *workspace, bool &use_mfma, bool *use
     }
     bool fast = false;
     if (use_fast != nullptr) {
-        fast = use_mfma && g_opt_engine == GLA_ENGINE_MFMA_FP16 && fast_engine_supports(p);   // (opt-in for now)
+        fast = use_mfma && g_opt_engine != GLA_ENGINE_MFMA && fast_engine_supports(p);
         if (g_opt_engine == GLA_ENGINE_MFMA_FP16 && !fast) return GLA_ERR_UNSUPPORTED;
         *use_fast = fast;
     }
@@ -396,7 +397,7 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     hipError_t e = hipSuccess;
     mark(0);
     if (p.nspans > 1) {
-        e = span(kModeState);
+        e = (use_fast && g_opt_fast_state) ? launch_fast_state(p, stream) : span(kModeState);
         if (e != hipSuccess) return GLA_ERR_HIP;
     }
     mark(1);
@@ -411,8 +412,15 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
         e = launch_fast_output(p, stream);
         if (e != hipSuccess) return GLA_ERR_HIP;
         if (g_opt_range_fallback) {
-            p.only_flagged = 1;
-            e = launch_mfma_span(p, kModeOutput, stream);
+            // one work-group per (batch, head) walks the whole sequence from the caller's initial state; those of
+            // heads without a raised flag return at once
+            Params pf = p;
+            pf.fail_spans = p.nspans;
+            pf.only_flagged = 1;
+            pf.nspans = 1;
+            pf.span_len = ((p.T + kChunk - 1) / kChunk) * kChunk;
+            pf.chain_in_output = 0;
+            e = launch_mfma_span(pf, kModeOutput, stream);
         }
     } else {
         e = span(kModeOutput);

@@ -65,11 +65,12 @@ struct Params {
     const float *log_beta;
     const void *z_beta;     // or (with z_gate) its pre-activation: log beta = logsigmoid(z_beta) * inv_tau, like v
     float *ws_lgam_b;       // [B*H, nspans, dv]  summed log_beta of each span (phase 1 -> phase 2)
-    // fp16 engine (gla_fast.hip): one flag per span, raised by the output pass when the span's gates or operands
-    // leave the range its fp16 operands cover; with only_flagged the bf16 hi/lo output pass recomputes those
-    // spans and leaves the others alone
-    int *ws_fail;           // [B*H, nspans]
+    // fp16 engine (gla_fast.hip): one flag per span, raised by its passes when the span's gates or operands leave
+    // the range its fp16 operands cover; with only_flagged the bf16 hi/lo output pass (launched with one span per
+    // head) recomputes the (batch, head) sequences that have a raised flag and leaves the others alone
+    int *ws_fail;           // [B*H, nspans of the fp16 engine's plan]
     int only_flagged;
+    int fail_spans;         // flags per (batch, head) when only_flagged is set
 };
 
 // the gate has a value-side factor
@@ -133,6 +134,7 @@ bool mfma_engine_supports(const Params &p);
 bool fast_engine_supports(const Params &p);
 int fast_groups_per_cu(const Params &p);
 hipError_t launch_fast_output(const Params &p, hipStream_t stream);
+hipError_t launch_fast_state(const Params &p, hipStream_t stream);   // its span-state pass (phase 1)
 // backward-only kernels: r_s[c] = sum_n S_s[c,n] w_s[n] over the states of (p.k, p.v, p.log_alpha); and
 // dlog_alpha = reverse cumulative sum of q * dq - k * dk (totals: [B*H, dg_spans(T), dk] floats of scratch)
 hipError_t launch_row_read(const Params &p, const void *w, float *r, hipStream_t stream);

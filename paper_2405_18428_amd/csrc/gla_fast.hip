@@ -144,8 +144,17 @@ __host__ __device__ constexpr int owned_start(int w) {
 
 constexpr int kFastThreads = 512;    // 4 producer waves + 4 consumer waves
 
-template <int CLS, typename TOut, int MINW>
-__global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params p) {
+// Last statement of a code path that exists once per consumer wave (W = compile-time wave index).  The paths end in
+// the same instructions on different registers of the accumulator arrays; when the compiler merges such tails the
+// arrays are addressed through a pointer that depends on the wave and leave the registers for scratch memory.
+// A statement that differs between the copies keeps them apart.
+#define WAVE_CODE_END(W) asm volatile("; end of the code of consumer wave %0" ::"n"(W))
+
+// STATE: the span-state pass (phase 1 of the span plan): the same producers without q, the consumers only update
+// their state tiles from a zero state and leave U_r (anchored at the end of the span) and log Gamma_r in the workspace.
+// DEPTH: chunks of rows a producer has in flight beyond the one it works on (register sets it alternates between).
+template <int CLS, typename TOut, int MINW, bool STATE, int DEPTH>
+__global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p) {
     using C = FastCfg<CLS>;
     using L = FastLayout<CLS>;
     constexpr int NCT = C::NCT, NDV16 = C::NDV16, NK32 = C::NK32, KST = C::KST, VS = C::VS, SST = C::SST;
@@ -178,9 +187,12 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
         const int nb = gridDim.x;
         if ((nb & 7) == 0) blk = (blk & 7) * (nb >> 3) + (blk >> 3);
     }
-    const int bh = blk / p.nspans;
-    int sp_ = blk - bh * p.nspans;
-    if (p.chain_in_output && (bh & 1)) sp_ = p.nspans - 1 - sp_;
+    // spans per (batch, head) that this launch covers: the state pass leaves out the last one when the output
+    // pass chains the span states itself (nothing reads that U)
+    const int spans_here = (STATE && p.chain_in_output) ? p.nspans - 1 : p.nspans;
+    const int bh = blk / spans_here;
+    int sp_ = blk - bh * spans_here;
+    if (!STATE && p.chain_in_output && (bh & 1)) sp_ = spans_here - 1 - sp_;
     const int sp = sp_;
     const int dk = p.dk, dv = p.dv, T = p.T;
     const int s_begin = sp * p.span_len;
@@ -255,42 +267,47 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
 #pragma unroll
         for (int i = 0; i < NVP; ++i) vpb[i] = 2u * (uint32_t)min(8 * (g + 4 * i), dv - 8);
 
-        f32x4 r_la[NCT];           // log_alpha pieces waiting for the scan
+        // (the rows of chunk x travel in register set x % DEPTH)
+        f32x4 r_la[DEPTH][NCT];    // log_alpha pieces waiting for the scan
         float r_b[NV];             // scanned gates (log2, prefix inside the 16-token tile) waiting for the gate stage
-        u32x2 r_q[NCT], r_k[NCT];  // raw q, k pieces waiting for the gate stage
-        u32x4 r_v[NVP];            // v pieces on their way to LDS
+        u32x2 r_q[DEPTH][NCT], r_k[DEPTH][NCT];  // raw q, k pieces waiting for the gate stage
+        u32x4 r_v[DEPTH][NVP];     // v pieces on their way to LDS
         // fp16 range check of the span: largest half-chunk decay (log2), largest |q|, |k|, |v|
         float trk_q = 0.f, trk_k = 0.f, trk_v = 0.f;
 
         // the rows of the walker's current token
-        auto issue_la = [&]() {
+        auto issue_la = [&](auto set_c) {
+            constexpr int R = decltype(set_c)::value;
             const uint32_t off = 2u * ((uint32_t)tok * dk2 + chb0);
 #pragma unroll
-            for (int u = 0; u < NCT - 1; ++u) r_la[u] = *reinterpret_cast<const f32x4 *>(gla_ + off + 64u * u);
-            r_la[NCT - 1] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * ((uint32_t)tok * dk2 + chb_last));
+            for (int u = 0; u < NCT - 1; ++u) r_la[R][u] = *reinterpret_cast<const f32x4 *>(gla_ + off + 64u * u);
+            r_la[R][NCT - 1] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * ((uint32_t)tok * dk2 + chb_last));
         };
-        auto issue_qk = [&](int tk) {
+        auto issue_qk = [&](auto set_c, int tk) {
+            constexpr int R = decltype(set_c)::value;
             const uint32_t off = (uint32_t)tk * dk2 + chb0;
 #pragma unroll
             for (int u = 0; u < NCT - 1; ++u) {
-                r_q[u] = *reinterpret_cast<const u32x2 *>(gq + off + 32u * u);
-                r_k[u] = *reinterpret_cast<const u32x2 *>(gk + off + 32u * u);
+                if constexpr (!STATE) r_q[R][u] = *reinterpret_cast<const u32x2 *>(gq + off + 32u * u);
+                r_k[R][u] = *reinterpret_cast<const u32x2 *>(gk + off + 32u * u);
             }
-            r_q[NCT - 1] = *reinterpret_cast<const u32x2 *>(gq + (uint32_t)tk * dk2 + chb_last);
-            r_k[NCT - 1] = *reinterpret_cast<const u32x2 *>(gk + (uint32_t)tk * dk2 + chb_last);
+            if constexpr (!STATE) r_q[R][NCT - 1] = *reinterpret_cast<const u32x2 *>(gq + (uint32_t)tk * dk2 + chb_last);
+            r_k[R][NCT - 1] = *reinterpret_cast<const u32x2 *>(gk + (uint32_t)tk * dk2 + chb_last);
         };
-        auto issue_v = [&](int tk) {   // (rows past the span keep the values of its last token: their k~ is zero)
+        auto issue_v = [&](auto set_c, int tk) {   // (rows past the span keep the values of its last token: their k~ is zero)
+            constexpr int R = decltype(set_c)::value;
 #pragma unroll
-            for (int i = 0; i < NVP; ++i) r_v[i] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tk * dv2 + vpb[i]);
+            for (int i = 0; i < NVP; ++i) r_v[R][i] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tk * dv2 + vpb[i]);
         };
 
         // scan: prefix sums of log2(alpha) inside this wave's tile, tile totals to LDS
-        auto scan = [&](int x) {
+        auto scan = [&](auto set_c, int x) {
+            constexpr int R = decltype(set_c)::value;
             float *tot = s_tot + ((x % 3) * 4 + w) * 4 * NV + g * NV;
 #pragma unroll
             for (int u = 0; u < NCT; ++u)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) r_b[4 * u + e] = r_la[u][e] * kLog2e;
+                for (int e = 0; e < 4; ++e) r_b[4 * u + e] = r_la[R][u][e] * kLog2e;
             if (x >= ragged_from) {
                 const bool valid = row_is_token(x);
 #pragma unroll
@@ -313,7 +330,8 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
         const int tile_a = w == 0 ? 0 : -1, tile_b = w <= 1 ? 1 : (w == 3 ? 2 : -1);
         const float off_sign = w == 3 ? 1.f : -1.f;
         const float *s_zero = reinterpret_cast<const float *>(smem + L::oZero) + g * NV;
-        auto gate = [&](int x) {
+        auto gate = [&](auto set_c, int x) {
+            constexpr int R = decltype(set_c)::value;
             const float *tot = s_tot + (x % 3) * 16 * NV + g * NV;      // + tile * 4 * NV
             const float *pa = tile_a >= 0 ? tot + tile_a * 4 * NV : s_zero;
             const float *pb = tile_b >= 0 ? tot + tile_b * 4 * NV : s_zero;
@@ -330,7 +348,11 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
             for (int u = 0; u < NCT; ++u) {
                 const f32x4 ta = *reinterpret_cast<const f32x4 *>(pa + 4 * u);
                 const f32x4 tb = *reinterpret_cast<const f32x4 *>(pb + 4 * u);
-                uint32_t q0 = r_q[u][0], q1 = r_q[u][1], k0 = r_k[u][0], k1 = r_k[u][1];
+                uint32_t q0 = 0u, q1 = 0u, k0 = r_k[R][u][0], k1 = r_k[R][u][1];
+                if constexpr (!STATE) {
+                    q0 = r_q[R][u][0];
+                    q1 = r_q[R][u][1];
+                }
                 if (u == NCT - 1) {
                     q0 &= keep_last; q1 &= keep_last; k0 &= keep_last; k1 &= keep_last;
                 } else if (ragged) {
@@ -339,23 +361,27 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
                 float qx[4], kx[4];
                 qx[0] = bf16_lo_as_float(q0); qx[1] = bf16_hi_as_float(q0); qx[2] = bf16_lo_as_float(q1); qx[3] = bf16_hi_as_float(q1);
                 kx[0] = bf16_lo_as_float(k0); kx[1] = bf16_hi_as_float(k0); kx[2] = bf16_lo_as_float(k1); kx[3] = bf16_hi_as_float(k1);
-                trk_q = fmaxf(fmaxf(trk_q, fabsf(qx[0])), fabsf(qx[1]));
-                trk_q = fmaxf(fmaxf(trk_q, fabsf(qx[2])), fabsf(qx[3]));
+                if constexpr (!STATE) {
+                    trk_q = fmaxf(fmaxf(trk_q, fabsf(qx[0])), fabsf(qx[1]));
+                    trk_q = fmaxf(fmaxf(trk_q, fabsf(qx[2])), fabsf(qx[3]));
+                }
                 trk_k = fmaxf(fmaxf(trk_k, fabsf(kx[0])), fabsf(kx[1]));
                 trk_k = fmaxf(fmaxf(trk_k, fabsf(kx[2])), fabsf(kx[3]));
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float ex = fmaf(off_sign, ta[e] + tb[e], r_b[4 * u + e]);
-                    qx[e] *= exp2_fast(ex);
+                    if constexpr (!STATE) qx[e] *= exp2_fast(ex);
                     kx[e] *= exp2_fast(-ex);
                 }
-                *reinterpret_cast<u32x2 *>(qrow + 16 * u) = u32x2{pack_f16(qx[0], qx[1]), pack_f16(qx[2], qx[3])};
+                if constexpr (!STATE)
+                    *reinterpret_cast<u32x2 *>(qrow + 16 * u) = u32x2{pack_f16(qx[0], qx[1]), pack_f16(qx[2], qx[3])};
                 *reinterpret_cast<u32x2 *>(krow + 16 * u) = u32x2{pack_f16(kx[0], kx[1]), pack_f16(kx[2], kx[3])};
             }
         };
 
         // v rows of chunk x: bf16 -> fp16 (exact inside fp16's range), to LDS
-        auto park_v = [&](int x) {
+        auto park_v = [&](auto set_c, int x) {
+            constexpr int R = decltype(set_c)::value;
             uint16_t *vrow = s_v + (x & 1) * (kChunk * VS) + (16 * w + lm) * VS + 8 * g;
 #pragma unroll
             for (int i = 0; i < NVP; ++i) {
@@ -363,7 +389,7 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
                     u32x4 h;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const uint32_t x2 = r_v[i][j];
+                        const uint32_t x2 = r_v[R][i][j];
                         const float lo = bf16_lo_as_float(x2), hi = bf16_hi_as_float(x2);
                         trk_v = fmaxf(fmaxf(trk_v, fabsf(lo)), fabsf(hi));
                         h[j] = pack_f16(lo, hi);
@@ -374,8 +400,21 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
         };
 
         // ---- pipeline fill ----
-        issue_la();                // chunk 0: on their way while the span's start state is formed
-        {
+        // (every load is issued as soon as the registers it fills have been read; the loads of chunk x are issued
+        // DEPTH iterations before the stage that reads them)
+        using Set0 = std::integral_constant<int, 0>;
+        using Set1 = std::integral_constant<int, DEPTH - 1>;     // set of odd chunks
+        int tok_qkv = tok;
+        issue_la(Set0{});              // chunk 0: on their way while the span's start state is formed
+        issue_qk(Set0{}, tok);
+        issue_v(Set0{}, tok);
+        if constexpr (DEPTH == 2) {
+            next_row_token();
+            issue_la(Set1{});          // chunk 1
+            issue_qk(Set1{}, tok);
+            issue_v(Set1{}, tok);
+        }
+        if constexpr (!STATE) {
             const bool chain = p.chain_in_output && (sp > 0 || p.initial_state != nullptr);   // uniform
             if (chain) {
                 constexpr int kV4 = (16 * NCT * 16 * NDV16 / 4 + kFastThreads - 1) / kFastThreads;
@@ -384,44 +423,48 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
                 __syncthreads();
             }
         }
-        // (every load is issued as soon as the registers it fills have been read)
-        scan(0);
-        issue_qk(tok);             // chunk 0
-        issue_v(tok);
-        next_row_token();
-        issue_la();                // chunk 1
-        __syncthreads();           // totals of chunk 0 are in LDS; the chained state has been read
-        gate(0);
-        int tok_qkv = tok;
-        issue_qk(tok_qkv);         // chunk 1
-        if (1 < nch) scan(1);
-        next_row_token();
-        issue_la();                // chunk 2
-        park_v(0);
-        issue_v(tok_qkv);
-        __syncthreads();
-
-        for (int c = 0; c < nch; ++c) {
-            if (c + 1 < nch) gate(c + 1);
-            tok_qkv = tok;
-            issue_qk(tok_qkv);     // chunk c + 2
-            if (c + 2 < nch) scan(c + 2);
+        // One iteration of the producers, c = chunk the consumers contract meanwhile (-2, -1: pipeline fill):
+        // gate and park chunk c + 1, scan chunk c + 2, refill the register sets just read.
+        auto iteration = [&](auto par_c, int c) {
+            constexpr int P = decltype(par_c)::value;                       // c mod DEPTH
+            using SetG = std::integral_constant<int, (P + 1) % DEPTH>;      // set of chunk c + 1 (and c + 1 + DEPTH)
+            using SetS = std::integral_constant<int, (P + 2) % DEPTH>;      // set of chunk c + 2 (and c + 2 + DEPTH)
+            if (c + 1 >= 0 && c + 1 < nch) gate(SetG{}, c + 1);
+            if (c + 1 >= 0) {
+                tok_qkv = tok;                                              // token of chunk c + 1 + DEPTH
+                issue_qk(SetG{}, tok_qkv);
+            }
+            if (c + 2 < nch) scan(SetS{}, c + 2);
             next_row_token();
-            issue_la();            // chunk c + 3
-            if (c + 1 < nch) park_v(c + 1);
-            issue_v(tok_qkv);
+            issue_la(SetS{});                                               // chunk c + 2 + DEPTH
+            if (c + 1 >= 0) {
+                if (c + 1 < nch) park_v(SetG{}, c + 1);
+                issue_v(SetG{}, tok_qkv);
+            }
             __syncthreads();
+        };
+        iteration(std::integral_constant<int, 0>{}, -2);      // (after it: totals of chunk 0 in LDS, chained state read)
+        iteration(std::integral_constant<int, DEPTH - 1>{}, -1);
+        for (int c = 0; c < nch; c += DEPTH) {
+            iteration(std::integral_constant<int, 0>{}, c);
+            if constexpr (DEPTH == 2) {
+                if (c + 1 < nch) iteration(std::integral_constant<int, 1>{}, c + 1);
+            }
         }
 
         // Outside the range: inputs so large or so small that the gated operands (within 2^kMaxHalfDecay of them)
         // overflow or lose their leading bits.  (Comparisons are written so that NaN fails them.)
-        bad = !(trk_q <= kMaxInput) || !(trk_k <= kMaxInput) || !(trk_v <= kMaxOperand) ||
-              !(trk_q >= kMinInput) || !(trk_k >= kMinInput) || !(trk_v >= kMinInput);
+        bad = !(trk_k <= kMaxInput) || !(trk_v <= kMaxOperand) || !(trk_k >= kMinInput) || !(trk_v >= kMinInput);
+        if constexpr (!STATE) bad = bad || !(trk_q <= kMaxInput) || !(trk_q >= kMinInput);
     } else {
         // =========================== consumers ===========================
         char *gout = static_cast<char *>(p.out) + base_v * sizeof(TOut);
         float trk_o = 0.f;         // largest |output| (a non-finite one: an operand overflowed after all)
         float trk_e = 0.f;         // largest decay of a channel over half a chunk (log2)
+        static_assert(C::kOwned[0] >= NCT, "consumer wave 0 owns a tile of every channel unit");
+        f32x4 lg_sum[NCT];         // STATE, consumer wave 0: log2 of the span's total decay, channels 16 ct + 4 g + r
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) lg_sum[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
         // ---- state tiles owned by this wave ----
         constexpr int MAXOWN = C::kOwned[0];
@@ -430,7 +473,7 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
         for (int i = 0; i < MAXOWN; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
         // ---- state entering the span ----
-        {
+        if constexpr (!STATE) {
             const bool chain = p.chain_in_output && (sp > 0 || p.initial_state != nullptr);   // uniform
             const float *s0 = nullptr;
             if (p.nspans > 1 && !p.chain_in_output)
@@ -451,11 +494,13 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
                     for (int i = 0; i < C::kOwned[W]; ++i) {
                         const int t = owned_start<CLS>(W) + i;
                         const int n = 16 * (t / NCT) + lm;
+                        float x[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
                             const int c = 16 * (t % NCT) + 4 * g + r;
-                            if (c < dk && n < dv) acc[i][r] = s0[c * dv + n];
+                            x[r] = (c < dk && n < dv) ? s0[min(c, dk - 1) * dv + min(n, dv - 1)] : 0.f;
                         }
+                        acc[i] = f32x4{x[0], x[1], x[2], x[3]};
                     }
                 };
                 switch (w) {
@@ -475,6 +520,7 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
             const float *t_c = s_tot + ((c + 3) % 3) * 16 * NV + g * NV;        // totals of chunk c (c = -1: unused)
             const float *t_n = s_tot + ((c + 1) % 3) * 16 * NV + g * NV;        // totals of chunk c + 1
             uint16_t *srow = s_s + ((c + 1) & 1) * (16 * NDV16 * SST);
+            (void)srow;
             f32x4 fac[NCT];
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct) {
@@ -491,23 +537,29 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
                         h0 = *reinterpret_cast<const f32x4 *>(t_n + 0 * 4 * NV + 4 * ct) +
                              *reinterpret_cast<const f32x4 *>(t_n + 1 * 4 * NV + 4 * ct);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        trk_e = fmaxf(fmaxf(trk_e, fabsf(h1[r])), fabsf(h0[r]));
-                        fac[ct][r] = exp2_fast(h1[r] + h0[r]);
-                    }
+                    for (int r = 0; r < 4; ++r) trk_e = fmaxf(fmaxf(trk_e, fabsf(h1[r])), fabsf(h0[r]));
+                    // (whole-vector assignments: element-wise stores into these arrays keep them out of registers
+                    // once the compiler merges the tails of the four wave-specific copies of this code)
+                    const f32x4 hs = h1 + h0;
+                    fac[ct] = f32x4{exp2_fast(hs[0]), exp2_fast(hs[1]), exp2_fast(hs[2]), exp2_fast(hs[3])};
+                    if constexpr (STATE && W == 0) lg_sum[ct] = lg_sum[ct] + hs;   // over the span: log2 Gamma
                 }
             }
 #pragma unroll
             for (int i = 0; i < t_hi - t_lo; ++i) {
                 const int t = t_lo + i;
                 const int ct = t % NCT, nt = t / NCT;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc[i][r] *= fac[ct][r];
+                acc[i] = acc[i] * fac[ct];
                 // slot of channel 16 ct + 4 g + r in a row of P: the 32-channel steps interleave two units per lane group
-                const int pos = (ct < 2 * NK32) ? 32 * (ct >> 1) + 8 * g + 4 * (ct & 1) : 32 * NK32 + 4 * g;
-                *reinterpret_cast<u32x2 *>(srow + (16 * nt + lm) * SST + pos) =
-                    u32x2{pack_f16(acc[i][0], acc[i][1]), pack_f16(acc[i][2], acc[i][3])};
+                if constexpr (!STATE) {
+                    const int pos = (ct < 2 * NK32) ? 32 * (ct >> 1) + 8 * g + 4 * (ct & 1) : 32 * NK32 + 4 * g;
+                    *reinterpret_cast<u32x2 *>(srow + (16 * nt + lm) * SST + pos) =
+                        u32x2{pack_f16(acc[i][0], acc[i][1]), pack_f16(acc[i][2], acc[i][3])};
+                } else {
+                    (void)nt;
+                }
             }
+            WAVE_CODE_END(W);
         };
 
         const int tr_row = lm >> 2, tr_col = 4 * (lm & 3);   // transposing reads: token-in-4 and column quad of this lane
@@ -520,7 +572,7 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
             const uint16_t *sb = s_s + (c & 1) * (16 * NDV16 * SST);
             // ---- q~ of this wave's tokens: the B operand of the score tiles and of q~ P ----
             uint32_t qf[NCT][2];
-            {
+            if constexpr (!STATE) {
                 const uint16_t *qrow = s_q + (c & 1) * (kChunk * KST) + (16 * W + lm) * KST + 4 * g;
 #pragma unroll
                 for (int u = 0; u < NCT; ++u) {
@@ -532,7 +584,7 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
             // ---- score tiles, transposed: lane (lm, g) gets A[i = 16 W + lm][j = 16 jt + 4 g + r] ----
             f32x4 d[W + 1];
 #pragma unroll
-            for (int jt = 0; jt <= W; ++jt) {
+            for (int jt = 0; jt <= (STATE ? -1 : W); ++jt) {
                 const uint16_t *krow = kb + (16 * jt + lm) * KST + 4 * g;
                 d[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -548,21 +600,20 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
                     d[jt] = mfma_h16(a, u32x2{qf[2 * NK32][0], qf[2 * NK32][1]}, d[jt]);
                 }
             }
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (4 * g + r > lm) d[W][r] = 0.f;            // causal mask of the diagonal tile
+            if constexpr (!STATE) {
+                // causal mask of the diagonal tile
+                d[W] = f32x4{4 * g + 0 > lm ? 0.f : d[W][0], 4 * g + 1 > lm ? 0.f : d[W][1],
+                             4 * g + 2 > lm ? 0.f : d[W][2], 4 * g + 3 > lm ? 0.f : d[W][3]};
+            }
             u32x4 pa[NQ];                                     // A^T as the B operand of O^T += V^T A^T
 #pragma unroll
-            for (int q32 = 0; q32 < NQ; ++q32) {
-                pa[q32][0] = pack_f16(d[2 * q32][0], d[2 * q32][1]);
-                pa[q32][1] = pack_f16(d[2 * q32][2], d[2 * q32][3]);
+            for (int q32 = 0; q32 < (STATE ? 0 : NQ); ++q32) {
+                uint32_t hi0 = 0u, hi1 = 0u;
                 if (2 * q32 + 1 <= W) {
-                    pa[q32][2] = pack_f16(d[2 * q32 + 1][0], d[2 * q32 + 1][1]);
-                    pa[q32][3] = pack_f16(d[2 * q32 + 1][2], d[2 * q32 + 1][3]);
-                } else {
-                    pa[q32][2] = 0u;
-                    pa[q32][3] = 0u;
+                    hi0 = pack_f16(d[2 * q32 + 1][0], d[2 * q32 + 1][1]);
+                    hi1 = pack_f16(d[2 * q32 + 1][2], d[2 * q32 + 1][3]);
                 }
+                pa[q32] = u32x4{pack_f16(d[2 * q32][0], d[2 * q32][1]), pack_f16(d[2 * q32][2], d[2 * q32][3]), hi0, hi1};
             }
             // ---- v fragments (contraction slot (g, e) of step q32 = token 32 q32 + 16 (e / 4) + 4 g + e % 4) ----
             const uint16_t *vrow = vb + (4 * g + tr_row) * VS + tr_col;
@@ -584,28 +635,38 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
                 const bool owned_col = x >= NT_LO && x <= NT_HI;
 #pragma unroll
                 for (int q32 = 0; q32 < 2; ++q32) {
-                    if (q32 < NQ || owned_col) {
+                    if ((!STATE && q32 < NQ) || owned_col) {
                         const u32x4 vf = v_frag(q32, x);
-                        if (q32 < NQ) o[x] = mfma_h32(vf, pa[q32], o[x]);
+                        if constexpr (!STATE) {
+                            if (q32 < NQ) o[x] = mfma_h32(vf, pa[q32], o[x]);
+                        }
                         if (owned_col) vown[q32][owned_col ? x - NT_LO : 0] = vf;
                     }
                 }
-                const uint16_t *srow = sb + (16 * x + lm) * SST;
+                if constexpr (!STATE) {
+                    const uint16_t *srow = sb + (16 * x + lm) * SST;
 #pragma unroll
-                for (int ks = 0; ks < NK32; ++ks) {
-                    const u32x4 st = *reinterpret_cast<const u32x4 *>(srow + 32 * ks + 8 * g);
-                    o[x] = mfma_h32(st, u32x4{qf[2 * ks][0], qf[2 * ks][1], qf[2 * ks + 1][0], qf[2 * ks + 1][1]},
-                                    o[x]);
-                }
-                if constexpr (TAIL) {
-                    const u32x2 st = *reinterpret_cast<const u32x2 *>(srow + 32 * NK32 + 4 * g);
-                    o[x] = mfma_h16(st, u32x2{qf[2 * NK32][0], qf[2 * NK32][1]}, o[x]);
+                    for (int ks = 0; ks < NK32; ++ks) {
+                        const u32x4 st = *reinterpret_cast<const u32x4 *>(srow + 32 * ks + 8 * g);
+                        o[x] = mfma_h32(st, u32x4{qf[2 * ks][0], qf[2 * ks][1], qf[2 * ks + 1][0], qf[2 * ks + 1][1]},
+                                        o[x]);
+                    }
+                    if constexpr (TAIL) {
+                        const u32x2 st = *reinterpret_cast<const u32x2 *>(srow + 32 * NK32 + 4 * g);
+                        o[x] = mfma_h16(st, u32x2{qf[2 * NK32][0], qf[2 * NK32][1]}, o[x]);
+                    }
                 }
             }
 #pragma unroll
-            for (int x = 0; x < NDV16; ++x)
-                trk_o = fmaxf(trk_o, fmaxf(fmaxf(fabsf(o[x][0]), fabsf(o[x][1])), fmaxf(fabsf(o[x][2]), fabsf(o[x][3]))));
-            if (c < ragged_from || row_is_token(c)) {
+            for (int x = 0; x < (STATE ? 0 : NDV16); x += 2) {
+                trk_o = fmaxf(fmaxf(trk_o, fabsf(o[x][0])), fabsf(o[x][1]));
+                trk_o = fmaxf(fmaxf(trk_o, fabsf(o[x][2])), fabsf(o[x][3]));
+                if (x + 1 < NDV16) {
+                    trk_o = fmaxf(fmaxf(trk_o, fabsf(o[x + 1][0])), fabsf(o[x + 1][1]));
+                    trk_o = fmaxf(fmaxf(trk_o, fabsf(o[x + 1][2])), fabsf(o[x + 1][3]));
+                }
+            }
+            if (!STATE && (c < ragged_from || row_is_token(c))) {
                 char *orow = gout + ((uint32_t)tok * (uint32_t)p.st_v + 4u * (uint32_t)g) * (uint32_t)sizeof(TOut);
 #pragma unroll
                 for (int x = 0; x < NDV16; ++x) {
@@ -642,6 +703,7 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
                     acc[i] = mfma_h32(kt[t % NCT][1], vown[1][t / NCT - NT_LO], acc[i]);
                 }
             }
+            WAVE_CODE_END(W);
         };
 
         auto per_wave = [&](auto fn, int c) {
@@ -660,15 +722,35 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
         for (int c = 0; c < nch; ++c) {
             per_wave(contract, c);
             per_wave(publish, c);
-            next_row_token();
+            if constexpr (!STATE) next_row_token();
             __syncthreads();
         }
 
-        // a half-chunk decay beyond what fp16's exponent covers around the anchor, or a non-finite output
+        // a half-chunk decay beyond what fp16's exponent covers around the anchor, or a non-finite output / state
+        if constexpr (STATE) {
+#pragma unroll
+            for (int i = 0; i < MAXOWN; ++i) {
+                trk_o = fmaxf(fmaxf(trk_o, fabsf(acc[i][0])), fabsf(acc[i][1]));
+                trk_o = fmaxf(fmaxf(trk_o, fabsf(acc[i][2])), fabsf(acc[i][3]));
+            }
+        }
         bad = !(trk_e <= kMaxHalfDecay) || !(trk_o <= 3.0e38f);
 
-        if ((p.nspans == 1 || p.chain_in_output) && sp == p.nspans - 1 && p.final_state != nullptr) {
-            float *dst = p.final_state + (size_t)bh * dk * dv;
+        float *dst = nullptr;
+        if constexpr (STATE) {
+            dst = p.ws_state + ((size_t)bh * p.nspans + sp) * dk * dv;      // U of the span (the last chunk's publish anchored it at the span's end)
+            if (w == 0 && lm == 0) {                                         // the workspace keeps natural logarithms
+                float *lg = p.ws_lgam + ((size_t)bh * p.nspans + sp) * dk;
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (16 * ct + 4 * g + r < dk) lg[16 * ct + 4 * g + r] = lg_sum[ct][r] * kLn2;
+            }
+        } else if ((p.nspans == 1 || p.chain_in_output) && sp == p.nspans - 1 && p.final_state != nullptr) {
+            dst = p.final_state + (size_t)bh * dk * dv;
+        }
+        if (dst != nullptr) {
             auto put = [&](auto wave_c, int) {
                 constexpr int W = decltype(wave_c)::value;
 #pragma unroll
@@ -687,48 +769,81 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_output_kernel(Params 
     }
 
     // ---- fp16 range flag of the span ----
+    // (the state pass runs first and leaves out the last span of a head whose states the output pass chains)
     if (__any(bad) && lane == 0) atomicOr(s_flag, 1);
     __syncthreads();
-    if (tid == 0) p.ws_fail[(size_t)bh * p.nspans + sp] = *s_flag;
+    if (tid == 0) {
+        int *flag = p.ws_fail + (size_t)bh * p.nspans + sp;
+        if constexpr (STATE) {
+            *flag = *s_flag;
+            if (spans_here < p.nspans && sp == 0) p.ws_fail[(size_t)bh * p.nspans + p.nspans - 1] = 0;
+        } else {
+            *flag = *s_flag | (p.nspans > 1 ? *flag : 0);
+        }
+    }
 }
 
-template <int CLS, typename TOut>
+template <int CLS, typename TOut, bool STATE>
 hipError_t launch_cls(const Params &p, hipStream_t stream) {
     using L = FastLayout<CLS>;
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int MINW = kGroupsPerCu >= 2 ? 4 : 2;    // waves per SIMD: two resident groups of 8 waves, or one
-    auto kernel = fast_output_kernel<CLS, TOut, MINW>;
+    // the state pass has the registers for a second set of rows in flight
+    constexpr int DEPTH = 1;   // (a second set of rows in flight gained nothing in either pass: measured)
+    auto kernel = fast_span_kernel<CLS, TOut, MINW, STATE, DEPTH>;
     static bool configured[kMaxDevices] = {};
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), L::kBytes, configured);
     if (e != hipSuccess) return e;
-    dim3 grid((unsigned)(p.B * p.H * p.nspans)), block(kFastThreads);
+    const int spans = (STATE && p.chain_in_output) ? p.nspans - 1 : p.nspans;
+    if (spans <= 0) return hipSuccess;
+    dim3 grid((unsigned)(p.B * p.H * spans)), block(kFastThreads);
     hipLaunchKernelGGL(kernel, grid, block, L::kBytes, stream, p);
     return hipGetLastError();
 }
 
 }  // namespace
 
+// head-size class of a call, or -1: the producers fetch whole 16-channel units and clear only the last one's
+// channels past dk, so the class must have exactly ceil(dk / 16) units
+static int fast_class(const Params &p) {
+    const int ndk16 = (p.dk + 15) / 16, ndv16 = (p.dv + 15) / 16;
+    if (ndk16 == 2 && ndv16 <= 4) return 0;
+    if (ndk16 == 3 && ndv16 <= 5) return 1;
+    if (ndk16 == 4 && ndv16 <= 8) return 2;
+    return -1;
+}
+
 bool fast_engine_supports(const Params &p) {
-    if (!mfma_engine_supports(p)) return false;
+    if (!mfma_engine_supports(p) || fast_class(p) < 0) return false;
     // plain key-side recurrence only: no gate prologue / epilogue, no value-side gate, no accumulation, no gate shift
     return !two_sided(p) && p.z_gate == nullptr && p.r_pre == nullptr && !p.accumulate && p.gate_shift == 0;
 }
 
 int fast_groups_per_cu(const Params &p) {
-    const int ndk16 = (p.dk + 15) / 16, ndv16 = (p.dv + 15) / 16;
-    if (ndk16 <= 2 && ndv16 <= 4) return (160 * 1024) / FastLayout<0>::kBytes >= 2 ? 2 : 1;
-    if (ndk16 <= 3 && ndv16 <= 5) return (160 * 1024) / FastLayout<1>::kBytes >= 2 ? 2 : 1;
-    return (160 * 1024) / FastLayout<2>::kBytes >= 2 ? 2 : 1;
+    switch (fast_class(p)) {
+    case 0: return (160 * 1024) / FastLayout<0>::kBytes >= 2 ? 2 : 1;
+    case 1: return (160 * 1024) / FastLayout<1>::kBytes >= 2 ? 2 : 1;
+    default: return (160 * 1024) / FastLayout<2>::kBytes >= 2 ? 2 : 1;
+    }
 }
 
 hipError_t launch_fast_output(const Params &p, hipStream_t stream) {
-    const int ndk16 = (p.dk + 15) / 16, ndv16 = (p.dv + 15) / 16;
     const bool bf16_out = p.out_dtype == GLA_DT_BF16;
-    if (ndk16 <= 2 && ndv16 <= 4)
-        return bf16_out ? launch_cls<0, uint16_t>(p, stream) : launch_cls<0, float>(p, stream);
-    if (ndk16 <= 3 && ndv16 <= 5)
-        return bf16_out ? launch_cls<1, uint16_t>(p, stream) : launch_cls<1, float>(p, stream);
-    return bf16_out ? launch_cls<2, uint16_t>(p, stream) : launch_cls<2, float>(p, stream);
+    switch (fast_class(p)) {
+    case 0: return bf16_out ? launch_cls<0, uint16_t, false>(p, stream) : launch_cls<0, float, false>(p, stream);
+    case 1: return bf16_out ? launch_cls<1, uint16_t, false>(p, stream) : launch_cls<1, float, false>(p, stream);
+    case 2: return bf16_out ? launch_cls<2, uint16_t, false>(p, stream) : launch_cls<2, float, false>(p, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_fast_state(const Params &p, hipStream_t stream) {
+    switch (fast_class(p)) {
+    case 0: return launch_cls<0, float, true>(p, stream);
+    case 1: return launch_cls<1, float, true>(p, stream);
+    case 2: return launch_cls<2, float, true>(p, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace gla

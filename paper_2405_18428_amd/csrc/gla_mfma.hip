@@ -192,8 +192,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void mfma_span_kernel(Params p) {
     if (OUT && p.chain_in_output && (bh & 1)) sp_ = spans_here - 1 - sp_;
     const int sp = sp_;
     if constexpr (OUT) {
-        // second opinion for the fp16 engine: only the spans it flagged are recomputed (uniform over the group)
-        if (p.only_flagged && p.ws_fail[(size_t)bh * p.nspans + sp] == 0) return;
+        // second opinion for the fp16 engine: a (batch, head) is recomputed if one of its spans raised its flag
+        if (p.only_flagged) {
+            int any = 0;
+            for (int i = tid; i < p.fail_spans; i += NW * 64) any |= p.ws_fail[(size_t)bh * p.fail_spans + i];
+            if (!__syncthreads_or(any)) return;   // (uniform over the group)
+        }
     }
     const int dk = p.dk, dv = p.dv, T = p.T;
     const int s_begin = sp * p.span_len;
