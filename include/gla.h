@@ -380,6 +380,16 @@ int gla_fwd_timed(const void *q, const void *k, const void *v, const float *log_
                   void *workspace, size_t workspace_bytes, gla_stream_t stream,
                   int iters, float *phase_ms);
 
+/*
+ * gla_calibrate_mfma - measurement aid: the rate at which this GPU retires v_mfma_f32_16x16x32_bf16 when nothing
+ * else limits it (every wave of a grid that fills the chip runs a loop of eight independent accumulator chains
+ * held in registers, no memory traffic), in TFLOP/s (2 flops per multiply-add), written to *tflops (HOST pointer).
+ * It is the figure to hold next to the published dense bf16 peak when a kernel's MFMA rate is priced.  Runs on
+ * `stream`, synchronises it before returning, allocates 4 KiB of device memory for the duration of the call.
+ * GLA_ERR_NULL for a NULL pointer, GLA_ERR_HIP if a runtime call fails.
+ */
+int gla_calibrate_mfma(double *tflops, gla_stream_t stream);
+
 /* Process-wide tuning knobs; returns GLA_ERR_SHAPE for an unknown option or value.  They are plain process
  * globals read at the start of every call: set them before, not while, other threads call the library. */
 int gla_set_option(int option, int value);

@@ -6,7 +6,7 @@ only marshals arguments.  Importing the package does not load the library;
 calling any entry point without a built library raises.
 """
 from .binding import (  # noqa: F401
-    GlaError, gla_fwd, gla_fwd_static, gla_fwd_ex, gla_fwd_layout, gla_fwd_workspace_bytes, gla_fwd_timed,
+    GlaError, gla_fwd, gla_fwd_static, gla_fwd_ex, gla_fwd_layout, gla_fwd_workspace_bytes, gla_fwd_timed, gla_calibrate_mfma,
     gla_bwd, gla_bwd_layout, gla_bwd_workspace_bytes, gla_bwd_gates, gla_bwd_gates_workspace_bytes, gla_fwd_fused, gla_fwd_fused_gates, gla_fwd_multi, gla_fwd_gates, gla_srem_dwconv,
     gla_set_option, gla_get_option, gla_status_string, gla_version,
     library_path, load_library, lib_symbols,

@@ -85,6 +85,8 @@ def load_library():
     lib.gla_bwd_gates_workspace_bytes.argtypes = [i] * 6
     lib.gla_bwd_workspace_bytes.restype = sz
     lib.gla_bwd_workspace_bytes.argtypes = [i] * 6
+    lib.gla_calibrate_mfma.restype = i
+    lib.gla_calibrate_mfma.argtypes = [ctypes.POINTER(ctypes.c_double), vp]
     lib.gla_fwd_timed.restype = i
     lib.gla_fwd_timed.argtypes = [vp, vp, vp, vp] + shape + [i, i, vp, vp, vp, sz, vp, i, fp]
     lib.gla_fwd_workspace_bytes.restype = sz
@@ -535,6 +537,14 @@ def gla_bwd(q, k, v, log_alpha, d_out, grid_h, grid_w, scan_dir=SCAN_ROW_FWD, wo
                                      dq.data_ptr(), dk_.data_ptr(), dv_.data_ptr(), dg.data_ptr(),
                                      workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
     return dq, dk_, dv_, dg
+
+
+def gla_calibrate_mfma(stream=None):
+    """TFLOP/s of a register-resident v_mfma_f32_16x16x32_bf16 loop on the current device."""
+    lib = load_library()
+    x = ctypes.c_double(0.0)
+    _check(lib.gla_calibrate_mfma(ctypes.byref(x), _stream_ptr(stream)))
+    return float(x.value)
 
 
 def gla_fwd_timed(q, k, v, log_alpha, grid_h, grid_w, scan_dir, out, final_state,

@@ -656,6 +656,60 @@ size_t gla_fwd_workspace_bytes(int B, int H, int T, int dk, int dv, int qkv_dtyp
     return workspace_bytes(B, H, T, dk, dv);
 }
 
+namespace {
+// register-resident MFMA loop: eight independent accumulator chains per wave, operands never change
+__global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, float *sink) {
+    typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+    const uint32_t seed = 0x3f803f80u + (threadIdx.x & 3);   // bf16 pairs near 1.0
+    const bf16x8_t a = __builtin_bit_cast(bf16x8_t, u32x4_t{seed, seed, seed, seed});
+    const bf16x8_t b = __builtin_bit_cast(bf16x8_t, u32x4_t{seed ^ 1u, seed, seed ^ 1u, seed});
+    f32x4_t acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+    if (s == 12345.678f) sink[threadIdx.x] = s;   // keeps the loop alive; never true for these operands
+}
+}  // namespace
+
+int gla_calibrate_mfma(double *tflops, gla_stream_t stream) {
+    if (!tflops) return GLA_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *sink = nullptr;
+    if (hipMalloc(&sink, 4096) != hipSuccess) return GLA_ERR_HIP;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int status = GLA_OK;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) status = GLA_ERR_HIP;
+    constexpr int kGroups = 256 * 8, kIters = 4096;     // 8 work-groups of 4 waves per compute unit
+    if (status == GLA_OK) {
+        hipLaunchKernelGGL(mfma_rate_kernel, dim3(kGroups), dim3(256), 0, s, 64, sink);   // warm-up
+        (void)hipEventRecord(e0, s);
+        hipLaunchKernelGGL(mfma_rate_kernel, dim3(kGroups), dim3(256), 0, s, kIters, sink);
+        (void)hipEventRecord(e1, s);
+        if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess) status = GLA_ERR_HIP;
+    }
+    if (status == GLA_OK) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess || !(ms > 0.f)) {
+            status = GLA_ERR_HIP;
+        } else {
+            const double flops = (double)kGroups * 4 /*waves*/ * kIters * 8 /*chains*/ * (2.0 * 16 * 16 * 32);
+            *tflops = flops / (ms * 1e-3) / 1e12;
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipFree(sink);
+    return status;
+}
+
 int gla_fwd_timed(const void *q, const void *k, const void *v, const float *log_alpha,
                   int B, int H, int T, int dk, int dv, int grid_h, int grid_w, int scan_dir,
                   int qkv_dtype, int out_dtype, void *out, float *final_state,
