@@ -71,12 +71,32 @@ int validate(const void *q, const void *k, const void *v, const float *log_alpha
 // per-work-group prologue; short spans give the 256 compute units more
 // work-groups.  Two resident work-groups per compute unit is the sweet spot
 // measured on MI355X for the output pass.
-int plan_chunks_per_span(int bh, int nchunks, bool mfma_engine, int groups_per_cu = 2) {
+int plan_chunks_per_span(int bh, int nchunks, bool mfma_engine, int groups_per_cu = 2, bool fp16_engine = false) {
     int cps = g_opt_chunks_per_span;
+    if (cps <= 0 && fp16_engine) {
+        // fp16 engine: a work-group spends about three chunk periods on its prologue (span-state chain, pipeline
+        // fill) whatever the span length, and a chunk period is about 0.62 as long when the group has its compute
+        // unit to itself (measured on MI355X: 1024 / 2048 / 4096 chunks of DiG-XL/2 and 1176 of DiG-S/2 at 1792 px
+        // with 1..16 chunks per span).  Cost of a plan in chunk periods: rounds of resident groups x (cps + 3) x
+        // (1 if two groups share a compute unit, else 0.62); the cheapest plan wins, ties go to the shorter span.
+        const long long total = (long long)bh * nchunks;
+        double best = 0.0;
+        for (int c = 1; c <= nchunks; ++c) {
+            const long long groups = (long long)bh * ((nchunks + c - 1) / c);
+            const long long resident = 256LL * groups_per_cu;
+            const double rounds = (double)((groups + resident - 1) / resident);
+            const double period = (groups_per_cu >= 2 && groups > 256) ? 1.0 : 0.62;
+            const double cost = rounds * (c + 3) * period;
+            if (cps <= 0 || cost < best - 1e-9) {
+                best = cost;
+                cps = c;
+            }
+            if (groups <= 128 && total > 128) break;   // longer spans only idle more compute units
+        }
+    }
     if (cps <= 0) {
-        // no more work-groups than are resident at once (two per compute unit; three of the fp16 engine's where
-        // its LDS allows); sequences of up to four chunks are walked in one pass (a second kernel costs more than
-        // the chunks it would save)
+        // no more work-groups than are resident at once (two per compute unit); sequences of up to four chunks are
+        // walked in one pass (a second kernel costs more than the chunks it would save)
         const long long resident_groups = 256LL * groups_per_cu;
         cps = (int)(((long long)bh * nchunks + resident_groups - 1) / resident_groups);
         if (cps < 1) cps = 1;
@@ -105,7 +125,12 @@ int choose_engine_and_plan(Params &p, void *workspace, bool &use_mfma, bool *use
         *use_fast = fast;
     }
     const int nchunks = (p.T + kChunk - 1) / kChunk;
-    const int cps = plan_chunks_per_span(p.B * p.H, nchunks, use_mfma, fast ? fast_groups_per_cu(p) : 2);
+    // short sequences are one span on the bf16 hi/lo kernel: a single pass, and no launch for the range fallback
+    if (fast && nchunks <= 4 && g_opt_engine != GLA_ENGINE_MFMA_FP16 && g_opt_chunks_per_span <= 0) {
+        fast = false;
+        *use_fast = false;
+    }
+    const int cps = plan_chunks_per_span(p.B * p.H, nchunks, use_mfma, fast ? fast_groups_per_cu(p) : 2, fast);
     p.span_len = cps * kChunk;
     p.nspans = (nchunks + cps - 1) / cps;
     const size_t bh = (size_t)p.B * p.H;

@@ -139,8 +139,14 @@ def test_sequence_fed_in_two_pieces_matches_one_call():
         o, state = run(dp, gh // 2, gw, 0, gla.LAYOUT_BHTD, state)
         outs.append(o)
     pieces = np.concatenate(outs, axis=2)
-    assert rel_err(pieces, whole) <= 1e-3
-    assert rel_err(state, whole_fin) <= 1e-3
+    # (the pieces are four chunks long and run on the bf16 hi/lo kernel, the whole sequence on the fp16 kernels:
+    # the two differ by the latter's rounding, a few 1e-3 of the RMS; a lost or misplaced state would be O(1))
+    assert rel_err(pieces, whole) <= 1e-2
+    assert rel_err(state, whole_fin) <= 1e-2
+    from oracle import gla_oracle
+    ref, ref_fin = gla_oracle.gla_fwd(d["q"], d["k"], d["v"], d["log_alpha"], gh, gw, 0)
+    assert rel_err(pieces, ref) <= TOL_BF16 and rel_err(state, ref_fin) <= TOL_BF16
+    assert rel_err(whole, ref) <= TOL_BF16 and rel_err(whole_fin, ref_fin) <= TOL_BF16
 
 
 @pytest.mark.parametrize("z_mean", [0.0, 3.0, 6.0])
