@@ -44,12 +44,41 @@
  * Outputs must not alias inputs.  The current HIP device must be the one that
  * owns the buffers.
  *
- * Every function returns a gla_status (0 = success).  On any error nothing has
- * been enqueued and no output byte has been written.  Preconditions that are
- * not checked on the device: log_alpha <= 0 and finite inputs.  The bf16 tensor-
- * core engine additionally needs the summed |log_alpha| over any 64 consecutive
- * scan steps of one key channel to stay below 80 (true for alpha =
- * sigmoid(z)^(1/16) whenever z > -20); GLA_ENGINE_RECURRENT has no such limit.
+ * Every function returns a gla_status (0 = success).  An argument error (every
+ * status but GLA_ERR_HIP) is found before anything is enqueued: no kernel has
+ * run and no output byte has been written.  GLA_ERR_HIP reports a failed runtime
+ * call or launch; a call is several kernels, so the earlier ones of that call
+ * may already be enqueued and the outputs are then undefined.
+ *
+ * Preconditions that are not checked: log_alpha <= 0 and finite inputs.  Further
+ * limits of the engines (see gla_engine):
+ *  - bf16 hi/lo MFMA engine: the summed |log_alpha| over any 64 consecutive scan
+ *    steps of one key channel stays below 80 (true for alpha = sigmoid(z)^(1/16)
+ *    whenever z > -20).  GLA_ENGINE_RECURRENT has no such limit.
+ *  - fp16 MFMA engine (what GLA_ENGINE_AUTO takes for the plain forward pass on
+ *    bf16 inputs with 17..64 key channels and more than four chunks): its operands
+ *    cover a decay of at most 2^-11 per key channel over 32 consecutive scan steps
+ *    (alpha above about 0.79 on average; sigmoid(z)^(1/16) with z > -3.7) and
+ *    inputs whose largest |q|, |k| lie in [2^-8, 8] and |v| in [2^-8, 2^14].  This
+ *    IS checked, on the device: a (batch, head) sequence outside the range is
+ *    recomputed in the same call by the bf16 hi/lo kernel, one work-group walking
+ *    the whole sequence - correct, but many times slower for that sequence.
+ *    Callers whose gates close faster than that as a rule should select
+ *    GLA_ENGINE_MFMA.
+ *  - Where the output pass chains the span states itself (gla_carry), a thread
+ *    stops adding earlier spans once the decay accumulated on its key channels is
+ *    below 2^-40: what is left out is at most 2^-40 of what those earlier states
+ *    hold.  The bound is relative to the earlier states, not to the sum so far
+ *    (a thread whose sum is still exactly zero, e.g. behind a padded tail of
+ *    all-zero k or v, does go on): sequences whose later spans are many orders
+ *    of magnitude smaller than the earlier ones lose the decayed remainder of
+ *    the earlier ones.  GLA_CARRY_KERNEL has no cut-off.
+ *
+ * The entry points that take a caller workspace only enqueue kernels, with one
+ * exception: the first use of a kernel instantiation on a device raises its
+ * dynamic-LDS limit (hipFuncSetAttribute).  Before capturing calls into a HIP
+ * graph, or entering a region that must not touch the runtime, run each call
+ * once with the same shapes and options.
  */
 #ifndef GLA_H_
 #define GLA_H_
@@ -86,22 +115,27 @@ typedef enum {
     GLA_OPT_CARRY = 2,           /* gla_carry */
     GLA_OPT_BWD_SPLIT = 3,       /* 0 = the backward pass computes dk and dv of a chunk in one kernel (MFMA engine);
                                     1 = in two kernels (the forward output pass for dv, the row read for dk) */
-    GLA_OPT_RANGE_FALLBACK = 4   /* 1 (default) = after the fp16 output pass, the spans that left its range are
-                                    recomputed by the bf16 hi/lo pass; 0 = that second launch is skipped (for
-                                    callers that know their gates and inputs stay in range, and for measurements) */
+    GLA_OPT_RANGE_FALLBACK = 4   /* 1 (default) = after the fp16 engine's passes, the (batch, head) sequences that
+                                    left its range are recomputed by the bf16 hi/lo kernel (one more launch, whose
+                                    work-groups return at once when no flag is raised); 0 = that launch is skipped
+                                    (for callers that know their gates and inputs stay in range, and for
+                                    measurements) */
 } gla_option;
 typedef enum {
-    GLA_ENGINE_AUTO = 0,      /* bf16 inputs with dk % 4 == 0 and dv % 8 == 0 -> MFMA, else recurrent */
+    GLA_ENGINE_AUTO = 0,      /* bf16 inputs with dk % 4 == 0 and dv % 8 == 0 -> an MFMA engine (the fp16 one for the
+                                 plain forward pass with 17..64 key channels and more than four chunks, else the
+                                 bf16 hi/lo one), otherwise recurrent */
     GLA_ENGINE_RECURRENT = 1, /* fp32 token-by-token arithmetic inside each span; any dtype, any gates */
     GLA_ENGINE_MFMA = 2,      /* bf16 hi/lo MFMA chunk form (Sec. 3.5) in every pass; bf16 inputs only */
-    GLA_ENGINE_MFMA_FP16 = 3  /* as AUTO picks for the plain forward pass on bf16 inputs: fp16 operands in the output
-                                 pass with the bf16 hi/lo pass as its range fallback; GLA_ERR_UNSUPPORTED elsewhere */
+    GLA_ENGINE_MFMA_FP16 = 3  /* fp16 operands in both passes of the plain forward call (producer / consumer waves),
+                                 the bf16 hi/lo kernel as range fallback; GLA_ERR_UNSUPPORTED where it does not
+                                 apply (other entry points, fp32 inputs, fewer than 17 key channels) */
 } gla_engine;
 
 /* Where the states of the spans of one (batch, head) are chained, S_start(r+1) = diag(Gamma_r) S_start(r) + U_r
  * (the recurrence of Eq. (attn_gla) applied span by span). */
 typedef enum {
-    GLA_CARRY_AUTO = 0,          /* in the output pass when the MFMA engine runs with at most 48 spans per head */
+    GLA_CARRY_AUTO = 0,          /* in the output pass when an MFMA engine runs with at most 128 spans per head */
     GLA_CARRY_KERNEL = 1,        /* a kernel of its own between the two passes */
     GLA_CARRY_IN_OUTPUT_PASS = 2 /* each output work-group chains the local states before its span, whatever the
                                     span count (the recurrent engine has no such path and keeps the kernel) */

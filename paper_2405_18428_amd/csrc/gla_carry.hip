@@ -29,12 +29,13 @@ __global__ __launch_bounds__(kCarryThreads) void carry_kernel(Params p) {
     __shared__ float s_gam[kGroups][kElems];
     __shared__ float s_u[kGroups][kElems];
 
-    const int bh = blockIdx.y;
+    // (batch, head) on grid.x, whose limit is 2^31 - 1; the blocks of elements (at most 128) on grid.y
+    const int bh = blockIdx.x;
     const int el = threadIdx.x % kElems;
     const int grp = threadIdx.x / kElems;
     const int ne = p.dk * p.dv;
-    const int e = min(blockIdx.x * kElems + el, ne - 1);  // threads past the end repeat the last element
-    const bool writer = blockIdx.x * kElems + el < ne;
+    const int e = min((int)blockIdx.y * kElems + el, ne - 1);  // threads past the end repeat the last element
+    const bool writer = (int)blockIdx.y * kElems + el < ne;
     const int c = e / p.dv;
     float *st = p.ws_state + (size_t)bh * p.nspans * ne + e;
     const float *lg = p.ws_lgam + (size_t)bh * p.nspans * p.dk + c;
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(kCarryThreads) void carry_kernel(Params p) {
 }  // namespace
 
 hipError_t launch_carry(const Params &p, hipStream_t stream) {
-    dim3 grid((unsigned)((p.dk * p.dv + kElems - 1) / kElems), (unsigned)(p.B * p.H));
+    dim3 grid((unsigned)(p.B * p.H), (unsigned)((p.dk * p.dv + kElems - 1) / kElems));
     hipLaunchKernelGGL(carry_kernel, grid, dim3(kCarryThreads), 0, stream, p);
     return hipGetLastError();
 }

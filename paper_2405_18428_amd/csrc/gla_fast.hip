@@ -143,6 +143,12 @@ __host__ __device__ constexpr int owned_start(int w) {
 }
 
 constexpr int kFastThreads = 512;    // 4 producer waves + 4 consumer waves
+#ifndef FAST_STATE_DEPTH
+#define FAST_STATE_DEPTH 1
+#endif
+#ifndef FAST_OUT_DEPTH
+#define FAST_OUT_DEPTH 1
+#endif
 
 // Last statement of a code path that exists once per consumer wave (W = compile-time wave index).  The paths end in
 // the same instructions on different registers of the accumulator arrays; when the compiler merges such tails the
@@ -399,21 +405,15 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
             }
         };
 
-        // ---- pipeline fill ----
-        // (every load is issued as soon as the registers it fills have been read; the loads of chunk x are issued
-        // DEPTH iterations before the stage that reads them)
-        using Set0 = std::integral_constant<int, 0>;
-        using Set1 = std::integral_constant<int, DEPTH - 1>;     // set of odd chunks
-        int tok_qkv = tok;
-        issue_la(Set0{});              // chunk 0: on their way while the span's start state is formed
-        issue_qk(Set0{}, tok);
-        issue_v(Set0{}, tok);
-        if constexpr (DEPTH == 2) {
-            next_row_token();
-            issue_la(Set1{});          // chunk 1
-            issue_qk(Set1{}, tok);
-            issue_v(Set1{}, tok);
-        }
+        // ---- the producers' loop ----
+        // Iteration c runs beside the consumers' contraction of chunk c: gate and park chunk c + 1, scan chunk
+        // c + 2, and refill the register sets just read with the rows of chunks c + 1 + DEPTH (q, k, v) and
+        // c + 2 + DEPTH (log_alpha): every load is issued as soon as the registers it fills have been read, DEPTH
+        // iterations before the stage that reads them.  The iterations that fill the pipeline (c < 0) are passes of
+        // the same loop with the stages of chunks that do not exist left out: the order of the loads is the same in
+        // every pass, so the counts of younger loads that the waits before the stages allow are those of the
+        // steady state (a separate prologue with another order makes the compiler wait for more).  A load of a chunk
+        // before the first is a repeat of chunk 0's; the consumers' barriers start with iteration -2.
         if constexpr (!STATE) {
             const bool chain = p.chain_in_output && (sp > 0 || p.initial_state != nullptr);   // uniform
             if (chain) {
@@ -423,33 +423,27 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
                 __syncthreads();
             }
         }
-        // One iteration of the producers, c = chunk the consumers contract meanwhile (-2, -1: pipeline fill):
-        // gate and park chunk c + 1, scan chunk c + 2, refill the register sets just read.
+        constexpr int kFirst = -2 - DEPTH;
+        int tok_qkv = tok;
         auto iteration = [&](auto par_c, int c) {
-            constexpr int P = decltype(par_c)::value;                       // c mod DEPTH
-            using SetG = std::integral_constant<int, (P + 1) % DEPTH>;      // set of chunk c + 1 (and c + 1 + DEPTH)
-            using SetS = std::integral_constant<int, (P + 2) % DEPTH>;      // set of chunk c + 2 (and c + 2 + DEPTH)
+            constexpr int P = decltype(par_c)::value;                       // (c - kFirst) mod DEPTH
+            using SetG = std::integral_constant<int, (P + kFirst + 1 + 4 * DEPTH) % DEPTH>;      // set of chunk c + 1
+            using SetS = std::integral_constant<int, (P + kFirst + 2 + 4 * DEPTH) % DEPTH>;      // set of chunk c + 2
             if (c + 1 >= 0 && c + 1 < nch) gate(SetG{}, c + 1);
-            if (c + 1 >= 0) {
-                tok_qkv = tok;                                              // token of chunk c + 1 + DEPTH
-                issue_qk(SetG{}, tok_qkv);
-            }
-            if (c + 2 < nch) scan(SetS{}, c + 2);
-            next_row_token();
+            tok_qkv = tok;                                                  // token of chunk c + 1 + DEPTH
+            issue_qk(SetG{}, tok_qkv);
+            if (c + 2 >= 0 && c + 2 < nch) scan(SetS{}, c + 2);
+            if (c > kFirst) next_row_token();
             issue_la(SetS{});                                               // chunk c + 2 + DEPTH
-            if (c + 1 >= 0) {
-                if (c + 1 < nch) park_v(SetG{}, c + 1);
-                issue_v(SetG{}, tok_qkv);
-            }
-            __syncthreads();
+            if (c + 1 >= 0 && c + 1 < nch) park_v(SetG{}, c + 1);
+            issue_v(SetG{}, tok_qkv);
+            if (c >= -2) __syncthreads();
         };
-        iteration(std::integral_constant<int, 0>{}, -2);      // (after it: totals of chunk 0 in LDS, chained state read)
-        iteration(std::integral_constant<int, DEPTH - 1>{}, -1);
-        for (int c = 0; c < nch; c += DEPTH) {
+        // (with two register sets the loop body is a pair of iterations, both always executed: an iteration past
+        // the last chunk only issues repeats of the last loads and meets the consumers at one more barrier)
+        for (int c = kFirst; c < nch; c += DEPTH) {
             iteration(std::integral_constant<int, 0>{}, c);
-            if constexpr (DEPTH == 2) {
-                if (c + 1 < nch) iteration(std::integral_constant<int, 1>{}, c + 1);
-            }
+            if constexpr (DEPTH == 2) iteration(std::integral_constant<int, 1>{}, c + 1);
         }
 
         // Outside the range: inputs so large or so small that the gated operands (within 2^kMaxHalfDecay of them)
@@ -725,6 +719,7 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
             if constexpr (!STATE) next_row_token();
             __syncthreads();
         }
+        if (DEPTH == 2 && ((nch + 2 + DEPTH) & 1)) __syncthreads();   // the producers' loop runs in pairs of iterations
 
         // a half-chunk decay beyond what fp16's exponent covers around the anchor, or a non-finite output / state
         if constexpr (STATE) {
@@ -789,7 +784,7 @@ hipError_t launch_cls(const Params &p, hipStream_t stream) {
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int MINW = kGroupsPerCu >= 2 ? 4 : 2;    // waves per SIMD: two resident groups of 8 waves, or one
     // the state pass has the registers for a second set of rows in flight
-    constexpr int DEPTH = 1;   // (a second set of rows in flight gained nothing in either pass: measured)
+    constexpr int DEPTH = STATE ? FAST_STATE_DEPTH : FAST_OUT_DEPTH;
     auto kernel = fast_span_kernel<CLS, TOut, MINW, STATE, DEPTH>;
     static bool configured[kMaxDevices] = {};
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), L::kBytes, configured);

@@ -124,9 +124,10 @@ __device__ inline void wave_inclusive_scan4(float &a, float &b, float &c, float 
 //     S_start(sp) = U_{sp-1} + Gamma_{sp-1} U_{sp-2} + Gamma_{sp-1} Gamma_{sp-2} U_{sp-3} + ... (+ the decayed initial state)
 // Each thread owns kV4 pieces of 4 consecutive state elements (one key channel each) and walks the spans from the
 // nearest one backwards, 2 spans first, then kRun at a time (loads of a run issued together).  A thread stops
-// when the decay accumulated on all its channels is below 2^-40: a term that much smaller than the ones already
-// summed does not change an fp32 sum.  With the gates of the DiG configurations a span of a few hundred tokens
-// decays by more than that, so one or two spans are read whatever the span count.
+// when the decay accumulated on all its channels is below 2^-40 and it has summed something other than zero: a
+// term that much smaller than the earlier states hold does not change an fp32 sum of terms of their size.
+// With the gates of the DiG configurations a span of a few hundred tokens decays by more than that, so one or
+// two spans are read whatever the span count.
 // The result is written to s_chain[dk * dv] (LDS, row-major [dk][dv]).
 // BETA (two-sided gate): element (c, n) also decays by the value-side sums of the spans (ws_lgam_b, per column n);
 // the stopping rule stays the key-side one (the value side only makes the skipped terms smaller).
@@ -188,10 +189,14 @@ __device__ inline void chain_span_states(const Params &p, int bh, int sp, int ti
             }
         }
     };
+    // a piece goes on while its accumulated decay is above 2^-40, and also while everything it has summed is
+    // exactly zero (all-zero k or v over the nearer spans, e.g. a padded tail: then even a strongly decayed
+    // earlier state is the whole result)
     auto alive = [&]() {
         bool a = false;
 #pragma unroll
-        for (int m = 0; m < kV4; ++m) a = a || wl[m] > -40.f;
+        for (int m = 0; m < kV4; ++m)
+            a = a || wl[m] > -40.f || (st[m][0] == 0.f && st[m][1] == 0.f && st[m][2] == 0.f && st[m][3] == 0.f);
         return a;
     };
     int r = sp - 1;

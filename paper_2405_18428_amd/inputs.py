@@ -62,6 +62,7 @@ CONFIGS: Dict[str, GlaConfig] = {c.name: c for c in [
     GlaConfig("dig_xl2_2048_longmem", 1, 16, 128, 128, 36, 72, "bf16", (SCAN_ROW_FWD,), z_mean=3.0),
     GlaConfig("dig_s2_1792", 1, 6, 112, 112, 32, 64, "bf16", (SCAN_ROW_FWD,)),
     GlaConfig("dig_s2_1792_longmem", 1, 6, 112, 112, 32, 64, "bf16", (SCAN_ROW_FWD,), z_mean=3.0),
+    GlaConfig("dig_xl2_1792", 1, 16, 112, 112, 36, 72, "bf16", (SCAN_ROW_FWD,)),
 ]}
 CONFIG_ORDER = ["tiny_f32", "dig_s2_256", "dig_xl2_512", "dig_xl2_1024", "dig_xl2_2048"]
 

@@ -68,7 +68,9 @@ def check(d, gh, gw, scan, tol):
     # the first scan step): its error is measured against the size of the terms when the sum itself is smaller
     floors = [0.0, 0.0, 0.0, float(np.sqrt(np.mean((d["q"].astype(np.float64) * ref[0]) ** 2)))]
     errs = [rel_err(g.cpu().numpy(), r, f) for g, r, f in zip(got, ref, floors)]
-    print("  scan=%d  err dq=%.3e dk=%.3e dv=%.3e dlog_alpha=%.3e" % (scan, *errs), flush=True)
+    plain = rel_err(got[3].cpu().numpy(), ref[3], 0.0)    # the same error over RMS(dlog_alpha) alone
+    print("  scan=%d  err dq=%.3e dk=%.3e dv=%.3e dlog_alpha=%.3e (over RMS(dlog_alpha): %.3e)" % (scan, *errs, plain),
+          flush=True)
     for g in got:
         assert bool(torch.isfinite(g).all())
     assert max(errs) <= tol, errs
@@ -108,6 +110,15 @@ def test_contract_workloads(name, scan):
     d = make_problem(cfg.B, cfg.H, cfg.grid_h, cfg.grid_w, cfg.dk, cfg.dv, cfg.dtype, seed=cfg.seed)
     print(f"\n{name}", flush=True)
     check(d, cfg.grid_h, cfg.grid_w, scan, TOL_BF16)
+
+
+@pytest.mark.parametrize("name", ["dig_s2_1792", "dig_xl2_1792"])
+def test_1792_px_shapes(name):
+    """T = 12544 (112 x 112 tokens) with the head sizes of DiG-S/2 and DiG-XL/2, default launch plan."""
+    cfg = gi.CONFIGS[name]
+    d = make_problem(cfg.B, cfg.H, cfg.grid_h, cfg.grid_w, cfg.dk, cfg.dv, cfg.dtype, seed=cfg.seed)
+    print(f"\n{name}", flush=True)
+    check(d, cfg.grid_h, cfg.grid_w, 0, TOL_BF16)
 
 
 def test_headline_shape_long_spans():

@@ -169,3 +169,27 @@ def test_long_chains_of_span_states(z_mean):
             e_out, e_fin = rel_err(out, ref), rel_err(fin, ref_fin)
             print(f"  z_mean={z_mean} carry={carry} scan={scan} err(out)={e_out:.3e} err(state)={e_fin:.3e}", flush=True)
             assert e_out <= TOL_BF16 and e_fin <= TOL_BF16
+
+
+@pytest.mark.parametrize("engine", [gla.ENGINE_MFMA, gla.ENGINE_AUTO])
+def test_chain_behind_a_zero_tail(engine):
+    """k = 0 over the last 60 chunks (a padded tail): the final state is the state after chunk 68 decayed by about
+    2^-70, far below the 2^-40 at which the in-pass chain of the span states otherwise stops.  The chain has to go
+    on while everything it has summed is exactly zero; the carry kernel has no cut-off and serves as second opinion."""
+    from oracle import gla_oracle
+    B, H, gh, gw, dk, dv = 1, 2, 64, 128, 36, 72        # 128 chunks
+    d = gi.make_inputs(B, H, gh * gw, dk, dv, "bf16", seed=21, z_mean=1.5)
+    k = d["k"].copy()
+    k[:, :, 68 * 64:] = 0.0
+    d["k"] = k
+    d["k_bits"] = gi.round_to_bf16_bits(k)
+    ref, ref_fin = gla_oracle.gla_fwd(d["q"], d["k"], d["v"], d["log_alpha"], gh, gw, 0)
+    assert 0.0 < np.abs(ref_fin).max() < 1e-12          # tiny, but not zero
+    gla.gla_set_option(gla.OPT_ENGINE, engine)
+    gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 1)
+    for carry in (gla.CARRY_IN_OUTPUT_PASS, gla.CARRY_KERNEL):
+        gla.gla_set_option(gla.OPT_CARRY, carry)
+        out, fin = run(d, gh, gw, 0, gla.LAYOUT_BHTD)
+        e_out, e_fin = rel_err(out, ref), rel_err(fin, ref_fin)
+        print(f"  engine={engine} carry={carry} err(out)={e_out:.3e} err(state)={e_fin:.3e}", flush=True)
+        assert e_out <= TOL_BF16 and e_fin <= TOL_BF16

@@ -130,13 +130,23 @@ def test_plans_and_engines_agree_with_oracle(engine, carry, cps):
                                        (6, gla.CARRY_KERNEL)])
 def test_many_spans_per_head_at_full_size(cps, carry):
     """The 2048 px workload cut into 256, 128, 64 and 43 spans per head: long chains in the output pass (forced at
-    256 spans), the carry kernel, and the automatic choice on both sides of its limit of 48 spans."""
+    256 spans), the carry kernel, and the automatic choice on both sides of its limit of 128 spans."""
     name, scan = "dig_xl2_2048", 1
     cfg = gi.CONFIGS[name]
     gla.gla_set_option(gla.OPT_CARRY, carry)
     gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, cps)
     ref, ref_fin = _oracle(name, scan)
     print(f"\ncarry={carry} chunks_per_span={cps}", flush=True)
+    check(_config_inputs(name), cfg.grid_h, cfg.grid_w, scan, ref, ref_fin, TOL_BF16)
+
+
+@pytest.mark.parametrize("name,scan", [("dig_s2_1792", 0), ("dig_s2_1792", 3), ("dig_xl2_1792", 0), ("dig_xl2_1792", 2)])
+def test_1792_px_shapes(name, scan):
+    """T = 12544 (112 x 112 tokens, the 1792 px case of the paper's Fig. 1) with the head sizes of DiG-S/2 and of
+    DiG-XL/2, in the launch plan the benchmark times: 196 chunks per head, which no power of two divides."""
+    cfg = gi.CONFIGS[name]
+    ref, ref_fin = _oracle(name, scan)
+    print(f"\n{name}: B={cfg.B} H={cfg.H} T={cfg.T} dk={cfg.dk} dv={cfg.dv}", flush=True)
     check(_config_inputs(name), cfg.grid_h, cfg.grid_w, scan, ref, ref_fin, TOL_BF16)
 
 
