@@ -126,13 +126,17 @@ struct FastLayout {
     static constexpr int oTot = 0;
     static constexpr int oFlag = oTot + kTot;                            // int: the span left the fp16 range
     static constexpr int oZero = oFlag + 16;                             // float[g][NV] of zeros (a tile total that is not there)
+    // two sets of operand buffers (k~, q~, v, P of one chunk each); chunk x uses set x % 2
+    static constexpr int kSet = 2 * kK + kV + kS;
     static constexpr int oK = oZero + 4 * (4 * C::NCT) * 4;
-    static constexpr int oQ = oK + 2 * kK;
-    static constexpr int oV = oQ + 2 * kK;
-    static constexpr int oS = oV + 2 * kV;
-    static constexpr int kBytes = oS + 2 * kS;
-    static constexpr int oChain = oK;                                    // float[dk * dv] before the first chunk
-    static_assert(kBytes - oChain >= 16 * C::NCT * 16 * C::NDV16 * 4, "the chained start state must fit");
+    static constexpr int oQ = oK + kK;
+    static constexpr int oV = oQ + kK;
+    static constexpr int oS = oV + kV;
+    static constexpr int kBytes = oK + 2 * kSet;
+    // float[dk * dv] before the first chunk: in the second set, which nothing writes before chunk 1 is gated
+    static constexpr int oChain = oK + kSet;
+    static_assert(kSet >= 16 * C::NCT * 16 * C::NDV16 * 4, "the chained start state must fit");
+    static_assert(kSet % 16 == 0 && kK % 16 == 0 && kV % 16 == 0, "16-byte LDS accesses");
 };
 
 template <int CLS>
@@ -143,12 +147,6 @@ __host__ __device__ constexpr int owned_start(int w) {
 }
 
 constexpr int kFastThreads = 512;    // 4 producer waves + 4 consumer waves
-#ifndef FAST_STATE_DEPTH
-#define FAST_STATE_DEPTH 1
-#endif
-#ifndef FAST_OUT_DEPTH
-#define FAST_OUT_DEPTH 1
-#endif
 
 // Last statement of a code path that exists once per consumer wave (W = compile-time wave index).  The paths end in
 // the same instructions on different registers of the accumulator arrays; when the compiler merges such tails the
@@ -158,8 +156,7 @@ constexpr int kFastThreads = 512;    // 4 producer waves + 4 consumer waves
 
 // STATE: the span-state pass (phase 1 of the span plan): the same producers without q, the consumers only update
 // their state tiles from a zero state and leave U_r (anchored at the end of the span) and log Gamma_r in the workspace.
-// DEPTH: chunks of rows a producer has in flight beyond the one it works on (register sets it alternates between).
-template <int CLS, typename TOut, int MINW, bool STATE, int DEPTH>
+template <int CLS, typename TOut, int MINW, bool STATE>
 __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p) {
     using C = FastCfg<CLS>;
     using L = FastLayout<CLS>;
@@ -167,6 +164,7 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
     constexpr bool TAIL = C::TAIL != 0;
     constexpr int NV = 4 * NCT;                       // gate values per lane and chunk
     constexpr int NVP = (2 * NDV16 + 3) / 4;          // 16-byte pieces of a v row per lane
+    constexpr int SET = L::kSet / 2;                  // 16-bit elements from an operand buffer to its twin in the other set
     static_assert(2 * NK32 + (TAIL ? 1 : 0) == NCT, "units = slots of the MFMA steps");
     static_assert(owned_start<CLS>(4) == NCT * NDV16, "every state tile has an owner");
 
@@ -254,6 +252,11 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
 
     bool bad = false;     // this lane saw something outside the fp16 range
 
+    // Output pass: the consumers' chain (scores -> AV -> stores) sets the time of an iteration, the producers wait
+    // at the barrier with slack; when both have an instruction ready on a SIMD the consumer's goes first.  (The
+    // state pass has the shorter consumer side and measured no gain.)
+    if (!STATE && consumer) __builtin_amdgcn_s_setprio(2);
+
     if (!consumer) {
         // =========================== producers ===========================
         const char *gq = static_cast<const char *>(p.q) + base_k * 2;
@@ -273,47 +276,42 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
 #pragma unroll
         for (int i = 0; i < NVP; ++i) vpb[i] = 2u * (uint32_t)min(8 * (g + 4 * i), dv - 8);
 
-        // (the rows of chunk x travel in register set x % DEPTH)
-        f32x4 r_la[DEPTH][NCT];    // log_alpha pieces waiting for the scan
+        f32x4 r_la[NCT];           // log_alpha pieces waiting for the scan
         float r_b[NV];             // scanned gates (log2, prefix inside the 16-token tile) waiting for the gate stage
-        u32x2 r_q[DEPTH][NCT], r_k[DEPTH][NCT];  // raw q, k pieces waiting for the gate stage
-        u32x4 r_v[DEPTH][NVP];     // v pieces on their way to LDS
+        u32x2 r_q[NCT], r_k[NCT];  // raw q, k pieces waiting for the gate stage
+        u32x4 r_v[NVP];            // v pieces on their way to LDS
         // fp16 range check of the span: largest half-chunk decay (log2), largest |q|, |k|, |v|
         float trk_q = 0.f, trk_k = 0.f, trk_v = 0.f;
 
         // the rows of the walker's current token
-        auto issue_la = [&](auto set_c) {
-            constexpr int R = decltype(set_c)::value;
+        auto issue_la = [&](f32x4 (&dst)[NCT]) {
             const uint32_t off = 2u * ((uint32_t)tok * dk2 + chb0);
 #pragma unroll
-            for (int u = 0; u < NCT - 1; ++u) r_la[R][u] = *reinterpret_cast<const f32x4 *>(gla_ + off + 64u * u);
-            r_la[R][NCT - 1] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * ((uint32_t)tok * dk2 + chb_last));
+            for (int u = 0; u < NCT - 1; ++u) dst[u] = *reinterpret_cast<const f32x4 *>(gla_ + off + 64u * u);
+            dst[NCT - 1] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * ((uint32_t)tok * dk2 + chb_last));
         };
-        auto issue_qk = [&](auto set_c, int tk) {
-            constexpr int R = decltype(set_c)::value;
+        auto issue_qk = [&](int tk) {
             const uint32_t off = (uint32_t)tk * dk2 + chb0;
 #pragma unroll
             for (int u = 0; u < NCT - 1; ++u) {
-                if constexpr (!STATE) r_q[R][u] = *reinterpret_cast<const u32x2 *>(gq + off + 32u * u);
-                r_k[R][u] = *reinterpret_cast<const u32x2 *>(gk + off + 32u * u);
+                if constexpr (!STATE) r_q[u] = *reinterpret_cast<const u32x2 *>(gq + off + 32u * u);
+                r_k[u] = *reinterpret_cast<const u32x2 *>(gk + off + 32u * u);
             }
-            if constexpr (!STATE) r_q[R][NCT - 1] = *reinterpret_cast<const u32x2 *>(gq + (uint32_t)tk * dk2 + chb_last);
-            r_k[R][NCT - 1] = *reinterpret_cast<const u32x2 *>(gk + (uint32_t)tk * dk2 + chb_last);
+            if constexpr (!STATE) r_q[NCT - 1] = *reinterpret_cast<const u32x2 *>(gq + (uint32_t)tk * dk2 + chb_last);
+            r_k[NCT - 1] = *reinterpret_cast<const u32x2 *>(gk + (uint32_t)tk * dk2 + chb_last);
         };
-        auto issue_v = [&](auto set_c, int tk) {   // (rows past the span keep the values of its last token: their k~ is zero)
-            constexpr int R = decltype(set_c)::value;
+        auto issue_v = [&](int tk) {   // (rows past the span keep the values of its last token: their k~ is zero)
 #pragma unroll
-            for (int i = 0; i < NVP; ++i) r_v[R][i] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tk * dv2 + vpb[i]);
+            for (int i = 0; i < NVP; ++i) r_v[i] = *reinterpret_cast<const u32x4 *>(gv + (uint32_t)tk * dv2 + vpb[i]);
         };
 
         // scan: prefix sums of log2(alpha) inside this wave's tile, tile totals to LDS
-        auto scan = [&](auto set_c, int x) {
-            constexpr int R = decltype(set_c)::value;
+        auto scan = [&](int x) {
             float *tot = s_tot + ((x % 3) * 4 + w) * 4 * NV + g * NV;
 #pragma unroll
             for (int u = 0; u < NCT; ++u)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) r_b[4 * u + e] = r_la[R][u][e] * kLog2e;
+                for (int e = 0; e < 4; ++e) r_b[4 * u + e] = r_la[u][e] * kLog2e;
             if (x >= ragged_from) {
                 const bool valid = row_is_token(x);
 #pragma unroll
@@ -336,13 +334,12 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
         const int tile_a = w == 0 ? 0 : -1, tile_b = w <= 1 ? 1 : (w == 3 ? 2 : -1);
         const float off_sign = w == 3 ? 1.f : -1.f;
         const float *s_zero = reinterpret_cast<const float *>(smem + L::oZero) + g * NV;
-        auto gate = [&](auto set_c, int x) {
-            constexpr int R = decltype(set_c)::value;
+        auto gate = [&](int x) {
             const float *tot = s_tot + (x % 3) * 16 * NV + g * NV;      // + tile * 4 * NV
             const float *pa = tile_a >= 0 ? tot + tile_a * 4 * NV : s_zero;
             const float *pb = tile_b >= 0 ? tot + tile_b * 4 * NV : s_zero;
-            uint16_t *krow = s_k + (x & 1) * (kChunk * KST) + (16 * w + lm) * KST + 4 * g;
-            uint16_t *qrow = s_q + (x & 1) * (kChunk * KST) + (16 * w + lm) * KST + 4 * g;
+            uint16_t *krow = s_k + (x & 1) * SET + (16 * w + lm) * KST + 4 * g;
+            uint16_t *qrow = s_q + (x & 1) * SET + (16 * w + lm) * KST + 4 * g;
             uint32_t keep_last = mask_last, keep = 0xffffffffu;
             const bool ragged = x >= ragged_from;       // (uniform)
             if (ragged) {
@@ -354,10 +351,10 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
             for (int u = 0; u < NCT; ++u) {
                 const f32x4 ta = *reinterpret_cast<const f32x4 *>(pa + 4 * u);
                 const f32x4 tb = *reinterpret_cast<const f32x4 *>(pb + 4 * u);
-                uint32_t q0 = 0u, q1 = 0u, k0 = r_k[R][u][0], k1 = r_k[R][u][1];
+                uint32_t q0 = 0u, q1 = 0u, k0 = r_k[u][0], k1 = r_k[u][1];
                 if constexpr (!STATE) {
-                    q0 = r_q[R][u][0];
-                    q1 = r_q[R][u][1];
+                    q0 = r_q[u][0];
+                    q1 = r_q[u][1];
                 }
                 if (u == NCT - 1) {
                     q0 &= keep_last; q1 &= keep_last; k0 &= keep_last; k1 &= keep_last;
@@ -386,16 +383,15 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
         };
 
         // v rows of chunk x: bf16 -> fp16 (exact inside fp16's range), to LDS
-        auto park_v = [&](auto set_c, int x) {
-            constexpr int R = decltype(set_c)::value;
-            uint16_t *vrow = s_v + (x & 1) * (kChunk * VS) + (16 * w + lm) * VS + 8 * g;
+        auto park_v = [&](int x) {
+            uint16_t *vrow = s_v + (x & 1) * SET + (16 * w + lm) * VS + 8 * g;
 #pragma unroll
             for (int i = 0; i < NVP; ++i) {
                 if (8 * (g + 4 * i) < 16 * NDV16) {
                     u32x4 h;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const uint32_t x2 = r_v[R][i][j];
+                        const uint32_t x2 = r_v[i][j];
                         const float lo = bf16_lo_as_float(x2), hi = bf16_hi_as_float(x2);
                         trk_v = fmaxf(fmaxf(trk_v, fabsf(lo)), fabsf(hi));
                         h[j] = pack_f16(lo, hi);
@@ -407,43 +403,43 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
 
         // ---- the producers' loop ----
         // Iteration c runs beside the consumers' contraction of chunk c: gate and park chunk c + 1, scan chunk
-        // c + 2, and refill the register sets just read with the rows of chunks c + 1 + DEPTH (q, k, v) and
-        // c + 2 + DEPTH (log_alpha): every load is issued as soon as the registers it fills have been read, DEPTH
-        // iterations before the stage that reads them.  The iterations that fill the pipeline (c < 0) are passes of
-        // the same loop with the stages of chunks that do not exist left out: the order of the loads is the same in
-        // every pass, so the counts of younger loads that the waits before the stages allow are those of the
-        // steady state (a separate prologue with another order makes the compiler wait for more).  A load of a chunk
-        // before the first is a repeat of chunk 0's; the consumers' barriers start with iteration -2.
-        if constexpr (!STATE) {
-            const bool chain = p.chain_in_output && (sp > 0 || p.initial_state != nullptr);   // uniform
-            if (chain) {
-                constexpr int kV4 = (16 * NCT * 16 * NDV16 / 4 + kFastThreads - 1) / kFastThreads;
-                constexpr int kRun = 8 / kV4 > 0 ? 8 / kV4 : 1;
-                chain_span_states<kFastThreads, kV4, kRun, false>(p, bh, sp, tid, reinterpret_cast<float *>(smem + L::oChain));
-                __syncthreads();
+        // c + 2, and refill the registers just read with the rows of chunks c + 2 (q, k, v) and c + 3 (log_alpha):
+        // every load is issued as soon as the registers it fills have been read, one iteration before the stage
+        // that reads them.
+        // Filling the pipeline: everything the first stages need (log_alpha of chunks 0 and 1; q, k, v of chunk 0)
+        // is requested at once, so the fill costs one trip to memory; chunk 0 is scanned, and after the barrier
+        // that makes its tile totals visible the loop starts with iteration -1.  The loop is entered with no load
+        // in flight, so the counts of younger loads that the waits inside it allow are those of the steady state.
+        {
+            f32x4 la1[NCT];
+            issue_la(r_la);
+            issue_qk(tok);
+            issue_v(tok);
+            next_row_token();
+            issue_la(la1);
+            if constexpr (!STATE) {
+                // with those loads in flight, the producers' half of the span-state chain
+                if (p.chain_in_output && (sp > 0 || p.initial_state != nullptr)) {   // uniform
+                    constexpr int kV4 = (16 * NCT * 16 * NDV16 / 4 + kFastThreads - 1) / kFastThreads;
+                    constexpr int kRun = 8 / kV4 > 0 ? 8 / kV4 : 1;
+                    chain_span_states<kFastThreads, kV4, kRun, false>(p, bh, sp, tid, reinterpret_cast<float *>(smem + L::oChain));
+                }
             }
+            scan(0);
+#pragma unroll
+            for (int u = 0; u < NCT; ++u) r_la[u] = la1[u];
         }
-        constexpr int kFirst = -2 - DEPTH;
-        int tok_qkv = tok;
-        auto iteration = [&](auto par_c, int c) {
-            constexpr int P = decltype(par_c)::value;                       // (c - kFirst) mod DEPTH
-            using SetG = std::integral_constant<int, (P + kFirst + 1 + 4 * DEPTH) % DEPTH>;      // set of chunk c + 1
-            using SetS = std::integral_constant<int, (P + kFirst + 2 + 4 * DEPTH) % DEPTH>;      // set of chunk c + 2
-            if (c + 1 >= 0 && c + 1 < nch) gate(SetG{}, c + 1);
-            tok_qkv = tok;                                                  // token of chunk c + 1 + DEPTH
-            issue_qk(SetG{}, tok_qkv);
-            if (c + 2 >= 0 && c + 2 < nch) scan(SetS{}, c + 2);
-            if (c > kFirst) next_row_token();
-            issue_la(SetS{});                                               // chunk c + 2 + DEPTH
-            if (c + 1 >= 0 && c + 1 < nch) park_v(SetG{}, c + 1);
-            issue_v(SetG{}, tok_qkv);
-            if (c >= -2) __syncthreads();
-        };
-        // (with two register sets the loop body is a pair of iterations, both always executed: an iteration past
-        // the last chunk only issues repeats of the last loads and meets the consumers at one more barrier)
-        for (int c = kFirst; c < nch; c += DEPTH) {
-            iteration(std::integral_constant<int, 0>{}, c);
-            if constexpr (DEPTH == 2) iteration(std::integral_constant<int, 1>{}, c + 1);
+        __syncthreads();                    // tile totals of chunk 0 (and, for the consumers, the chained state)
+        for (int c = -1; c < nch; ++c) {
+            if (c + 1 < nch) gate(c + 1);
+            const int tok_qkv = tok;        // token of chunk c + 2
+            issue_qk(tok_qkv);
+            if (c + 2 < nch) scan(c + 2);
+            next_row_token();
+            issue_la(r_la);                 // chunk c + 3
+            if (c + 1 < nch) park_v(c + 1);
+            issue_v(tok_qkv);
+            __syncthreads();
         }
 
         // Outside the range: inputs so large or so small that the gated operands (within 2^kMaxHalfDecay of them)
@@ -475,12 +471,13 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
             else if (p.nspans == 1 && p.initial_state != nullptr)
                 s0 = p.initial_state + (size_t)bh * dk * dv;
             if (chain) {
+                // (the producers do their half once the loads that fill the pipeline are on their way)
                 constexpr int kV4 = (16 * NCT * 16 * NDV16 / 4 + kFastThreads - 1) / kFastThreads;
                 constexpr int kRun = 8 / kV4 > 0 ? 8 / kV4 : 1;
                 chain_span_states<kFastThreads, kV4, kRun, false>(p, bh, sp, tid, reinterpret_cast<float *>(smem + L::oChain));
-                __syncthreads();
                 s0 = reinterpret_cast<const float *>(smem + L::oChain);      // (LDS is addressable through flat loads)
             }
+            __syncthreads();               // the chained state is in LDS; so are the tile totals of chunk 0
             if (s0 != nullptr) {
                 auto fetch = [&](auto wave_c) {
                     constexpr int W = decltype(wave_c)::value;
@@ -513,7 +510,7 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
             constexpr int t_lo = owned_start<CLS>(W), t_hi = owned_start<CLS>(W + 1);
             const float *t_c = s_tot + ((c + 3) % 3) * 16 * NV + g * NV;        // totals of chunk c (c = -1: unused)
             const float *t_n = s_tot + ((c + 1) % 3) * 16 * NV + g * NV;        // totals of chunk c + 1
-            uint16_t *srow = s_s + ((c + 1) & 1) * (16 * NDV16 * SST);
+            uint16_t *srow = s_s + ((c + 1) & 1) * SET;
             (void)srow;
             f32x4 fac[NCT];
 #pragma unroll
@@ -561,13 +558,13 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
         auto contract = [&](auto wave_c, int c) {
             constexpr int W = decltype(wave_c)::value;
             constexpr int NQ = W / 2 + 1;                     // 32-token steps that hold causal tokens for this wave
-            const uint16_t *kb = s_k + (c & 1) * (kChunk * KST);
-            const uint16_t *vb = s_v + (c & 1) * (kChunk * VS);
-            const uint16_t *sb = s_s + (c & 1) * (16 * NDV16 * SST);
+            const uint16_t *kb = s_k + (c & 1) * SET;
+            const uint16_t *vb = s_v + (c & 1) * SET;
+            const uint16_t *sb = s_s + (c & 1) * SET;
             // ---- q~ of this wave's tokens: the B operand of the score tiles and of q~ P ----
             uint32_t qf[NCT][2];
             if constexpr (!STATE) {
-                const uint16_t *qrow = s_q + (c & 1) * (kChunk * KST) + (16 * W + lm) * KST + 4 * g;
+                const uint16_t *qrow = s_q + (c & 1) * SET + (16 * W + lm) * KST + 4 * g;
 #pragma unroll
                 for (int u = 0; u < NCT; ++u) {
                     const u32x2 x = *reinterpret_cast<const u32x2 *>(qrow + 16 * u);
@@ -709,7 +706,7 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
             }
         };
 
-        __syncthreads();               // the chained state has been read; totals of chunk 0 are in LDS
+        if constexpr (STATE) __syncthreads();   // the tile totals of chunk 0 are in LDS
         per_wave(publish, -1);
         __syncthreads();
 
@@ -719,7 +716,6 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
             if constexpr (!STATE) next_row_token();
             __syncthreads();
         }
-        if (DEPTH == 2 && ((nch + 2 + DEPTH) & 1)) __syncthreads();   // the producers' loop runs in pairs of iterations
 
         // a half-chunk decay beyond what fp16's exponent covers around the anchor, or a non-finite output / state
         if constexpr (STATE) {
@@ -783,9 +779,7 @@ hipError_t launch_cls(const Params &p, hipStream_t stream) {
     using L = FastLayout<CLS>;
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int MINW = kGroupsPerCu >= 2 ? 4 : 2;    // waves per SIMD: two resident groups of 8 waves, or one
-    // the state pass has the registers for a second set of rows in flight
-    constexpr int DEPTH = STATE ? FAST_STATE_DEPTH : FAST_OUT_DEPTH;
-    auto kernel = fast_span_kernel<CLS, TOut, MINW, STATE, DEPTH>;
+    auto kernel = fast_span_kernel<CLS, TOut, MINW, STATE>;
     static bool configured[kMaxDevices] = {};
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), L::kBytes, configured);
     if (e != hipSuccess) return e;

@@ -10,7 +10,7 @@
 //   order 3 (column-major reversed)                                       (-dx, -dy)
 // A thread owns VEC channels (4 when D allows: 8-byte bf16 pieces) of a strip of kStrip tokens of a grid row and
 // walks kRows rows of that strip from top to bottom.  The lanes of a wave cover 64 neighbouring channel groups of
-// the same tokens (contiguous addresses); the four waves of a work-group take four strips and share the weights
+// the same tokens (contiguous addresses); the kWaves waves of a work-group take neighbouring strips and share the weights
 // of their 64 channel groups, which are fetched once, coalesced, into LDS (a lane's 9 x VEC weights are VEC*36
 // bytes apart from its neighbour's in memory) and then held in registers.  The window is three rows of
 // kStrip + 2 pieces; the row below it is requested before the arithmetic of the current row starts, so loads and
@@ -23,7 +23,9 @@ namespace {
 
 constexpr int kStrip = 4;      // output tokens per thread and grid row
 constexpr int kRows = 8;       // grid rows a wave walks
-constexpr int kWaves = 4;      // strips per work-group
+constexpr int kWaves = 2;      // strips per work-group (2560 waves on the 2048 px shape: small groups spread evenly)
+constexpr int kAhead = 1;      // rows requested ahead of the window (2 and 3 measured no faster)
+constexpr int kRing = kAhead + 3;
 constexpr int kThreads = 64 * kWaves;
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -132,10 +134,9 @@ __global__ __launch_bounds__(kThreads) void srem_dwconv_kernel(const void *x, co
 #pragma unroll
         for (int t = 0; t < kStrip + 2; ++t) dst[t] = *reinterpret_cast<const Raw<TIn, VEC> *>(xin + (rowoff + coloff[t]));
     };
-    Raw<TIn, VEC> win[4][kStrip + 2];    // rows r-1, r, r+1 and the one in flight, rotating
-    load_row(r0 - 1, win[0]);
-    load_row(r0, win[1]);
-    load_row(r0 + 1, win[2]);
+    Raw<TIn, VEC> win[kRing][kStrip + 2];    // rows r-1, r, r+1 and the kAhead rows in flight, rotating
+#pragma unroll
+    for (int m = 0; m < kAhead + 2; ++m) load_row(r0 - 1 + m, win[m]);
     // weights of the block's channel groups: one contiguous piece of the [D, 3, 3] array
     {
         const float *src = w + (size_t)cg0 * VEC * 9;
@@ -173,7 +174,7 @@ __global__ __launch_bounds__(kThreads) void srem_dwconv_kernel(const void *x, co
     for (int ri = 0; ri < kRows; ++ri) {
         const int r = r0 + ri;
         if (r >= gh) break;                                   // uniform: the last band may be short
-        if (ri + 1 < kRows) load_row(r + 2, win[(ri + 3) & 3]);   // in flight during this row's arithmetic
+        if (ri + kAhead < kRows) load_row(r + 1 + kAhead, win[(ri + 2 + kAhead) % kRing]);   // in flight during the arithmetic of kAhead rows
         float acc[kStrip][VEC];
 #pragma unroll
         for (int t = 0; t < kStrip; ++t)
@@ -188,7 +189,7 @@ __global__ __launch_bounds__(kThreads) void srem_dwconv_kernel(const void *x, co
                 // a piece outside the matrix was fetched from a clamped position: clear it (zero padding);
                 // the cleared copy is a temporary, the window keeps the fetched bytes (a clamped bottom row is a
                 // real row for the output rows above it)
-                Raw<TIn, VEC> piece = win[(ri + j) & 3][t];
+                Raw<TIn, VEC> piece = win[(ri + j) % kRing][t];
                 and_mask(piece, (row_in && c >= 0 && c < gw) ? 0xffffffffu : 0u);
                 float xv[VEC];
                 to_floats(piece, xv);
