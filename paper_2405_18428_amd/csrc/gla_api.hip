@@ -15,7 +15,6 @@ int g_opt_engine = GLA_ENGINE_AUTO;
 int g_opt_carry = GLA_CARRY_AUTO;
 int g_opt_bwd_split = 0;
 int g_opt_range_fallback = 1;
-int g_opt_fast_state = 1;   // (experiment switch)
 
 // Most spans per (batch, head) that the output pass chains by itself: work-group r reads the r local states
 // before it, so the reads grow with the square of the span count while a carry kernel's grow linearly.
@@ -422,7 +421,7 @@ int run(const void *q, const void *k, const void *v, const float *log_alpha,
     hipError_t e = hipSuccess;
     mark(0);
     if (p.nspans > 1) {
-        e = (use_fast && g_opt_fast_state) ? launch_fast_state(p, stream) : span(kModeState);
+        e = use_fast ? launch_fast_state(p, stream) : span(kModeState);
         if (e != hipSuccess) return GLA_ERR_HIP;
     }
     mark(1);
