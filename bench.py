@@ -682,6 +682,8 @@ def main():
     achieved = alg_bytes / (ms_per_step * 1e-3) / 1e9
     kernel_achieved = alg_bytes / (phase[dom] * 1e-3) / 1e9
     traffic = measured_traffic(cfg.name, names[dom], args)
+    parts_traffic = [measured_traffic(cfg.name, n, args) for n in ("span_state", "output")]
+    call_traffic = None if (traffic is None or None in parts_traffic) else int(sum(parts_traffic))
     roofline = {
         "bound": "hbm", "kernel": names[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -694,6 +696,11 @@ def main():
         "whole_path_frac": round(achieved / HBM_PEAK_GBS, 4),
         "measured_copy_gbs": round(copy_gbs, 1),
         "frac_of_measured_copy": round(achieved / copy_gbs, 4),
+        # every kernel of the call: the HBM bytes the committed counter runs measured, moved in ms_per_step
+        "call_traffic": call_traffic,
+        "call_traffic_gbs": None if call_traffic is None else round(call_traffic / (ms_per_step * 1e-3) / 1e9, 1),
+        "call_traffic_frac_of_copy": None if call_traffic is None
+        else round(call_traffic / (ms_per_step * 1e-3) / 1e9 / copy_gbs, 4),
         "mfma_tflops": round(alg_flops / (ms_per_step * 1e-3) / 1e12, 2),
         "mfma_frac": round(alg_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5),
         "mfma_peak_nominal_tflops": MFMA_BF16_PEAK_TFLOPS,

@@ -91,6 +91,34 @@ def scan_order(scan_dir: int, grid_h: int, grid_w: int) -> np.ndarray:
     return np.ascontiguousarray(seq)
 
 
+SCHEDULE_BLOCK_PROCESS = 0   # Algorithm 1: transpose after blocks with even index, flip after odd ones
+SCHEDULE_BLOCK_SCAN = 1      # Algorithm 4 (supplement): flip after even, transpose after odd
+
+
+def block_scan_dir(block: int, schedule: int = SCHEDULE_BLOCK_PROCESS, grid: int = 4) -> int:
+    """Scan order in which DiG block ``block`` (1-based, the paper's l) sees the tokens when the transposes and flips
+    that the paper applies to the sequence after every block (Algorithm 1; Algorithm 4 with the parities swapped)
+    are left out and the sequence stays in canonical row-major order.
+
+    Done the paper's way on an index array of a ``grid`` x ``grid`` token matrix: start from the row-major
+    sequence, after every block before ``block`` apply its operator (reshape2d, transpose, flatten; or flip), and
+    name the resulting order by comparing it with the four scan orders.
+    """
+    if block < 1 or schedule not in (SCHEDULE_BLOCK_PROCESS, SCHEDULE_BLOCK_SCAN) or grid < 2:
+        raise ValueError("block / schedule / grid")
+    seq = np.arange(grid * grid, dtype=np.int64)
+    for l in range(1, block):
+        transpose = (l % 2 == 0) if schedule == SCHEDULE_BLOCK_PROCESS else (l % 2 == 1)
+        if transpose:
+            seq = np.ascontiguousarray(seq.reshape(grid, grid).T).reshape(-1)
+        else:
+            seq = seq[::-1].copy()
+    for d in (SCAN_ROW_FWD, SCAN_ROW_REV, SCAN_COL_FWD, SCAN_COL_REV):
+        if np.array_equal(seq, scan_order(d, grid, grid)):
+            return d
+    raise AssertionError("the sequence left the four scan orders")
+
+
 def _as_f64(x, shape):
     a = np.ascontiguousarray(np.asarray(x, dtype=np.float64))
     if a.shape != tuple(shape):

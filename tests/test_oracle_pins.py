@@ -232,6 +232,28 @@ def test_block_by_block_reorientation_cycles_four_orders(oracle):
         assert seen[0] == orders[ROW_FWD]
 
 
+def test_block_schedule_names_the_order_each_block_sees(oracle):
+    """Algorithm 1 (flip after odd blocks, transpose after even ones) and Algorithm 4 (parities swapped), worked out
+    by hand on a 2 x 2 grid with tokens 0 1 / 2 3: block 1 sees 0 1 2 3; Algorithm 1 then flips (3 2 1 0 = row
+    reversed), transposes (3 1 2 0 = column reversed), flips (0 2 1 3 = column forward), transposes (0 1 2 3)."""
+    assert [oracle.block_scan_dir(l, oracle.SCHEDULE_BLOCK_PROCESS) for l in range(1, 10)] == \
+        [ROW_FWD, ROW_REV, COL_REV, COL_FWD, ROW_FWD, ROW_REV, COL_REV, COL_FWD, ROW_FWD]
+    # Algorithm 4: transposes first (0 2 1 3 = column forward), flips (3 1 2 0), transposes (3 2 1 0), flips
+    assert [oracle.block_scan_dir(l, oracle.SCHEDULE_BLOCK_SCAN) for l in range(1, 10)] == \
+        [ROW_FWD, COL_FWD, COL_REV, ROW_REV, ROW_FWD, COL_FWD, COL_REV, ROW_REV, ROW_FWD]
+    # the hand-worked sequences themselves
+    assert list(oracle.scan_order(ROW_REV, 2, 2)) == [3, 2, 1, 0]
+    assert list(oracle.scan_order(COL_REV, 2, 2)) == [3, 1, 2, 0]
+    assert list(oracle.scan_order(COL_FWD, 2, 2)) == [0, 2, 1, 3]
+    # independent of the grid the index array is drawn on
+    for grid in (2, 3, 5):
+        for sched in (oracle.SCHEDULE_BLOCK_PROCESS, oracle.SCHEDULE_BLOCK_SCAN):
+            assert [oracle.block_scan_dir(l, sched, grid) for l in range(1, 6)] == \
+                [oracle.block_scan_dir(l, sched) for l in range(1, 6)]
+    with pytest.raises(ValueError):
+        oracle.block_scan_dir(0)
+
+
 # --------------------------------------------------------------------------
 # structure: chunked evaluation, carried state, linearity
 # --------------------------------------------------------------------------
