@@ -429,6 +429,24 @@ int gla_calibrate_mfma(double *tflops, gla_stream_t stream);
 int gla_set_option(int option, int value);
 int gla_get_option(int option);
 
+/*
+ * gla_block_scan_dir - the scan order that DiG block `block` uses (Sec. 3.3, Algorithm 1: after every block the
+ * token matrix is transposed, for even block indices, or the sequence flipped, for odd ones; supplement,
+ * Algorithm 4 states the same schedule with the parities swapped).  This library leaves the tokens in canonical
+ * row-major order and folds those permutations into `scan_dir` of the gla_fwd* / gla_bwd* calls and `orient` of
+ * gla_srem_dwconv; this function names the order a block sees:
+ *   GLA_SCHEDULE_BLOCK_PROCESS (Algorithm 1):  block 1, 2, 3, 4, 5 ... -> ROW_FWD, ROW_REV, COL_REV, COL_FWD, ROW_FWD ...
+ *   GLA_SCHEDULE_BLOCK_SCAN    (Algorithm 4):  block 1, 2, 3, 4, 5 ... -> ROW_FWD, COL_FWD, COL_REV, ROW_REV, ROW_FWD ...
+ * (the paper's reshape2d takes a square token matrix; on a grid_h x grid_w grid the orders are those of
+ * gla_scan_dir on that grid).  Host only, no GPU work.
+ *
+ *   block      1-based index of the block (the paper's l)
+ *   schedule   a gla_schedule
+ * Returns the gla_scan_dir, or -1 for block < 1 or an unknown schedule.
+ */
+typedef enum { GLA_SCHEDULE_BLOCK_PROCESS = 0, GLA_SCHEDULE_BLOCK_SCAN = 1 } gla_schedule;
+int gla_block_scan_dir(int block, int schedule);
+
 /* Static, NUL-terminated description of a status code. */
 const char *gla_status_string(int status);
 

@@ -99,6 +99,8 @@ def load_library():
     lib.gla_status_string.argtypes = [i]
     lib.gla_version.restype = i
     lib.gla_version.argtypes = []
+    lib.gla_block_scan_dir.restype = i
+    lib.gla_block_scan_dir.argtypes = [i, i]
     _lib = lib
     return lib
 
@@ -109,6 +111,17 @@ def gla_status_string(status: int) -> str:
 
 def gla_version() -> int:
     return int(load_library().gla_version())
+
+
+SCHEDULE_BLOCK_PROCESS, SCHEDULE_BLOCK_SCAN = 0, 1
+
+
+def gla_block_scan_dir(block: int, schedule: int = SCHEDULE_BLOCK_PROCESS) -> int:
+    """Scan order of DiG block `block` (1-based) under Algorithm 1's (or Algorithm 4's) transposes and flips."""
+    d = int(load_library().gla_block_scan_dir(int(block), int(schedule)))
+    if d < 0:
+        raise GlaError(2, gla_status_string(2))
+    return d
 
 
 def gla_set_option(option: int, value: int) -> None:

@@ -814,6 +814,17 @@ int gla_get_option(int option) {
     }
 }
 
+int gla_block_scan_dir(int block, int schedule) {
+    // the order entering block l is the composition of the operators after blocks 1 .. l-1; both schedules walk
+    // the four orders with period four
+    static const int kBlockProcess[4] = {GLA_SCAN_ROW_FWD, GLA_SCAN_ROW_REV, GLA_SCAN_COL_REV, GLA_SCAN_COL_FWD};
+    static const int kBlockScan[4] = {GLA_SCAN_ROW_FWD, GLA_SCAN_COL_FWD, GLA_SCAN_COL_REV, GLA_SCAN_ROW_REV};
+    if (block < 1) return -1;
+    if (schedule == GLA_SCHEDULE_BLOCK_PROCESS) return kBlockProcess[(block - 1) & 3];
+    if (schedule == GLA_SCHEDULE_BLOCK_SCAN) return kBlockScan[(block - 1) & 3];
+    return -1;
+}
+
 const char *gla_status_string(int status) {
     switch (status) {
     case GLA_OK: return "ok";

@@ -36,6 +36,18 @@ def test_host_only_entry_points():
     assert gla.gla_fwd_workspace_bytes(0, 1, 1, 1, 1) == 0
 
 
+def test_block_schedule_matches_the_oracle():
+    """gla_block_scan_dir (host only) against the oracle's literal transposes / flips of Algorithms 1 and 4."""
+    from oracle import gla_oracle
+    for sched_lib, sched_ref in ((gla.SCHEDULE_BLOCK_PROCESS, gla_oracle.SCHEDULE_BLOCK_PROCESS),
+                                 (gla.SCHEDULE_BLOCK_SCAN, gla_oracle.SCHEDULE_BLOCK_SCAN)):
+        for block in range(1, 30):
+            assert gla.gla_block_scan_dir(block, sched_lib) == gla_oracle.block_scan_dir(block, sched_ref, grid=3)
+    for bad in ((0, 0), (-3, 1), (1, 2), (1, -1)):
+        with pytest.raises(gla.GlaError):
+            gla.gla_block_scan_dir(*bad)
+
+
 def test_options_round_trip():
     gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, 3)
     assert gla.gla_get_option(gla.OPT_CHUNKS_PER_SPAN) == 3

@@ -82,3 +82,44 @@ def test_empty_direction_set_is_refused():
     d = gi.make_inputs(1, 1, 16, 8, 8, "bf16", seed=1)
     with pytest.raises(gla.GlaError):
         gla.gla_fwd_multi(*(upload(d, n) for n in ("q", "k", "v", "log_alpha")), 4, 4, ())
+
+
+@pytest.mark.parametrize("schedule", [0, 1])
+def test_block_by_block_schedule_against_literal_permutations(schedule):
+    """Algorithm 1 / Algorithm 4: the paper flips or transposes the token sequence after every block and always scans
+    it front to back.  Here the tokens stay in canonical order and block l is given gla_block_scan_dir(l): the mixer
+    (gla_fwd_ex) and the SREM convolution (gla_srem_dwconv) of five consecutive blocks must equal what the literal
+    route gives - permute the tensors the way the sequence has been permuted so far, run the row-major forward
+    oracle (and the oracle's convolution on the reshaped matrix), undo the permutation."""
+    from oracle import gla_oracle, srem_oracle
+    N, B, H, dk, dv = 12, 1, 2, 36, 72
+    T = N * N
+    d = gi.make_inputs(B, H, T, dk, dv, "bf16", seed=77)
+    rng = np.random.default_rng(3)
+    D = 16
+    x = rng.standard_normal((B, T, D)).astype(np.float32)
+    w = rng.standard_normal((D, 3, 3)).astype(np.float32)
+    xg = torch.from_numpy(x).cuda()
+    wg = torch.from_numpy(w).cuda()
+    perm = np.arange(T)                       # perm[s] = canonical token at position s of the paper's sequence
+    for block in range(1, 6):
+        sd = gla.gla_block_scan_dir(block, schedule)
+        # the literal route on the permuted sequence
+        qp, kp, vp, gp = (d[n][:, :, perm] for n in ("q", "k", "v", "log_alpha"))
+        ref_p, _ = gla_oracle.gla_fwd(qp, kp, vp, gp, N, N, gla.SCAN_ROW_FWD)
+        ref = np.empty_like(ref_p)
+        ref[:, :, perm] = ref_p
+        out, _ = gla.gla_fwd_ex(*(upload(d, n) for n in ("q", "k", "v", "log_alpha")), N, N, sd)
+        torch.cuda.synchronize()
+        err = float(np.abs(out.cpu().numpy() - ref).max() / np.sqrt(np.mean(ref ** 2)))
+        yp = srem_oracle.srem_dwconv(x[:, perm], w, None, N, N, 0)
+        yref = np.empty_like(yp)
+        yref[:, perm] = yp
+        y = gla.gla_srem_dwconv(xg, wg, None, N, N, orient=sd)
+        torch.cuda.synchronize()
+        erry = float(np.abs(y.cpu().numpy() - yref).max())
+        print(f"  schedule {schedule} block {block}: scan order {sd}, mixer err {err:.3e}, conv err {erry:.3e}", flush=True)
+        assert err <= TOL_BF16 and erry <= 1e-4
+        # the operator the paper applies after this block
+        transpose = (block % 2 == 0) if schedule == 0 else (block % 2 == 1)
+        perm = perm.reshape(N, N).T.reshape(-1).copy() if transpose else perm[::-1].copy()
