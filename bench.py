@@ -126,10 +126,13 @@ def bench_fused(args, cfg, gla, gi, torch, np):
                                                  torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev),
                                                  torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)])
 
+    epi = not args.no_epilogue
+
     def step(i):
         q, k, v, z, r, lw, lb, out, fin, ws = sets[i % len(sets)]
-        return gla.gla_fwd_fused(q, k, v, z, 16.0, cfg.grid_h, cfg.grid_w, args.scan, r_pre=r, ln_weight=lw,
-                                 ln_bias=lb, ln_eps=1e-5, out=out, final_state=fin, workspace=ws)
+        return gla.gla_fwd_fused(q, k, v, z, 16.0, cfg.grid_h, cfg.grid_w, args.scan, r_pre=r if epi else None,
+                                 ln_weight=lw if epi else None, ln_bias=lb if epi else None, ln_eps=1e-5, out=out,
+                                 final_state=fin, workspace=ws)
 
     for i in range(args.warmup):
         step(i)
@@ -141,10 +144,11 @@ def bench_fused(args, cfg, gla, gi, torch, np):
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     qb = 2 if bf16 else 4
     ob = 2 if args.out_dtype == "bf16" else 4
-    alg_bytes = (3 * dk * qb + 2 * dv * qb + dv * ob) * B * H * T   # q, k, z, v, r read once; y written once
+    alg_bytes = (3 * dk * qb + (2 if epi else 1) * dv * qb + dv * ob) * B * H * T   # q, k, z, v (, r) read once; y written once
     achieved = alg_bytes / (ms * 1e-3) / 1e9
     result = {
-        "metric": "GLA fwd (gate prologue + Swish/LayerNorm epilogue) tokens/s at DiG-XL/2 shape T=16384",
+        "metric": "GLA fwd (gate prologue + Swish/LayerNorm epilogue) tokens/s at DiG-XL/2 shape T=16384" if epi
+        else "GLA fwd (gate prologue: gates from bf16 pre-activations) tokens/s at DiG-XL/2 shape T=16384",
         "value": round(B * T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
@@ -157,7 +161,8 @@ def bench_fused(args, cfg, gla, gi, torch, np):
     }
     if not args.no_check:
         from oracle import gla_oracle_fused as fo
-        ref, ref_fin = fo.gla_fused(d["q"], d["k"], d["v"], d["z"], 16.0, d["r"], d["ln_w"], d["ln_b"], 1e-5,
+        ref, ref_fin = fo.gla_fused(d["q"], d["k"], d["v"], d["z"], 16.0, d["r"] if epi else None,
+                                    d["ln_w"] if epi else None, d["ln_b"] if epi else None, 1e-5,
                                     cfg.grid_h, cfg.grid_w, args.scan)
         got, fin = step(0)
         torch.cuda.synchronize()
@@ -538,6 +543,8 @@ def main():
                          "with --pass bwdgates: hand the forward outputs to gla_bwd_gates")
     ap.add_argument("--no-range-fallback", action="store_true",
                     help="skip the launch that recomputes spans outside the fp16 engine's range (none in these workloads)")
+    ap.add_argument("--no-epilogue", action="store_true",
+                    help="with --pass fused: gate prologue only (plain o is stored)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-table", action="store_true",
                     help="skip the `configs` table (the other contract workloads, timed and checked after the headline)")

@@ -55,8 +55,9 @@
  *  - bf16 hi/lo MFMA engine: the summed |log_alpha| over any 64 consecutive scan
  *    steps of one key channel stays below 80 (true for alpha = sigmoid(z)^(1/16)
  *    whenever z > -20).  GLA_ENGINE_RECURRENT has no such limit.
- *  - fp16 MFMA engine (what GLA_ENGINE_AUTO takes for the plain forward pass on
- *    bf16 inputs with 17..64 key channels and more than four chunks): its operands
+ *  - fp16 MFMA engine (what GLA_ENGINE_AUTO takes for the plain forward pass, and for
+ *    gla_fwd_fused without the output epilogue, on bf16 inputs with 17..64 key
+ *    channels and more than four chunks): its operands
  *    cover a decay of at most 2^-11 per key channel over 32 consecutive scan steps
  *    (alpha above about 0.79 on average; sigmoid(z)^(1/16) with z > -3.7) and
  *    inputs whose largest |q|, |k| lie in [2^-8, 8] and |v| in [2^-8, 2^14].  This
@@ -123,13 +124,14 @@ typedef enum {
 } gla_option;
 typedef enum {
     GLA_ENGINE_AUTO = 0,      /* bf16 inputs with dk % 4 == 0 and dv % 8 == 0 -> an MFMA engine (the fp16 one for the
-                                 plain forward pass with 17..64 key channels and more than four chunks, else the
-                                 bf16 hi/lo one), otherwise recurrent */
+                                 plain forward pass and for gla_fwd_fused without r_pre, with 17..64 key channels
+                                 and more than four chunks, else the bf16 hi/lo one), otherwise recurrent */
     GLA_ENGINE_RECURRENT = 1, /* fp32 token-by-token arithmetic inside each span; any dtype, any gates */
     GLA_ENGINE_MFMA = 2,      /* bf16 hi/lo MFMA chunk form (Sec. 3.5) in every pass; bf16 inputs only */
-    GLA_ENGINE_MFMA_FP16 = 3  /* fp16 operands in both passes of the plain forward call (producer / consumer waves),
-                                 the bf16 hi/lo kernel as range fallback; GLA_ERR_UNSUPPORTED where it does not
-                                 apply (other entry points, fp32 inputs, fewer than 17 key channels) */
+    GLA_ENGINE_MFMA_FP16 = 3  /* fp16 operands in both passes of the plain forward call and of gla_fwd_fused without
+                                 r_pre (producer / consumer waves), the bf16 hi/lo kernel as range fallback;
+                                 GLA_ERR_UNSUPPORTED where it does not apply (the output epilogue, other entry
+                                 points, fp32 inputs, fewer than 17 key channels) */
 } gla_engine;
 
 /* Where the states of the spans of one (batch, head) are chained, S_start(r+1) = diag(Gamma_r) S_start(r) + U_r

@@ -156,7 +156,12 @@ constexpr int kFastThreads = 512;    // 4 producer waves + 4 consumer waves
 
 // STATE: the span-state pass (phase 1 of the span plan): the same producers without q, the consumers only update
 // their state tiles from a zero state and leave U_r (anchored at the end of the span) and log Gamma_r in the workspace.
-template <int CLS, typename TOut, int MINW, bool STATE>
+// FUSE: the gates come from their bf16 pre-activations z (Eq. (gate_gla): log alpha = logsigmoid(z) / tau), formed by
+// the producers where the plain kernel reads log_alpha: 72 instead of 144 bytes per token-head in either pass.
+// (The output epilogue Swish(r) * LN(o) stays with the bf16 hi/lo kernel: the per-token normalisation divides by
+// the spread of a row of o, and on rows whose outputs are small the error of the fp16 operands, 3e-3 of the RMS
+// over all rows, came out at 2.7e-2 of the RMS of the normalised output at 1024 px, above the 2e-2 bar.)
+template <int CLS, typename TOut, int MINW, bool STATE, bool FUSE>
 __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p) {
     using C = FastCfg<CLS>;
     using L = FastLayout<CLS>;
@@ -262,7 +267,9 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
         const char *gq = static_cast<const char *>(p.q) + base_k * 2;
         const char *gk = static_cast<const char *>(p.k) + base_k * 2;
         const char *gv = static_cast<const char *>(p.v) + base_v * 2;
-        const char *gla_ = reinterpret_cast<const char *>(p.log_alpha) + base_k * 4;
+        // gate rows: fp32 log_alpha, or (FUSE) the bf16 pre-activations z, laid out like q and k
+        const char *gla_ = FUSE ? static_cast<const char *>(p.z_gate) + base_k * 2
+                                : reinterpret_cast<const char *>(p.log_alpha) + base_k * 4;
         const uint32_t dk2 = 2u * (uint32_t)p.st_k, dv2 = 2u * (uint32_t)p.st_v;   // bytes from one bf16 row to the next
 
         // unit u: channels 16u + 4g .. +3.  Every load is issued by every lane: a piece past the row repeats the
@@ -276,7 +283,8 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
 #pragma unroll
         for (int i = 0; i < NVP; ++i) vpb[i] = 2u * (uint32_t)min(8 * (g + 4 * i), dv - 8);
 
-        f32x4 r_la[NCT];           // log_alpha pieces waiting for the scan
+        using GatePiece = std::conditional_t<FUSE, u32x2, f32x4>;
+        GatePiece r_la[NCT];       // log_alpha (or z) pieces waiting for the scan
         float r_b[NV];             // scanned gates (log2, prefix inside the 16-token tile) waiting for the gate stage
         u32x2 r_q[NCT], r_k[NCT];  // raw q, k pieces waiting for the gate stage
         u32x4 r_v[NVP];            // v pieces on their way to LDS
@@ -284,11 +292,18 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
         float trk_q = 0.f, trk_k = 0.f, trk_v = 0.f;
 
         // the rows of the walker's current token
-        auto issue_la = [&](f32x4 (&dst)[NCT]) {
-            const uint32_t off = 2u * ((uint32_t)tok * dk2 + chb0);
+        auto issue_la = [&](GatePiece (&dst)[NCT]) {
+            if constexpr (FUSE) {
+                const uint32_t off = (uint32_t)tok * dk2 + chb0;
 #pragma unroll
-            for (int u = 0; u < NCT - 1; ++u) dst[u] = *reinterpret_cast<const f32x4 *>(gla_ + off + 64u * u);
-            dst[NCT - 1] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * ((uint32_t)tok * dk2 + chb_last));
+                for (int u = 0; u < NCT - 1; ++u) dst[u] = *reinterpret_cast<const u32x2 *>(gla_ + off + 32u * u);
+                dst[NCT - 1] = *reinterpret_cast<const u32x2 *>(gla_ + (uint32_t)tok * dk2 + chb_last);
+            } else {
+                const uint32_t off = 2u * ((uint32_t)tok * dk2 + chb0);
+#pragma unroll
+                for (int u = 0; u < NCT - 1; ++u) dst[u] = *reinterpret_cast<const f32x4 *>(gla_ + off + 64u * u);
+                dst[NCT - 1] = *reinterpret_cast<const f32x4 *>(gla_ + 2u * ((uint32_t)tok * dk2 + chb_last));
+            }
         };
         auto issue_qk = [&](int tk) {
             const uint32_t off = (uint32_t)tk * dk2 + chb0;
@@ -308,10 +323,24 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
         // scan: prefix sums of log2(alpha) inside this wave's tile, tile totals to LDS
         auto scan = [&](int x) {
             float *tot = s_tot + ((x % 3) * 4 + w) * 4 * NV + g * NV;
+            if constexpr (FUSE) {
+                // log2(alpha) = log2(sigmoid(z)) / tau = (min(t, 0) - log2(1 + 2^-|t|)) / tau with t = z log2(e)
+                auto gate2 = [&](uint32_t pair, float &lo, float &hi) {
+                    const float t0 = bf16_lo_as_float(pair) * kLog2e, t1 = bf16_hi_as_float(pair) * kLog2e;
+                    lo = (fminf(t0, 0.f) - __builtin_amdgcn_logf(1.f + exp2_fast(-fabsf(t0)))) * p.inv_tau;
+                    hi = (fminf(t1, 0.f) - __builtin_amdgcn_logf(1.f + exp2_fast(-fabsf(t1)))) * p.inv_tau;
+                };
 #pragma unroll
-            for (int u = 0; u < NCT; ++u)
+                for (int u = 0; u < NCT; ++u) {
+                    gate2(r_la[u][0], r_b[4 * u], r_b[4 * u + 1]);
+                    gate2(r_la[u][1], r_b[4 * u + 2], r_b[4 * u + 3]);
+                }
+            } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) r_b[4 * u + e] = r_la[u][e] * kLog2e;
+                for (int u = 0; u < NCT; ++u)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) r_b[4 * u + e] = r_la[u][e] * kLog2e;
+            }
             if (x >= ragged_from) {
                 const bool valid = row_is_token(x);
 #pragma unroll
@@ -411,7 +440,7 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
         // that makes its tile totals visible the loop starts with iteration -1.  The loop is entered with no load
         // in flight, so the counts of younger loads that the waits inside it allow are those of the steady state.
         {
-            f32x4 la1[NCT];
+            GatePiece la1[NCT];
             issue_la(r_la);
             issue_qk(tok);
             issue_v(tok);
@@ -774,12 +803,12 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
     }
 }
 
-template <int CLS, typename TOut, bool STATE>
+template <int CLS, typename TOut, bool STATE, bool FUSE>
 hipError_t launch_cls(const Params &p, hipStream_t stream) {
     using L = FastLayout<CLS>;
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int MINW = kGroupsPerCu >= 2 ? 4 : 2;    // waves per SIMD: two resident groups of 8 waves, or one
-    auto kernel = fast_span_kernel<CLS, TOut, MINW, STATE>;
+    auto kernel = fast_span_kernel<CLS, TOut, MINW, STATE, FUSE>;
     static bool configured[kMaxDevices] = {};
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), L::kBytes, configured);
     if (e != hipSuccess) return e;
@@ -804,8 +833,9 @@ static int fast_class(const Params &p) {
 
 bool fast_engine_supports(const Params &p) {
     if (!mfma_engine_supports(p) || fast_class(p) < 0) return false;
-    // plain key-side recurrence only: no gate prologue / epilogue, no value-side gate, no accumulation, no gate shift
-    return !two_sided(p) && p.z_gate == nullptr && p.r_pre == nullptr && !p.accumulate && p.gate_shift == 0;
+    // key-side recurrence, gates read or formed from their pre-activations: no output epilogue, no value-side gate,
+    // no accumulation, no gate shift
+    return !two_sided(p) && p.r_pre == nullptr && !p.accumulate && p.gate_shift == 0;
 }
 
 int fast_groups_per_cu(const Params &p) {
@@ -816,23 +846,33 @@ int fast_groups_per_cu(const Params &p) {
     }
 }
 
-hipError_t launch_fast_output(const Params &p, hipStream_t stream) {
+template <bool FUSE>
+static hipError_t launch_output(const Params &p, hipStream_t stream) {
     const bool bf16_out = p.out_dtype == GLA_DT_BF16;
     switch (fast_class(p)) {
-    case 0: return bf16_out ? launch_cls<0, uint16_t, false>(p, stream) : launch_cls<0, float, false>(p, stream);
-    case 1: return bf16_out ? launch_cls<1, uint16_t, false>(p, stream) : launch_cls<1, float, false>(p, stream);
-    case 2: return bf16_out ? launch_cls<2, uint16_t, false>(p, stream) : launch_cls<2, float, false>(p, stream);
+    case 0: return bf16_out ? launch_cls<0, uint16_t, false, FUSE>(p, stream) : launch_cls<0, float, false, FUSE>(p, stream);
+    case 1: return bf16_out ? launch_cls<1, uint16_t, false, FUSE>(p, stream) : launch_cls<1, float, false, FUSE>(p, stream);
+    case 2: return bf16_out ? launch_cls<2, uint16_t, false, FUSE>(p, stream) : launch_cls<2, float, false, FUSE>(p, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_fast_output(const Params &p, hipStream_t stream) {
+    return p.z_gate != nullptr ? launch_output<true>(p, stream) : launch_output<false>(p, stream);
+}
+
+template <bool FUSE>
+static hipError_t launch_state(const Params &p, hipStream_t stream) {
+    switch (fast_class(p)) {
+    case 0: return launch_cls<0, float, true, FUSE>(p, stream);
+    case 1: return launch_cls<1, float, true, FUSE>(p, stream);
+    case 2: return launch_cls<2, float, true, FUSE>(p, stream);
     default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_fast_state(const Params &p, hipStream_t stream) {
-    switch (fast_class(p)) {
-    case 0: return launch_cls<0, float, true>(p, stream);
-    case 1: return launch_cls<1, float, true>(p, stream);
-    case 2: return launch_cls<2, float, true>(p, stream);
-    default: return hipErrorInvalidValue;
-    }
+    return p.z_gate != nullptr ? launch_state<true>(p, stream) : launch_state<false>(p, stream);
 }
 
 }  // namespace gla

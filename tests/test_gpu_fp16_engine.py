@@ -214,3 +214,68 @@ def test_zero_inputs_and_open_gates():
     ref, ref_fin = oracle(e, gh, gw, 0)
     out, fin = run(e, gh, gw, 0, gla.ENGINE_MFMA_FP16, cps=2)
     assert rel_err(out, ref) <= TOL_BF16 and rel_err(fin, ref_fin) <= TOL_BF16
+
+
+# ---------------------------------------------------------------------------
+# gates from their pre-activations (gla_fwd_fused without the output epilogue) on the same engine
+# ---------------------------------------------------------------------------
+def run_fused(d, gh, gw, scan, engine, cps=0, tau=16.0):
+    gla.gla_set_option(gla.OPT_ENGINE, engine)
+    gla.gla_set_option(gla.OPT_CHUNKS_PER_SPAN, cps)
+    dev = torch.device("cuda:0")
+    f = lambda n: torch.from_numpy(d[n + "_bits"].view(np.int16)).to(dev).view(torch.bfloat16)
+    out, fin = gla.gla_fwd_fused(f("q"), f("k"), f("v"), f("z"), tau, gh, gw, scan)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy(), fin.cpu().numpy()
+
+
+def oracle_fused(d, gh, gw, scan, tau=16.0):
+    from oracle import gla_oracle_fused as fo
+    return fo.gla_fused(d["q"], d["k"], d["v"], d["z"], tau, None, None, None, 1e-5, gh, gw, scan)
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 16, 16, 32, 64), (1, 2, 30, 30, 36, 72), (1, 2, 16, 24, 64, 128),
+                                   (1, 2, 13, 11, 20, 24), (1, 2, 21, 13, 52, 96)])
+def test_gate_prologue_shapes_plans_scans(shape):
+    B, H, gh, gw, dk, dv = shape
+    d = gi.make_fused_inputs(B, H, gh * gw, dk, dv, "bf16", seed=13)
+    for cps in (0, 2):
+        for scan in range(4):
+            ref, ref_fin = oracle_fused(d, gh, gw, scan)
+            out, fin = run_fused(d, gh, gw, scan, gla.ENGINE_MFMA_FP16, cps=cps)
+            e_out, e_fin = rel_err(out, ref), rel_err(fin, ref_fin)
+            print(f"  {shape} cps={cps} scan={scan}: err(out)={e_out:.3e} err(state)={e_fin:.3e}", flush=True)
+            assert np.isfinite(out).all() and e_out <= TOL_BF16 and e_fin <= TOL_BF16
+
+
+def test_gate_prologue_auto_engine_temperature_and_closed_gates():
+    gh, gw, dk, dv = 32, 24, 36, 72
+    d = gi.make_fused_inputs(1, 3, gh * gw, dk, dv, "bf16", seed=4)
+    ref, ref_fin = oracle_fused(d, gh, gw, 1)
+    auto = run_fused(d, gh, gw, 1, gla.ENGINE_AUTO)
+    fp16 = run_fused(d, gh, gw, 1, gla.ENGINE_MFMA_FP16)
+    hilo = run_fused(d, gh, gw, 1, gla.ENGINE_MFMA)
+    assert np.array_equal(auto[0], fp16[0]) and np.array_equal(auto[1], fp16[1])   # AUTO takes this engine
+    assert rel_err(hilo[0], ref) < rel_err(fp16[0], ref) <= TOL_BF16
+    # another temperature; and gates that close fast (z around -8 at tau = 16: a channel decays by 2^-23 over half a
+    # chunk), which leave the fp16 range and are recomputed by the hi/lo kernel with the prologue
+    ref4, fin4 = oracle_fused(d, gh, gw, 2, tau=4.0)
+    out4, f4 = run_fused(d, gh, gw, 2, gla.ENGINE_MFMA_FP16, cps=2, tau=4.0)
+    assert rel_err(out4, ref4) <= TOL_BF16 and rel_err(f4, fin4) <= TOL_BF16
+    dc = gi.make_fused_inputs(1, 3, gh * gw, dk, dv, "bf16", seed=4, z_mean=-8.0)
+    refc, finc = oracle_fused(dc, gh, gw, 0)
+    outc, fc = run_fused(dc, gh, gw, 0, gla.ENGINE_MFMA_FP16, cps=2)
+    e_out, e_fin = rel_err(outc, refc), rel_err(fc, finc)
+    print(f"  closed gates: err(out)={e_out:.3e} err(state)={e_fin:.3e}", flush=True)
+    assert np.isfinite(outc).all() and e_out <= 5e-4 and e_fin <= 5e-4
+
+
+@pytest.mark.parametrize("name,scan", [("dig_xl2_1024", 2), ("dig_xl2_2048", 0)])
+def test_gate_prologue_contract_workloads(name, scan):
+    cfg = gi.CONFIGS[name]
+    d = gi.make_fused_inputs(cfg.B, cfg.H, cfg.T, cfg.dk, cfg.dv, cfg.dtype, seed=cfg.seed, z_mean=cfg.z_mean)
+    ref, ref_fin = oracle_fused(d, cfg.grid_h, cfg.grid_w, scan)
+    out, fin = run_fused(d, cfg.grid_h, cfg.grid_w, scan, gla.ENGINE_AUTO)
+    e_out, e_fin = rel_err(out, ref), rel_err(fin, ref_fin)
+    print(f"  {name} scan={scan}: err(out)={e_out:.3e} err(state)={e_fin:.3e}", flush=True)
+    assert e_out <= TOL_BF16 and e_fin <= TOL_BF16
