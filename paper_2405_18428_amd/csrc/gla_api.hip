@@ -1,5 +1,6 @@
 // Host side of the C ABI declared in include/gla.h: argument validation, launch
 // plan, library-owned scratch for gla_fwd, and the timing aid.
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -10,11 +11,13 @@ namespace {
 
 constexpr int kVersion = 330;  // 0.3.3
 
-int g_opt_chunks_per_span = 0;
-int g_opt_engine = GLA_ENGINE_AUTO;
-int g_opt_carry = GLA_CARRY_AUTO;
-int g_opt_bwd_split = 0;
-int g_opt_range_fallback = 1;
+// process-wide options (gla_set_option): atomics, so that a setter on one host thread and calls on another do not
+// race on them; a call reads them as it goes, so options are meant to be set between calls, not during one
+std::atomic<int> g_opt_chunks_per_span{0};
+std::atomic<int> g_opt_engine{GLA_ENGINE_AUTO};
+std::atomic<int> g_opt_carry{GLA_CARRY_AUTO};
+std::atomic<int> g_opt_bwd_split{0};
+std::atomic<int> g_opt_range_fallback{1};
 
 // Most spans per (batch, head) that the output pass chains by itself: work-group r reads the r local states
 // before it, so the reads grow with the square of the span count while a carry kernel's grow linearly.

@@ -385,7 +385,7 @@ template <typename TIn, int PW>
 hipError_t launch_dg(const Params &p, const float *dq, const float *dk_grad, float *dg, float *totals, int ndg,
                      hipStream_t stream) {
     auto kernel = dg_local_kernel<TIn, PW>;
-    static bool configured[kMaxDevices] = {};  // per instantiation and device
+    static std::atomic<bool> configured[kMaxDevices] = {};  // per instantiation and device
     {
         hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), (int)kDgLdsMax, configured);
         if (e != hipSuccess) return e;

@@ -14,6 +14,7 @@
 // the SREM convolution reuse this plan and these parameters.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -111,7 +112,7 @@ __host__ __device__ inline size_t slab_v(const Params &p, int bh) {
 // Raises a kernel's dynamic-LDS limit once per device and kernel (`done` is the caller's per-kernel flag array,
 // indexed by device ordinal; the attribute is per device).
 constexpr int kMaxDevices = 64;
-inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, bool (&done)[kMaxDevices]) {
+inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, std::atomic<bool> (&done)[kMaxDevices]) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;

@@ -809,7 +809,7 @@ hipError_t launch_cls(const Params &p, hipStream_t stream) {
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int MINW = kGroupsPerCu >= 2 ? 4 : 2;    // waves per SIMD: two resident groups of 8 waves, or one
     auto kernel = fast_span_kernel<CLS, TOut, MINW, STATE, FUSE>;
-    static bool configured[kMaxDevices] = {};
+    static std::atomic<bool> configured[kMaxDevices] = {};
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), L::kBytes, configured);
     if (e != hipSuccess) return e;
     const int spans = (STATE && p.chain_in_output) ? p.nspans - 1 : p.nspans;

@@ -1036,7 +1036,7 @@ hipError_t launch_depth(const Params &p, hipStream_t stream) {
     constexpr int kWavesPerSimd = kGroupsPerCu * NW / 4;
     constexpr int MINW = kWavesPerSimd >= 4 ? 4 : (kWavesPerSimd >= 2 ? 2 : 1);
     auto kernel = mfma_span_kernel<MODE, NDK8, NDV16, NW, MINW, DEPTH, FUSE, ACC, TOut, BETA>;
-    static bool configured[kMaxDevices] = {};  // per instantiation and device
+    static std::atomic<bool> configured[kMaxDevices] = {};  // per instantiation and device
     {
         hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), L::kBytes, configured);
         if (e != hipSuccess) return e;

@@ -669,7 +669,7 @@ hipError_t launch_one(const Params &p, const void *w, float *r, hipStream_t stre
     constexpr int kGroupsPerCu = (160 * 1024) / L::kBytes;
     constexpr int MINW = kGroupsPerCu >= 2 ? 2 : 1;
     auto kernel = mfma_row_read_kernel<NDK8, NDV16, MINW, DV, BETA>;
-    static bool configured[kMaxDevices] = {};  // per instantiation and device
+    static std::atomic<bool> configured[kMaxDevices] = {};  // per instantiation and device
     {
         hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), L::kBytes, configured);
         if (e != hipSuccess) return e;
