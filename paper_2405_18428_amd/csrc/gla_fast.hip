@@ -440,12 +440,17 @@ __global__ __launch_bounds__(kFastThreads, MINW) void fast_span_kernel(Params p)
         // that makes its tile totals visible the loop starts with iteration -1.  The loop is entered with no load
         // in flight, so the counts of younger loads that the waits inside it allow are those of the steady state.
         {
+            // (requested in the order the loop leaves its loads in at the end of an iteration - q and k, the gates of
+            // the chunk after, v: the compiler merges the two states at the loop's entry, and a gate row that
+            // looked younger than a v row there would make every scan of the loop wait for the v rows requested
+            // just before it)
             GatePiece la1[NCT];
+            const int tok0 = tok;
             issue_la(r_la);
-            issue_qk(tok);
-            issue_v(tok);
+            issue_qk(tok0);
             next_row_token();
             issue_la(la1);
+            issue_v(tok0);
             if constexpr (!STATE) {
                 // with those loads in flight, the producers' half of the span-state chain
                 if (p.chain_in_output && (sp > 0 || p.initial_state != nullptr)) {   // uniform
